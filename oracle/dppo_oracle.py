@@ -1,0 +1,203 @@
+"""Float64 CPU oracle for the DPPO per-token divergence trust-region loss.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+GPU library is checked against.  It is imported by the tests, by the smoke
+check and by the benchmark's CPU-baseline leg; no product code path may call
+it.  It shares no code with the HIP kernels and imports nothing from the
+product package.
+
+Everything is numpy float64, one row (one response token) at a time, in the
+order and notation of the paper:
+
+  * log-softmax of the trainer logits            (Sec. 3, token distribution pi(.|s_t))
+  * ratio r_t = pi(a_t|s_t) / mu(a_t|s_t), mu the ROLLOUT policy
+                                                  (Eq. ppo-clip; Sec. 5.2 Takeaway 2)
+  * Binary-TV / Binary-KL                         (Eq. binary_tv, Eq. binary_kl)
+  * Top-K reduced distributions, TV and KL        (Sec. 4.4 "Top-K Approximation",
+                                                   Eq. topk_tv, Eq. topk_kl)
+  * DPPO mask and masked surrogate                (Eq. dppo_obj)
+  * gradient wrt the logits, mask held constant   (Eq. unified_grad with C = infinity)
+  * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL)
+
+Readings taken where the paper is silent (each is listed in the design notes):
+  - the library returns the quantity to MINIMISE: loss = -loss_scale * sum_t M_t r_t A_t;
+    loss_scale is the caller's normalisation (the paper writes an expectation of a sum);
+  - KL is D(mu || pi) in nats;
+  - comparisons are strict, and "r > 1" is evaluated as log pi(a) > log mu(a);
+  - x*log(x/y) = 0 when x = 0; a vanishing denominator y is floored at 1e-30;
+  - mu probabilities > 1 from rounding are clamped to 1, and the "other" bucket of either
+    policy is clamped to >= 0;
+  - a top-K id equal to a_t is dropped (a_t's own mu log-prob is used), ids < 0 are padding;
+  - a row with sampled id < 0 is ignored: D = 0, M = 0, loss term 0, zero gradient row.
+
+All pins for these functions live in tests/test_oracle_*.py; none is "parity unpinned"
+except the two parameterised-away choices named in the design notes (loss normalisation,
+finite ratio cap C).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+VARIANT_NAMES = {BINARY_TV: "binary_tv", BINARY_KL: "binary_kl",
+                 TOPK_TV: "topk_tv", TOPK_KL: "topk_kl"}
+_TINY = 1e-30
+
+
+# --------------------------------------------------------------------------- softmax
+def log_softmax(z):
+    """log pi_j = z_j - (m + ln sum_j exp(z_j - m)) for one row z[V]  (Sec. 3)."""
+    z = np.asarray(z, dtype=np.float64)
+    m = z.max()
+    S = np.exp(z - m).sum()
+    return z - (m + np.log(S))
+
+
+# --------------------------------------------------------------------------- divergences
+def _xlogx_over_y(x, y):
+    """x * ln(x / y) with 0*ln 0 = 0 and y floored at 1e-30 (reading for saturated cases)."""
+    if x <= 0.0:
+        return 0.0
+    return x * (np.log(x) - np.log(max(y, _TINY)))
+
+
+def binary_tv(lmu_a, lpi_a):
+    """|mu(a_t) - pi(a_t)|  (Eq. binary_tv)."""
+    p = np.exp(min(lmu_a, 0.0))
+    q = np.exp(lpi_a)
+    return abs(p - q)
+
+
+def binary_kl(lmu_a, lpi_a, one_minus_q=None):
+    """mu ln(mu/pi) + (1-mu) ln((1-mu)/(1-pi))  (Eq. binary_kl).
+
+    one_minus_q, when given, is sum_{j != a} pi_j computed from the full row (avoids
+    1 - q cancellation); otherwise -expm1(lpi_a) is used.
+    """
+    lmu_a = min(lmu_a, 0.0)
+    p = np.exp(lmu_a)
+    q = np.exp(lpi_a)
+    one_minus_p = -np.expm1(lmu_a)
+    if one_minus_q is None:
+        one_minus_q = -np.expm1(min(lpi_a, 0.0))
+    return _xlogx_over_y(p, q) + _xlogx_over_y(one_minus_p, one_minus_q)
+
+
+def reduced_distributions(logpi, a, lmu_a, topk_ids, topk_logp):
+    """Reduced categorical distributions over A'' = TopK(mu, K) U {a_t} U {other}.
+
+    Returns (p, q, p_other, q_other) with p, q arrays over A' (a_t first).  For tokens in
+    A' the probabilities are the original ones; "other" is one minus their sum, clamped at
+    0 (Sec. 4.4, Top-K Approximation).
+    """
+    ids = [int(a)]
+    p = [np.exp(min(float(lmu_a), 0.0))]
+    if topk_ids is not None:
+        for i, lp in zip(np.asarray(topk_ids).tolist(), np.asarray(topk_logp, dtype=np.float64).tolist()):
+            if i < 0 or i == int(a):
+                continue  # padding, or a_t already present
+            ids.append(int(i))
+            p.append(np.exp(min(lp, 0.0)))
+    p = np.asarray(p, dtype=np.float64)
+    q = np.exp(logpi[np.asarray(ids, dtype=np.int64)])
+    p_other = max(1.0 - p.sum(), 0.0)
+    q_other = max(1.0 - q.sum(), 0.0)
+    return p, q, p_other, q_other
+
+
+def topk_tv(p, q, p_other, q_other):
+    """1/2 sum_{A''} |p^mu - p^pi|  (Eq. topk_tv)."""
+    return 0.5 * (np.abs(p - q).sum() + abs(p_other - q_other))
+
+
+def topk_kl(p, q, p_other, q_other):
+    """sum_{A''} p^mu ln(p^mu / p^pi)  (Eq. topk_kl)."""
+    d = 0.0
+    for x, y in zip(p.tolist(), q.tolist()):
+        d += _xlogx_over_y(x, y)
+    return d + _xlogx_over_y(p_other, q_other)
+
+
+def full_tv(mu_probs, pi_probs):
+    """Exact D_TV = 1/2 sum_a |mu(a) - pi(a)|  (App. B.1)."""
+    mu_probs = np.asarray(mu_probs, dtype=np.float64)
+    pi_probs = np.asarray(pi_probs, dtype=np.float64)
+    return 0.5 * np.abs(mu_probs - pi_probs).sum()
+
+
+def full_kl(mu_probs, pi_probs):
+    """Exact D_KL(mu || pi) = sum_a mu(a) ln(mu(a)/pi(a))  (App. B.2)."""
+    d = 0.0
+    for x, y in zip(np.asarray(mu_probs, dtype=np.float64).tolist(),
+                    np.asarray(pi_probs, dtype=np.float64).tolist()):
+        d += _xlogx_over_y(x, y)
+    return d
+
+
+# --------------------------------------------------------------------------- mask
+def dppo_mask(D, delta, adv, lpi_a, lmu_a):
+    """M_t of Eq. dppo_obj: 0 iff D > delta and the update moves r further from 1 in the
+    direction the advantage favours; 1 otherwise.  r > 1 is tested as lpi_a > lmu_a."""
+    if D > delta and ((adv > 0.0 and lpi_a > lmu_a) or (adv < 0.0 and lpi_a < lmu_a)):
+        return 0
+    return 1
+
+
+# --------------------------------------------------------------------------- whole path
+def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
+              mu_topk_ids=None, mu_topk_logp=None, want_grad=True):
+    """The whole hot path for T rows.
+
+    logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
+    mu_logp [T], advantages [T], optional mu_topk_ids / mu_topk_logp [T, K].
+    Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
+    ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None.
+    """
+    logits = np.asarray(logits, dtype=np.float64)
+    T, V = logits.shape
+    sampled_ids = np.asarray(sampled_ids, dtype=np.int64)
+    mu_logp = np.asarray(mu_logp, dtype=np.float64)
+    advantages = np.asarray(advantages, dtype=np.float64)
+    topk = variant in (TOPK_TV, TOPK_KL)
+    if variant not in VARIANT_NAMES:
+        raise ValueError("unknown variant")
+
+    out = {
+        "loss_tok": np.zeros(T), "divergence": np.zeros(T), "mask": np.zeros(T, dtype=np.uint8),
+        "ratio": np.zeros(T), "logp": np.zeros(T), "lse": np.zeros(T),
+        "grad_logits": np.zeros((T, V)) if want_grad else None,
+    }
+    for t in range(T):
+        a = int(sampled_ids[t])
+        if a < 0:
+            continue  # ignored row: everything stays 0
+        z = logits[t]
+        logpi = log_softmax(z)                       # step 1
+        lpi = logpi[a]
+        lmu = float(mu_logp[t])
+        r = np.exp(lpi - lmu)                        # step 2
+        if variant == BINARY_TV:                     # step 3
+            D = binary_tv(lmu, lpi)
+        elif variant == BINARY_KL:
+            pi_row = np.exp(logpi)
+            one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()
+            D = binary_kl(lmu, lpi, one_minus_q)
+        else:
+            ids = mu_topk_ids[t] if (mu_topk_ids is not None) else None
+            lps = mu_topk_logp[t] if (mu_topk_logp is not None) else None
+            p, q, po, qo = reduced_distributions(logpi, a, lmu, ids, lps)
+            D = topk_tv(p, q, po, qo) if variant == TOPK_TV else topk_kl(p, q, po, qo)
+        A = float(advantages[t])
+        M = dppo_mask(D, delta, A, lpi, lmu)         # step 4
+        out["divergence"][t] = D
+        out["mask"][t] = M
+        out["ratio"][t] = r
+        out["logp"][t] = lpi
+        out["lse"][t] = z[a] - lpi
+        out["loss_tok"][t] = -M * r * A              # step 5
+        if want_grad:                                # step 6
+            g = np.exp(logpi)
+            g[a] -= 1.0
+            out["grad_logits"][t] = (loss_scale * M * A * r) * g
+    out["loss"] = float(loss_scale * out["loss_tok"].sum())
+    return out

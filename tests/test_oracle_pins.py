@@ -1,0 +1,411 @@
+"""Pins for the float64 oracle: each test ties one part of oracle/dppo_oracle.py to
+something other than itself -- values the paper prints, a library routine, a closed form,
+a theorem of App. B, brute force on tiny vocabularies, finite differences, autograd."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+import torch
+
+from oracle import dppo_oracle as O
+from paper_2602_04879_amd import workloads as W
+
+RNG = np.random.default_rng(20260204)
+
+
+def _rand_dist(V, peaked=False):
+    z = RNG.normal(0, 3.0 if peaked else 1.0, size=V)
+    p = np.exp(z - z.max())
+    return p / p.sum()
+
+
+def _logits_for(probs):
+    """Logits whose softmax is exactly `probs` (up to float64 rounding)."""
+    return np.log(np.asarray(probs, dtype=np.float64))
+
+
+# ------------------------------------------------------------------ log-softmax (Sec. 3)
+@pytest.mark.parametrize("V", [1, 2, 7, 1000])
+def test_log_softmax_matches_library(V):
+    z = RNG.normal(0, 5, size=V) + 30.0
+    got = O.log_softmax(z)
+    np.testing.assert_allclose(got, scipy.special.log_softmax(z), rtol=0, atol=1e-12)
+    assert abs(np.exp(got).sum() - 1.0) < 1e-12
+    # shift invariance and no overflow at large offsets
+    np.testing.assert_allclose(O.log_softmax(z + 1e4), got, atol=1e-9)
+
+
+# ------------------------------------------------------------------ paper's worked example
+def _worked_rows(golden_dir):
+    rows = {}
+    with open(os.path.join(golden_dir, "worked_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, mu, pi, r, d = line.split()
+            rows[name] = tuple(map(float, (mu, pi, r, d)))
+    return rows
+
+
+def _row_with(pi_a, V=50, a=3):
+    """A logits row whose softmax gives exactly pi_a to token a, the rest spread randomly."""
+    rest = _rand_dist(V - 1) * (1.0 - pi_a)
+    probs = np.insert(rest, a, pi_a)
+    return _logits_for(probs)
+
+
+def test_worked_example_ratio_divergence_mask(golden_dir):
+    rows = _worked_rows(golden_dir)
+    a = 3
+    for name, (mu, pi, r_printed, d_printed) in rows.items():
+        z = _row_with(pi, a=a)
+        for adv in (+1.0, -1.0):
+            out = O.dppo_loss(z[None, :], [a], [math.log(mu)], [adv], delta=0.2, variant=O.BINARY_TV)
+            assert out["ratio"][0] == pytest.approx(r_printed, rel=1e-3)   # 0.808 is printed to 3 digits
+            assert out["divergence"][0] == pytest.approx(d_printed, rel=1e-9)
+    mu, pi, _, _ = rows["low"]
+    z = _row_with(pi, a=a)
+    # r = 100 with a positive advantage: PPO would clip it, DPPO keeps it (D = 0.0099 << delta)
+    out = O.dppo_loss(z[None, :], [a], [math.log(mu)], [1.0], delta=0.15, variant=O.BINARY_TV)
+    assert out["ratio"][0] == pytest.approx(100.0, rel=1e-12) and out["mask"][0] == 1
+    mu, pi, _, _ = rows["high"]
+    z = _row_with(pi, a=a)
+    # r = 0.808 stays inside a 0.2 ratio clip, but removes 0.19 mass: blocked at delta_TV = 0.15
+    # (App. C.1 threshold) for a negative advantage, allowed at delta_TV = 0.2 (App. E).
+    for delta, adv, m in ((0.15, -1.0, 0), (0.2, -1.0, 1), (0.15, +1.0, 1)):
+        out = O.dppo_loss(z[None, :], [a], [math.log(mu)], [adv], delta=delta, variant=O.BINARY_TV)
+        assert out["mask"][0] == m, (delta, adv)
+
+
+# ------------------------------------------------------------------ Binary-KL (Eq. binary_kl)
+def test_binary_kl_is_bernoulli_kl_from_library():
+    for _ in range(200):
+        p, q = RNG.uniform(1e-6, 1 - 1e-6, size=2)
+        ref = scipy.special.rel_entr([p, 1 - p], [q, 1 - q]).sum()
+        assert O.binary_kl(math.log(p), math.log(q)) == pytest.approx(ref, rel=1e-9, abs=1e-15)
+        assert O.binary_kl(math.log(p), math.log(q), one_minus_q=1 - q) == pytest.approx(ref, rel=1e-9, abs=1e-15)
+        # Pinsker on the Bernoulli pair (Sec. 2): TV^2 <= KL / 2
+        assert O.binary_tv(math.log(p), math.log(q)) ** 2 <= 0.5 * ref + 1e-15
+    assert O.binary_kl(math.log(0.3), math.log(0.3)) == pytest.approx(0.0, abs=1e-16)
+    # direction: D(mu || pi), not D(pi || mu)
+    p, q = 0.9, 0.1
+    assert O.binary_kl(math.log(p), math.log(q)) == pytest.approx(
+        p * math.log(p / q) + (1 - p) * math.log((1 - p) / (1 - q)), rel=1e-12)
+    p, q = 0.5, 0.01
+    assert O.binary_kl(math.log(p), math.log(q)) != pytest.approx(O.binary_kl(math.log(q), math.log(p)))
+
+
+def test_binary_saturation_readings():
+    # mu log-prob slightly above 0 from fp32 noise: p clamps to 1, (1-p) term vanishes
+    d = O.binary_kl(1e-7, math.log(0.9))
+    assert d == pytest.approx(-math.log(0.9), rel=1e-12)
+    assert O.binary_tv(1e-7, math.log(0.9)) == pytest.approx(0.1, rel=1e-12)
+    # pi(a) == 1 exactly while mu(a) < 1: denominator floored -> finite and large
+    d = O.binary_kl(math.log(0.5), 0.0, one_minus_q=0.0)
+    assert np.isfinite(d) and d > 10.0
+
+
+# ------------------------------------------------------------------ exact divergences (App. B)
+def test_full_tv_and_kl_match_definitions_and_identities():
+    for V in (2, 5, 64):
+        mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+        tv = O.full_tv(mu, pi)
+        # Eq. tv_as_expectation: D_TV = 1/2 E_{a~mu} |r(a) - 1|
+        assert tv == pytest.approx(0.5 * (mu * np.abs(pi / mu - 1.0)).sum(), rel=1e-12)
+        assert 0.0 <= tv <= 1.0
+        assert O.full_kl(mu, pi) == pytest.approx(scipy.stats.entropy(mu, pi), rel=1e-10)
+        assert tv ** 2 <= 0.5 * O.full_kl(mu, pi) + 1e-15      # Pinsker
+    assert O.full_tv([1, 0], [0, 1]) == 1.0
+    assert O.full_kl([0.5, 0.5, 0.0], [0.25, 0.25, 0.5]) == pytest.approx(math.log(2))  # 0 ln 0 = 0
+
+
+# ------------------------------------------------------------------ Top-K (Sec. 4.4)
+def _topk_inputs(mu, K, a):
+    ids = np.argsort(-mu, kind="stable")[:K].astype(np.int64)
+    return ids, np.log(mu[ids])
+
+
+@pytest.mark.parametrize("variant_pair", [(O.BINARY_TV, O.TOPK_TV), (O.BINARY_KL, O.TOPK_KL)])
+def test_topk_with_k0_is_binary(variant_pair):
+    vb, vt = variant_pair
+    V = 40
+    for _ in range(20):
+        mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+        a = int(RNG.integers(V))
+        z = _logits_for(pi)[None, :]
+        ob = O.dppo_loss(z, [a], [math.log(mu[a])], [1.0], 0.1, vb)
+        ot = O.dppo_loss(z, [a], [math.log(mu[a])], [1.0], 0.1, vt)          # no top-K given
+        ot2 = O.dppo_loss(z, [a], [math.log(mu[a])], [1.0], 0.1, vt,
+                          mu_topk_ids=np.full((1, 3), -1), mu_topk_logp=np.zeros((1, 3)))  # all padding
+        assert ot["divergence"][0] == pytest.approx(ob["divergence"][0], rel=1e-9, abs=1e-15)
+        assert ot2["divergence"][0] == pytest.approx(ob["divergence"][0], rel=1e-9, abs=1e-15)
+
+
+def test_topk_with_whole_vocabulary_is_exact_divergence():
+    V = 24
+    for _ in range(20):
+        mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+        a = int(RNG.integers(V))
+        z = _logits_for(pi)
+        ids, lps = _topk_inputs(mu, V, a)          # K = V: "other" is empty
+        p, q, po, qo = O.reduced_distributions(O.log_softmax(z), a, math.log(mu[a]), ids, lps)
+        assert len(p) == V and po == pytest.approx(0, abs=1e-12) and qo == pytest.approx(0, abs=1e-12)
+        assert O.topk_tv(p, q, po, qo) == pytest.approx(O.full_tv(mu, pi), rel=1e-9)
+        assert O.topk_kl(p, q, po, qo) == pytest.approx(scipy.stats.entropy(mu, pi), rel=1e-9)
+        ids, lps = _topk_inputs(mu, V - 1, a)      # K = V-1: "other" is a single token -> still exact
+        p, q, po, qo = O.reduced_distributions(O.log_softmax(z), a, math.log(mu[a]), ids, lps)
+        assert O.topk_tv(p, q, po, qo) == pytest.approx(O.full_tv(mu, pi), rel=1e-9)
+        assert O.topk_kl(p, q, po, qo) == pytest.approx(scipy.stats.entropy(mu, pi), rel=1e-8)
+
+
+def test_lower_bound_chain_binary_topk_full():
+    """Coarsening cannot raise TV (triangle inequality) or KL (log-sum inequality): App. B.
+    The Top-K partition refines the Binary one, so D_bin <= D_topK <= D_full; and the TV gap
+    is at most half the mass both policies put on "other"."""
+    V = 64
+    for trial in range(100):
+        mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+        a = int(RNG.choice(V, p=mu))
+        K = int(RNG.integers(1, 12))
+        ids, lps = _topk_inputs(mu, K, a)
+        lpi = O.log_softmax(_logits_for(pi))
+        p, q, po, qo = O.reduced_distributions(lpi, a, math.log(mu[a]), ids, lps)
+        tv_b, tv_k, tv_f = O.binary_tv(math.log(mu[a]), lpi[a]), O.topk_tv(p, q, po, qo), O.full_tv(mu, pi)
+        kl_b, kl_k, kl_f = O.binary_kl(math.log(mu[a]), lpi[a]), O.topk_kl(p, q, po, qo), O.full_kl(mu, pi)
+        assert tv_b <= tv_k + 1e-14 <= tv_f + 2e-14
+        assert -1e-15 <= kl_b <= kl_k + 1e-14 <= kl_f + 2e-14
+        assert tv_f - tv_k <= 0.5 * (po + qo) + 1e-14
+        assert tv_k ** 2 <= 0.5 * kl_k + 1e-15
+
+
+def test_equality_conditions():
+    V, K, a = 32, 5, 7
+    mu = _rand_dist(V, True)
+    ids, lps = _topk_inputs(mu, K, a)
+    inside = set(ids.tolist()) | {a}
+    tail = np.array([j for j in range(V) if j not in inside])
+    # TV equality: mu - pi has one sign inside every cell.  Move mass from the tail
+    # (every tail token loses) onto tokens of A'.
+    pi = mu.copy()
+    take = 0.5 * mu[tail]
+    pi[tail] -= take
+    pi[ids[0]] += take.sum()
+    lpi = O.log_softmax(_logits_for(pi))
+    p, q, po, qo = O.reduced_distributions(lpi, a, math.log(mu[a]), ids, lps)
+    assert O.topk_tv(p, q, po, qo) == pytest.approx(O.full_tv(mu, pi), rel=1e-10)
+    # ... and a tail perturbation of mixed sign leaves a strict gap
+    pi2 = mu.copy()
+    pi2[tail[0]] += 0.5 * mu[tail[1]]
+    pi2[tail[1]] -= 0.5 * mu[tail[1]]
+    lpi2 = O.log_softmax(_logits_for(pi2))
+    p, q, po, qo = O.reduced_distributions(lpi2, a, math.log(mu[a]), ids, lps)
+    assert O.topk_tv(p, q, po, qo) < O.full_tv(mu, pi2) - 1e-6
+    # KL equality: mu/pi constant on "other" -> scale the whole tail by one factor
+    pi3 = mu.copy()
+    pi3[tail] *= 0.25
+    pi3[ids[1]] += 0.75 * mu[tail].sum()
+    lpi3 = O.log_softmax(_logits_for(pi3))
+    p, q, po, qo = O.reduced_distributions(lpi3, a, math.log(mu[a]), ids, lps)
+    assert O.topk_kl(p, q, po, qo) == pytest.approx(O.full_kl(mu, pi3), rel=1e-9)
+    # Binary-KL equality: all tokens other than a_t scaled by one factor
+    pi4 = mu.copy()
+    pi4[a] = 0.5 * mu[a]
+    others = np.arange(V) != a
+    pi4[others] *= (1 - pi4[a]) / (1 - mu[a])
+    lpi4 = O.log_softmax(_logits_for(pi4))
+    assert O.binary_kl(math.log(mu[a]), lpi4[a]) == pytest.approx(O.full_kl(mu, pi4), rel=1e-9)
+    assert O.binary_tv(math.log(mu[a]), lpi4[a]) == pytest.approx(O.full_tv(mu, pi4), rel=1e-9)
+
+
+def test_topk_dedupes_sampled_token_and_skips_padding():
+    V, a = 16, 2
+    mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+    lpi = O.log_softmax(_logits_for(pi))
+    ids = np.array([5, a, 9, -1])
+    lps = np.log(mu[[5, a, 9, 0]])
+    lps[1] = math.log(0.999)          # the top-K copy of a_t's log-prob must NOT be used
+    p, q, po, qo = O.reduced_distributions(lpi, a, math.log(mu[a]), ids, lps)
+    np.testing.assert_allclose(p, mu[[a, 5, 9]], rtol=1e-12)
+    np.testing.assert_allclose(q, pi[[a, 5, 9]], rtol=1e-12)
+    assert po == pytest.approx(1 - mu[[a, 5, 9]].sum(), rel=1e-12)
+    assert qo == pytest.approx(1 - pi[[a, 5, 9]].sum(), rel=1e-12)
+    # mu log-probs summing past 1 (fp32 noise): "other" clamps to 0, never negative
+    p, q, po, qo = O.reduced_distributions(lpi, a, math.log(0.6), np.array([5]), np.array([math.log(0.5)]))
+    assert po == 0.0
+
+
+def test_topk_tv_hand_computed():
+    # 4 tokens, A' = {0 (sampled), 1}, other = {2, 3}
+    mu = np.array([0.5, 0.3, 0.15, 0.05])
+    pi = np.array([0.4, 0.35, 0.05, 0.20])
+    lpi = O.log_softmax(_logits_for(pi))
+    p, q, po, qo = O.reduced_distributions(lpi, 0, math.log(0.5), np.array([1]), np.array([math.log(0.3)]))
+    assert po == pytest.approx(0.2) and qo == pytest.approx(0.25)
+    assert O.topk_tv(p, q, po, qo) == pytest.approx(0.5 * (0.1 + 0.05 + 0.05))
+    assert O.full_tv(mu, pi) == pytest.approx(0.5 * (0.1 + 0.05 + 0.10 + 0.15))
+    kl = 0.5 * math.log(0.5 / 0.4) + 0.3 * math.log(0.3 / 0.35) + 0.2 * math.log(0.2 / 0.25)
+    assert O.topk_kl(p, q, po, qo) == pytest.approx(kl, rel=1e-12)
+
+
+# ------------------------------------------------------------------ mask (Eq. dppo_obj)
+def test_mask_truth_table(golden_dir):
+    delta = 0.1
+    val = {"gt": 1, "eq": 0, "lt": -1}
+    n = 0
+    with open(os.path.join(golden_dir, "mask_truth_table.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            s, rr, dd, m = line.split()
+            adv = {"+": 0.7, "0": 0.0, "-": -0.7}[s]
+            lmu = -1.25
+            lpi = lmu + 0.5 * val[rr]
+            D = delta + 0.03 * val[dd]
+            assert O.dppo_mask(D, delta, adv, lpi, lmu) == int(m), line
+            n += 1
+    assert n == 27
+
+
+def test_mask_with_ratio_distance_recovers_ppo_clip():
+    """Replacing D by |r - 1| gives the PPO/GRPO clip mask with a symmetric epsilon (Sec. 4.3);
+    the GRPO mask is written out from App. C.1."""
+    eps = 0.2
+    for _ in range(2000):
+        lmu = -RNG.uniform(0.01, 5)
+        lpi = lmu + RNG.normal(0, 0.3)
+        adv = RNG.choice([-1.0, 0.0, 1.0]) * RNG.uniform(0.1, 2)
+        r = math.exp(lpi - lmu)
+        grpo = 0 if ((adv > 0 and r > 1 + eps) or (adv < 0 and r < 1 - eps)) else 1
+        assert O.dppo_mask(abs(r - 1.0), eps, adv, lpi, lmu) == grpo
+
+
+# ------------------------------------------------------------------ whole path on generated batches
+def _small_batch(variant, K=0, V=257, n_seq=4, seq_len=6, noise=0.3, shift=0.0, seed=7):
+    w = W.Workload("t", n_seq, seq_len, V, variant, 0.05, K=K, logit_std=2.0, noise_std=noise,
+                   adv="normal", seed=seed)
+    b = W.make_batch(w, "cpu", keep_mu_full=True, shift_sampled=shift)
+    return W.to_host(b)
+
+
+def _run(h, **kw):
+    args = dict(logits=h["logits"], sampled_ids=h["sampled_ids"], mu_logp=h["mu_logp"],
+                advantages=h["advantages"], delta=h["delta"], variant=h["variant"],
+                loss_scale=h["loss_scale"], mu_topk_ids=h["mu_topk_ids"], mu_topk_logp=h["mu_topk_logp"])
+    args.update(kw)
+    return O.dppo_loss(**args)
+
+
+@pytest.mark.parametrize("variant,K", [(O.BINARY_TV, 0), (O.BINARY_KL, 0), (O.TOPK_TV, 8), (O.TOPK_KL, 8)])
+def test_generated_batch_against_brute_force(variant, K):
+    h = _small_batch(variant, K, shift=3.0)
+    out = _run(h)
+    mu_full = np.exp(h["mu_logp_full"].astype(np.float64))
+    pi_full = np.exp(np.stack([O.log_softmax(r) for r in h["logits"]]))
+    masked = 0
+    for t in range(h["T"]):
+        exact = O.full_tv(mu_full[t], pi_full[t]) if variant in (O.BINARY_TV, O.TOPK_TV) \
+            else O.full_kl(mu_full[t], pi_full[t])
+        # mu comes in fp32, so allow its rounding in the bound
+        assert -1e-12 <= out["divergence"][t] <= exact + 1e-6
+        a = int(h["sampled_ids"][t])
+        assert out["ratio"][t] == pytest.approx(pi_full[t, a] / math.exp(h["mu_logp"][t]), rel=1e-9)
+        masked += int(out["mask"][t] == 0)
+    assert 0 < masked < h["T"]          # the stress recipe exercises both mask values
+
+
+def test_topk_tv_gap_shrinks_with_k():
+    h = _small_batch(O.TOPK_TV, 16, V=300, shift=1.0)
+    d_prev = _run(h, variant=O.BINARY_TV)["divergence"]
+    for k in (1, 4, 16):
+        d = _run(h, mu_topk_ids=h["mu_topk_ids"][:, :k], mu_topk_logp=h["mu_topk_logp"][:, :k])["divergence"]
+        assert np.all(d >= d_prev - 1e-12)
+        d_prev = d
+
+
+@pytest.mark.parametrize("variant,K", [(O.BINARY_TV, 0), (O.BINARY_KL, 0), (O.TOPK_TV, 5), (O.TOPK_KL, 5)])
+def test_identical_policies_give_zero_divergence_full_mask_closed_form_loss(variant, K):
+    h = _small_batch(variant, K, V=129, noise=0.0)
+    # with zero rollout noise mu is the fp32 log-softmax of the same logits: pi == mu to ~1e-7
+    out = _run(h, delta=1e-5)
+    assert np.all(out["divergence"] < 5e-6) and np.all(out["divergence"] >= -1e-14)
+    assert np.all(out["mask"] == 1)
+    np.testing.assert_allclose(out["ratio"], 1.0, atol=1e-5)
+    assert out["loss"] == pytest.approx(-h["loss_scale"] * h["advantages"].astype(np.float64).sum(), rel=1e-5, abs=1e-7)
+    # exactly identical: feed float64 log-probs of pi itself
+    lp = np.stack([O.log_softmax(r) for r in h["logits"]])
+    a = h["sampled_ids"].astype(np.int64)
+    lmu = lp[np.arange(h["T"]), a]
+    tk = np.take_along_axis(lp, h["mu_topk_ids"].astype(np.int64), 1) if K else None
+    out = _run(h, mu_logp=lmu, mu_topk_logp=tk, delta=0.0)
+    assert np.all(np.abs(out["divergence"]) <= 1e-14) and np.all(out["mask"] == 1)
+    assert out["loss"] == pytest.approx(-h["loss_scale"] * h["advantages"].astype(np.float64).sum(), rel=1e-12)
+
+
+@pytest.mark.parametrize("variant,K", [(O.BINARY_TV, 0), (O.TOPK_KL, 4)])
+def test_gradient_finite_differences_and_structure(variant, K):
+    h = _small_batch(variant, K, V=33, n_seq=2, seq_len=3, shift=1.0)
+    out = _run(h)
+    g = out["grad_logits"]
+    z = h["logits"].astype(np.float64)
+    eps = 1e-6
+
+    def frozen_loss(zz):
+        """Step 5 with the mask of the unperturbed point held constant (Eq. unified_grad treats
+        M as a factor, not a function of theta)."""
+        tot = 0.0
+        for t in range(h["T"]):
+            lpi = O.log_softmax(zz[t])[int(h["sampled_ids"][t])]
+            tot += -float(out["mask"][t]) * math.exp(lpi - float(h["mu_logp"][t])) * float(h["advantages"][t])
+        return h["loss_scale"] * tot
+
+    for t in range(h["T"]):
+        for j in list(RNG.choice(33, 6, replace=False)) + [int(h["sampled_ids"][t])]:
+            zp, zm = z.copy(), z.copy()
+            zp[t, j] += eps
+            zm[t, j] -= eps
+            fd = (frozen_loss(zp) - frozen_loss(zm)) / (2 * eps)
+            assert g[t, j] == pytest.approx(fd, rel=1e-6, abs=1e-9)
+    for t in range(h["T"]):
+        a, A, M = int(h["sampled_ids"][t]), float(h["advantages"][t]), int(out["mask"][t])
+        assert abs(g[t].sum()) < 1e-12                         # softmax-minus-onehot sums to 0
+        if M == 0 or A == 0:
+            assert np.all(g[t] == 0)
+        else:
+            assert np.sign(g[t, a]) == -np.sign(A)
+            others = np.delete(g[t], a)
+            assert np.all(np.sign(others) == np.sign(A))
+
+
+@pytest.mark.parametrize("variant,K", [(O.BINARY_KL, 0), (O.TOPK_TV, 6)])
+def test_gradient_matches_autograd_of_masked_surrogate(variant, K):
+    h = _small_batch(variant, K, V=65, shift=1.0)
+    out = _run(h)
+    z = torch.tensor(h["logits"], dtype=torch.float64, requires_grad=True)
+    lp = torch.log_softmax(z, -1).gather(1, torch.tensor(h["sampled_ids"], dtype=torch.int64)[:, None]).squeeze(1)
+    r = torch.exp(lp - torch.tensor(h["mu_logp"], dtype=torch.float64))
+    M = torch.tensor(out["mask"], dtype=torch.float64)        # constant
+    loss = -(M * r * torch.tensor(h["advantages"], dtype=torch.float64)).sum() * h["loss_scale"]
+    loss.backward()
+    assert out["loss"] == pytest.approx(float(loss.detach()), rel=1e-12)
+    np.testing.assert_allclose(out["grad_logits"], z.grad.numpy(), rtol=1e-9, atol=1e-15)
+
+
+def test_ignored_rows_and_loss_scale():
+    h = _small_batch(O.BINARY_TV, 0, V=40)
+    ids = h["sampled_ids"].copy()
+    ids[::3] = -1
+    out = _run(h, sampled_ids=ids)
+    for t in range(h["T"]):
+        if ids[t] < 0:
+            assert out["divergence"][t] == 0 and out["mask"][t] == 0 and out["loss_tok"][t] == 0
+            assert np.all(out["grad_logits"][t] == 0)
+    ref = _run(h)
+    keep = ids >= 0
+    np.testing.assert_array_equal(out["divergence"][keep], ref["divergence"][keep])
+    assert out["loss"] == pytest.approx(h["loss_scale"] * ref["loss_tok"][keep].sum(), rel=1e-12)
+    out2 = _run(h, loss_scale=3.0 * h["loss_scale"])
+    assert out2["loss"] == pytest.approx(3.0 * ref["loss"], rel=1e-12)
+    np.testing.assert_allclose(out2["grad_logits"], 3.0 * ref["grad_logits"], rtol=1e-12)
