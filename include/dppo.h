@@ -1,0 +1,133 @@
+/*
+ * dppo.h -- C ABI of the DPPO per-token divergence trust-region loss for AMD MI355X (gfx950).
+ *
+ * One call evaluates, for T response tokens (rows) over a vocabulary of V entries, the policy
+ * loss of Divergence Proximal Policy Optimization ("Rethinking the Trust Region in LLM
+ * Reinforcement Learning", Sec. 4.3-4.4, App. C.1):
+ *
+ *   log pi(.|s_t)  = log-softmax of the trainer logits z[t, 0..V)                 (Sec. 3)
+ *   r_t            = pi(a_t|s_t) / mu(a_t|s_t),  mu = the ROLLOUT policy          (Eq. ppo-clip,
+ *                                                                                  Sec. 5.2)
+ *   D_t            = Binary-TV | Binary-KL | Top-K-TV | Top-K-KL of (mu || pi)    (Eq. binary_tv,
+ *                    over {a_t, rest} or over TopK(mu,K) U {a_t} U {other}         binary_kl,
+ *                                                                                  topk_tv, topk_kl)
+ *   M_t            = 0 iff D_t > delta and ((A_t>0 and r_t>1) or (A_t<0 and r_t<1)), else 1
+ *                                                                                  (Eq. dppo_obj)
+ *   loss           = loss_scale * sum_t ( - M_t r_t A_t )      (the negated objective of
+ *                                                               Eq. dppo_obj: to be minimised)
+ *   grad_logits    = loss_scale * M_t A_t r_t (pi(j|s_t) - 1[j = a_t])   for every j < V
+ *                    (Eq. unified_grad with C = infinity; M_t is a constant factor)
+ *
+ * All pointers are DEVICE pointers owned by the caller.  Inputs are read-only and, like the
+ * outputs and the workspace, must stay valid until the work enqueued on `stream` has finished.
+ * The library allocates nothing, never synchronises and never touches another stream; every
+ * kernel is enqueued on `stream` (a hipStream_t passed as void*; NULL = the legacy default
+ * stream) and the call returns at once.  The return value reports host-side argument checks
+ * and launch errors only.  Results are bitwise reproducible for identical arguments on the
+ * same device.
+ */
+#ifndef DPPO_H
+#define DPPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DPPO_VERSION 100          /* major*10000 + minor*100 + patch                          */
+#define DPPO_KMAX 1024            /* largest accepted K                                        */
+#define DPPO_WORKSPACE_BYTES 65536
+
+/* Which approximation of D(mu || pi) gates the update (Sec. 4.4).  KL is in nats. */
+typedef enum {
+  DPPO_BINARY_TV = 0,             /* |mu(a_t) - pi(a_t)|                       (Eq. binary_tv) */
+  DPPO_BINARY_KL = 1,             /* Bernoulli KL on {a_t, not a_t}            (Eq. binary_kl) */
+  DPPO_TOPK_TV   = 2,             /* 1/2 sum over A'' of |p_mu - p_pi|         (Eq. topk_tv)   */
+  DPPO_TOPK_KL   = 3              /* sum over A'' of p_mu ln(p_mu / p_pi)      (Eq. topk_kl)   */
+} dppo_variant_t;
+
+typedef enum {
+  DPPO_OK = 0,
+  DPPO_ERR_NULL = 1,              /* a required pointer is NULL                                */
+  DPPO_ERR_SHAPE = 2,             /* T < 0, V < 1, ld < V, or sizes beyond int32 row indexing  */
+  DPPO_ERR_ALIGN = 3,             /* logits / grad_logits not 2-byte aligned, workspace not 8  */
+  DPPO_ERR_VARIANT = 4,           /* variant is not a dppo_variant_t                           */
+  DPPO_ERR_K = 5,                 /* K < 0, K > DPPO_KMAX, or K > 0 without top-K pointers     */
+  DPPO_ERR_WORKSPACE = 6,         /* workspace NULL or smaller than dppo_workspace_bytes()     */
+  DPPO_ERR_LAUNCH = 7,            /* the HIP runtime refused a launch (see hipGetLastError)    */
+  DPPO_ERR_VALUE = 8              /* delta or loss_scale is NaN                                */
+} dppo_status_t;
+
+/* flags */
+#define DPPO_FLAG_FORCE_STREAMING 1u /* use the general two-pass kernel even where the
+                                        register-resident one applies (testing / comparison)  */
+
+typedef struct {
+  /* ---- inputs ---- */
+  const void*    logits;       /* bf16 [T, ld] row-major; only columns 0..V-1 are read         */
+  int64_t        T;            /* rows (response tokens; the caller packs responses only)      */
+  int64_t        V;            /* vocabulary size, 1 <= V < 2^31                               */
+  int64_t        ld;           /* row pitch in elements, ld >= V (any value; rows whose start  */
+                               /* is 16-byte aligned take the fastest path)                    */
+  const int32_t* sampled_ids;  /* [T] a_t.  An id outside [0, V) marks an ignored row:         */
+                               /* divergence 0, mask 0, no loss term, zero gradient row        */
+  const float*   mu_logp;      /* [T] log mu(a_t|s_t) as returned by the rollout engine        */
+  const int32_t* mu_topk_ids;  /* [T, K] ids of mu's K most probable tokens (distinct per row; */
+                               /* an id outside [0, V) is padding and is skipped; an id equal  */
+                               /* to a_t is skipped, a_t always uses mu_logp).  NULL iff K = 0 */
+  const float*   mu_topk_logp; /* [T, K] their log-probs under mu.  NULL iff K = 0             */
+  int32_t        K;            /* 0 <= K <= DPPO_KMAX.  Used by the Top-K variants only; a     */
+                               /* Top-K variant with K = 0 equals the Binary one               */
+  int32_t        variant;      /* dppo_variant_t                                               */
+  const float*   advantages;   /* [T] A_t per token (caller broadcasts sequence-level values)  */
+  float          delta;        /* divergence threshold delta of Eq. dppo_obj                   */
+  float          loss_scale;   /* multiplies loss and gradient, e.g. 1/T_total (the paper      */
+                               /* leaves the minibatch normalisation to the trainer)           */
+  /* ---- outputs (fully overwritten) ---- */
+  float*         loss;         /* [1]                                                          */
+  float*         loss_tok;     /* [T] -M_t r_t A_t, unscaled; may be NULL                      */
+  float*         divergence;   /* [T] D_t                                                      */
+  uint8_t*       mask;         /* [T] M_t in {0, 1}                                            */
+  void*          grad_logits;  /* bf16 [T, ld] (columns >= V untouched), round-to-nearest-even;*/
+                               /* dppo_loss_fwd_bwd only; may be the same buffer as logits     */
+                               /* (in place) but must not overlap it otherwise                 */
+  /* ---- scratch ---- */
+  void*          workspace;    /* >= dppo_workspace_bytes(T, V, K) bytes, 8-byte aligned;      */
+                               /* contents on entry are irrelevant, calls that overlap in time */
+                               /* need distinct workspaces                                     */
+  size_t         workspace_bytes;
+  uint32_t       flags;        /* DPPO_FLAG_*                                                  */
+} dppo_args_t;
+
+/* Bytes of device scratch one call needs (currently a constant, DPPO_WORKSPACE_BYTES). */
+size_t dppo_workspace_bytes(int64_t T, int64_t V, int32_t K);
+
+/* Forward only: loss, loss_tok, divergence, mask.  grad_logits is ignored.
+ * T = 0 is valid and stores loss = 0.  (Sec. 4.3, Eq. dppo_obj; Sec. 4.4) */
+dppo_status_t dppo_loss_fwd(const dppo_args_t* args, void* stream);
+
+/* Forward and backward in one fused pass per row: the outputs of dppo_loss_fwd plus
+ * grad_logits.  (Eq. dppo_obj for the loss, Eq. unified_grad with C = infinity for the
+ * gradient.) */
+dppo_status_t dppo_loss_fwd_bwd(const dppo_args_t* args, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* dppo_status_str(dppo_status_t status);
+
+/* DPPO_VERSION of the loaded library. */
+int dppo_version(void);
+
+/* sizeof(dppo_args_t) as the library was compiled: lets a foreign-language binding verify its
+ * mirror of the struct. */
+size_t dppo_args_size(void);
+
+/* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
+ * "resident" (row held in registers between the two passes) or "streaming" (row re-read). */
+const char* dppo_last_path(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPPO_H */

@@ -27,8 +27,10 @@ Readings taken where the paper is silent (each is listed in the design notes):
   - x*log(x/y) = 0 when x = 0; a vanishing denominator y is floored at 1e-30;
   - mu probabilities > 1 from rounding are clamped to 1, and the "other" bucket of either
     policy is clamped to >= 0;
-  - a top-K id equal to a_t is dropped (a_t's own mu log-prob is used), ids < 0 are padding;
-  - a row with sampled id < 0 is ignored: D = 0, M = 0, loss term 0, zero gradient row.
+  - a top-K id equal to a_t is dropped (a_t's own mu log-prob is used), ids outside [0, V)
+    are padding;
+  - a row whose sampled id is outside [0, V) is ignored: D = 0, M = 0, loss term 0, zero
+    gradient row.
 
 All pins for these functions live in tests/test_oracle_*.py; none is "parity unpinned"
 except the two parameterised-away choices named in the design notes (loss normalisation,
@@ -94,8 +96,8 @@ def reduced_distributions(logpi, a, lmu_a, topk_ids, topk_logp):
     p = [np.exp(min(float(lmu_a), 0.0))]
     if topk_ids is not None:
         for i, lp in zip(np.asarray(topk_ids).tolist(), np.asarray(topk_logp, dtype=np.float64).tolist()):
-            if i < 0 or i == int(a):
-                continue  # padding, or a_t already present
+            if i < 0 or i >= len(logpi) or i == int(a):
+                continue  # padding (id outside the vocabulary), or a_t already present
             ids.append(int(i))
             p.append(np.exp(min(lp, 0.0)))
     p = np.asarray(p, dtype=np.float64)
@@ -169,8 +171,8 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     }
     for t in range(T):
         a = int(sampled_ids[t])
-        if a < 0:
-            continue  # ignored row: everything stays 0
+        if a < 0 or a >= V:
+            continue  # ignored row (id outside the vocabulary): everything stays 0
         z = logits[t]
         logpi = log_softmax(z)                       # step 1
         lpi = logpi[a]

@@ -1,0 +1,149 @@
+"""Thin ctypes binding of the C ABI in include/dppo.h.
+
+Argument marshalling only: every step of the loss runs in the HIP kernels of libdppo.so.
+PyTorch is used for device memory and the stream handle.  There is no CPU fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+FLAG_FORCE_STREAMING = 1
+WORKSPACE_BYTES = 65536
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo.so")
+_lib = None
+
+
+class DppoArgs(C.Structure):
+    """Mirror of dppo_args_t."""
+    _fields_ = [
+        ("logits", C.c_void_p), ("T", C.c_int64), ("V", C.c_int64), ("ld", C.c_int64),
+        ("sampled_ids", C.c_void_p), ("mu_logp", C.c_void_p),
+        ("mu_topk_ids", C.c_void_p), ("mu_topk_logp", C.c_void_p),
+        ("K", C.c_int32), ("variant", C.c_int32),
+        ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
+        ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
+        ("mask", C.c_void_p), ("grad_logits", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("flags", C.c_uint32),
+    ]
+
+
+class DppoError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"dppo status {status}: {lib().dppo_status_str(status).decode()}")
+
+
+def lib() -> C.CDLL:
+    """Open libdppo.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2602_04879_amd.build` "
+                              "(there is no fallback implementation)")
+        l = C.CDLL(_LIB_PATH)
+        l.dppo_workspace_bytes.restype = C.c_size_t
+        l.dppo_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32]
+        for f in (l.dppo_loss_fwd, l.dppo_loss_fwd_bwd):
+            f.restype = C.c_int
+            f.argtypes = [C.POINTER(DppoArgs), C.c_void_p]
+        l.dppo_status_str.restype = C.c_char_p
+        l.dppo_status_str.argtypes = [C.c_int]
+        l.dppo_version.restype = C.c_int
+        l.dppo_last_path.restype = C.c_char_p
+        l.dppo_args_size.restype = C.c_size_t
+        if l.dppo_args_size() != C.sizeof(DppoArgs):
+            raise ImportError("dppo_args_t layout differs between libdppo.so and this binding")
+        _lib = l
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def workspace_bytes(T: int, V: int, K: int) -> int:
+    return lib().dppo_workspace_bytes(T, V, K)
+
+
+def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, out,
+              mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None) -> DppoArgs:
+    """Fill a dppo_args_t from torch tensors.  `out` is a dict with loss [1] f32, divergence [T]
+    f32, mask [T] u8, workspace (u8), optional loss_tok [T] f32."""
+    T, ld = logits.shape[0], (logits.stride(0) if logits.shape[0] > 1 else logits.shape[1])
+    a = DppoArgs()
+    a.logits, a.T, a.V, a.ld = _ptr(logits), T, (logits.shape[1] if V is None else V), ld
+    a.sampled_ids, a.mu_logp = _ptr(sampled_ids), _ptr(mu_logp)
+    a.mu_topk_ids, a.mu_topk_logp = _ptr(mu_topk_ids), _ptr(mu_topk_logp)
+    a.K = 0 if mu_topk_ids is None else mu_topk_ids.shape[1]
+    a.variant = variant
+    a.advantages, a.delta, a.loss_scale = _ptr(advantages), delta, loss_scale
+    a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
+    a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
+    a.grad_logits = _ptr(grad_logits)
+    a.workspace, a.workspace_bytes = _ptr(out["workspace"]), out["workspace"].numel()
+    a.flags = flags
+    return a
+
+
+def alloc_outputs(T: int, device, want_loss_tok: bool = True) -> dict:
+    return {
+        "loss": torch.empty(1, dtype=torch.float32, device=device),
+        "loss_tok": torch.empty(T, dtype=torch.float32, device=device) if want_loss_tok else None,
+        "divergence": torch.empty(T, dtype=torch.float32, device=device),
+        "mask": torch.empty(T, dtype=torch.uint8, device=device),
+        "workspace": torch.empty(WORKSPACE_BYTES, dtype=torch.uint8, device=device),
+    }
+
+
+def _stream_handle(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def dppo_loss_fwd(args: DppoArgs, stream=None) -> None:
+    """dppo_loss_fwd of include/dppo.h on `stream` (default: torch's current stream)."""
+    st = lib().dppo_loss_fwd(C.byref(args), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def dppo_loss_fwd_bwd(args: DppoArgs, stream=None) -> None:
+    """dppo_loss_fwd_bwd of include/dppo.h on `stream` (default: torch's current stream)."""
+    st = lib().dppo_loss_fwd_bwd(C.byref(args), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def last_path() -> str:
+    return lib().dppo_last_path().decode()
+
+
+def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags: int = 0, out=None,
+              grad=None, stream=None, rows=None) -> dict:
+    """Convenience for tests and benchmarks: run one workload batch (see workloads.make_batch),
+    optionally restricted to rows [r0, r1).  Returns the output tensors (device)."""
+    r0, r1 = (0, batch["T"]) if rows is None else rows
+    sl = slice(r0, r1)
+    logits = batch["logits"][sl]
+    T = r1 - r0
+    if out is None:
+        out = alloc_outputs(T, logits.device)
+    if backward and grad is None:
+        grad = logits if in_place else torch.empty_like(logits)
+    tk_i = batch["mu_topk_ids"][sl] if batch["mu_topk_ids"] is not None else None
+    tk_l = batch["mu_topk_logp"][sl] if batch["mu_topk_logp"] is not None else None
+    args = make_args(logits, batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
+                     batch["delta"], batch["variant"], batch["loss_scale"], out, tk_i, tk_l,
+                     V=batch["V"], flags=flags, grad_logits=grad if backward else None)
+    args.ld = batch["ld"]
+    (dppo_loss_fwd_bwd if backward else dppo_loss_fwd)(args, stream)
+    res = dict(out)
+    res["grad_logits"] = grad if backward else None
+    res["args"] = args
+    return res

@@ -1,0 +1,134 @@
+// C ABI of the DPPO loss library: argument checks, kernel-path choice, launches.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "dppo.h"
+#include "dppo_common.hpp"
+#include "dppo_launch.hpp"
+
+namespace {
+
+struct DeviceInfo {
+  int cus = 0;
+};
+
+// Compute-unit count of a device, queried once per device.
+const DeviceInfo& device_info(int dev) {
+  static DeviceInfo info[64];
+  static std::once_flag once[64];
+  if (dev < 0 || dev >= 64) dev = 0;
+  std::call_once(once[dev], [dev]() {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    info[dev].cus = n;
+  });
+  return info[dev];
+}
+
+thread_local const char* g_last_path = "none";
+
+dppo_status_t check_args(const dppo_args_t* a, bool grad) {
+  if (!a) return DPPO_ERR_NULL;
+  if (a->T < 0 || a->V < 1 || a->ld < a->V || a->V >= (int64_t(1) << 31) || a->T >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
+  if (a->variant < DPPO_BINARY_TV || a->variant > DPPO_TOPK_KL) return DPPO_ERR_VARIANT;
+  if (a->K < 0 || a->K > DPPO_KMAX) return DPPO_ERR_K;
+  const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
+  if (topk && a->K > 0 && (!a->mu_topk_ids || !a->mu_topk_logp)) return DPPO_ERR_K;
+  if (!a->loss) return DPPO_ERR_NULL;
+  if (std::isnan(a->delta) || std::isnan(a->loss_scale)) return DPPO_ERR_VALUE;
+  if (!a->workspace || a->workspace_bytes < dppo_workspace_bytes(a->T, a->V, a->K)) return DPPO_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
+  if (a->T > 0) {
+    if (!a->logits || !a->sampled_ids || !a->mu_logp || !a->advantages || !a->divergence || !a->mask) return DPPO_ERR_NULL;
+    if (grad && !a->grad_logits) return DPPO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(a->logits) & 1u) return DPPO_ERR_ALIGN;
+    if (grad && (reinterpret_cast<uintptr_t>(a->grad_logits) & 1u)) return DPPO_ERR_ALIGN;
+  }
+  return DPPO_OK;
+}
+
+dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
+  const dppo_status_t st = check_args(a, grad);
+  if (st != DPPO_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  double* partial = static_cast<double*>(a->workspace);
+  const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
+
+  int nparts = 0;
+  if (a->T > 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DPPO_ERR_LAUNCH;
+    const int cus = device_info(dev).cus;
+
+    dppo::KParams p;
+    p.logits = static_cast<const uint16_t*>(a->logits);
+    p.grad = grad ? static_cast<uint16_t*>(a->grad_logits) : nullptr;
+    p.sampled = a->sampled_ids;
+    p.mu_logp = a->mu_logp;
+    const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
+    p.tk_ids = topk ? a->mu_topk_ids : nullptr;
+    p.tk_lp = topk ? a->mu_topk_logp : nullptr;
+    p.K = topk ? a->K : 0;
+    p.adv = a->advantages;
+    p.loss_tok = a->loss_tok;
+    p.divergence = a->divergence;
+    p.mask = a->mask;
+    p.partial = partial;
+    p.ld = a->ld;
+    p.T = static_cast<int32_t>(a->T);
+    p.V = static_cast<int32_t>(a->V);
+    p.variant = a->variant;
+    p.delta = a->delta;
+    p.loss_scale = a->loss_scale;
+
+    // 16-byte vectors need logits and grad rows to share their misalignment.
+    const bool vec = !grad || (((reinterpret_cast<uintptr_t>(a->logits) - reinterpret_cast<uintptr_t>(a->grad_logits)) & 15u) == 0);
+    // Workgroup size by row length; a few rows in flight per compute unit so that the re-read
+    // of pass 2 still finds the row in cache.
+    const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
+    const int per_cu = 2048 / threads;
+    int64_t grid = static_cast<int64_t>(cus) * per_cu;
+    if (grid > a->T) grid = a->T;
+    if (grid > max_parts) grid = max_parts;
+    nparts = static_cast<int>(grid);
+    if (dppo::launch_streaming(p, vec, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+    g_last_path = "streaming";
+  }
+  if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  return DPPO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dppo_workspace_bytes(int64_t, int64_t, int32_t) { return DPPO_WORKSPACE_BYTES; }
+
+dppo_status_t dppo_loss_fwd(const dppo_args_t* args, void* stream) { return run(args, stream, false); }
+
+dppo_status_t dppo_loss_fwd_bwd(const dppo_args_t* args, void* stream) { return run(args, stream, true); }
+
+const char* dppo_status_str(dppo_status_t status) {
+  switch (status) {
+    case DPPO_OK: return "ok";
+    case DPPO_ERR_NULL: return "a required pointer is NULL";
+    case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld, T and V below 2^31";
+    case DPPO_ERR_ALIGN: return "misaligned pointer: bf16 buffers need 2-byte, workspace 8-byte alignment";
+    case DPPO_ERR_VARIANT: return "variant is not one of DPPO_BINARY_TV/KL, DPPO_TOPK_TV/KL";
+    case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
+    case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes()";
+    case DPPO_ERR_LAUNCH: return "HIP kernel launch failed";
+    case DPPO_ERR_VALUE: return "delta or loss_scale is NaN";
+  }
+  return "unknown status";
+}
+
+int dppo_version(void) { return DPPO_VERSION; }
+
+size_t dppo_args_size(void) { return sizeof(dppo_args_t); }
+
+const char* dppo_last_path(void) { return g_last_path; }
+
+}  // extern "C"

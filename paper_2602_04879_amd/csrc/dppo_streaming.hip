@@ -1,0 +1,205 @@
+// General two-pass kernel: one workgroup per row, any V, any row pitch, any alignment.
+//
+// Pass 1 streams the row once from HBM with 16-byte loads (per-thread online max / sum of
+// exponentials in fp32), the workgroup combines the statistics, one wave evaluates the
+// per-token epilogue, and pass 2 re-reads the row (normally still in L2 / Infinity Cache),
+// and writes the bf16 gradient with non-temporal 16-byte stores.  Rows whose gradient
+// coefficient is zero (masked, zero advantage, ignored) are zero-filled without the re-read.
+#include "dppo_common.hpp"
+#include "dppo_launch.hpp"
+
+namespace dppo {
+namespace {
+
+struct OnlineStat {
+  float m = kNegBig;   // running maximum of the logits seen by this thread
+  float s = 0.f;       // sum of exp(z - m)
+  __device__ __forceinline__ void add8(const float (&z)[8]) {
+    float vm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+    const float mn = fmaxf(m, vm);
+    const float mb = -mn * kLog2e;
+    float acc = s * fast_exp2(fmaf(m, kLog2e, mb));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += fast_exp2(fmaf(z[i], kLog2e, mb));
+    s = acc;
+    m = mn;
+  }
+  __device__ __forceinline__ void add1(float z) {
+    const float mn = fmaxf(m, z);
+    const float mb = -mn * kLog2e;
+    s = s * fast_exp2(fmaf(m, kLog2e, mb)) + fast_exp2(fmaf(z, kLog2e, mb));
+    m = mn;
+  }
+};
+
+__device__ __forceinline__ void unpack8(const u32x4& v, float (&z)[8]) {
+  z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xffff0000u);
+  z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xffff0000u);
+  z[4] = __uint_as_float(v.z << 16); z[5] = __uint_as_float(v.z & 0xffff0000u);
+  z[6] = __uint_as_float(v.w << 16); z[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+template <int THREADS, bool VEC, bool GRAD>
+__global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p) {
+  constexpr int NW = THREADS / kWave;
+  __shared__ float sh_max[NW];
+  __shared__ double sh_sum[NW];
+  __shared__ RowCoef sh_rc;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
+  double loss_acc = 0.0;   // meaningful in wave 0 only
+
+  for (int row = blockIdx.x; row < p.T; row += gridDim.x) {
+    const int a = p.sampled[row];
+    const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
+    uint16_t* grow = GRAD ? p.grad + static_cast<int64_t>(row) * p.ld : nullptr;
+    // Split the row into [head | 16-byte vectors | tail]; VEC=false makes everything "head".
+    int head = p.V, nvec = 0;
+    if (VEC) {
+      const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(zrow) & 15u) >> 1);
+      head = min((8 - mis) & 7, p.V);
+      nvec = (p.V - head) >> 3;
+    }
+    const int tail0 = head + (nvec << 3);       // first tail element
+    const int nscalar = head + (p.V - tail0);   // head + tail element count
+    const bool live = (a >= 0 && a < p.V);
+
+    RowCoef rc;
+    rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
+    const int av = (live && a >= head && a < tail0) ? ((a - head) >> 3) : -1;   // vector holding a_t
+    if (live) {
+      // ---- pass 1: online max / sum-exp over j != a_t -----------------------------------
+      OnlineStat st;
+      st.m = fmaxf(kNegBig, bf16_bits_to_float(zrow[a]));   // the reference must cover z[a_t]
+      const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
+      for (int v = tid; v < nvec; v += THREADS) {
+        float z[8];
+        unpack8(zv[v], z);
+        if (v == av) {
+          const int sub = (a - head) & 7;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) z[i] = (i == sub) ? -INFINITY : z[i];
+        }
+        st.add8(z);
+      }
+      for (int e = tid; e < nscalar; e += THREADS) {
+        const int j = (e < head) ? e : tail0 + (e - head);
+        if (j != a) st.add1(bf16_bits_to_float(zrow[j]));
+      }
+      // workgroup maximum
+      float wm = wave_max(st.m);
+      if (lane == 0) sh_max[wid] = wm;
+      __syncthreads();
+      float m = sh_max[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) m = fmaxf(m, sh_max[w]);
+      // rescale to the common maximum, sum in double
+      double sd = static_cast<double>(st.s * fast_exp2((st.m - m) * kLog2e));
+      sd = wave_sum(sd);
+      if (lane == 0) sh_sum[wid] = sd;
+      __syncthreads();
+      // ---- epilogue on wave 0 -----------------------------------------------------------
+      if (wid == 0) {
+        double S_rest = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) S_rest += sh_sum[w];
+        double lt;
+        rc = row_epilogue(p, row, a, zrow, m, S_rest, lane, &lt);
+        loss_acc += lt;
+        if (GRAD && lane == 0) sh_rc = rc;
+      }
+      if (GRAD) {
+        __syncthreads();
+        rc = sh_rc;
+      }
+    } else if (tid == 0) {
+      p.divergence[row] = 0.f;
+      p.mask[row] = 0;
+      if (p.loss_tok) p.loss_tok[row] = 0.f;
+    }
+
+    if (GRAD) {
+      // ---- pass 2: gradient --------------------------------------------------------------
+      u32x4* gv = reinterpret_cast<u32x4*>(grow + head);
+      if (rc.coef == 0.f) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int v = tid; v < nvec; v += THREADS) __builtin_nontemporal_store(zero, gv + v);
+        for (int e = tid; e < nscalar; e += THREADS) grow[(e < head) ? e : tail0 + (e - head)] = 0;
+      } else {
+        const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
+        const float kexp = rc.kexp;
+        const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
+        for (int v = tid; v < nvec; v += THREADS) {
+          float z[8];
+          unpack8(zv[v], z);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) z[i] = fast_exp2(fmaf(z[i], kLog2e, kexp));
+          uint32_t w[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(z[2 * i], z[2 * i + 1]) ^ sgn;
+          if (v == av) {   // the vector holding a_t: overwrite that one entry
+            const int sub = (a - head) & 7;
+            const uint32_t ga = float_to_bf16_bits(rc.g_a);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if ((sub >> 1) == i) w[i] = (sub & 1) ? ((w[i] & 0x0000ffffu) | (ga << 16)) : ((w[i] & 0xffff0000u) | ga);
+          }
+          const u32x4 o = {w[0], w[1], w[2], w[3]};
+          __builtin_nontemporal_store(o, gv + v);
+        }
+        for (int e = tid; e < nscalar; e += THREADS) {
+          const int j = (e < head) ? e : tail0 + (e - head);
+          float g = fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, kexp));
+          g = (rc.coef < 0.f) ? -g : g;
+          if (j == a) g = rc.g_a;
+          grow[j] = float_to_bf16_bits(g);
+        }
+      }
+    }
+    // The shared statistics are rewritten by the next row: make sure everyone has read them.
+    __syncthreads();
+  }
+  if (tid == 0) p.partial[blockIdx.x] = loss_acc;
+}
+
+}  // namespace
+
+template <int THREADS>
+static hipError_t launch_streaming_t(const KParams& p, bool vec, bool grad, int grid, hipStream_t s) {
+  if (vec) {
+    if (grad) hipLaunchKernelGGL((dppo_streaming_kernel<THREADS, true, true>), dim3(grid), dim3(THREADS), 0, s, p);
+    else      hipLaunchKernelGGL((dppo_streaming_kernel<THREADS, true, false>), dim3(grid), dim3(THREADS), 0, s, p);
+  } else {
+    if (grad) hipLaunchKernelGGL((dppo_streaming_kernel<THREADS, false, true>), dim3(grid), dim3(THREADS), 0, s, p);
+    else      hipLaunchKernelGGL((dppo_streaming_kernel<THREADS, false, false>), dim3(grid), dim3(THREADS), 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, int grid, hipStream_t s) {
+  switch (threads) {
+    case 256: return launch_streaming_t<256>(p, vec, grad, grid, s);
+    case 512: return launch_streaming_t<512>(p, vec, grad, grid, s);
+    default:  return launch_streaming_t<1024>(p, vec, grad, grid, s);
+  }
+}
+
+// Sum the per-workgroup partial sums in a fixed order and store loss = loss_scale * sum.
+__global__ __launch_bounds__(256) void dppo_finalize_kernel(const double* partial, int n, float loss_scale, float* loss) {
+  __shared__ double sh[256];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
+  sh[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (static_cast<int>(threadIdx.x) < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = static_cast<float>(static_cast<double>(loss_scale) * sh[0]);
+}
+
+hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s) {
+  hipLaunchKernelGGL(dppo_finalize_kernel, dim3(1), dim3(256), 0, s, partial, n, loss_scale, loss);
+  return hipGetLastError();
+}
+
+}  // namespace dppo

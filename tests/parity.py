@@ -1,0 +1,107 @@
+"""Element-by-element comparison of the HIP path with the float64 oracle.
+
+Tolerances (see the design notes for the derivation):
+  divergence : |gpu - ref| <= 1e-4 |ref| + 1e-6
+  loss_tok   : |gpu - ref| <= 1e-4 |ref| + 1e-6 |A|   (compared under the GPU's own mask for
+               tokens inside the exemption band)
+  loss       : |gpu - ref| <= 1e-4 |ref| + 1e-6 * loss_scale * sum|A|
+  mask       : bit-exact, except tokens with |D_ref - delta| < 1e-6 or, where the divergence can
+               exceed delta while r is at 1 (Top-K variants), |log pi(a) - log mu(a)| < 1e-6
+  grad_logits: |gpu - ref| <= 1e-2 |ref| + 1e-30   (bf16 output, round to nearest even)
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import dppo_oracle as O
+
+RTOL_D, ATOL_D = 1e-4, 1e-6
+RTOL_G, ATOL_G = 1e-2, 1e-30
+BAND = 1e-6
+
+
+def oracle_rows(batch: dict, rows, want_grad=True) -> dict:
+    """Run the oracle on the given rows of a (device or host) batch."""
+    idx = torch.as_tensor(np.asarray(rows, dtype=np.int64))
+    dev = batch["logits"].device
+    sel = idx.to(dev)
+    V = batch["V"]
+    z = batch["logits"][sel][:, :V].float().cpu().numpy()
+    tk_i = batch["mu_topk_ids"][sel].cpu().numpy() if batch["mu_topk_ids"] is not None else None
+    tk_l = batch["mu_topk_logp"][sel].cpu().numpy() if batch["mu_topk_logp"] is not None else None
+    return O.dppo_loss(z, batch["sampled_ids"][sel].cpu().numpy(), batch["mu_logp"][sel].cpu().numpy(),
+                       batch["advantages"][sel].cpu().numpy(), batch["delta"], batch["variant"],
+                       batch["loss_scale"], tk_i, tk_l, want_grad=want_grad)
+
+
+def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, ref=None) -> dict:
+    """Compare GPU outputs `res` (tensors indexed by row - row_offset) with the oracle on `rows`.
+    Returns summary statistics (max errors, mask counts)."""
+    rows = np.asarray(rows, dtype=np.int64)
+    if ref is None:
+        ref = oracle_rows(batch, rows, want_grad=check_grad)
+    loc = torch.as_tensor(rows - row_offset).to(res["divergence"].device)
+    D = res["divergence"][loc].double().cpu().numpy()
+    M = res["mask"][loc].cpu().numpy()
+    A = batch["advantages"][torch.as_tensor(rows).to(batch["advantages"].device)].double().cpu().numpy()
+    delta = float(np.float32(batch["delta"]))
+    lmu = batch["mu_logp"][torch.as_tensor(rows).to(batch["mu_logp"].device)].double().cpu().numpy()
+
+    errD = np.abs(D - ref["divergence"])
+    assert np.all(errD <= RTOL_D * np.abs(ref["divergence"]) + ATOL_D), \
+        f"divergence: max err {errD.max():.3e} at row {rows[errD.argmax()]}"
+    exempt = np.abs(ref["divergence"] - delta) < BAND
+    if batch["variant"] in (O.TOPK_TV, O.TOPK_KL):
+        exempt |= np.abs(ref["logp"] - lmu) < BAND
+    bad = (M != ref["mask"]) & ~exempt
+    assert not bad.any(), f"mask differs outside the band at rows {rows[bad][:8]}"
+    assert np.all((M == 0) | (M == 1))
+
+    if res.get("loss_tok") is not None:
+        lt = res["loss_tok"][loc].double().cpu().numpy()
+        lt_ref = np.where(M == ref["mask"], ref["loss_tok"], -M * ref["ratio"] * A)
+        errL = np.abs(lt - lt_ref)
+        assert np.all(errL <= RTOL_D * np.abs(lt_ref) + 1e-6 * np.abs(A)), f"loss_tok: max err {errL.max():.3e}"
+    stats = {"max_abs_err_D": float(errD.max()) if len(rows) else 0.0, "masked": int((M == 0).sum()),
+             "exempt": int(exempt.sum()), "rows": int(len(rows))}
+
+    if check_grad and res.get("grad_logits") is not None:
+        V = batch["V"]
+        g = res["grad_logits"][loc][:, :V].float().cpu().numpy().astype(np.float64)
+        g_ref = ref["grad_logits"].copy()
+        flip = M != ref["mask"]          # exempt tokens: compare under the GPU's mask
+        for i in np.nonzero(flip)[0]:
+            if M[i] == 0:
+                g_ref[i] = 0.0
+            else:
+                row = oracle_single_grad_unmasked(batch, int(rows[i]))
+                g_ref[i] = row
+        err = np.abs(g - g_ref)
+        tol = RTOL_G * np.abs(g_ref) + ATOL_G
+        if not np.all(err <= tol):
+            i, j = np.unravel_index(np.argmax(err - tol), err.shape)
+            raise AssertionError(f"grad_logits row {rows[i]} col {j}: gpu {g[i, j]:.6e} ref {g_ref[i, j]:.6e}")
+        nz = g_ref != 0
+        stats["max_rel_err_grad"] = float((err[nz] / np.abs(g_ref[nz])).max()) if nz.any() else 0.0
+    return stats
+
+
+def oracle_single_grad_unmasked(batch: dict, row: int) -> np.ndarray:
+    """Oracle gradient of one row with M forced to 1 (delta = +inf)."""
+    b = dict(batch)
+    b["delta"] = float("inf")
+    return oracle_rows(b, [row])["grad_logits"][0]
+
+
+def check_loss_scalar(batch: dict, res: dict, ref_loss_tok_sum: float | None = None):
+    """loss == loss_scale * sum(loss_tok) (GPU-internal consistency, any size) and, if the
+    oracle's sum is given, agreement with it."""
+    lt = res["loss_tok"].double().sum().item()
+    A_abs = batch["advantages"].double().abs().sum().item() if res["loss_tok"].numel() == batch["advantages"].numel() else None
+    got = float(res["loss"].item())
+    want = batch["loss_scale"] * lt
+    assert abs(got - want) <= 2e-6 * abs(want) + 1e-7 * batch["loss_scale"] * (A_abs or 1.0) + 1e-12, (got, want)
+    if ref_loss_tok_sum is not None:
+        ref = batch["loss_scale"] * ref_loss_tok_sum
+        assert abs(got - ref) <= 1e-4 * abs(ref) + 1e-6 * batch["loss_scale"] * (A_abs or 1.0), (got, ref)

@@ -1,0 +1,304 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 oracle, element by element.
+
+Small and medium cases compare every row; the full-size cases run the launch configuration
+bench.py times and compare a sample of rows the oracle can do one by one, plus properties
+that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_04879_amd import binding as B
+from paper_2602_04879_amd import workloads as W
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run_and_compare(w, *, backward=True, in_place=False, flags=0, ld=None, shift=0.0, rows=None,
+                     check_grad=True, **mk):
+    _say(f"[case] {w.name} T={w.T} V={w.V} K={w.K} variant={w.variant} ld={ld} in_place={in_place} flags={flags} shift={shift}")
+    b = W.make_batch(w, DEV, ld=ld, shift_sampled=shift, **mk)
+    rows = np.arange(b["T"]) if rows is None else rows
+    ref = P.oracle_rows(b, rows, want_grad=backward and check_grad)   # before an in-place run overwrites the logits
+    res = B.run_batch(b, backward=backward, in_place=in_place, flags=flags)
+    torch.cuda.synchronize()
+    st = P.compare_rows(b, res, rows, check_grad=backward and check_grad, ref=ref)
+    if len(rows) == b["T"]:
+        P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    _say(f"       path={B.last_path()} {st}")
+    return b, res, st
+
+
+# --------------------------------------------------------------------------- small: every row
+@pytest.mark.parametrize("name", ["c1_tiny_binary_tv"])
+def test_c1_tiny_all_rows(name):
+    _run_and_compare(W.WORKLOADS[name])
+
+
+@pytest.mark.parametrize("variant,K", [(W.BINARY_TV, 0), (W.BINARY_KL, 0), (W.TOPK_TV, 20), (W.TOPK_KL, 64)])
+@pytest.mark.parametrize("shift", [0.0, 2.0])
+def test_c1_shape_all_variants_with_mask_stress(variant, K, shift):
+    w = W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], variant=variant, K=K,
+                 noise_std=1.0 if shift else 0.05, delta=0.05 if variant in (W.BINARY_KL, W.TOPK_KL) else 0.2)
+    b, res, st = _run_and_compare(w, shift=shift)
+    if shift:
+        assert 0 < st["masked"] < b["T"]     # the stress recipe exercises both mask values
+
+
+@pytest.mark.parametrize("name", ["c2_binary_tv", "c2_binary_kl"])
+def test_c2_shape_subset_of_sequences(name):
+    # full vocabulary and distribution of C2, 2 of its 16 sequences (the oracle does 1024 rows in seconds)
+    w = W.scaled(W.WORKLOADS[name], n_seq=2)
+    _run_and_compare(w)
+    _run_and_compare(w, shift=2.0, in_place=True)
+
+
+@pytest.mark.parametrize("name", ["c3_qwen3_binary_tv", "c4_qwen3_topk_tv", "c5_long_topk_kl"])
+def test_qwen3_vocab_small_t(name):
+    # V = 151936 (several tiles per row and a ragged tail: 151936 = 8 * 18992), 2 x 48 rows
+    w = W.scaled(W.WORKLOADS[name], n_seq=2, seq_len=48, group=2)
+    _run_and_compare(w)
+    _run_and_compare(w, shift=2.0, flags=B.FLAG_FORCE_STREAMING)
+
+
+# --------------------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("V,ld", [(1, 1), (1, 8), (2, 2), (7, 7), (8, 8), (9, 11), (63, 63), (1001, 1001),
+                                  (1000, 1003), (4097, 4100), (32768 + 5, 32768 + 8)])
+@pytest.mark.parametrize("variant,K", [(W.BINARY_KL, 0), (W.TOPK_TV, 5)])
+def test_ragged_vocab_and_pitch(V, ld, variant, K):
+    K = min(K, V)
+    w = W.Workload("ragged", 3, 5, V, variant, 0.05, K=K, logit_std=2.0, noise_std=0.5, adv="normal", seed=11)
+    _run_and_compare(w, ld=ld)      # with ld > V the pad columns hold a poison value that must not be read
+
+
+def test_pitch_columns_untouched_and_canaries():
+    """Writes stay inside [T, V) of grad_logits and inside [T) of the per-token outputs."""
+    w = W.Workload("canary", 4, 9, 1000, W.TOPK_KL, 0.05, K=7, logit_std=2.0, noise_std=0.5, adv="normal", seed=5)
+    ld = 1016
+    b = W.make_batch(w, DEV, ld=ld)
+    T, V = b["T"], b["V"]
+    pad = 64
+    gbuf = torch.full((T * ld + 2 * pad,), 7.0, dtype=torch.bfloat16, device=DEV)
+    grad = gbuf[pad:pad + T * ld].view(T, ld)
+    dbuf = torch.full((T + 2 * pad,), -3.0, dtype=torch.float32, device=DEV)
+    lbuf = torch.full((T + 2 * pad,), -3.0, dtype=torch.float32, device=DEV)
+    mbuf = torch.full((T + 2 * pad,), 9, dtype=torch.uint8, device=DEV)
+    out = B.alloc_outputs(T, DEV)
+    out["divergence"], out["loss_tok"], out["mask"] = dbuf[pad:pad + T], lbuf[pad:pad + T], mbuf[pad:pad + T]
+    res = B.run_batch(b, out=out, grad=grad)
+    torch.cuda.synchronize()
+    assert torch.all(gbuf[:pad] == 7.0) and torch.all(gbuf[pad + T * ld:] == 7.0)
+    assert torch.all(grad[:, V:] == 7.0)
+    for buf, v in ((dbuf, -3.0), (lbuf, -3.0), (mbuf, 9)):
+        assert torch.all(buf[:pad] == v) and torch.all(buf[pad + T:] == v)
+    P.compare_rows(b, res, np.arange(T))
+
+
+def test_misaligned_gradient_buffer_takes_elementwise_path():
+    w = W.Workload("misaligned", 2, 7, 2051, W.BINARY_TV, 0.1, logit_std=2.0, noise_std=0.5, adv="pm1", seed=3)
+    b = W.make_batch(w, DEV)
+    T, V = b["T"], b["V"]
+    gbuf = torch.zeros(T * V + 8, dtype=torch.bfloat16, device=DEV)
+    grad = gbuf[3:3 + T * V].view(T, V)      # 6 bytes off the logits' alignment
+    res = B.run_batch(b, grad=grad)
+    torch.cuda.synchronize()
+    P.compare_rows(b, res, np.arange(T))
+    # logits themselves at an odd element offset
+    lbuf = torch.zeros(T * V + 8, dtype=torch.bfloat16, device=DEV)
+    lbuf[5:5 + T * V] = b["logits"].reshape(-1)
+    b2 = dict(b)
+    b2["logits"] = lbuf[5:5 + T * V].view(T, V)
+    res = B.run_batch(b2)
+    torch.cuda.synchronize()
+    P.compare_rows(b2, res, np.arange(T))
+    res = B.run_batch(b2, in_place=True)
+    torch.cuda.synchronize()
+    P.compare_rows(b, res, np.arange(T))
+
+
+def test_ignored_rows_padding_ids_and_zero_advantage():
+    w = W.Workload("ignored", 4, 8, 3000, W.TOPK_TV, 0.05, K=12, logit_std=2.0, noise_std=0.5, adv="normal", seed=9)
+    b = W.make_batch(w, DEV)
+    b["sampled_ids"][::5] = -1
+    b["sampled_ids"][3::7] = b["V"] + 10          # outside the vocabulary: also ignored
+    b["mu_topk_ids"][:, 4] = -1                   # padding entries
+    b["mu_topk_ids"][1::2, 9] = b["V"]
+    b["advantages"][2::6] = 0.0
+    res = B.run_batch(b)
+    torch.cuda.synchronize()
+    P.compare_rows(b, res, np.arange(b["T"]))
+    ign = (b["sampled_ids"] < 0) | (b["sampled_ids"] >= b["V"])
+    assert torch.all(res["grad_logits"][ign] == 0) and torch.all(res["mask"][ign] == 0)
+    assert torch.all(res["divergence"][ign] == 0) and torch.all(res["loss_tok"][ign] == 0)
+    assert torch.all(res["grad_logits"][b["advantages"] == 0] == 0)
+
+
+def test_topk_contains_sampled_token_and_k_beyond_one_wave():
+    w = W.Workload("bigk", 2, 6, 5000, W.TOPK_KL, 0.05, K=150, logit_std=3.0, noise_std=0.3, adv="pm1", seed=13)
+    b, res, _ = _run_and_compare(w)
+    hit = (b["mu_topk_ids"] == b["sampled_ids"][:, None]).any(1)
+    assert hit.any()       # a_t inside mu's top-K: the de-duplication path ran
+
+
+def test_topk_with_k0_equals_binary():
+    w = W.Workload("k0", 2, 8, 777, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.5, adv="pm1", seed=17)
+    b = W.make_batch(w, DEV)
+    r_bin = B.run_batch(b)
+    b2 = dict(b)
+    b2["variant"] = W.TOPK_KL
+    r_top = B.run_batch(b2)
+    torch.cuda.synchronize()
+    assert torch.equal(r_bin["divergence"], r_top["divergence"]) and torch.equal(r_bin["mask"], r_top["mask"])
+    assert torch.equal(r_bin["grad_logits"], r_top["grad_logits"])
+
+
+def test_saturated_and_minus_inf_logits():
+    w = W.Workload("sat", 2, 6, 4096, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=21)
+    b = W.make_batch(w, DEV)
+    a = b["sampled_ids"].long()
+    rows = torch.arange(b["T"], device=DEV)
+    b["logits"][rows[:4], a[:4]] = 60.0            # pi(a) == 1 to fp32: 1 - pi(a) underflows
+    b["logits"][4:8, 100:2000] = float("-inf")     # masked vocabulary entries
+    b["logits"][8, :] = -1.0e4                     # flat, far from 0
+    b["logits"][9, :] = 3.0e4
+    res = B.run_batch(b)
+    torch.cuda.synchronize()
+    assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["loss"]).all()
+    assert torch.isfinite(res["grad_logits"].float()).all()
+    P.compare_rows(b, res, np.arange(b["T"]))
+    assert torch.all(res["grad_logits"][4:8, 100:2000] == 0)
+
+
+def test_empty_and_single_row():
+    w = W.Workload("one", 1, 1, 513, W.BINARY_TV, 0.1, logit_std=2.0, noise_std=0.5, adv="pm1", seed=2)
+    _run_and_compare(w)
+    b = W.make_batch(w, DEV)
+    out = B.alloc_outputs(0, DEV)
+    out["loss"].fill_(5.0)
+    args = B.make_args(b["logits"][:0], b["sampled_ids"][:0], b["mu_logp"][:0], b["advantages"][:0], 0.1,
+                       W.BINARY_TV, 1.0, out, V=513, grad_logits=b["logits"][:0])
+    args.ld = 513
+    B.dppo_loss_fwd_bwd(args)
+    B.dppo_loss_fwd(args)
+    torch.cuda.synchronize()
+    assert out["loss"].item() == 0.0
+
+
+def test_forward_only_matches_forward_backward_and_runs_are_bitwise_reproducible():
+    w = W.scaled(W.WORKLOADS["c4_qwen3_topk_tv"], n_seq=2, seq_len=40, group=2)
+    b = W.make_batch(w, DEV)
+    r1 = B.run_batch(b)
+    r2 = B.run_batch(b)
+    rf = B.run_batch(b, backward=False)
+    torch.cuda.synchronize()
+    for k in ("loss", "loss_tok", "divergence", "mask"):
+        assert torch.equal(r1[k], r2[k]) and torch.equal(r1[k], rf[k]), k
+    assert torch.equal(r1["grad_logits"], r2["grad_logits"])
+
+
+def test_other_stream_and_loss_tok_optional():
+    w = W.Workload("stream", 2, 16, 2048, W.TOPK_TV, 0.1, K=8, logit_std=2.0, noise_std=0.5, adv="pm1", seed=4)
+    b = W.make_batch(w, DEV)
+    ref = B.run_batch(b)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    out = B.alloc_outputs(b["T"], DEV, want_loss_tok=False)
+    res = B.run_batch(b, out=out, stream=s)
+    s.synchronize()
+    assert torch.equal(ref["divergence"], res["divergence"]) and torch.equal(ref["grad_logits"], res["grad_logits"])
+    assert torch.equal(ref["loss"], res["loss"])
+
+
+def test_error_codes_on_device():
+    w = W.Workload("err", 1, 4, 64, W.BINARY_TV, 0.1, seed=1)
+    b = W.make_batch(w, DEV)
+    out = B.alloc_outputs(b["T"], DEV)
+    args = B.make_args(b["logits"], b["sampled_ids"], b["mu_logp"], b["advantages"], 0.1, 7, 1.0, out,
+                       grad_logits=torch.empty_like(b["logits"]))
+    with pytest.raises(B.DppoError) as e:
+        B.dppo_loss_fwd_bwd(args)
+    assert e.value.status == 4
+
+
+# --------------------------------------------------------------------------- full size
+def _sample_rows(b, res, n=40, seed=0):
+    """First, last, masked rows, zero-advantage rows, the largest |coefficient| row, random rows."""
+    T = b["T"]
+    rng = np.random.default_rng(seed)
+    rows = {0, T - 1}
+    M = res["mask"].cpu().numpy()
+    A = b["advantages"].cpu().numpy()
+    lt = res["loss_tok"].abs().cpu().numpy()
+    rows |= set(np.nonzero(M == 0)[0][:6].tolist())
+    rows |= set(np.nonzero(A == 0)[0][:3].tolist())
+    rows.add(int(lt.argmax()))
+    rows |= set(rng.choice(T, n, replace=False).tolist())
+    return np.array(sorted(rows))
+
+
+def _full_size_properties(b, res):
+    T = b["T"]
+    M, D = res["mask"], res["divergence"]
+    assert torch.all((M == 0) | (M == 1)) and torch.all(D >= -1e-7) and torch.isfinite(D).all()
+    P.check_loss_scalar(b, res)
+    # softmax-minus-onehot rows sum to ~0 (bf16 rounding of ~V entries) -- checked on a slice
+    g = res["grad_logits"][: min(T, 2048), : b["V"]].float()
+    s = g.sum(1).abs()
+    scale = g.abs().sum(1)
+    assert torch.all(s <= 4e-3 * scale + 1e-30)
+    zero = torch.nonzero((b["advantages"] == 0) | (M == 0)).flatten()[:64]
+    assert torch.all(res["grad_logits"][zero] == 0)
+
+
+@pytest.mark.parametrize("name", ["c3_qwen3_binary_tv", "c4_qwen3_topk_tv"])
+def test_full_size_headline_configs(name):
+    w = W.WORKLOADS[name]
+    _say(f"[case] full size {name} T={w.T} V={w.V}")
+    b = W.make_batch(w, DEV, rows_per_step=2048)
+    res = B.run_batch(b)
+    torch.cuda.synchronize()
+    _say(f"       path={B.last_path()} loss={res['loss'].item():.6e} masked={(res['mask'] == 0).sum().item()}")
+    _full_size_properties(b, res)
+    rows = _sample_rows(b, res)
+    st = P.compare_rows(b, res, rows)
+    _say(f"       {st}")
+    # every row's per-token scalars on a larger sample (no gradient): 512 rows
+    rows2 = np.random.default_rng(1).choice(b["T"], 512, replace=False)
+    st2 = P.compare_rows(b, res, np.sort(rows2), check_grad=False)
+    _say(f"       {st2}")
+
+
+def test_full_size_long_response_chunked_in_place():
+    """C5: T = 131072 rows processed as 8 calls of 16384 rows on one stream, gradient written in
+    place over the logits; the 8 scalar losses add up."""
+    w = W.WORKLOADS["c5_long_topk_kl"]
+    _say(f"[case] full size {w.name} T={w.T} V={w.V} chunks of {w.chunk_rows}")
+    b = W.make_batch(w, DEV, rows_per_step=2048)
+    T = b["T"]
+    rng = np.random.default_rng(5)
+    rows = np.sort(np.unique(np.concatenate([[0, T - 1, w.chunk_rows - 1, w.chunk_rows], rng.choice(T, 28, replace=False)])))
+    ref = P.oracle_rows(b, rows)                   # before the logits are overwritten
+    out = B.alloc_outputs(T, DEV)
+    losses = []
+    for c0 in range(0, T, w.chunk_rows):
+        c1 = min(T, c0 + w.chunk_rows)
+        o = dict(out)
+        o["loss"] = torch.empty(1, dtype=torch.float32, device=DEV)
+        for k in ("loss_tok", "divergence", "mask"):
+            o[k] = out[k][c0:c1]
+        B.run_batch(b, in_place=True, out=o, rows=(c0, c1))
+        losses.append(o["loss"])
+    torch.cuda.synchronize()
+    res = dict(out)
+    res["grad_logits"] = b["logits"]
+    res["loss"] = torch.stack(losses).double().sum().float()
+    _say(f"       path={B.last_path()} loss={res['loss'].item():.6e} masked={(res['mask'] == 0).sum().item()}")
+    st = P.compare_rows(b, res, rows, ref=ref)
+    _say(f"       {st}")
+    P.check_loss_scalar(b, res)

@@ -1,0 +1,99 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header
+declares, the ctypes mirror matches the C struct, and host-side argument validation returns
+the documented codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_04879_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if fn.endswith(".h"):
+            src = open(os.path.join(ROOT, "include", fn)).read()
+            src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+            names += re.findall(r"\b(dppo_[a-z_0-9]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared_functions()
+    assert {"dppo_loss_fwd", "dppo_loss_fwd_bwd", "dppo_workspace_bytes", "dppo_status_str"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_mirror_and_constants():
+    lib = B.lib()
+    assert lib.dppo_args_size() == C.sizeof(B.DppoArgs)
+    assert lib.dppo_version() >= 100
+    assert B.workspace_bytes(32768, 151936, 20) == B.WORKSPACE_BYTES
+    for code in range(0, 9):
+        assert len(lib.dppo_status_str(code)) > 0
+
+
+def _valid_args():
+    a = B.DppoArgs()
+    # fake non-NULL device addresses: validation must reject before touching them
+    a.logits, a.T, a.V, a.ld = 0x1000, 4, 16, 16
+    a.sampled_ids = a.mu_logp = a.advantages = 0x2000
+    a.loss = a.divergence = a.mask = a.grad_logits = 0x3000
+    a.workspace, a.workspace_bytes = 0x4000, B.WORKSPACE_BYTES
+    a.K, a.variant, a.delta, a.loss_scale = 0, B.BINARY_TV, 0.1, 1.0
+    return a
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda a: setattr(a, "V", 0), 2),
+    (lambda a: setattr(a, "ld", 8), 2),
+    (lambda a: setattr(a, "T", -1), 2),
+    (lambda a: setattr(a, "V", 1 << 31), 2),
+    (lambda a: setattr(a, "variant", 4), 4),
+    (lambda a: setattr(a, "variant", -1), 4),
+    (lambda a: setattr(a, "K", -1), 5),
+    (lambda a: setattr(a, "K", 1025), 5),
+    (lambda a: (setattr(a, "variant", B.TOPK_TV), setattr(a, "K", 4)), 5),      # K > 0, no top-K pointers
+    (lambda a: setattr(a, "loss", None), 1),
+    (lambda a: setattr(a, "logits", None), 1),
+    (lambda a: setattr(a, "sampled_ids", None), 1),
+    (lambda a: setattr(a, "divergence", None), 1),
+    (lambda a: setattr(a, "grad_logits", None), 1),
+    (lambda a: setattr(a, "logits", 0x1001), 3),
+    (lambda a: setattr(a, "workspace", 0x4004), 3),
+    (lambda a: setattr(a, "workspace", None), 6),
+    (lambda a: setattr(a, "workspace_bytes", 16), 6),
+    (lambda a: setattr(a, "delta", float("nan")), 8),
+])
+def test_argument_validation_codes(mutate, code):
+    a = _valid_args()
+    mutate(a)
+    assert B.lib().dppo_loss_fwd_bwd(C.byref(a), None) == code
+    assert str(code) in str(B.DppoError(code))
+
+
+def test_null_args_pointer():
+    assert B.lib().dppo_loss_fwd(None, None) == 1
+
+
+def test_forward_ignores_missing_grad_pointer():
+    a = _valid_args()
+    a.grad_logits = None
+    a.V = 0     # still invalid for another reason, so nothing is launched
+    assert B.lib().dppo_loss_fwd(C.byref(a), None) == 2
+
+
+def test_product_package_never_reaches_the_oracle():
+    """The product path must not import, call or link anything under oracle/."""
+    pat = re.compile(r"^\s*(from|import)\s+oracle\b|oracle[/.]dppo_oracle|dppo_oracle", re.M)
+    for top in ("paper_2602_04879_amd", "include"):
+        for dirpath, _, files in os.walk(os.path.join(ROOT, top)):
+            for f in files:
+                if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                    assert not pat.search(open(os.path.join(dirpath, f)).read()), os.path.join(dirpath, f)
