@@ -74,20 +74,25 @@ __device__ __forceinline__ double xlogx_over_y(double x, double y) {
 }
 
 // Per-row epilogue, executed by ONE full wave (all 64 lanes call it with the same scalars).
-//   m      : the reference value the row's exponentials were taken against; m >= z[a_t]
-//   S_rest : sum over j != a_t of exp(z_j - m).  The sampled token's own term is left out so
-//            that 1 - pi(a_t) = S_rest / S keeps full relative accuracy when pi(a_t) -> 1.
+// The row statistics arrive in the base-2 domain the streaming passes work in:
+//   b      : offset (an integer-valued float) with z_j*log2e + b <= 0 for every j
+//   S_rest : sum over j != a_t of 2^(z_j*log2e + b).  The sampled token's own term is left out
+//            so that 1 - pi(a_t) = S_rest / S keeps full relative accuracy when pi(a_t) -> 1.
+// log2e is the fp32 constant kLog2e everywhere (passes and epilogue), so the probabilities
+// are mutually consistent; its rounding (1.3e-8 relative) acts as a temperature of 1+1.3e-8.
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
 // mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
 // Lane 0 stores the per-token outputs; every lane returns the same RowCoef and *loss_term.
 __device__ __forceinline__ RowCoef row_epilogue(const KParams& p, int row, int a, const uint16_t* zrow,
-                                                float m, double S_rest, int lane, double* loss_term) {
-  const double md = static_cast<double>(m);
-  const double za = static_cast<double>(bf16_bits_to_float(zrow[a]));
-  const double ea = exp(za - md);
+                                                float b, double S_rest, int lane, double* loss_term) {
+  constexpr double kL = static_cast<double>(kLog2e);
+  constexpr double kLn2 = 0.6931471805599453;
+  const double bd = static_cast<double>(b);
+  const double xa = static_cast<double>(bf16_bits_to_float(zrow[a])) * kL + bd;   // log2 of a_t's term
+  const double ea = exp2(xa);
   const double S = S_rest + ea;
-  const double lnS = log(S);
-  const double lpi = (za - md) - lnS;
+  const double log2S = log2(S);
+  const double lpi = (xa - log2S) * kLn2;
   const double lmu_raw = static_cast<double>(p.mu_logp[row]);
   const double lmu = fmin(lmu_raw, 0.0);
   const double pa = exp(lmu), qa = ea / S;
@@ -107,7 +112,7 @@ __device__ __forceinline__ RowCoef row_epilogue(const KParams& p, int row, int a
       const int id = ids[k];
       if (id >= 0 && id < p.V && id != a) {
         const double pk = exp(fmin(static_cast<double>(lps[k]), 0.0));
-        const double qk = exp((static_cast<double>(bf16_bits_to_float(zrow[id])) - md) - lnS);
+        const double qk = exp2(static_cast<double>(bf16_bits_to_float(zrow[id])) * kL + bd - log2S);
         sp += pk;
         sq += qk;
         acc += tv ? fabs(pk - qk) : xlogx_over_y(pk, qk);
@@ -135,8 +140,8 @@ __device__ __forceinline__ RowCoef row_epilogue(const KParams& p, int row, int a
   RowCoef rc;
   rc.coef = static_cast<float>(c);
   rc.g_a = static_cast<float>(-c * one_minus_qa);
-  // c * exp(z - m - lnS) = sgn(c) * exp2(z*log2e + kexp)
-  rc.kexp = (c != 0.0) ? static_cast<float>(log2(fabs(c)) - (md + lnS) * 1.4426950408889634) : 0.f;
+  // c * pi_j = sgn(c) * 2^(z_j*log2e + kexp)
+  rc.kexp = (c != 0.0) ? static_cast<float>(log2(fabs(c)) + bd - log2S) : 0.f;
   return rc;
 }
 

@@ -11,24 +11,28 @@
 namespace dppo {
 namespace {
 
+// Per-thread running statistics of a row, kept in the base-2 domain:
+//   s = sum_j 2^(z_j*log2e + b)   with b an INTEGER-valued offset, b <= -max_j(z_j*log2e).
+// Because b is an integer, changing it rescales s by an exact power of two, and offsets of
+// different threads combine without any rounding.
 struct OnlineStat {
-  float m = kNegBig;   // running maximum of the logits seen by this thread
-  float s = 0.f;       // sum of exp(z - m)
+  float b = -kNegBig;  // current offset (starts at "+infinity": nothing seen yet)
+  float s = 0.f;
+  __device__ __forceinline__ void cover(float zmax) {   // make the offset cover a logit value
+    const float bn = fminf(b, -ceilf(zmax * kLog2e));
+    s *= fast_exp2(bn - b);
+    b = bn;
+  }
   __device__ __forceinline__ void add8(const float (&z)[8]) {
-    float vm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-    const float mn = fmaxf(m, vm);
-    const float mb = -mn * kLog2e;
-    float acc = s * fast_exp2(fmaf(m, kLog2e, mb));
+    cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+    float acc = s;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc += fast_exp2(fmaf(z[i], kLog2e, mb));
+    for (int i = 0; i < 8; ++i) acc += fast_exp2(fmaf(z[i], kLog2e, b));
     s = acc;
-    m = mn;
   }
   __device__ __forceinline__ void add1(float z) {
-    const float mn = fmaxf(m, z);
-    const float mb = -mn * kLog2e;
-    s = s * fast_exp2(fmaf(m, kLog2e, mb)) + fast_exp2(fmaf(z, kLog2e, mb));
-    m = mn;
+    cover(z);
+    s += fast_exp2(fmaf(z, kLog2e, b));
   }
 };
 
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
     if (live) {
       // ---- pass 1: online max / sum-exp over j != a_t -----------------------------------
       OnlineStat st;
-      st.m = fmaxf(kNegBig, bf16_bits_to_float(zrow[a]));   // the reference must cover z[a_t]
+      st.cover(fmaxf(kNegBig, bf16_bits_to_float(zrow[a])));   // the offset must cover z[a_t]
       const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
       for (int v = tid; v < nvec; v += THREADS) {
         float z[8];
@@ -85,15 +89,14 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
         const int j = (e < head) ? e : tail0 + (e - head);
         if (j != a) st.add1(bf16_bits_to_float(zrow[j]));
       }
-      // workgroup maximum
-      float wm = wave_max(st.m);
-      if (lane == 0) sh_max[wid] = wm;
+      // workgroup-wide offset = the smallest one; rescaling to it is exact
+      float wb = -wave_max(-st.b);
+      if (lane == 0) sh_max[wid] = wb;
       __syncthreads();
-      float m = sh_max[0];
+      float b = sh_max[0];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) m = fmaxf(m, sh_max[w]);
-      // rescale to the common maximum, sum in double
-      double sd = static_cast<double>(st.s * fast_exp2((st.m - m) * kLog2e));
+      for (int w = 1; w < NW; ++w) b = fminf(b, sh_max[w]);
+      double sd = static_cast<double>(st.s * fast_exp2(b - st.b));
       sd = wave_sum(sd);
       if (lane == 0) sh_sum[wid] = sd;
       __syncthreads();
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
 #pragma unroll
         for (int w = 0; w < NW; ++w) S_rest += sh_sum[w];
         double lt;
-        rc = row_epilogue(p, row, a, zrow, m, S_rest, lane, &lt);
+        rc = row_epilogue(p, row, a, zrow, b, S_rest, lane, &lt);
         loss_acc += lt;
         if (GRAD && lane == 0) sh_rc = rc;
       }
