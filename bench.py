@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the DPPO loss hot path (forward + backward over the full vocabulary) on ONE
+MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A step is one pass of the whole path (log-softmax statistics, gathers, divergence, mask,
+loss, gradient over all V logits) over one synthetic batch that is already resident in HBM.
+Prints ONE JSON line.  The default workload is the Qwen3-vocabulary Binary-TV configuration
+(T = 32768 tokens, V = 151936), the one the headline metric is quoted on.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E peak
+DEFAULT_WORKLOAD = "c3_qwen3_binary_tv"
+DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_streaming_kernel"}
+
+
+def kernel_source_hash() -> str:
+    """Hash of the HIP sources: the stored HBM-traffic counters are only valid for it."""
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
+    for fn in sorted(os.listdir(src)):
+        if fn.endswith((".hip", ".hpp")):
+            h.update(open(os.path.join(src, fn), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(workload: str, path: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None when there is
+    none for this workload / kernel path or the kernels have changed since it was taken."""
+    fn = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(fn):
+        return None
+    try:
+        rec = json.load(open(fn)).get(f"{workload}:{path}")
+    except Exception:
+        return None
+    if not rec or rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return rec.get("bytes_per_launch")
+
+
+def algorithmic_bytes_per_token(V: int, K: int) -> int:
+    """What the method itself must move per token, forward + backward: the bf16 logits row read
+    once, the bf16 gradient row written once, and the per-token side inputs/outputs."""
+    side_in = 4 + 4 + 4 + 8 * K          # sampled id, mu log-prob, advantage, top-K ids + log-probs
+    side_out = 4 + 4 + 1                 # divergence, per-token loss, mask
+    return 2 * V + 2 * V + side_in + side_out
+
+
+def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
+    """Time the float64 oracle, as it stands, on leading rows of the same batch: chunks of
+    chunk_rows rows until about budget_s seconds of CPU work are spent (or the batch ends)."""
+    from oracle import dppo_oracle as O
+    V, T = batch["V"], batch["T"]
+    done, wall, cpu = 0, 0.0, 0.0
+    while done < T and wall < budget_s:
+        sl = slice(done, min(T, done + chunk_rows))
+        z = batch["logits"][sl, :V].float().cpu().numpy()
+        ids = batch["sampled_ids"][sl].cpu().numpy()
+        lmu = batch["mu_logp"][sl].cpu().numpy()
+        adv = batch["advantages"][sl].cpu().numpy()
+        tk_i = batch["mu_topk_ids"][sl].cpu().numpy() if batch["mu_topk_ids"] is not None else None
+        tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
+        t0, c0 = time.perf_counter(), time.process_time()
+        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=True)
+        wall += time.perf_counter() - t0
+        cpu += time.process_time() - c0
+        done += len(ids)
+    return {"value": done / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)), "kind": "oracle",
+            "sample": f"first {done} of {T} rows of the same batch, fwd+bwd, float64 numpy, {wall:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures ONE GPU: the path is data-parallel over tokens with no exchange "
+              "but one scalar; run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2602_04879_amd import binding as B
+    from paper_2602_04879_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    batch = W.make_batch(w, dev, rows_per_step=2048)
+    T, V, K = batch["T"], batch["V"], batch["K"]
+    chunk = w.chunk_rows or T
+    flags = B.FLAG_FORCE_STREAMING if args.force_streaming else 0
+
+    # caller-side buffers, allocated once: gradient (separate from the logits so that every
+    # step sees the same input), per-token outputs, one loss scalar per T-chunk
+    grad = torch.empty_like(batch["logits"])
+    out = B.alloc_outputs(T, dev)
+    calls = []
+    for c0 in range(0, T, chunk):
+        c1 = min(T, c0 + chunk)
+        o = dict(out)
+        o["loss"] = torch.empty(1, dtype=torch.float32, device=dev)
+        for k in ("loss_tok", "divergence", "mask"):
+            o[k] = out[k][c0:c1]
+        sl = slice(c0, c1)
+        a = B.make_args(batch["logits"][sl], batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
+                        batch["delta"], batch["variant"], batch["loss_scale"], o,
+                        batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
+                        V=V, flags=flags, grad_logits=grad[sl])
+        a.ld = batch["ld"]
+        calls.append((a, o))
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for a, _ in calls:
+            B.dppo_loss_fwd_bwd(a, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    path = B.last_path()
+
+    launches = len(calls)
+    alg_bytes_launch = algorithmic_bytes_per_token(V, K) * (T // launches)
+    kernel_ms = ms_per_step / launches           # the step is the dominant kernel plus a ~3 us reduction
+    achieved = alg_bytes_launch / (kernel_ms * 1e-3) / 1e9
+    loss = sum(float(o["loss"].item()) for _, o in calls)
+
+    rec = {
+        "metric": "dppo_loss_fwd_bwd_tokens_per_s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
+                   "delta": batch["delta"], "logits_dtype": "bf16", "launches_per_step": launches,
+                   "kernel_path": path, "grad": "separate buffer"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(args.workload, path),
+                     "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
+                     "kernel_ms": kernel_ms},
+        "loss": loss, "masked_tokens": int((out["mask"] == 0).sum().item()),
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(batch, args.cpu_seconds)
+    print(json.dumps(rec), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

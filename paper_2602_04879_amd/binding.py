@@ -57,6 +57,10 @@ def lib() -> C.CDLL:
         l.dppo_version.restype = C.c_int
         l.dppo_last_path.restype = C.c_char_p
         l.dppo_args_size.restype = C.c_size_t
+        l.dppo_probe_copy.restype = C.c_int
+        l.dppo_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.dppo_probe_read.restype = C.c_int
+        l.dppo_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         if l.dppo_args_size() != C.sizeof(DppoArgs):
             raise ImportError("dppo_args_t layout differs between libdppo.so and this binding")
         _lib = l
@@ -116,6 +120,23 @@ def dppo_loss_fwd(args: DppoArgs, stream=None) -> None:
 def dppo_loss_fwd_bwd(args: DppoArgs, stream=None) -> None:
     """dppo_loss_fwd_bwd of include/dppo.h on `stream` (default: torch's current stream)."""
     st = lib().dppo_loss_fwd_bwd(C.byref(args), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def probe_copy(dst, src, stream=None) -> None:
+    """dppo_probe_copy: plain 16-byte-vector device copy of src into dst (same byte size)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    st = lib().dppo_probe_copy(dst.data_ptr(), src.data_ptr(), n, C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def probe_read(src, sink, stream=None) -> None:
+    """dppo_probe_read: read-only pass over src."""
+    st = lib().dppo_probe_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                               C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
 

@@ -12,6 +12,8 @@ namespace {
 
 struct DeviceInfo {
   int cus = 0;
+  int resident_per_cu_1024 = 1;
+  int resident_per_cu_256 = 1;
 };
 
 // Compute-unit count of a device, queried once per device.
@@ -23,6 +25,8 @@ const DeviceInfo& device_info(int dev) {
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
     info[dev].cus = n;
+    info[dev].resident_per_cu_1024 = dppo::resident_blocks_per_cu(1024);
+    info[dev].resident_per_cu_256 = dppo::resident_blocks_per_cu(256);
   });
   return info[dev];
 }
@@ -83,18 +87,34 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     p.delta = a->delta;
     p.loss_scale = a->loss_scale;
 
-    // 16-byte vectors need logits and grad rows to share their misalignment.
-    const bool vec = !grad || (((reinterpret_cast<uintptr_t>(a->logits) - reinterpret_cast<uintptr_t>(a->grad_logits)) & 15u) == 0);
-    // Workgroup size by row length; a few rows in flight per compute unit so that the re-read
-    // of pass 2 still finds the row in cache.
-    const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
-    const int per_cu = 2048 / threads;
-    int64_t grid = static_cast<int64_t>(cus) * per_cu;
-    if (grid > a->T) grid = a->T;
-    if (grid > max_parts) grid = max_parts;
-    nparts = static_cast<int>(grid);
-    if (dppo::launch_streaming(p, vec, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
-    g_last_path = "streaming";
+    const DeviceInfo& di = device_info(dev);
+    const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
+    // Register-resident kernel: rows of 8192 .. 163840 entries with 16-byte aligned rows.
+    const int r_threads = (a->V <= 256 * dppo::kResidentChunks * 8) ? 256 : 1024;
+    const bool resident = grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && a->V >= 8192 && (a->V % 8 == 0) &&
+                          (a->V / 8 <= static_cast<int64_t>(r_threads) * dppo::kResidentChunks) &&
+                          (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0;
+    if (resident) {
+      int64_t grid = static_cast<int64_t>(cus) * (r_threads == 1024 ? di.resident_per_cu_1024 : di.resident_per_cu_256);
+      if (grid > a->T) grid = a->T;
+      if (grid > max_parts) grid = max_parts;
+      nparts = static_cast<int>(grid);
+      if (dppo::launch_resident(p, r_threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      g_last_path = "resident";
+    } else {
+      // 16-byte vectors need logits and grad rows to share their misalignment.
+      const bool vec = !grad || (((lz - lg) & 15u) == 0);
+      // Workgroup size by row length; a few rows in flight per compute unit so that the re-read
+      // of pass 2 still finds the row in cache.
+      const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
+      const int per_cu = 2048 / threads;
+      int64_t grid = static_cast<int64_t>(cus) * per_cu;
+      if (grid > a->T) grid = a->T;
+      if (grid > max_parts) grid = max_parts;
+      nparts = static_cast<int>(grid);
+      if (dppo::launch_streaming(p, vec, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      g_last_path = "streaming";
+    }
   }
   if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
   return DPPO_OK;

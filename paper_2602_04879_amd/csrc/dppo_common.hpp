@@ -83,7 +83,10 @@ __device__ __forceinline__ double xlogx_over_y(double x, double y) {
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
 // mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
 // Lane 0 stores the per-token outputs; every lane returns the same RowCoef and *loss_term.
-__device__ __forceinline__ RowCoef row_epilogue(const KParams& p, int row, int a, const uint16_t* zrow,
+// Deliberately NOT inlined: its float64 arithmetic needs many registers, and as a real call its
+// register traffic stays inside the one wave that runs it instead of raising the pressure of
+// the streaming phases around it.
+__device__ __attribute__((noinline)) static RowCoef row_epilogue(const KParams& p, int row, int a, const uint16_t* zrow,
                                                 float b, double S_rest, int lane, double* loss_term) {
   constexpr double kL = static_cast<double>(kLog2e);
   constexpr double kLn2 = 0.6931471805599453;
