@@ -12,7 +12,7 @@ namespace {
 
 struct DeviceInfo {
   int cus = 0;
-  int resident_per_cu_1024 = 1;
+  int resident_per_cu_512 = 1;
   int resident_per_cu_256 = 1;
 };
 
@@ -25,7 +25,7 @@ const DeviceInfo& device_info(int dev) {
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
     info[dev].cus = n;
-    info[dev].resident_per_cu_1024 = dppo::resident_blocks_per_cu(1024);
+    info[dev].resident_per_cu_512 = dppo::resident_blocks_per_cu(512);
     info[dev].resident_per_cu_256 = dppo::resident_blocks_per_cu(256);
   });
   return info[dev];
@@ -89,13 +89,14 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
 
     const DeviceInfo& di = device_info(dev);
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
-    // Register-resident kernel: rows of 8192 .. 163840 entries with 16-byte aligned rows.
-    const int r_threads = (a->V <= 256 * dppo::kResidentChunks * 8) ? 256 : 1024;
+    // Register-resident kernel: rows of 8192 .. 155648 entries with 16-byte aligned rows.
+    const bool small_row = a->V <= 256 * dppo::kResidentChunksSmall * 8;
+    const int r_threads = small_row ? 256 : 512;
+    const int64_t r_cap = small_row ? 256 * dppo::kResidentChunksSmall : 512 * dppo::kResidentChunksBig;
     const bool resident = grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && a->V >= 8192 && (a->V % 8 == 0) &&
-                          (a->V / 8 <= static_cast<int64_t>(r_threads) * dppo::kResidentChunks) &&
-                          (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0;
+                          (a->V / 8 <= r_cap) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0;
     if (resident) {
-      int64_t grid = static_cast<int64_t>(cus) * (r_threads == 1024 ? di.resident_per_cu_1024 : di.resident_per_cu_256);
+      int64_t grid = static_cast<int64_t>(cus) * (r_threads == 512 ? di.resident_per_cu_512 : di.resident_per_cu_256);
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);

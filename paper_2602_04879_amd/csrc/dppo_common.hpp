@@ -45,6 +45,29 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte vector = 8 bf16
+// Pointers known to be in global memory (address space 1): lets the compiler emit global_*
+// instructions with a scalar base instead of flat_* ones.
+typedef const __attribute__((address_space(1))) u32x4* gvec_cptr;
+typedef __attribute__((address_space(1))) u32x4* gvec_ptr;
+typedef const __attribute__((address_space(1))) uint16_t* gu16_cptr;
+typedef __attribute__((address_space(1))) uint16_t* gu16_ptr;
+typedef const __attribute__((address_space(1))) char* gbyte_cptr;
+typedef __attribute__((address_space(1))) char* gbyte_ptr;
+
+// 16-byte access at (uniform base) + (per-lane unsigned 32-bit byte offset): the form that maps
+// to a global_load/store with a scalar base register and one vector offset register.
+__device__ __forceinline__ u32x4 gload16(gbyte_cptr base, uint32_t voff) {
+  return *reinterpret_cast<gvec_cptr>(base + voff);
+}
+__device__ __forceinline__ void gstore16_nt(gbyte_ptr base, uint32_t voff, u32x4 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<gvec_ptr>(base + voff));
+}
+
+// A value every lane of the wave holds identically, moved to a scalar register.
+__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform_f(float v) {
+  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2_t v = {lo, hi};
   bf16x2_t b = __builtin_convertvector(v, bf16x2_t);

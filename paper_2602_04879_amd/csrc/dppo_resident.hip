@@ -35,38 +35,70 @@ __device__ __forceinline__ u32x4 patch16(u32x4 v, int sub, uint32_t bits) {
   return r;
 }
 
+// Phase C for one row: write the gradient of every resident chunk and (MORE) refill the chunk
+// with the workgroup's next row.  ZERO rows (masked, zero advantage, ignored) store zeros.
+template <int THREADS, int NCHUNK, bool ZERO, bool MORE>
+__device__ __forceinline__ void phase_c(u32x4 (&buf)[NCHUNK], int cnt, uint32_t voff, gbyte_ptr grow, gbyte_cptr znext,
+                                        float kexp, uint32_t sgn) {
+  constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
+#pragma unroll
+  for (int i = 0; i < NCHUNK; ++i) {
+    if (i < cnt) {
+      u32x4 o = {0u, 0u, 0u, 0u};
+      if (!ZERO) {
+        const uint32_t w[4] = {buf[i].x, buf[i].y, buf[i].z, buf[i].w};
+        uint32_t r[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+          r[d] = pack_bf16x2(fast_exp2(fmaf(__uint_as_float(w[d] << 16), kLog2e, kexp)),
+                             fast_exp2(fmaf(__uint_as_float(w[d] & 0xffff0000u), kLog2e, kexp))) ^ sgn;
+        o = u32x4{r[0], r[1], r[2], r[3]};
+      }
+      gstore16_nt(grow + i * kStride, voff, o);
+      if (MORE) buf[i] = gload16(znext + i * kStride, voff);
+    }
+  }
+}
+
 template <int THREADS, int NCHUNK>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
+  static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
+  constexpr uint32_t kStride = THREADS * 16u;
   __shared__ float sh_b[NW];
   __shared__ double sh_s[NW];
   __shared__ RowCoef sh_rc;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wid = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform, in a scalar register
+  const int wid = uniform_i(tid / kWave);
   const int nvec = p.V >> 3;
   // Thread tid owns vectors tid, tid+THREADS, ...: `cnt` of them (chunk i <-> vector i*THREADS+tid).
   const int cnt = (nvec - tid + THREADS - 1) / THREADS;
+  const uint32_t voff = static_cast<uint32_t>(tid) * 16u;
   const u32x4 neg_inf = {kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair};
+  const int64_t pitch = p.ld * 2;               // row pitch in bytes
+  const gbyte_cptr logits = (gbyte_cptr)p.logits;
+  const gbyte_ptr grad = (gbyte_ptr)p.grad;
   double loss_acc = 0.0;                        // meaningful in wave 0 only
 
   // The resident row.  Slots past the row hold -inf for the whole kernel: they add nothing.
   u32x4 buf[NCHUNK];
   int row = blockIdx.x;
   {
-    const u32x4* zv = reinterpret_cast<const u32x4*>(p.logits + static_cast<int64_t>(row) * p.ld);
+    const gbyte_cptr zr = logits + row * pitch;
 #pragma unroll
     for (int i = 0; i < NCHUNK; ++i) {
       buf[i] = neg_inf;
-      if (i < cnt && row < p.T) buf[i] = zv[i * THREADS + tid];
+      if (i < cnt) buf[i] = gload16(zr + i * kStride, voff);
     }
   }
 
   for (; row < p.T; row += gridDim.x) {
-    const int a = p.sampled[row];
+    const int a = uniform_i(p.sampled[row]);
     const bool live = (a >= 0 && a < p.V);
+    const gbyte_cptr zr = logits + row * pitch;
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
-    const int avec = live ? (a >> 3) : -1;
-    const int ia = live ? avec / THREADS : -1;             // chunk holding a_t (uniform)
+    const int avec = a >> 3;
+    const int ia = live ? avec / THREADS : -1;               // chunk holding a_t (uniform)
     const bool owner = live && (avec - ia * THREADS == tid);
     const int sub = a & 7;
 
@@ -74,10 +106,17 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
     if (live) {
       // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
-      // with -inf in the resident copy; the epilogue reads z[a_t] from memory.
-#pragma unroll
-      for (int i = 0; i < NCHUNK; ++i)
-        if (i == ia) { if (owner) buf[i] = patch16(buf[i], sub, 0xFF80u); }
+      // with -inf in the resident copy; the epilogue reads z[a_t] from memory.  `ia` is uniform,
+      // so this is one scalar jump, not a test per chunk.
+#define DPPO_PATCH_CASE(I) case I: if (I < NCHUNK && owner) buf[I < NCHUNK ? I : 0] = patch16(buf[I < NCHUNK ? I : 0], sub, 0xFF80u); break;
+#define DPPO_PATCH_CASES10(B) DPPO_PATCH_CASE(B + 0) DPPO_PATCH_CASE(B + 1) DPPO_PATCH_CASE(B + 2) DPPO_PATCH_CASE(B + 3) \
+  DPPO_PATCH_CASE(B + 4) DPPO_PATCH_CASE(B + 5) DPPO_PATCH_CASE(B + 6) DPPO_PATCH_CASE(B + 7) DPPO_PATCH_CASE(B + 8) DPPO_PATCH_CASE(B + 9)
+      switch (ia) {
+        DPPO_PATCH_CASES10(0) DPPO_PATCH_CASES10(10) DPPO_PATCH_CASES10(20) DPPO_PATCH_CASES10(30)
+        default: break;
+      }
+#undef DPPO_PATCH_CASES10
+#undef DPPO_PATCH_CASE
 
       // ---- phase A: maximum, on the packed bf16 patterns --------------------------------
       // As signed 16-bit integers, non-negative bf16 order like floats and every negative one
@@ -93,6 +132,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       int m16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) m16 = max(m16, __shfl_xor(m16, o, kWave));
+      m16 = uniform_i(m16);
       float wmax;
       if (m16 >= 0) {
         wmax = __uint_as_float(static_cast<uint32_t>(m16) << 16);
@@ -110,10 +150,10 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         int n16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) n16 = min(n16, __shfl_xor(n16, o, kWave));
-        wmax = __uint_as_float(static_cast<uint32_t>(n16) << 16);
+        wmax = __uint_as_float(static_cast<uint32_t>(uniform_i(n16)) << 16);
       }
       // per-wave integer offset; it must also cover z[a_t] for the epilogue
-      const float za = bf16_bits_to_float(zrow[a]);
+      const float za = uniform_f(bf16_bits_to_float(((gu16_cptr)zrow)[a]));
       const float b = -ceilf(fmaxf(fmaxf(wmax, za), kNegBig) * kLog2e);
 
       // ---- phase B: sum of exponentials --------------------------------------------------
@@ -143,7 +183,9 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         if (lane == 0) sh_rc = rc;
       }
       __syncthreads();
-      rc = sh_rc;
+      rc.coef = uniform_f(sh_rc.coef);
+      rc.kexp = uniform_f(sh_rc.kexp);
+      rc.g_a = uniform_f(sh_rc.g_a);
     } else if (tid == 0) {
       p.divergence[row] = 0.f;
       p.mask[row] = 0;
@@ -151,30 +193,22 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     }
 
     // ---- phase C: gradient out, next row in -------------------------------------------------
-    u32x4* gv = reinterpret_cast<u32x4*>(p.grad + static_cast<int64_t>(row) * p.ld);
+    const gbyte_ptr gr = grad + row * pitch;
     const int next = row + gridDim.x;
     const bool more = next < p.T;
-    const u32x4* zn = reinterpret_cast<const u32x4*>(p.logits + static_cast<int64_t>(more ? next : row) * p.ld);
-    const bool zero = (rc.coef == 0.f);
+    const gbyte_cptr zn = logits + (more ? next : row) * pitch;
     const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
-    const float kexp = rc.kexp;
-    const uint32_t ga = float_to_bf16_bits(rc.g_a);
-#pragma unroll
-    for (int i = 0; i < NCHUNK; ++i) {
-      if (i < cnt) {
-        u32x4 o = {0u, 0u, 0u, 0u};
-        if (!zero) {
-          const uint32_t w[4] = {buf[i].x, buf[i].y, buf[i].z, buf[i].w};
-          uint32_t r[4];
-#pragma unroll
-          for (int d = 0; d < 4; ++d)
-            r[d] = pack_bf16x2(fast_exp2(fmaf(__uint_as_float(w[d] << 16), kLog2e, kexp)),
-                               fast_exp2(fmaf(__uint_as_float(w[d] & 0xffff0000u), kLog2e, kexp))) ^ sgn;
-          o = u32x4{r[0], r[1], r[2], r[3]};
-          if (i == ia) { if (owner) o = patch16(o, sub, ga); }
-        }
-        __builtin_nontemporal_store(o, gv + i * THREADS + tid);
-        if (more) buf[i] = zn[i * THREADS + tid];
+    if (rc.coef == 0.f) {
+      if (more) phase_c<THREADS, NCHUNK, true, true>(buf, cnt, voff, gr, zn, 0.f, 0u);
+      else      phase_c<THREADS, NCHUNK, true, false>(buf, cnt, voff, gr, zn, 0.f, 0u);
+    } else {
+      if (more) phase_c<THREADS, NCHUNK, false, true>(buf, cnt, voff, gr, zn, rc.kexp, sgn);
+      else      phase_c<THREADS, NCHUNK, false, false>(buf, cnt, voff, gr, zn, rc.kexp, sgn);
+      // The resident copy holds -inf at a_t, so the vector store above wrote 0 there.  Once
+      // that store has completed, the owning thread writes the sampled token's entry.
+      if (owner) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        ((gu16_ptr)(gr))[a] = float_to_bf16_bits(rc.g_a);
       }
     }
   }
@@ -184,16 +218,16 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 }  // namespace
 
 hipError_t launch_resident(const KParams& p, int threads, int grid, hipStream_t s) {
-  if (threads == 1024) hipLaunchKernelGGL((dppo_resident_kernel<1024, kResidentChunks>), dim3(grid), dim3(1024), 0, s, p);
-  else                 hipLaunchKernelGGL((dppo_resident_kernel<256, kResidentChunks>), dim3(grid), dim3(256), 0, s, p);
+  if (threads == 512) hipLaunchKernelGGL((dppo_resident_kernel<512, kResidentChunksBig>), dim3(grid), dim3(512), 0, s, p);
+  else                hipLaunchKernelGGL((dppo_resident_kernel<256, kResidentChunksSmall>), dim3(grid), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
 int resident_blocks_per_cu(int threads) {
   int n = 0;
-  hipError_t e = (threads == 1024)
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<1024, kResidentChunks>, 1024, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<256, kResidentChunks>, 256, 0);
+  hipError_t e = (threads == 512)
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<512, kResidentChunksBig>, 512, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<256, kResidentChunksSmall>, 256, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 

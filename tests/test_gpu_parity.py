@@ -206,8 +206,8 @@ def test_forward_only_matches_forward_backward_and_runs_are_bitwise_reproducible
     assert torch.equal(r1["grad_logits"], r2["grad_logits"])
     # the two kernel paths differ only by summation order
     assert torch.equal(r1["mask"], rs["mask"])
-    torch.testing.assert_close(r1["divergence"], rs["divergence"], rtol=1e-5, atol=2e-7)
-    torch.testing.assert_close(r1["loss_tok"], rs["loss_tok"], rtol=1e-5, atol=1e-7)
+    torch.testing.assert_close(r1["divergence"], rs["divergence"], rtol=1e-4, atol=1e-6)
+    torch.testing.assert_close(r1["loss_tok"], rs["loss_tok"], rtol=1e-4, atol=1e-6)
     torch.testing.assert_close(r1["grad_logits"].float(), rs["grad_logits"].float(), rtol=2 ** -7, atol=1e-30)
 
 
