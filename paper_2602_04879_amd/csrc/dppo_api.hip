@@ -12,8 +12,6 @@ namespace {
 
 struct DeviceInfo {
   int cus = 0;
-  int resident_per_cu_512 = 1;
-  int resident_per_cu_256 = 1;
 };
 
 // Compute-unit count of a device, queried once per device.
@@ -25,8 +23,6 @@ const DeviceInfo& device_info(int dev) {
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
     info[dev].cus = n;
-    info[dev].resident_per_cu_512 = dppo::resident_blocks_per_cu(512);
-    info[dev].resident_per_cu_256 = dppo::resident_blocks_per_cu(256);
   });
   return info[dev];
 }
@@ -87,20 +83,17 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     p.delta = a->delta;
     p.loss_scale = a->loss_scale;
 
-    const DeviceInfo& di = device_info(dev);
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
-    // Register-resident kernel: rows of 8192 .. 155648 entries with 16-byte aligned rows.
-    const bool small_row = a->V <= 256 * dppo::kResidentChunksSmall * 8;
-    const int r_threads = small_row ? 256 : 512;
-    const int64_t r_cap = small_row ? 256 * dppo::kResidentChunksSmall : 512 * dppo::kResidentChunksBig;
-    const bool resident = grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && a->V >= 8192 && (a->V % 8 == 0) &&
-                          (a->V / 8 <= r_cap) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0;
+    // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
+    int r_threads = 0, r_chunks = 0;
+    const bool resident = grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0 &&
+                          dppo::resident_shape(a->V, &r_threads, &r_chunks);
     if (resident) {
-      int64_t grid = static_cast<int64_t>(cus) * (r_threads == 512 ? di.resident_per_cu_512 : di.resident_per_cu_256);
+      int64_t grid = static_cast<int64_t>(cus) * dppo::resident_blocks_per_cu(r_threads, r_chunks);
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
-      if (dppo::launch_resident(p, r_threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      if (dppo::launch_resident(p, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident";
     } else {
       // 16-byte vectors need logits and grad rows to share their misalignment.

@@ -8,7 +8,6 @@ namespace dppo {
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;   // logits below this are treated as -inf
-constexpr double kTiny = 1e-30;       // floor for a vanishing denominator inside x*ln(x/y)
 
 enum : int { kBinaryTV = 0, kBinaryKL = 1, kTopkTV = 2, kTopkKL = 3 };
 
@@ -30,11 +29,34 @@ struct KParams {
   float delta, loss_scale;
 };
 
+// The subset of the arguments the per-row epilogue needs.  Each kernel makes ONE copy of it at
+// its start and hands the epilogue a reference to that copy: taking the address of the
+// kernel-argument struct itself would move all of it from scalar registers to the stack.
+struct EpiParams {
+  const int32_t* tk_ids;
+  const float* tk_lp;
+  float* loss_tok;
+  float* divergence;
+  uint8_t* mask;
+  int32_t V, K, variant;
+  float delta, loss_scale;
+};
+__device__ __forceinline__ EpiParams epi_params(const KParams& p) {
+  EpiParams e;
+  e.tk_ids = p.tk_ids; e.tk_lp = p.tk_lp; e.loss_tok = p.loss_tok; e.divergence = p.divergence; e.mask = p.mask;
+  e.V = p.V; e.K = p.K; e.variant = p.variant; e.delta = p.delta; e.loss_scale = p.loss_scale;
+  return e;
+}
+
 // What the per-row epilogue hands to the gradient pass.
 struct RowCoef {
   float kexp;     // g_j = sgn * exp2(z_j*log2e + kexp) for j != a_t ; -inf-like when coef == 0
   float coef;     // c_t = loss_scale * M_t * A_t * r_t
   float g_a;      // gradient entry of the sampled token, c_t * (pi(a_t) - 1)
+};
+struct RowResult {
+  RowCoef rc;
+  double loss_term;   // -M_t r_t A_t
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
@@ -59,8 +81,47 @@ typedef __attribute__((address_space(1))) char* gbyte_ptr;
 __device__ __forceinline__ u32x4 gload16(gbyte_cptr base, uint32_t voff) {
   return *reinterpret_cast<gvec_cptr>(base + voff);
 }
+__device__ __forceinline__ void gstore16(gbyte_ptr base, uint32_t voff, u32x4 v) {
+  *reinterpret_cast<gvec_ptr>(base + voff) = v;
+}
 __device__ __forceinline__ void gstore16_nt(gbyte_ptr base, uint32_t voff, u32x4 v) {
   __builtin_nontemporal_store(v, reinterpret_cast<gvec_ptr>(base + voff));
+}
+
+// Buffer resource over one row: base address in scalar registers, byte range checked by the
+// hardware (a load past `bytes` returns 0, a store past it is dropped), so a 16-byte access is
+// addressed by one per-lane 32-bit offset plus a scalar offset and needs no address arithmetic
+// in vector registers.
+typedef __amdgpu_buffer_rsrc_t row_rsrc_t;
+__device__ __forceinline__ row_rsrc_t make_row_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ u32x4 row_load16(row_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+__device__ __forceinline__ void row_store16(row_rsrc_t r, uint32_t voff, uint32_t soff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 0);
+}
+
+// The same store issued from inline assembly, over a descriptor built by hand.  The compiler
+// then does not count it among the pending vector-memory operations.  That matters where
+// loads issued around such stores are waited for one by one: with stores and loads both
+// pending the compiler falls back to waiting for everything (s_waitcnt vmcnt(0)), whereas loads
+// alone complete in order and it waits for exactly the one it needs (vmcnt = number of loads
+// issued after it, which stays correct however many stores are in flight).  The hardware reads
+// the store data when the instruction issues, so the data registers may be reused at once.
+typedef int row_desc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  row_desc_t d;
+  d.x = __builtin_amdgcn_readfirstlane(static_cast<int>(a));
+  d.y = __builtin_amdgcn_readfirstlane(static_cast<int>((a >> 32) & 0xffffu));
+  d.z = __builtin_amdgcn_readfirstlane(static_cast<int>(bytes));
+  d.w = 0x00020000;
+  return d;
+}
+__device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t voff, uint32_t soff, u32x4 v) {
+  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
 // A value every lane of the wave holds identically, moved to a scalar register.
@@ -90,10 +151,72 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// x * ln(x / y) with 0 ln 0 = 0 and the denominator floored.
-__device__ __forceinline__ double xlogx_over_y(double x, double y) {
-  if (x <= 0.0) return 0.0;
-  return x * (log(x) - log(fmax(y, kTiny)));
+// ---- scalar math for the per-row epilogue ----------------------------------------------------
+// The epilogue runs once per row on one wave while the rest of the workgroup waits, so it is
+// built from the hardware's single-instruction exp2/log2 (about 1 ulp in fp32) with the range
+// reduction and every sum or difference that could cancel carried in float64.  Each probability
+// comes out with a relative error of about 2e-7, which is also what the fp32 row sum carries.
+
+constexpr double kLn2 = 0.6931471805599453;
+constexpr double kLog2eD = 1.4426950408889634;
+constexpr double kLnTiny = -69.07755278982137;   // ln(1e-30): floor of a vanishing denominator
+
+// 2^x for a float64 argument, returned in fp32 (0 for x below the fp32 range).
+__device__ __forceinline__ float exp2_split(double x) {
+  if (!(x > -200.0)) return 0.f;
+  const double n = __builtin_rint(x);
+  const float f = static_cast<float>(x - n);            // |f| <= 0.5
+  return ldexpf(fast_exp2(f), static_cast<int>(n));
+}
+
+// log2(x) for a positive finite float64 x, absolute error about 1.5e-7.
+__device__ __forceinline__ double log2_fast(double x) {
+  const int e = __builtin_amdgcn_frexp_exp(x);
+  const float m = static_cast<float>(__builtin_amdgcn_frexp_mant(x));   // [0.5, 1)
+  return static_cast<double>(e) + static_cast<double>(__builtin_amdgcn_logf(m));
+}
+
+// x * (ln x - max(ln y, ln 1e-30)) with 0 ln 0 = 0; the logarithms are passed in.
+__device__ __forceinline__ double xlogx_over_y(double x, double ln_x, double ln_y) {
+  return (x > 0.0) ? x * (ln_x - fmax(ln_y, kLnTiny)) : 0.0;
+}
+
+// 1 - exp(t) for t <= 0 in float64, accurate when t -> 0.
+__device__ __forceinline__ double one_minus_exp(double t, float exp_t) {
+  if (t > -0.0625) {
+    const double u = t * (1.0 + t * (0.5 + t * (1.0 / 6 + t * (1.0 / 24 + t * (1.0 / 120 + t * (1.0 / 720))))));
+    return -u;
+  }
+  return 1.0 - static_cast<double>(exp_t);
+}
+
+// Per-row inputs the epilogue needs besides the row statistics.  The kernels fetch them early
+// in the row so that no memory latency is left on the epilogue's critical path.
+struct RowScalars {
+  int a;        // sampled id (valid: 0 <= a < V)
+  float za;     // z[a_t]
+  float lmu;    // log mu(a_t)
+  float adv;    // A_t
+};
+struct TopkLane {   // lane k holds top-K entry k (k < 64); id < 0 marks "no entry"
+  int id;
+  float lp;     // log mu(id)
+  float z;      // z[id]
+};
+
+template <typename P>
+__device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, const uint16_t* zrow, int lane) {
+  TopkLane t;
+  t.id = -1; t.lp = 0.f; t.z = 0.f;
+  if (lane < p.K) {
+    const int id = p.tk_ids[static_cast<int64_t>(row) * p.K + lane];
+    if (id >= 0 && id < p.V && id != a) {
+      t.id = id;
+      t.lp = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
+      t.z = bf16_bits_to_float(zrow[id]);
+    }
+  }
+  return t;
 }
 
 // Per-row epilogue, executed by ONE full wave (all 64 lanes call it with the same scalars).
@@ -105,56 +228,64 @@ __device__ __forceinline__ double xlogx_over_y(double x, double y) {
 // are mutually consistent; its rounding (1.3e-8 relative) acts as a temperature of 1+1.3e-8.
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
 // mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
-// Lane 0 stores the per-token outputs; every lane returns the same RowCoef and *loss_term.
-// Deliberately NOT inlined: its float64 arithmetic needs many registers, and as a real call its
-// register traffic stays inside the one wave that runs it instead of raising the pressure of
-// the streaming phases around it.
-__device__ __attribute__((noinline)) static RowCoef row_epilogue(const KParams& p, int row, int a, const uint16_t* zrow,
-                                                float b, double S_rest, int lane, double* loss_term) {
+// Lane 0 stores the per-token outputs; every lane returns the same RowResult.
+// Deliberately NOT inlined: as a real call, the registers it needs are saved and restored
+// around it by the one wave that runs it, instead of raising the register pressure of the
+// streaming phases that every wave runs.
+// Everything but the kernel arguments is passed and returned by value, i.e. in registers.
+__device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
+                                                                   const uint16_t* zrow, float b, double S_rest, int lane) {
   constexpr double kL = static_cast<double>(kLog2e);
-  constexpr double kLn2 = 0.6931471805599453;
   const double bd = static_cast<double>(b);
-  const double xa = static_cast<double>(bf16_bits_to_float(zrow[a])) * kL + bd;   // log2 of a_t's term
-  const double ea = exp2(xa);
-  const double S = S_rest + ea;
-  const double log2S = log2(S);
+  const double xa = static_cast<double>(rs.za) * kL + bd;   // log2 of a_t's own term
+  const float ea = exp2_split(xa);
+  const double S = S_rest + static_cast<double>(ea);
+  const double log2S = log2_fast(S);
+  const float inv_S = 1.0f / static_cast<float>(S);
   const double lpi = (xa - log2S) * kLn2;
-  const double lmu_raw = static_cast<double>(p.mu_logp[row]);
+  const double lmu_raw = static_cast<double>(rs.lmu);
   const double lmu = fmin(lmu_raw, 0.0);
-  const double pa = exp(lmu), qa = ea / S;
-  const double one_minus_qa = S_rest / S;
+  const float pa = exp2_split(lmu * kLog2eD);
+  const float qa = ea * inv_S;
+  const double one_minus_qa = static_cast<double>(static_cast<float>(S_rest) * inv_S);
+  const int variant = p.variant;
   double D;
-  if (p.variant == kBinaryTV || ((p.variant == kTopkTV) && p.K == 0)) {
-    D = fabs(pa - qa);
-  } else if (p.variant == kBinaryKL || ((p.variant == kTopkKL) && p.K == 0)) {
-    D = xlogx_over_y(pa, qa) + xlogx_over_y(-expm1(lmu), one_minus_qa);
+  if (variant == kBinaryTV || (variant == kTopkTV && p.K == 0)) {
+    D = fabs(static_cast<double>(pa) - static_cast<double>(qa));
+  } else if (variant == kBinaryKL || (variant == kTopkKL && p.K == 0)) {
+    const double omp = one_minus_exp(lmu, pa);
+    D = xlogx_over_y(pa, lmu, lpi) +
+        xlogx_over_y(omp, log2_fast(fmax(omp, 1e-300)) * kLn2, log2_fast(fmax(one_minus_qa, 1e-300)) * kLn2);
   } else {
     // reduced distributions over TopK(mu, K) U {a_t} U {other}  (Sec. 4.4)
-    const bool tv = (p.variant == kTopkTV);
+    const bool tv = (variant == kTopkTV);
     double sp = 0.0, sq = 0.0, acc = 0.0;
-    const int32_t* ids = p.tk_ids + static_cast<int64_t>(row) * p.K;
-    const float* lps = p.tk_lp + static_cast<int64_t>(row) * p.K;
-    for (int k = lane; k < p.K; k += kWave) {
-      const int id = ids[k];
-      if (id >= 0 && id < p.V && id != a) {
-        const double pk = exp(fmin(static_cast<double>(lps[k]), 0.0));
-        const double qk = exp2(static_cast<double>(bf16_bits_to_float(zrow[id])) * kL + bd - log2S);
+    TopkLane t = tk;
+    for (int k = lane;;) {
+      if (t.id >= 0) {
+        const double lpk = fmin(static_cast<double>(t.lp), 0.0);
+        const double xk = static_cast<double>(t.z) * kL + bd - log2S;     // log2 pi(id)
+        const float pk = exp2_split(lpk * kLog2eD), qk = exp2_split(xk);
         sp += pk;
         sq += qk;
-        acc += tv ? fabs(pk - qk) : xlogx_over_y(pk, qk);
+        acc += tv ? fabs(static_cast<double>(pk) - static_cast<double>(qk)) : xlogx_over_y(pk, lpk, xk * kLn2);
       }
+      k += kWave;
+      if (k >= p.K) break;
+      t = load_topk_lane(p, row, rs.a, zrow, k);    // K > 64: further entries, fetched here
     }
     sp = wave_sum(sp) + pa;
     sq = wave_sum(sq) + qa;
-    acc = wave_sum(acc) + (tv ? fabs(pa - qa) : xlogx_over_y(pa, qa));
+    acc = wave_sum(acc) + (tv ? fabs(static_cast<double>(pa) - static_cast<double>(qa)) : xlogx_over_y(pa, lmu, lpi));
     const double po = fmax(1.0 - sp, 0.0), qo = fmax(1.0 - sq, 0.0);
-    D = tv ? 0.5 * (acc + fabs(po - qo)) : acc + xlogx_over_y(po, qo);
+    D = tv ? 0.5 * (acc + fabs(po - qo))
+           : acc + xlogx_over_y(po, log2_fast(fmax(po, 1e-300)) * kLn2, log2_fast(fmax(qo, 1e-300)) * kLn2);
   }
-  const double A = static_cast<double>(p.adv[row]);
+  const double A = static_cast<double>(rs.adv);
   const bool blocked = (D > static_cast<double>(p.delta)) &&
                        ((A > 0.0 && lpi > lmu_raw) || (A < 0.0 && lpi < lmu_raw));
   const double M = blocked ? 0.0 : 1.0;
-  const double r = exp(lpi - lmu_raw);
+  const double r = static_cast<double>(exp2_split((lpi - lmu_raw) * kLog2eD));
   const double lt = -M * r * A;
   const double c = static_cast<double>(p.loss_scale) * M * A * r;
   if (lane == 0) {
@@ -162,13 +293,13 @@ __device__ __attribute__((noinline)) static RowCoef row_epilogue(const KParams& 
     p.mask[row] = blocked ? 0 : 1;
     if (p.loss_tok) p.loss_tok[row] = static_cast<float>(lt);
   }
-  *loss_term = lt;
-  RowCoef rc;
-  rc.coef = static_cast<float>(c);
-  rc.g_a = static_cast<float>(-c * one_minus_qa);
+  RowResult res;
+  res.loss_term = lt;
+  res.rc.coef = static_cast<float>(c);
+  res.rc.g_a = static_cast<float>(-c * one_minus_qa);
   // c * pi_j = sgn(c) * 2^(z_j*log2e + kexp)
-  rc.kexp = (c != 0.0) ? static_cast<float>(log2(fabs(c)) + bd - log2S) : 0.f;
-  return rc;
+  res.rc.kexp = (c != 0.0 && fabs(c) < 1e300) ? static_cast<float>(log2_fast(fabs(c)) + bd - log2S) : 0.f;
+  return res;
 }
 
 }  // namespace dppo

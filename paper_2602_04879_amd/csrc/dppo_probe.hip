@@ -25,7 +25,8 @@ __global__ __launch_bounds__(256) void dppo_probe_read_kernel(const dppo::u32x4*
 
 int probe_grid() {
   int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
   return cus * 8;
 }
 

@@ -35,67 +35,63 @@ __device__ __forceinline__ u32x4 patch16(u32x4 v, int sub, uint32_t bits) {
   return r;
 }
 
-// Phase C for one row: write the gradient of every resident chunk and (MORE) refill the chunk
-// with the workgroup's next row.  ZERO rows (masked, zero advantage, ignored) store zeros.
-template <int THREADS, int NCHUNK, bool ZERO, bool MORE>
-__device__ __forceinline__ void phase_c(u32x4 (&buf)[NCHUNK], int cnt, uint32_t voff, gbyte_ptr grow, gbyte_cptr znext,
-                                        float kexp, uint32_t sgn) {
-  constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
-#pragma unroll
-  for (int i = 0; i < NCHUNK; ++i) {
-    if (i < cnt) {
-      u32x4 o = {0u, 0u, 0u, 0u};
-      if (!ZERO) {
-        const uint32_t w[4] = {buf[i].x, buf[i].y, buf[i].z, buf[i].w};
-        uint32_t r[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d)
-          r[d] = pack_bf16x2(fast_exp2(fmaf(__uint_as_float(w[d] << 16), kLog2e, kexp)),
-                             fast_exp2(fmaf(__uint_as_float(w[d] & 0xffff0000u), kLog2e, kexp))) ^ sgn;
-        o = u32x4{r[0], r[1], r[2], r[3]};
-      }
-      gstore16_nt(grow + i * kStride, voff, o);
-      if (MORE) buf[i] = gload16(znext + i * kStride, voff);
-    }
-  }
+// 2^(z*log2e + k) for the two bf16 halves of a packed word.
+__device__ __forceinline__ float exp_lo(uint32_t w, float k) { return fast_exp2(fmaf(__uint_as_float(w << 16), kLog2e, k)); }
+__device__ __forceinline__ float exp_hi(uint32_t w, float k) { return fast_exp2(fmaf(__uint_as_float(w & 0xffff0000u), kLog2e, k)); }
+
+// Gradient of the eight entries of one chunk: sgn * 2^(z*log2e + kexp), rounded to bf16.
+__device__ __forceinline__ u32x4 grad8(u32x4 v, float kexp, uint32_t sgn) {
+  const u32x4 o = {pack_bf16x2(exp_lo(v.x, kexp), exp_hi(v.x, kexp)) ^ sgn, pack_bf16x2(exp_lo(v.y, kexp), exp_hi(v.y, kexp)) ^ sgn,
+                   pack_bf16x2(exp_lo(v.z, kexp), exp_hi(v.z, kexp)) ^ sgn, pack_bf16x2(exp_lo(v.w, kexp), exp_hi(v.w, kexp)) ^ sgn};
+  return o;
 }
 
+// Chunks whose lanes can lie past the end of the row: with NCHUNK a multiple of kChunkStep (or
+// the maximum), at most the last kChunkStep of them.
+constexpr int kChunkStep = 4;
+
+// The kernel.  THREADS x NCHUNK 16-byte vectors cover the row (V/8 <= THREADS*NCHUNK, with less
+// than kChunkStep chunks of slack).  Chunk i of thread tid is vector i*THREADS + tid of the row.
+// All row traffic goes through range-checked buffer resources, so the phases are straight-line
+// code with a fixed sequence of memory instructions: loads past the row return 0 (turned into
+// -inf where the row statistics consume them) and stores past it are dropped.
 template <int THREADS, int NCHUNK>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
-  constexpr uint32_t kStride = THREADS * 16u;
+  constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
+  constexpr int GC = 2;                          // chunks per group of the online row statistics
   __shared__ float sh_b[NW];
   __shared__ double sh_s[NW];
   __shared__ RowCoef sh_rc;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
   const int nvec = p.V >> 3;
-  // Thread tid owns vectors tid, tid+THREADS, ...: `cnt` of them (chunk i <-> vector i*THREADS+tid).
-  const int cnt = (nvec - tid + THREADS - 1) / THREADS;
+  const uint32_t row_bytes = static_cast<uint32_t>(p.V) * 2u;
   const uint32_t voff = static_cast<uint32_t>(tid) * 16u;
   const u32x4 neg_inf = {kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair};
   const int64_t pitch = p.ld * 2;               // row pitch in bytes
-  const gbyte_cptr logits = (gbyte_cptr)p.logits;
-  const gbyte_ptr grad = (gbyte_ptr)p.grad;
+  const char* logits = reinterpret_cast<const char*>(p.logits);
+  char* grad = reinterpret_cast<char*>(p.grad);
+  const EpiParams ep = epi_params(p);
   double loss_acc = 0.0;                        // meaningful in wave 0 only
 
-  // The resident row.  Slots past the row hold -inf for the whole kernel: they add nothing.
+  // The resident row.
   u32x4 buf[NCHUNK];
   int row = blockIdx.x;
   {
-    const gbyte_cptr zr = logits + row * pitch;
+    const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
 #pragma unroll
-    for (int i = 0; i < NCHUNK; ++i) {
-      buf[i] = neg_inf;
-      if (i < cnt) buf[i] = gload16(zr + i * kStride, voff);
-    }
+    for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zr, voff, i * kStride);
   }
+  int a_next = p.sampled[row];                   // fetched one row ahead
 
   for (; row < p.T; row += gridDim.x) {
-    const int a = uniform_i(p.sampled[row]);
+    const int a = uniform_i(a_next);
+    const int next = row + gridDim.x;
+    const bool more = next < p.T;
+    if (more) a_next = p.sampled[next];
     const bool live = (a >= 0 && a < p.V);
-    const gbyte_cptr zr = logits + row * pitch;
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
     const int avec = a >> 3;
     const int ia = live ? avec / THREADS : -1;               // chunk holding a_t (uniform)
@@ -105,81 +101,84 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     RowCoef rc;
     rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
     if (live) {
-      // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
-      // with -inf in the resident copy; the epilogue reads z[a_t] from memory.  `ia` is uniform,
-      // so this is one scalar jump, not a test per chunk.
-#define DPPO_PATCH_CASE(I) case I: if (I < NCHUNK && owner) buf[I < NCHUNK ? I : 0] = patch16(buf[I < NCHUNK ? I : 0], sub, 0xFF80u); break;
-#define DPPO_PATCH_CASES10(B) DPPO_PATCH_CASE(B + 0) DPPO_PATCH_CASE(B + 1) DPPO_PATCH_CASE(B + 2) DPPO_PATCH_CASE(B + 3) \
-  DPPO_PATCH_CASE(B + 4) DPPO_PATCH_CASE(B + 5) DPPO_PATCH_CASE(B + 6) DPPO_PATCH_CASE(B + 7) DPPO_PATCH_CASE(B + 8) DPPO_PATCH_CASE(B + 9)
-      switch (ia) {
-        DPPO_PATCH_CASES10(0) DPPO_PATCH_CASES10(10) DPPO_PATCH_CASES10(20) DPPO_PATCH_CASES10(30)
-        default: break;
+      // Inputs of the epilogue, requested now so that they have arrived when it runs.
+      RowScalars rs;
+      TopkLane tk;
+      tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
+      rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f;
+      if (wid == 0) {
+        rs.za = bf16_bits_to_float(zrow[a]);
+        rs.lmu = p.mu_logp[row];
+        rs.adv = p.adv[row];
+        tk = load_topk_lane(p, row, a, zrow, lane);
       }
-#undef DPPO_PATCH_CASES10
-#undef DPPO_PATCH_CASE
-
-      // ---- phase A: maximum, on the packed bf16 patterns --------------------------------
-      // As signed 16-bit integers, non-negative bf16 order like floats and every negative one
-      // is below them, so the integer maximum is the float maximum whenever it is >= 0.
-      s16x2 mx = as_s16x2(0x80008000u);
-#pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) {
-        mx = __builtin_elementwise_max(mx, as_s16x2(buf[i].x));
-        mx = __builtin_elementwise_max(mx, as_s16x2(buf[i].y));
-        mx = __builtin_elementwise_max(mx, as_s16x2(buf[i].z));
-        mx = __builtin_elementwise_max(mx, as_s16x2(buf[i].w));
-      }
-      int m16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) m16 = max(m16, __shfl_xor(m16, o, kWave));
-      m16 = uniform_i(m16);
-      float wmax;
-      if (m16 >= 0) {
-        wmax = __uint_as_float(static_cast<uint32_t>(m16) << 16);
-      } else {
-        // Every entry of this wave's share is negative (or -inf).  Among negative bf16 the
-        // float maximum has the smallest magnitude, i.e. the smallest signed 16-bit pattern.
-        s16x2 mn = as_s16x2(0xFFFFFFFFu);
-#pragma unroll
-        for (int i = 0; i < NCHUNK; ++i) {
-          mn = __builtin_elementwise_min(mn, as_s16x2(buf[i].x));
-          mn = __builtin_elementwise_min(mn, as_s16x2(buf[i].y));
-          mn = __builtin_elementwise_min(mn, as_s16x2(buf[i].z));
-          mn = __builtin_elementwise_min(mn, as_s16x2(buf[i].w));
-        }
-        int n16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) n16 = min(n16, __shfl_xor(n16, o, kWave));
-        wmax = __uint_as_float(static_cast<uint32_t>(uniform_i(n16)) << 16);
-      }
-      // per-wave integer offset; it must also cover z[a_t] for the epilogue
-      const float za = uniform_f(bf16_bits_to_float(((gu16_cptr)zrow)[a]));
-      const float b = -ceilf(fmaxf(fmaxf(wmax, za), kNegBig) * kLog2e);
-
-      // ---- phase B: sum of exponentials --------------------------------------------------
+      // ---- phases A+B, online over groups of GC chunks ------------------------------------
+      // Per thread: s = sum 2^(z*log2e + b) with an integer offset b <= -max(z, 0)*log2e that
+      // only ever decreases; lowering it rescales s by an exact power of two.  The maximum is
+      // taken on the packed bf16 patterns: as signed 16-bit integers the non-negative ones
+      // order like floats and the negative ones stay below them, so max(pattern, 0) is
+      // max(z, 0) exactly.  The first groups were loaded first, so their arithmetic hides the
+      // latency of the chunks requested last.
+      s16x2 mx = as_s16x2(0u);
+      float b = 0.f;
       float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) {
-        const uint32_t w[4] = {buf[i].x, buf[i].y, buf[i].z, buf[i].w};
-        s0 += fast_exp2(fmaf(__uint_as_float(w[0] << 16), kLog2e, b)) + fast_exp2(fmaf(__uint_as_float(w[0] & 0xffff0000u), kLog2e, b));
-        s1 += fast_exp2(fmaf(__uint_as_float(w[1] << 16), kLog2e, b)) + fast_exp2(fmaf(__uint_as_float(w[1] & 0xffff0000u), kLog2e, b));
-        s2 += fast_exp2(fmaf(__uint_as_float(w[2] << 16), kLog2e, b)) + fast_exp2(fmaf(__uint_as_float(w[2] & 0xffff0000u), kLog2e, b));
-        s3 += fast_exp2(fmaf(__uint_as_float(w[3] << 16), kLog2e, b)) + fast_exp2(fmaf(__uint_as_float(w[3] & 0xffff0000u), kLog2e, b));
+      for (int g0 = 0; g0 < NCHUNK; g0 += GC) {
+        // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
+        // with -inf in the resident copy, right where its chunk is first consumed.  `ia` is
+        // uniform: a scalar test per chunk, the patch itself runs once per row.
+#pragma unroll
+        for (int i = 0; i < GC; ++i) {
+          if (g0 + i < NCHUNK && g0 + i == ia) {
+            if (owner) buf[g0 + i < NCHUNK ? g0 + i : 0] = patch16(buf[g0 + i < NCHUNK ? g0 + i : 0], sub, 0xFF80u);
+          }
+        }
+        u32x4 v[GC];
+#pragma unroll
+        for (int i = 0; i < GC; ++i) {
+          const int c = (g0 + i < NCHUNK) ? g0 + i : NCHUNK - 1;
+          v[i] = (g0 + i < NCHUNK) ? buf[c] : neg_inf;
+          // lanes past the row loaded 0: make them -inf (only the last chunks can have any)
+          if (g0 + i < NCHUNK && g0 + i >= NCHUNK - kChunkStep && c * THREADS + tid >= nvec) v[i] = neg_inf;
+        }
+#pragma unroll
+        for (int i = 0; i < GC; ++i) {
+          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].x));
+          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].y));
+          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].z));
+          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].w));
+        }
+        const int m16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
+        const float bn = -ceilf(__uint_as_float(static_cast<uint32_t>(m16) << 16) * kLog2e);
+        const float sc = fast_exp2(bn - b);       // 1 when the maximum did not move
+        s0 *= sc; s1 *= sc; s2 *= sc; s3 *= sc;
+        b = bn;
+#pragma unroll
+        for (int i = 0; i < GC; ++i) {
+          s0 += exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
+          s1 += exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
+          s2 += exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
+          s3 += exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
       }
-      const double sw = wave_sum(static_cast<double>(s0 + s1) + static_cast<double>(s2 + s3));
-      if (lane == 0) { sh_b[wid] = b; sh_s[wid] = sw; }
+      // wave-level combine: common offset = the smallest one, rescaling is exact
+      const float bw = -wave_max(-b);
+      const double sw = wave_sum(static_cast<double>((s0 + s1) + (s2 + s3)) * static_cast<double>(fast_exp2(bw - b)));
+      if (lane == 0) { sh_b[wid] = bw; sh_s[wid] = sw; }
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------
       if (wid == 0) {
-        float bb = sh_b[0];
+        // the offset must also cover z[a_t], whose own term the epilogue adds
+        float bb = -ceilf(fmaxf(rs.za, 0.f) * kLog2e);
 #pragma unroll
-        for (int w = 1; w < NW; ++w) bb = fminf(bb, sh_b[w]);
+        for (int w = 0; w < NW; ++w) bb = fminf(bb, sh_b[w]);
         double S_rest = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) S_rest += sh_s[w] * static_cast<double>(fast_exp2(bb - sh_b[w]));   // exact powers of two
-        double lt;
-        rc = row_epilogue(p, row, a, zrow, bb, S_rest, lane, &lt);
-        loss_acc += lt;
+        const RowResult rr = row_epilogue(ep, row, rs, tk, zrow, bb, S_rest, lane);
+        rc = rr.rc;
+        loss_acc += rr.loss_term;
         if (lane == 0) sh_rc = rc;
       }
       __syncthreads();
@@ -193,42 +192,77 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     }
 
     // ---- phase C: gradient out, next row in -------------------------------------------------
-    const gbyte_ptr gr = grad + row * pitch;
-    const int next = row + gridDim.x;
-    const bool more = next < p.T;
-    const gbyte_cptr zn = logits + (more ? next : row) * pitch;
+    // Every chunk: store its gradient, then refill it with the same chunk of the workgroup's
+    // next row, in the order the next row's arithmetic will consume them.  Without a next row
+    // the refill goes through a resource of zero bytes: its loads touch no memory.
+    char* gr = grad + row * pitch;
+    const row_desc_t gout = make_row_desc(gr, row_bytes);
+    const row_rsrc_t zn = make_row_rsrc(logits + (more ? next : row) * pitch, more ? row_bytes : 0u);
     const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
     if (rc.coef == 0.f) {
-      if (more) phase_c<THREADS, NCHUNK, true, true>(buf, cnt, voff, gr, zn, 0.f, 0u);
-      else      phase_c<THREADS, NCHUNK, true, false>(buf, cnt, voff, gr, zn, 0.f, 0u);
-    } else {
-      if (more) phase_c<THREADS, NCHUNK, false, true>(buf, cnt, voff, gr, zn, rc.kexp, sgn);
-      else      phase_c<THREADS, NCHUNK, false, false>(buf, cnt, voff, gr, zn, rc.kexp, sgn);
-      // The resident copy holds -inf at a_t, so the vector store above wrote 0 there.  Once
+      // Masked, zero-advantage or ignored row: its gradient is exactly zero whatever the logits
+      // hold.  Overwrite the resident copy with -inf so that the loop below writes 2^-inf = 0.
+#pragma unroll
+      for (int i = 0; i < NCHUNK; ++i) buf[i] = neg_inf;
+    }
+#pragma unroll
+    for (int i = 0; i < NCHUNK; ++i) {
+      row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
+      buf[i] = row_load16(zn, voff, i * kStride);
+      // Keep the instruction scheduler from hoisting the refills above the stores they follow:
+      // a refill can only reuse its chunk's registers once the chunk has been consumed.
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (rc.coef != 0.f && owner) {
+      // The resident copy held -inf at a_t, so the vector store above wrote 0 there.  Once
       // that store has completed, the owning thread writes the sampled token's entry.
-      if (owner) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        ((gu16_ptr)(gr))[a] = float_to_bf16_bits(rc.g_a);
-      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      reinterpret_cast<uint16_t*>(gr)[a] = float_to_bf16_bits(rc.g_a);
     }
   }
   if (tid == 0) p.partial[blockIdx.x] = loss_acc;
 }
 
-}  // namespace
-
-hipError_t launch_resident(const KParams& p, int threads, int grid, hipStream_t s) {
-  if (threads == 512) hipLaunchKernelGGL((dppo_resident_kernel<512, kResidentChunksBig>), dim3(grid), dim3(512), 0, s, p);
-  else                hipLaunchKernelGGL((dppo_resident_kernel<256, kResidentChunksSmall>), dim3(grid), dim3(256), 0, s, p);
+// One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
+template <int THREADS, int NCHUNK>
+hipError_t launch_shape(const KParams& p, int grid, hipStream_t s) {
+  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK>), dim3(grid), dim3(THREADS), 0, s, p);
   return hipGetLastError();
 }
-
-int resident_blocks_per_cu(int threads) {
+template <int THREADS, int NCHUNK>
+int occupancy_shape() {
   int n = 0;
-  hipError_t e = (threads == 512)
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<512, kResidentChunksBig>, 512, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<256, kResidentChunksSmall>, 256, 0);
+  const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
+}
+
+}  // namespace
+
+#define DPPO_SHAPES(X) \
+  X(256, 4) X(256, 8) X(256, 12) X(256, 16) X(256, 20) \
+  X(512, 12) X(512, 16) X(512, 20) X(512, 24) X(512, 28) X(512, 32) X(512, 36) X(512, 38)
+
+bool resident_shape(int64_t V, int* threads, int* chunks) {
+  if (V < 8192 || V % 8 != 0) return false;
+  const int64_t nvec = V / 8;
+#define DPPO_TRY(T, C) if (nvec <= static_cast<int64_t>(T) * C) { *threads = T; *chunks = C; return true; }
+  DPPO_SHAPES(DPPO_TRY)
+#undef DPPO_TRY
+  return false;
+}
+
+hipError_t launch_resident(const KParams& p, int threads, int chunks, int grid, hipStream_t s) {
+#define DPPO_LAUNCH(T, C) if (threads == T && chunks == C) return launch_shape<T, C>(p, grid, s);
+  DPPO_SHAPES(DPPO_LAUNCH)
+#undef DPPO_LAUNCH
+  return hipErrorInvalidValue;
+}
+
+int resident_blocks_per_cu(int threads, int chunks) {
+#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>();
+  DPPO_SHAPES(DPPO_OCC)
+#undef DPPO_OCC
+  return 1;
 }
 
 }  // namespace dppo

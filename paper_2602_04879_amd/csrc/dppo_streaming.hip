@@ -50,6 +50,7 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
   __shared__ double sh_sum[NW];
   __shared__ RowCoef sh_rc;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
+  const EpiParams ep = epi_params(p);
   double loss_acc = 0.0;   // meaningful in wave 0 only
 
   for (int row = blockIdx.x; row < p.T; row += gridDim.x) {
@@ -105,9 +106,15 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
         double S_rest = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) S_rest += sh_sum[w];
-        double lt;
-        rc = row_epilogue(p, row, a, zrow, b, S_rest, lane, &lt);
-        loss_acc += lt;
+        RowScalars rs;
+        rs.a = a;
+        rs.za = bf16_bits_to_float(zrow[a]);
+        rs.lmu = p.mu_logp[row];
+        rs.adv = p.adv[row];
+        const TopkLane tk = load_topk_lane(p, row, a, zrow, lane);
+        const RowResult res = row_epilogue(ep, row, rs, tk, zrow, b, S_rest, lane);
+        rc = res.rc;
+        loss_acc += res.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
       }
       if (GRAD) {
