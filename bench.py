@@ -150,6 +150,24 @@ def main() -> int:
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     path = B.last_path()
 
+    # the device's streaming ceilings, measured with the library's plain copy / read kernels
+    ceil_src = batch["logits"].view(-1)[: (2 << 30)].view(torch.uint8) if batch["logits"].numel() * 2 >= (4 << 30) else None
+    ceilings = {}
+    if ceil_src is not None:
+        ceil_dst = grad.view(-1)[: (2 << 30)].view(torch.uint8)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for name, fn, moved in (("copy", lambda: B.probe_copy(ceil_dst, ceil_src, stream), 2 * ceil_src.numel()),
+                                ("read", lambda: B.probe_read(ceil_src, sink, stream), ceil_src.numel())):
+            fn()
+            torch.cuda.synchronize()
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record(stream)
+            for _ in range(5):
+                fn()
+            c1.record(stream)
+            torch.cuda.synchronize()
+            ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
+
     launches = len(calls)
     alg_bytes_launch = algorithmic_bytes_per_token(V, K) * (T // launches)
     kernel_ms = ms_per_step / launches           # the step is the dominant kernel plus a ~3 us reduction
@@ -167,7 +185,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
-                     "kernel_ms": kernel_ms},
+                     "kernel_ms": kernel_ms, "device_ceilings": ceilings,
+                     "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},
         "loss": loss, "masked_tokens": int((out["mask"] == 0).sum().item()),
     }
     if not args.no_cpu_baseline:

@@ -129,11 +129,13 @@ const char* dppo_last_path(void);
 
 /* ---- measurement utilities (not part of the loss) ------------------------------------------
  * Plain device-to-device copy of `bytes` bytes with 16-byte vector loads/stores (dst, src and
- * bytes multiples of 16; buffers must not overlap), and a read-only pass over `bytes` bytes
- * (`sink` is a 4-byte device location that is practically never written).  bench.py and the
+ * bytes multiples of 16; buffers must not overlap), a write-only fill of `bytes` bytes with a
+ * 32-bit pattern, and a read-only pass over `bytes` bytes (`sink` is a 4-byte device location
+ * that is practically never written).  bench.py and the
  * counter-calibration probe use them: a copy of known size scales the HBM byte counters, and
  * their bandwidth is the device's streaming ceiling the loss kernels are compared with. */
 dppo_status_t dppo_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+dppo_status_t dppo_probe_fill(void* dst, size_t bytes, uint32_t value, void* stream);
 dppo_status_t dppo_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus

@@ -15,7 +15,8 @@ BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
 FLAG_FORCE_STREAMING = 1
 WORKSPACE_BYTES = 65536
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo.so")
+# DPPO_LIB overrides the library path (e.g. a build with other compile-time settings).
+_LIB_PATH = os.environ.get("DPPO_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo.so")
 _lib = None
 
 
@@ -59,6 +60,8 @@ def lib() -> C.CDLL:
         l.dppo_args_size.restype = C.c_size_t
         l.dppo_probe_copy.restype = C.c_int
         l.dppo_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.dppo_probe_fill.restype = C.c_int
+        l.dppo_probe_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         l.dppo_probe_read.restype = C.c_int
         l.dppo_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         if l.dppo_args_size() != C.sizeof(DppoArgs):
@@ -129,6 +132,13 @@ def probe_copy(dst, src, stream=None) -> None:
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     st = lib().dppo_probe_copy(dst.data_ptr(), src.data_ptr(), n, C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def probe_fill(dst, value: int = 0, stream=None) -> None:
+    """dppo_probe_fill: write-only pass over dst."""
+    st = lib().dppo_probe_fill(dst.data_ptr(), dst.numel() * dst.element_size(), value, C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
 

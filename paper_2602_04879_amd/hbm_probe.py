@@ -6,7 +6,7 @@ kernel over buffers of known size.
 Under `rocprofv3 --pmc FETCH_SIZE` (then `--pmc WRITE_SIZE`) the copy kernel's counter per
 dispatch, divided into the bytes it is known to move (`--gib` GiB read, `--gib` GiB written),
 gives the factor that turns the same counter of a loss kernel into HBM bytes.  Run plainly it
-prints the copy and read bandwidths (HIP events on the launch stream)."""
+prints the copy, read-only and write-only bandwidths (HIP events on the launch stream)."""
 import argparse
 import json
 
@@ -26,7 +26,8 @@ def main():
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     s = torch.cuda.current_stream()
     out = {"bytes": n, "iters": a.iters}
-    for name, fn in (("copy", lambda: B.probe_copy(dst, src, s)), ("read", lambda: B.probe_read(src, sink, s))):
+    for name, fn in (("copy", lambda: B.probe_copy(dst, src, s)), ("read", lambda: B.probe_read(src, sink, s)),
+                     ("fill", lambda: B.probe_fill(dst, 0x3c003c00, s))):
         for _ in range(2):
             fn()
         torch.cuda.synchronize()
@@ -40,7 +41,8 @@ def main():
         moved = 2 * n if name == "copy" else n
         out[name + "_ms"] = ms
         out[name + "_GBs"] = moved / (ms * 1e-3) / 1e9
-    assert torch.equal(src, dst)
+        if name == "copy":
+            assert torch.equal(src, dst)
     print(json.dumps(out), flush=True)
 
 
