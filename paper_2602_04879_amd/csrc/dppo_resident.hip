@@ -113,14 +113,15 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         tk = load_topk_lane(p, row, a, zrow, lane);
       }
       // ---- phases A+B, online over groups of GC chunks ------------------------------------
-      // Per thread: s = sum 2^(z*log2e + b) with an integer offset b <= -max(z, 0)*log2e that
-      // only ever decreases; lowering it rescales s by an exact power of two.  The maximum is
-      // taken on the packed bf16 patterns: as signed 16-bit integers the non-negative ones
-      // order like floats and the negative ones stay below them, so max(pattern, 0) is
-      // max(z, 0) exactly.  The first groups were loaded first, so their arithmetic hides the
-      // latency of the chunks requested last.
-      s16x2 mx = as_s16x2(0u);
-      float b = 0.f;
+      // Per thread: s = sum 2^(z*log2e + b) with an integer offset b <= -max(z)*log2e that only
+      // ever decreases; lowering it rescales s by an exact power of two.  The maximum is taken
+      // on the PACKED bf16 patterns, as signed 16-bit integers: non-negative patterns order like
+      // the floats and every negative one stays below them, so the integer maximum is the float
+      // maximum whenever it is >= 0; if every entry so far is negative, the float maximum is
+      // the negative of smallest magnitude, which is the integer MINIMUM.  The first groups
+      // were loaded first, so their arithmetic hides the latency of the chunks requested last.
+      s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
+      float b = 3.0e38f;                       // "+infinity": nothing seen yet
       float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
       for (int g0 = 0; g0 < NCHUNK; g0 += GC) {
@@ -147,9 +148,15 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
           mx = __builtin_elementwise_max(mx, as_s16x2(v[i].y));
           mx = __builtin_elementwise_max(mx, as_s16x2(v[i].z));
           mx = __builtin_elementwise_max(mx, as_s16x2(v[i].w));
+          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].x));
+          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].y));
+          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].z));
+          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].w));
         }
-        const int m16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
-        const float bn = -ceilf(__uint_as_float(static_cast<uint32_t>(m16) << 16) * kLog2e);
+        const int hi16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
+        const int lo16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
+        const float zmax = __uint_as_float(static_cast<uint32_t>(hi16 >= 0 ? hi16 : lo16) << 16);
+        const float bn = -ceilf(fmaxf(zmax, kNegBig) * kLog2e);
         const float sc = fast_exp2(bn - b);       // 1 when the maximum did not move
         s0 *= sc; s1 *= sc; s2 *= sc; s3 *= sc;
         b = bn;
@@ -170,7 +177,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // ---- epilogue on wave 0 -----------------------------------------------------------
       if (wid == 0) {
         // the offset must also cover z[a_t], whose own term the epilogue adds
-        float bb = -ceilf(fmaxf(rs.za, 0.f) * kLog2e);
+        float bb = -ceilf(fmaxf(rs.za, kNegBig) * kLog2e);
 #pragma unroll
         for (int w = 0; w < NW; ++w) bb = fminf(bb, sh_b[w]);
         double S_rest = 0.0;

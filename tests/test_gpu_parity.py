@@ -67,6 +67,64 @@ def test_qwen3_vocab_small_t(name):
     _run_and_compare(w, shift=2.0, flags=B.FLAG_FORCE_STREAMING)
 
 
+# --------------------------------------------------------------------------- resident-kernel shapes
+@pytest.mark.parametrize("V,ld,expect", [
+    (8192, 8192, "resident"),          # smallest resident row: 256 threads x 4 chunks, exactly full
+    (8200, 8200, "resident"),          # one vector into the next shape (256 x 8), 3 chunks of slack
+    (12296, 12304, "resident"),        # pitch > V (still a multiple of 8)
+    (40960, 40960, "resident"),        # 256 x 20 exactly full
+    (40968, 40968, "resident"),        # first 512-thread shape (512 x 12)
+    (100000, 100000, "resident"),      # 512 x 28, ragged last chunk
+    (128256, 128256, "resident"),      # a Llama-3 sized vocabulary: 512 x 32
+    (155648, 155648, "resident"),      # largest resident row: 512 x 38 exactly full
+    (155656, 155656, "streaming"),     # one vector more: falls back to the two-pass kernel
+    (40004, 40004, "streaming"),       # V not a multiple of 8
+    (16384, 16388, "streaming"),       # pitch not a multiple of 8: rows not 16-byte aligned
+])
+@pytest.mark.parametrize("variant,K", [(W.BINARY_KL, 0), (W.TOPK_KL, 20)])
+def test_resident_shapes_and_fallback(V, ld, expect, variant, K):
+    w = W.Workload("shape", 3, 4, V, variant, 0.05, K=K, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=31)
+    b, res, st = _run_and_compare(w, ld=ld, shift=2.0)
+    assert B.last_path() == expect
+
+
+def test_resident_more_rows_than_workgroups_in_place_with_special_rows():
+    """Several rows per persistent workgroup (T > 256 compute units), gradient in place, with ignored
+    rows, zero-advantage rows and masked rows scattered among them."""
+    w = W.Workload("persist", 3, 250, 16384, W.TOPK_TV, 0.1, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=37)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    b["sampled_ids"][::11] = -1
+    b["advantages"][5::13] = 0.0
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, in_place=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    st = P.compare_rows(b, res, rows, ref=ref)
+    assert st["masked"] > 50
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    _say(f"       {st}")
+
+
+def test_resident_saturated_rows():
+    """pi(a_t) -> 1 on the register-resident path: 1 - pi(a_t) must keep its relative accuracy."""
+    w = W.Workload("sat_res", 2, 8, 16384, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=41)
+    b = W.make_batch(w, DEV)
+    a = b["sampled_ids"].long()
+    rows = torch.arange(b["T"], device=DEV)
+    b["logits"][rows[:6], a[:6]] = torch.tensor([20.0, 30.0, 40.0, 50.0, 60.0, 80.0], device=DEV).bfloat16()
+    b["logits"][6:10, 1000:9000] = float("-inf")
+    b["logits"][10, :] = -1.0e4                    # every logit negative and far from 0
+    b["logits"][11, :] = -50.0
+    b["logits"][12, :] = 3.0e4
+    res = B.run_batch(b)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["grad_logits"].float()).all()
+    st = P.compare_rows(b, res, np.arange(b["T"]))
+    _say(f"       {st}")
+
+
 # --------------------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("V,ld", [(1, 1), (1, 8), (2, 2), (7, 7), (8, 8), (9, 11), (63, 63), (1001, 1001),
                                   (1000, 1003), (4097, 4100), (32768 + 5, 32768 + 8)])
