@@ -86,14 +86,14 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
     // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
     int r_threads = 0, r_chunks = 0;
-    const bool resident = grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0 &&
+    const bool resident = !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);
     if (resident) {
-      int64_t grid = static_cast<int64_t>(cus) * dppo::resident_blocks_per_cu(r_threads, r_chunks);
+      int64_t grid = static_cast<int64_t>(cus) * dppo::resident_blocks_per_cu(grad, r_threads, r_chunks);
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
-      if (dppo::launch_resident(p, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      if (dppo::launch_resident(p, grad, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident";
     } else {
       // 16-byte vectors need logits and grad rows to share their misalignment.

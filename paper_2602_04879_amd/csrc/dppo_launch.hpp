@@ -9,13 +9,13 @@ namespace dppo {
 // and grad_logits rows do not share their 16-byte misalignment).
 hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, int grid, hipStream_t s);
 
-// Register-resident fused forward+backward kernel.  A shape is (threads per workgroup, 16-byte
+// Register-resident kernel (fused forward+backward, or forward only).  A shape is (threads per workgroup, 16-byte
 // chunks per thread); resident_shape() picks the smallest instantiated one that covers a row of
 // V entries (false: none does, or V is not a multiple of 8).  Needs 16-byte aligned rows of
 // logits and grad.  resident_blocks_per_cu() is the occupancy the runtime reports for a shape.
 bool resident_shape(int64_t V, int* threads, int* chunks);
-hipError_t launch_resident(const KParams& p, int threads, int chunks, int grid, hipStream_t s);
-int resident_blocks_per_cu(int threads, int chunks);
+hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s);
+int resident_blocks_per_cu(bool grad, int threads, int chunks);
 
 // loss[0] = loss_scale * sum(partial[0..n)) in a fixed order.
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s);

@@ -55,7 +55,8 @@ constexpr int kChunkStep = 4;
 // All row traffic goes through range-checked buffer resources, so the phases are straight-line
 // code with a fixed sequence of memory instructions: loads past the row return 0 (turned into
 // -inf where the row statistics consume them) and stores past it are dropped.
-template <int THREADS, int NCHUNK>
+// GRAD = false is the forward-only form: phase C only refills (no gradient, no stores).
+template <int THREADS, int NCHUNK, bool GRAD>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
@@ -84,13 +85,28 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 #pragma unroll
     for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zr, voff, i * kStride);
   }
-  int a_next = p.sampled[row];                   // fetched one row ahead
+  // Fetched one row ahead, so that neither the row loop nor wave 0's gathers ever wait on a load
+  // that queues behind the row's own refills: the sampled id, and (wave 0, lane k < K) the id
+  // and log-prob of top-K entry k.
+  int a_next = p.sampled[row];
+  int tkid_next = -1;
+  float tklp_next = 0.f;
+  if (wid == 0 && lane < p.K) {
+    tkid_next = p.tk_ids[static_cast<int64_t>(row) * p.K + lane];
+    tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
+  }
 
   for (; row < p.T; row += gridDim.x) {
     const int a = uniform_i(a_next);
     const int next = row + gridDim.x;
     const bool more = next < p.T;
     if (more) a_next = p.sampled[next];
+    const int tkid = tkid_next;
+    const float tklp = tklp_next;
+    if (more && wid == 0 && lane < p.K) {
+      tkid_next = p.tk_ids[static_cast<int64_t>(next) * p.K + lane];
+      tklp_next = p.tk_lp[static_cast<int64_t>(next) * p.K + lane];
+    }
     const bool live = (a >= 0 && a < p.V);
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
     const int avec = a >> 3;
@@ -110,7 +126,11 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         rs.za = bf16_bits_to_float(zrow[a]);
         rs.lmu = p.mu_logp[row];
         rs.adv = p.adv[row];
-        tk = load_topk_lane(p, row, a, zrow, lane);
+        if (tkid >= 0 && tkid < p.V && tkid != a) {
+          tk.id = tkid;
+          tk.lp = tklp;
+          tk.z = bf16_bits_to_float(zrow[tkid]);
+        }
       }
       // ---- phases A+B, online over groups of GC chunks ------------------------------------
       // Per thread: s = sum 2^(z*log2e + b) with an integer offset b <= -max(z)*log2e that only
@@ -186,12 +206,14 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         const RowResult rr = row_epilogue(ep, row, rs, tk, zrow, bb, S_rest, lane);
         rc = rr.rc;
         loss_acc += rr.loss_term;
-        if (lane == 0) sh_rc = rc;
+        if (GRAD && lane == 0) sh_rc = rc;
       }
-      __syncthreads();
-      rc.coef = uniform_f(sh_rc.coef);
-      rc.kexp = uniform_f(sh_rc.kexp);
-      rc.g_a = uniform_f(sh_rc.g_a);
+      if (GRAD) {
+        __syncthreads();
+        rc.coef = uniform_f(sh_rc.coef);
+        rc.kexp = uniform_f(sh_rc.kexp);
+        rc.g_a = uniform_f(sh_rc.g_a);
+      }
     } else if (tid == 0) {
       p.divergence[row] = 0.f;
       p.mask[row] = 0;
@@ -202,29 +224,34 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     // Every chunk: store its gradient, then refill it with the same chunk of the workgroup's
     // next row, in the order the next row's arithmetic will consume them.  Without a next row
     // the refill goes through a resource of zero bytes: its loads touch no memory.
-    char* gr = grad + row * pitch;
-    const row_desc_t gout = make_row_desc(gr, row_bytes);
     const row_rsrc_t zn = make_row_rsrc(logits + (more ? next : row) * pitch, more ? row_bytes : 0u);
-    const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
-    if (rc.coef == 0.f) {
-      // Masked, zero-advantage or ignored row: its gradient is exactly zero whatever the logits
-      // hold.  Overwrite the resident copy with -inf so that the loop below writes 2^-inf = 0.
+    if (GRAD) {
+      char* gr = grad + row * pitch;
+      const row_desc_t gout = make_row_desc(gr, row_bytes);
+      const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
+      if (rc.coef == 0.f) {
+        // Masked, zero-advantage or ignored row: its gradient is exactly zero whatever the logits
+        // hold.  Overwrite the resident copy with -inf so that the loop below writes 2^-inf = 0.
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) buf[i] = neg_inf;
-    }
+        for (int i = 0; i < NCHUNK; ++i) buf[i] = neg_inf;
+      }
 #pragma unroll
-    for (int i = 0; i < NCHUNK; ++i) {
-      row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
-      buf[i] = row_load16(zn, voff, i * kStride);
-      // Keep the instruction scheduler from hoisting the refills above the stores they follow:
-      // a refill can only reuse its chunk's registers once the chunk has been consumed.
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (rc.coef != 0.f && owner) {
-      // The resident copy held -inf at a_t, so the vector store above wrote 0 there.  Once
-      // that store has completed, the owning thread writes the sampled token's entry.
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      reinterpret_cast<uint16_t*>(gr)[a] = float_to_bf16_bits(rc.g_a);
+      for (int i = 0; i < NCHUNK; ++i) {
+        row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
+        buf[i] = row_load16(zn, voff, i * kStride);
+        // Keep the instruction scheduler from hoisting the refills above the stores they follow:
+        // a refill can only reuse its chunk's registers once the chunk has been consumed.
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (rc.coef != 0.f && owner) {
+        // The resident copy held -inf at a_t, so the vector store above wrote 0 there.  Once
+        // that store has completed, the owning thread writes the sampled token's entry.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        reinterpret_cast<uint16_t*>(gr)[a] = float_to_bf16_bits(rc.g_a);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zn, voff, i * kStride);
     }
   }
   if (tid == 0) p.partial[blockIdx.x] = loss_acc;
@@ -232,14 +259,16 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 
 // One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
 template <int THREADS, int NCHUNK>
-hipError_t launch_shape(const KParams& p, int grid, hipStream_t s) {
-  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK>), dim3(grid), dim3(THREADS), 0, s, p);
+hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
+  if (grad) hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true>), dim3(grid), dim3(THREADS), 0, s, p);
+  else      hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false>), dim3(grid), dim3(THREADS), 0, s, p);
   return hipGetLastError();
 }
 template <int THREADS, int NCHUNK>
-int occupancy_shape() {
+int occupancy_shape(bool grad) {
   int n = 0;
-  const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK>, THREADS, 0);
+  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true>, THREADS, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 
@@ -258,15 +287,15 @@ bool resident_shape(int64_t V, int* threads, int* chunks) {
   return false;
 }
 
-hipError_t launch_resident(const KParams& p, int threads, int chunks, int grid, hipStream_t s) {
-#define DPPO_LAUNCH(T, C) if (threads == T && chunks == C) return launch_shape<T, C>(p, grid, s);
+hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s) {
+#define DPPO_LAUNCH(T, C) if (threads == T && chunks == C) return launch_shape<T, C>(p, grad, grid, s);
   DPPO_SHAPES(DPPO_LAUNCH)
 #undef DPPO_LAUNCH
   return hipErrorInvalidValue;
 }
 
-int resident_blocks_per_cu(int threads, int chunks) {
-#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>();
+int resident_blocks_per_cu(bool grad, int threads, int chunks) {
+#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>(grad);
   DPPO_SHAPES(DPPO_OCC)
 #undef DPPO_OCC
   return 1;

@@ -254,19 +254,29 @@ def test_forward_only_matches_forward_backward_and_runs_are_bitwise_reproducible
     r1 = B.run_batch(b)
     path1 = B.last_path()
     r2 = B.run_batch(b)
-    rs = B.run_batch(b, flags=B.FLAG_FORCE_STREAMING)
     rf = B.run_batch(b, backward=False)
+    pathf = B.last_path()
+    rs = B.run_batch(b, flags=B.FLAG_FORCE_STREAMING)
+    rsf = B.run_batch(b, backward=False, flags=B.FLAG_FORCE_STREAMING)
     torch.cuda.synchronize()
-    assert path1 == "resident" and B.last_path() == "streaming"
+    assert path1 == "resident" and pathf == "resident" and B.last_path() == "streaming"
     for k in ("loss", "loss_tok", "divergence", "mask"):
         assert torch.equal(r1[k], r2[k]), k                 # same path twice: bit for bit
-        assert torch.equal(rs[k], rf[k]), k                 # forward-only == forward of fwd+bwd (same kernel)
+        assert torch.equal(r1[k], rf[k]), k                 # forward-only == forward of fwd+bwd (same statistics code)
+        assert torch.equal(rs[k], rsf[k]), k                # ... on the two-pass kernel too
     assert torch.equal(r1["grad_logits"], r2["grad_logits"])
     # the two kernel paths differ only by summation order
     assert torch.equal(r1["mask"], rs["mask"])
     torch.testing.assert_close(r1["divergence"], rs["divergence"], rtol=1e-4, atol=1e-6)
     torch.testing.assert_close(r1["loss_tok"], rs["loss_tok"], rtol=1e-4, atol=1e-6)
     torch.testing.assert_close(r1["grad_logits"].float(), rs["grad_logits"].float(), rtol=2 ** -7, atol=1e-30)
+
+
+@pytest.mark.parametrize("name", ["c2_binary_kl", "c5_long_topk_kl"])
+def test_forward_only_against_oracle(name):
+    w = W.scaled(W.WORKLOADS[name], n_seq=2, seq_len=40, group=2)
+    _run_and_compare(w, backward=False, shift=2.0)
+    _run_and_compare(w, backward=False, shift=2.0, flags=B.FLAG_FORCE_STREAMING)
 
 
 def test_other_stream_and_loss_tok_optional():
