@@ -1,0 +1,82 @@
+"""The pins must notice a plausible mistake anywhere in the oracle.  Each case plants ONE mistake
+in a copy of oracle/dppo_oracle.py (on the CPU; the GPU path is not involved) and checks that
+at least one pin of tests/test_oracle_pins.py then fails."""
+import importlib.util
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = open(os.path.join(ROOT, "oracle", "dppo_oracle.py")).read()
+
+MUTATIONS = [
+    ("softmax: max not subtracted inside exp", "S = np.exp(z - m).sum()", "S = np.exp(z).sum()"),
+    ("ratio inverted", "r = np.exp(lpi - lmu)", "r = np.exp(lmu - lpi)"),
+    ("binary TV signed", "return abs(p - q)", "return p - q"),
+    ("binary KL: second term dropped", "return _xlogx_over_y(p, q) + _xlogx_over_y(one_minus_p, one_minus_q)",
+     "return _xlogx_over_y(p, q)"),
+    ("binary KL: direction swapped", "return _xlogx_over_y(p, q) + _xlogx_over_y(one_minus_p, one_minus_q)",
+     "return _xlogx_over_y(q, p) + _xlogx_over_y(one_minus_q, one_minus_p)"),
+    ("top-K TV: half missing", "return 0.5 * (np.abs(p - q).sum() + abs(p_other - q_other))",
+     "return np.abs(p - q).sum() + abs(p_other - q_other)"),
+    ("top-K TV: other bucket dropped", "return 0.5 * (np.abs(p - q).sum() + abs(p_other - q_other))",
+     "return 0.5 * np.abs(p - q).sum()"),
+    ("top-K KL: other bucket dropped", "return d + _xlogx_over_y(p_other, q_other)", "return d"),
+    ("top-K: sampled token not de-duplicated", "if i < 0 or i >= len(logpi) or i == int(a):", "if i < 0 or i >= len(logpi):"),
+    ("top-K: pi gathered at wrong ids", "q = np.exp(logpi[np.asarray(ids, dtype=np.int64)])",
+     "q = np.exp(logpi[np.asarray(ids, dtype=np.int64)[::-1]])"),
+    ("mask: non-strict threshold", "if D > delta and", "if D >= delta and"),
+    ("mask: wrong side for negative advantage", "(adv < 0.0 and lpi_a < lmu_a)", "(adv < 0.0 and lpi_a > lmu_a)"),
+    ("mask: symmetric (blocks moves toward r = 1 too)", "if D > delta and ((adv > 0.0 and lpi_a > lmu_a) or (adv < 0.0 and lpi_a < lmu_a)):",
+     "if D > delta and adv != 0.0:"),
+    ("loss sign", 'out["loss_tok"][t] = -M * r * A', 'out["loss_tok"][t] = M * r * A'),
+    ("loss ignores mask", 'out["loss_tok"][t] = -M * r * A', 'out["loss_tok"][t] = -r * A'),
+    ("grad: one-hot not subtracted", "g[a] -= 1.0", "g[a] -= 0.0"),
+    ("grad: ratio missing", "(loss_scale * M * A * r) * g", "(loss_scale * M * A) * g"),
+    ("grad: sign", "(loss_scale * M * A * r) * g", "(-loss_scale * M * A * r) * g"),
+    ("full TV: half missing", "return 0.5 * np.abs(mu_probs - pi_probs).sum()", "return np.abs(mu_probs - pi_probs).sum()"),
+    ("binary KL uses clamped-away 1-q", "one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()", "one_minus_q = pi_row[:a].sum()"),
+]
+
+
+def _count_failing_pins(source, tmp_path, monkeypatch):
+    mutated = tmp_path / "dppo_oracle_mutated.py"
+    mutated.write_text(source)
+    spec = importlib.util.spec_from_file_location("dppo_oracle_mutated", str(mutated))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+
+    from tests import test_oracle_pins as pins
+    monkeypatch.setattr(pins, "O", mod)
+    golden = os.path.join(ROOT, "tests", "golden")
+    failures = 0
+    for attr in dir(pins):
+        fn = getattr(pins, attr)
+        if not (attr.startswith("test_") and callable(fn)):
+            continue
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        argsets = [()]
+        if marks:
+            names = [n.strip() for n in marks[0].args[0].split(",")]
+            argsets = [a if isinstance(a, tuple) and len(names) > 1 else (a,) for a in marks[0].args[1]]
+        for args in argsets:
+            kwargs = {}
+            code = fn.__code__
+            if "golden_dir" in code.co_varnames[:code.co_argcount]:
+                kwargs["golden_dir"] = golden
+            try:
+                fn(*args, **kwargs)
+            except Exception:      # any failing pin (assertion or crash) notices the mistake
+                failures += 1
+    return failures
+
+
+def test_the_unmodified_oracle_passes_every_pin_under_this_harness(tmp_path, monkeypatch):
+    assert _count_failing_pins(SRC, tmp_path, monkeypatch) == 0
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_a_planted_mistake_fails_some_pin(name, old, new, tmp_path, monkeypatch):
+    assert SRC.count(old) == 1, f"mutation target not unique/present: {old!r}"
+    assert _count_failing_pins(SRC.replace(old, new), tmp_path, monkeypatch) > 0, f"no pin noticed: {name}"
