@@ -19,7 +19,7 @@ order and notation of the paper:
   * gradient wrt the logits, mask held constant   (Eq. unified_grad with C = infinity)
   * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL)
 
-Readings taken where the paper is silent (each is listed in the design notes):
+Readings taken where the paper is silent:
   - the library returns the quantity to MINIMISE: loss = -loss_scale * sum_t M_t r_t A_t;
     loss_scale is the caller's normalisation (the paper writes an expectation of a sum);
   - KL is D(mu || pi) in nats;
@@ -32,9 +32,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
   - a row whose sampled id is outside [0, V) is ignored: D = 0, M = 0, loss term 0, zero
     gradient row.
 
-All pins for these functions live in tests/test_oracle_*.py; none is "parity unpinned"
-except the two parameterised-away choices named in the design notes (loss normalisation,
-finite ratio cap C).
+All pins for these functions live in tests/test_oracle_*.py.  "parity unpinned": the loss
+normalisation (the paper fixes no minibatch formula; it is the caller's loss_scale) and a finite
+ratio cap C (not implemented; C = infinity as in Eq. dppo_obj).
 """
 from __future__ import annotations
 

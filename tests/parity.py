@@ -1,6 +1,6 @@
 """Element-by-element comparison of the HIP path with the float64 oracle.
 
-Tolerances (see the design notes for the derivation):
+Tolerances (the absolute terms are what fp32 accumulation of V terms leaves on a probability):
   divergence : |gpu - ref| <= 1e-4 |ref| + 1e-6
   loss_tok   : |gpu - ref| <= 1e-4 |ref| + 1e-6 |A|   (compared under the GPU's own mask for
                tokens inside the exemption band)
