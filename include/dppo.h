@@ -40,6 +40,18 @@ extern "C" {
 #define DPPO_KMAX 1024            /* largest accepted K                                        */
 #define DPPO_WORKSPACE_BYTES 65536
 
+/* Columns of the optional per-token diagnostics output [T, DPPO_NDIAG] (fp32): the health
+ * metrics the paper monitors during training (App. F.1: mean |pi - mu| of the sampled token,
+ * policy entropy) and the mass the top-K set covers (App. B.1), plus the ratio itself. */
+#define DPPO_NDIAG 8
+#define DPPO_DIAG_RATIO     0     /* r_t = pi(a_t) / mu(a_t)                                    */
+#define DPPO_DIAG_LOGP      1     /* log pi(a_t|s_t)                                            */
+#define DPPO_DIAG_ABS_DIFF  2     /* |pi(a_t) - mu(a_t)|                                        */
+#define DPPO_DIAG_ENTROPY   3     /* -sum_j pi_j ln pi_j, nats                                  */
+#define DPPO_DIAG_MASS_MU   4     /* mass mu puts on A' = TopK(mu,K) U {a_t} ({a_t} if Binary)  */
+#define DPPO_DIAG_MASS_PI   5     /* mass pi puts on A'                                         */
+                                  /* columns 6, 7: reserved, written as 0                      */
+
 /* Which approximation of D(mu || pi) gates the update (Sec. 4.4).  KL is in nats. */
 typedef enum {
   DPPO_BINARY_TV = 0,             /* |mu(a_t) - pi(a_t)|                       (Eq. binary_tv) */
@@ -52,7 +64,8 @@ typedef enum {
   DPPO_OK = 0,
   DPPO_ERR_NULL = 1,              /* a required pointer is NULL                                */
   DPPO_ERR_SHAPE = 2,             /* T < 0, V < 1, ld < V, or sizes beyond int32 row indexing  */
-  DPPO_ERR_ALIGN = 3,             /* logits / grad_logits not 2-byte aligned, workspace not 8  */
+  DPPO_ERR_ALIGN = 3,             /* logits / grad_logits not 2-byte aligned, workspace not 8, */
+                                  /* diagnostics not 16                                        */
   DPPO_ERR_VARIANT = 4,           /* variant is not a dppo_variant_t                           */
   DPPO_ERR_K = 5,                 /* K < 0, K > DPPO_KMAX, or K > 0 without top-K pointers     */
   DPPO_ERR_WORKSPACE = 6,         /* workspace NULL or smaller than dppo_workspace_bytes()     */
@@ -93,6 +106,8 @@ typedef struct {
   void*          grad_logits;  /* bf16 [T, ld] (columns >= V untouched), round-to-nearest-even;*/
                                /* dppo_loss_fwd_bwd only; may be the same buffer as logits     */
                                /* (in place) but must not overlap it otherwise                 */
+  float*         diagnostics;  /* [T, DPPO_NDIAG] per-token diagnostics (DPPO_DIAG_*), 16-byte  */
+                               /* aligned; may be NULL.  Ignored rows get zeros               */
   /* ---- scratch ---- */
   void*          workspace;    /* >= dppo_workspace_bytes(T, V, K) bytes, 8-byte aligned;      */
                                /* contents on entry are irrelevant, calls that overlap in time */

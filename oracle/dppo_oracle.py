@@ -18,6 +18,9 @@ order and notation of the paper:
   * DPPO mask and masked surrogate                (Eq. dppo_obj)
   * gradient wrt the logits, mask held constant   (Eq. unified_grad with C = infinity)
   * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL)
+  * per-token health metrics the paper monitors   (App. F.1: |pi - mu| of the sampled token,
+    (diagnostics)                                   policy entropy; App. B.1: mass covered by
+                                                    the top-K set)
 
 Readings taken where the paper is silent:
   - the library returns the quantity to MINIMISE: loss = -loss_scale * sum_t M_t r_t A_t;
@@ -136,6 +139,14 @@ def full_kl(mu_probs, pi_probs):
     return d
 
 
+def entropy(logpi):
+    """Token entropy -sum_j pi_j ln pi_j in nats, 0 ln 0 = 0  (the "policy entropy" of App. F.1)."""
+    logpi = np.asarray(logpi, dtype=np.float64)
+    pi = np.exp(logpi)
+    nz = pi > 0.0
+    return float(-(pi[nz] * logpi[nz]).sum())
+
+
 # --------------------------------------------------------------------------- mask
 def dppo_mask(D, delta, adv, lpi_a, lmu_a):
     """M_t of Eq. dppo_obj: 0 iff D > delta and the update moves r further from 1 in the
@@ -153,7 +164,9 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
     mu_logp [T], advantages [T], optional mu_topk_ids / mu_topk_logp [T, K].
     Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
-    ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None.
+    ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None, and the
+    diagnostics abs_diff [T] = |pi(a_t) - mu(a_t)|, entropy [T], mass_mu [T], mass_pi [T]
+    (probability mu resp. pi puts on A' = TopK(mu, K) U {a_t}; A' = {a_t} for the Binary variants).
     """
     logits = np.asarray(logits, dtype=np.float64)
     T, V = logits.shape
@@ -167,6 +180,7 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     out = {
         "loss_tok": np.zeros(T), "divergence": np.zeros(T), "mask": np.zeros(T, dtype=np.uint8),
         "ratio": np.zeros(T), "logp": np.zeros(T), "lse": np.zeros(T),
+        "abs_diff": np.zeros(T), "entropy": np.zeros(T), "mass_mu": np.zeros(T), "mass_pi": np.zeros(T),
         "grad_logits": np.zeros((T, V)) if want_grad else None,
     }
     for t in range(T):
@@ -178,6 +192,7 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         lpi = logpi[a]
         lmu = float(mu_logp[t])
         r = np.exp(lpi - lmu)                        # step 2
+        mass_mu, mass_pi = np.exp(min(lmu, 0.0)), np.exp(lpi)
         if variant == BINARY_TV:                     # step 3
             D = binary_tv(lmu, lpi)
         elif variant == BINARY_KL:
@@ -189,6 +204,7 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
             lps = mu_topk_logp[t] if (mu_topk_logp is not None) else None
             p, q, po, qo = reduced_distributions(logpi, a, lmu, ids, lps)
             D = topk_tv(p, q, po, qo) if variant == TOPK_TV else topk_kl(p, q, po, qo)
+            mass_mu, mass_pi = p.sum(), q.sum()
         A = float(advantages[t])
         M = dppo_mask(D, delta, A, lpi, lmu)         # step 4
         out["divergence"][t] = D
@@ -196,6 +212,10 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         out["ratio"][t] = r
         out["logp"][t] = lpi
         out["lse"][t] = z[a] - lpi
+        out["abs_diff"][t] = binary_tv(lmu, lpi)
+        out["entropy"][t] = entropy(logpi)
+        out["mass_mu"][t] = mass_mu
+        out["mass_pi"][t] = mass_pi
         out["loss_tok"][t] = -M * r * A              # step 5
         if want_grad:                                # step 6
             g = np.exp(logpi)

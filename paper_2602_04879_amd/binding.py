@@ -12,6 +12,8 @@ import os
 import torch
 
 BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+NDIAG = 8
+DIAG_RATIO, DIAG_LOGP, DIAG_ABS_DIFF, DIAG_ENTROPY, DIAG_MASS_MU, DIAG_MASS_PI = 0, 1, 2, 3, 4, 5
 FLAG_FORCE_STREAMING = 1
 WORKSPACE_BYTES = 65536
 
@@ -29,7 +31,7 @@ class DppoArgs(C.Structure):
         ("K", C.c_int32), ("variant", C.c_int32),
         ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
         ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
-        ("mask", C.c_void_p), ("grad_logits", C.c_void_p),
+        ("mask", C.c_void_p), ("grad_logits", C.c_void_p), ("diagnostics", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("flags", C.c_uint32),
     ]
 
@@ -93,13 +95,15 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
     a.grad_logits = _ptr(grad_logits)
+    a.diagnostics = _ptr(out.get("diagnostics"))
     a.workspace, a.workspace_bytes = _ptr(out["workspace"]), out["workspace"].numel()
     a.flags = flags
     return a
 
 
-def alloc_outputs(T: int, device, want_loss_tok: bool = True) -> dict:
+def alloc_outputs(T: int, device, want_loss_tok: bool = True, want_diagnostics: bool = False) -> dict:
     return {
+        "diagnostics": torch.empty((T, NDIAG), dtype=torch.float32, device=device) if want_diagnostics else None,
         "loss": torch.empty(1, dtype=torch.float32, device=device),
         "loss_tok": torch.empty(T, dtype=torch.float32, device=device) if want_loss_tok else None,
         "divergence": torch.empty(T, dtype=torch.float32, device=device),
@@ -156,7 +160,7 @@ def last_path() -> str:
 
 
 def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags: int = 0, out=None,
-              grad=None, stream=None, rows=None) -> dict:
+              grad=None, stream=None, rows=None, diagnostics: bool = False) -> dict:
     """Convenience for tests and benchmarks: run one workload batch (see workloads.make_batch),
     optionally restricted to rows [r0, r1).  Returns the output tensors (device)."""
     r0, r1 = (0, batch["T"]) if rows is None else rows
@@ -164,7 +168,7 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     logits = batch["logits"][sl]
     T = r1 - r0
     if out is None:
-        out = alloc_outputs(T, logits.device)
+        out = alloc_outputs(T, logits.device, want_diagnostics=diagnostics)
     if backward and grad is None:
         grad = logits if in_place else torch.empty_like(logits)
     tk_i = batch["mu_topk_ids"][sl] if batch["mu_topk_ids"] is not None else None

@@ -45,6 +45,7 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
     if (grad && !a->grad_logits) return DPPO_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(a->logits) & 1u) return DPPO_ERR_ALIGN;
     if (grad && (reinterpret_cast<uintptr_t>(a->grad_logits) & 1u)) return DPPO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(a->diagnostics) & 15u) return DPPO_ERR_ALIGN;
   }
   return DPPO_OK;
 }
@@ -75,6 +76,7 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     p.loss_tok = a->loss_tok;
     p.divergence = a->divergence;
     p.mask = a->mask;
+    p.diag = a->diagnostics;
     p.partial = partial;
     p.ld = a->ld;
     p.T = static_cast<int32_t>(a->T);
@@ -129,7 +131,7 @@ const char* dppo_status_str(dppo_status_t status) {
     case DPPO_OK: return "ok";
     case DPPO_ERR_NULL: return "a required pointer is NULL";
     case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld, T and V below 2^31";
-    case DPPO_ERR_ALIGN: return "misaligned pointer: bf16 buffers need 2-byte, workspace 8-byte alignment";
+    case DPPO_ERR_ALIGN: return "misaligned pointer: bf16 buffers need 2-byte, workspace 8-byte, diagnostics 16-byte alignment";
     case DPPO_ERR_VARIANT: return "variant is not one of DPPO_BINARY_TV/KL, DPPO_TOPK_TV/KL";
     case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
     case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes()";

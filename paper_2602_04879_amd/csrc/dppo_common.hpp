@@ -23,6 +23,7 @@ struct KParams {
   float* loss_tok;          // [T] or nullptr
   float* divergence;        // [T]
   uint8_t* mask;            // [T]
+  float* diag;              // [T, 8] or nullptr
   double* partial;          // [gridDim.x] per-workgroup loss partial sums (workspace)
   int64_t ld;
   int32_t T, V, K, variant;
@@ -38,12 +39,13 @@ struct EpiParams {
   float* loss_tok;
   float* divergence;
   uint8_t* mask;
+  float* diag;
   int32_t V, K, variant;
   float delta, loss_scale;
 };
 __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   EpiParams e;
-  e.tk_ids = p.tk_ids; e.tk_lp = p.tk_lp; e.loss_tok = p.loss_tok; e.divergence = p.divergence; e.mask = p.mask;
+  e.tk_ids = p.tk_ids; e.tk_lp = p.tk_lp; e.loss_tok = p.loss_tok; e.divergence = p.divergence; e.mask = p.mask; e.diag = p.diag;
   e.V = p.V; e.K = p.K; e.variant = p.variant; e.delta = p.delta; e.loss_scale = p.loss_scale;
   return e;
 }
@@ -139,6 +141,9 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float x) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// t + e * x for e = 2^x, safe for x = -inf (where e = 0): the exponent is clamped first, and
+// below the clamp e has long flushed to zero, so the product is unchanged.
+__device__ __forceinline__ float fma_ex(float e, float x, float t) { return fmaf(e, fmaxf(x, -256.f), t); }
 
 // Wave-wide reductions on the data-parallel-primitive path (no LDS crossbar): a butterfly inside
 // each row of 16 lanes (quad permutes, then half-row and row mirrors), then the four row results
@@ -248,6 +253,8 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
 //   b      : offset (an integer-valued float) with z_j*log2e + b <= 0 for every j
 //   S_rest : sum over j != a_t of 2^(z_j*log2e + b).  The sampled token's own term is left out
 //            so that 1 - pi(a_t) = S_rest / S keeps full relative accuracy when pi(a_t) -> 1.
+//   T_rest : sum over j != a_t of 2^(x_j) * x_j with x_j = z_j*log2e + b (for the entropy:
+//            sum_j pi_j log2 pi_j = T/S - log2 S).
 // log2e is the fp32 constant kLog2e everywhere (passes and epilogue), so the probabilities
 // are mutually consistent; its rounding (1.3e-8 relative) acts as a temperature of 1+1.3e-8.
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
@@ -258,7 +265,7 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
 // streaming phases that every wave runs.
 // Everything but the kernel arguments is passed and returned by value, i.e. in registers.
 __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
-                                                                   const uint16_t* zrow, float b, double S_rest, int lane) {
+                                                                   const uint16_t* zrow, float b, double S_rest, double T_rest, int lane) {
   constexpr double kL = static_cast<double>(kLog2e);
   const double bd = static_cast<double>(b);
   const double xa = static_cast<double>(rs.za) * kL + bd;   // log2 of a_t's own term
@@ -273,6 +280,7 @@ __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiPara
   const float qa = ea * inv_S;
   const double one_minus_qa = static_cast<double>(static_cast<float>(S_rest) * inv_S);
   const int variant = p.variant;
+  double mass_mu = pa, mass_pi = qa;      // mass on A' (= {a_t} for the Binary variants)
   double D;
   if (variant == kBinaryTV || (variant == kTopkTV && p.K == 0)) {
     D = fabs(static_cast<double>(pa) - static_cast<double>(qa));
@@ -300,6 +308,8 @@ __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiPara
     }
     sp = wave_sum(sp) + pa;
     sq = wave_sum(sq) + qa;
+    mass_mu = sp;
+    mass_pi = sq;
     acc = wave_sum(acc) + (tv ? fabs(static_cast<double>(pa) - static_cast<double>(qa)) : xlogx_over_y(pa, lmu, lpi));
     const double po = fmax(1.0 - sp, 0.0), qo = fmax(1.0 - sq, 0.0);
     D = tv ? 0.5 * (acc + fabs(po - qo))
@@ -316,6 +326,16 @@ __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiPara
     p.divergence[row] = static_cast<float>(D);
     p.mask[row] = blocked ? 0 : 1;
     if (p.loss_tok) p.loss_tok[row] = static_cast<float>(lt);
+    if (p.diag) {
+      // token entropy: -sum pi ln pi = ln2 * (log2 S - T/S), T including a_t's own term
+      const double T = T_rest + ((ea > 0.f) ? static_cast<double>(ea) * xa : 0.0);
+      const double H = kLn2 * (log2S - T / S);
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      f32x4* d = reinterpret_cast<f32x4*>(p.diag + static_cast<int64_t>(row) * 8);
+      d[0] = f32x4{static_cast<float>(r), static_cast<float>(lpi),
+                   static_cast<float>(fabs(static_cast<double>(pa) - static_cast<double>(qa))), static_cast<float>(fmax(H, 0.0))};
+      d[1] = f32x4{static_cast<float>(mass_mu), static_cast<float>(mass_pi), 0.f, 0.f};
+    }
   }
   RowResult res;
   res.loss_term = lt;

@@ -35,6 +35,15 @@ __device__ __forceinline__ u32x4 patch16(u32x4 v, int sub, uint32_t bits) {
   return r;
 }
 
+// One packed word (two bf16) into the running sums: s += e, t += e*x with x = z*log2e + b and
+// e = 2^x (t feeds the entropy; a vanished term, e = 0 with x = -inf, adds nothing).
+__device__ __forceinline__ void accum2(uint32_t w, float b, float& s, float& t) {
+  const float x0 = fmaf(__uint_as_float(w << 16), kLog2e, b), x1 = fmaf(__uint_as_float(w & 0xffff0000u), kLog2e, b);
+  const float e0 = fast_exp2(x0), e1 = fast_exp2(x1);
+  s += e0 + e1;
+  t = fma_ex(e0, x0, fma_ex(e1, x1, t));
+}
+
 // 2^(z*log2e + k) for the two bf16 halves of a packed word.
 __device__ __forceinline__ float exp_lo(uint32_t w, float k) { return fast_exp2(fmaf(__uint_as_float(w << 16), kLog2e, k)); }
 __device__ __forceinline__ float exp_hi(uint32_t w, float k) { return fast_exp2(fmaf(__uint_as_float(w & 0xffff0000u), kLog2e, k)); }
@@ -56,14 +65,16 @@ constexpr int kChunkStep = 4;
 // code with a fixed sequence of memory instructions: loads past the row return 0 (turned into
 // -inf where the row statistics consume them) and stores past it are dropped.
 // GRAD = false is the forward-only form: phase C only refills (no gradient, no stores).
-template <int THREADS, int NCHUNK, bool GRAD>
+// DIAG = true also accumulates sum e*x for the entropy diagnostic (two more instructions per
+// element in the statistics loop), selected when the caller passes a diagnostics buffer.
+template <int THREADS, int NCHUNK, bool GRAD, bool DIAG>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
   constexpr int GC = 2;                          // chunks per group of the online row statistics
   __shared__ float sh_b[NW];
-  __shared__ double sh_s[NW];
+  __shared__ double sh_s[NW], sh_t[NW];
   __shared__ RowCoef sh_rc;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
@@ -143,6 +154,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
       float b = 3.0e38f;                       // "+infinity": nothing seen yet
       float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;      // sum e*x, same offset as s
 #pragma unroll
       for (int g0 = 0; g0 < NCHUNK; g0 += GC) {
         // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
@@ -177,22 +189,35 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         const int lo16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
         const float zmax = __uint_as_float(static_cast<uint32_t>(hi16 >= 0 ? hi16 : lo16) << 16);
         const float bn = -ceilf(fmaxf(zmax, kNegBig) * kLog2e);
-        const float sc = fast_exp2(bn - b);       // 1 when the maximum did not move
+        // moving the offset by d: e -> e*2^d, x -> x + d, so s -> 2^d s and t -> 2^d (t + d s)
+        const float d = bn - b;
+        const float sc = fast_exp2(d);            // 1 when the maximum did not move
+        if (DIAG) { t0 = sc * fmaf(d, s0, t0); t1 = sc * fmaf(d, s1, t1); t2 = sc * fmaf(d, s2, t2); t3 = sc * fmaf(d, s3, t3); }
         s0 *= sc; s1 *= sc; s2 *= sc; s3 *= sc;
         b = bn;
 #pragma unroll
         for (int i = 0; i < GC; ++i) {
-          s0 += exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
-          s1 += exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
-          s2 += exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
-          s3 += exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
+          if (DIAG) {
+            accum2(v[i].x, b, s0, t0);
+            accum2(v[i].y, b, s1, t1);
+            accum2(v[i].z, b, s2, t2);
+            accum2(v[i].w, b, s3, t3);
+          } else {
+            s0 += exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
+            s1 += exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
+            s2 += exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
+            s3 += exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
       }
       // wave-level combine: common offset = the smallest one, rescaling is exact
       const float bw = -wave_max(-b);
-      const double sw = wave_sum(static_cast<double>((s0 + s1) + (s2 + s3)) * static_cast<double>(fast_exp2(bw - b)));
-      if (lane == 0) { sh_b[wid] = bw; sh_s[wid] = sw; }
+      const double dw = static_cast<double>(bw - b), scw = static_cast<double>(fast_exp2(bw - b));
+      const double st = static_cast<double>((s0 + s1) + (s2 + s3)), tt = static_cast<double>((t0 + t1) + (t2 + t3));
+      const double sw = wave_sum(st * scw);
+      const double tw = DIAG ? wave_sum(scw * (tt + dw * st)) : 0.0;
+      if (lane == 0) { sh_b[wid] = bw; sh_s[wid] = sw; sh_t[wid] = tw; }
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------
       if (wid == 0) {
@@ -200,10 +225,14 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         float bb = -ceilf(fmaxf(rs.za, kNegBig) * kLog2e);
 #pragma unroll
         for (int w = 0; w < NW; ++w) bb = fminf(bb, sh_b[w]);
-        double S_rest = 0.0;
+        double S_rest = 0.0, T_rest = 0.0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) S_rest += sh_s[w] * static_cast<double>(fast_exp2(bb - sh_b[w]));   // exact powers of two
-        const RowResult rr = row_epilogue(ep, row, rs, tk, zrow, bb, S_rest, lane);
+        for (int w = 0; w < NW; ++w) {
+          const double dd = static_cast<double>(bb - sh_b[w]), sc = static_cast<double>(fast_exp2(bb - sh_b[w]));   // exact power of two
+          S_rest += sh_s[w] * sc;
+          T_rest += sc * (sh_t[w] + dd * sh_s[w]);
+        }
+        const RowResult rr = row_epilogue(ep, row, rs, tk, zrow, bb, S_rest, T_rest, lane);
         rc = rr.rc;
         loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
@@ -218,6 +247,9 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       p.divergence[row] = 0.f;
       p.mask[row] = 0;
       if (p.loss_tok) p.loss_tok[row] = 0.f;
+      if (p.diag) {
+        for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+      }
     }
 
     // ---- phase C: gradient out, next row in -------------------------------------------------
@@ -260,15 +292,20 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 // One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
 template <int THREADS, int NCHUNK>
 hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
-  if (grad) hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true>), dim3(grid), dim3(THREADS), 0, s, p);
-  else      hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false>), dim3(grid), dim3(THREADS), 0, s, p);
+  const bool diag = p.diag != nullptr;
+  const dim3 g(grid), b(THREADS);
+  if (grad && diag)       hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true>), g, b, 0, s, p);
+  else if (grad)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false>), g, b, 0, s, p);
+  else if (diag)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, true>), g, b, 0, s, p);
+  else                    hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, false>), g, b, 0, s, p);
   return hipGetLastError();
 }
+// The diagnostics form needs a few more registers; its occupancy bounds both.
 template <int THREADS, int NCHUNK>
 int occupancy_shape(bool grad) {
   int n = 0;
-  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true>, THREADS, 0)
-                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false>, THREADS, 0);
+  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true>, THREADS, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 

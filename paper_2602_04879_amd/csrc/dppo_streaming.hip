@@ -16,23 +16,29 @@ namespace {
 // Because b is an integer, changing it rescales s by an exact power of two, and offsets of
 // different threads combine without any rounding.
 struct OnlineStat {
-  float b = -kNegBig;  // current offset (starts at "+infinity": nothing seen yet)
-  float s = 0.f;
+  float b = 3.0e38f;   // current offset (starts at "+infinity": nothing seen yet)
+  float s = 0.f;       // sum 2^x,      x = z*log2e + b
+  float t = 0.f;       // sum 2^x * x   (feeds the entropy)
   __device__ __forceinline__ void cover(float zmax) {   // make the offset cover a logit value
-    const float bn = fminf(b, -ceilf(zmax * kLog2e));
-    s *= fast_exp2(bn - b);
+    const float bn = fminf(b, -ceilf(fmaxf(zmax, kNegBig) * kLog2e));
+    const float d = bn - b, sc = fast_exp2(d);
+    t = sc * fmaf(d, s, t);     // e -> e*2^d, x -> x + d
+    s *= sc;
     b = bn;
-  }
-  __device__ __forceinline__ void add8(const float (&z)[8]) {
-    cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
-    float acc = s;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc += fast_exp2(fmaf(z[i], kLog2e, b));
-    s = acc;
   }
   __device__ __forceinline__ void add1(float z) {
     cover(z);
-    s += fast_exp2(fmaf(z, kLog2e, b));
+    add1_covered(z);
+  }
+  __device__ __forceinline__ void add1_covered(float z) {
+    const float x = fmaf(z, kLog2e, b), e = fast_exp2(x);
+    s += e;
+    t = fma_ex(e, x, t);
+  }
+  __device__ __forceinline__ void add8(const float (&z)[8]) {
+    cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) add1_covered(z[i]);
   }
 };
 
@@ -47,7 +53,7 @@ template <int THREADS, bool VEC, bool GRAD>
 __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p) {
   constexpr int NW = THREADS / kWave;
   __shared__ float sh_max[NW];
-  __shared__ double sh_sum[NW];
+  __shared__ double sh_sum[NW], sh_tsum[NW];
   __shared__ RowCoef sh_rc;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
   const EpiParams ep = epi_params(p);
@@ -97,22 +103,23 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
       float b = sh_max[0];
 #pragma unroll
       for (int w = 1; w < NW; ++w) b = fminf(b, sh_max[w]);
-      double sd = static_cast<double>(st.s * fast_exp2(b - st.b));
-      sd = wave_sum(sd);
-      if (lane == 0) sh_sum[wid] = sd;
+      const double dd = static_cast<double>(b - st.b), sc = static_cast<double>(fast_exp2(b - st.b));
+      const double sd = wave_sum(static_cast<double>(st.s) * sc);
+      const double td = wave_sum(sc * (static_cast<double>(st.t) + dd * static_cast<double>(st.s)));
+      if (lane == 0) { sh_sum[wid] = sd; sh_tsum[wid] = td; }
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------
       if (wid == 0) {
-        double S_rest = 0.0;
+        double S_rest = 0.0, T_rest = 0.0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) S_rest += sh_sum[w];
+        for (int w = 0; w < NW; ++w) { S_rest += sh_sum[w]; T_rest += sh_tsum[w]; }
         RowScalars rs;
         rs.a = a;
         rs.za = bf16_bits_to_float(zrow[a]);
         rs.lmu = p.mu_logp[row];
         rs.adv = p.adv[row];
         const TopkLane tk = load_topk_lane(p, row, a, zrow, lane);
-        const RowResult res = row_epilogue(ep, row, rs, tk, zrow, b, S_rest, lane);
+        const RowResult res = row_epilogue(ep, row, rs, tk, zrow, b, S_rest, T_rest, lane);
         rc = res.rc;
         loss_acc += res.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
@@ -125,6 +132,9 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
       p.divergence[row] = 0.f;
       p.mask[row] = 0;
       if (p.loss_tok) p.loss_tok[row] = 0.f;
+      if (p.diag) {
+        for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+      }
     }
 
     if (GRAD) {

@@ -7,6 +7,8 @@ Tolerances (the absolute terms are what fp32 accumulation of V terms leaves on a
   loss       : |gpu - ref| <= 1e-4 |ref| + 1e-6 * loss_scale * sum|A|
   mask       : bit-exact, except tokens with |D_ref - delta| < 1e-6 or, where the divergence can
                exceed delta while r is at 1 (Top-K variants), |log pi(a) - log mu(a)| < 1e-6
+  diagnostics: ratio 1e-4 rel; log pi(a) 1e-6 rel + 5e-6; |pi - mu| and covered masses 1e-6;
+               entropy 1e-4 rel + 1e-5
   grad_logits: |gpu - ref| <= 1e-2 |ref| + 1e-30   (bf16 output, round to nearest even); the
                sampled token's entry also gets the oracle's own float64 cancellation error
 """
@@ -66,6 +68,21 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
         assert np.all(errL <= RTOL_D * np.abs(lt_ref) + 1e-6 * np.abs(A)), f"loss_tok: max err {errL.max():.3e}"
     stats = {"max_abs_err_D": float(errD.max()) if len(rows) else 0.0, "masked": int((M == 0).sum()),
              "exempt": int(exempt.sum()), "rows": int(len(rows))}
+
+    if res.get("diagnostics") is not None:
+        dg = res["diagnostics"][loc].double().cpu().numpy()
+        live = (np.asarray(ref["logp"]) != 0) | (np.asarray(ref["ratio"]) != 0)      # ignored rows: all zeros
+        assert np.all(dg[~live] == 0)
+        checks = (("ratio", 0, 1e-4, 1e-7), ("logp", 1, 1e-6, 5e-6), ("abs_diff", 2, 0.0, 1e-6),
+                  ("entropy", 3, 1e-4, 1e-5), ("mass_mu", 4, 0.0, 1e-6), ("mass_pi", 5, 0.0, 1e-6))
+        for name, col, rtol, atol in checks:
+            got, want = dg[live, col], np.asarray(ref[name], dtype=np.float64)[live]
+            with np.errstate(invalid="ignore"):
+                err = np.where(got == want, 0.0, np.abs(got - want))      # equal infinities (log 0) agree
+                ok = err <= rtol * np.abs(want) + atol
+            assert np.all(ok), f"diagnostics {name}: max err {err.max():.3e}"
+        assert np.all(dg[:, 6:] == 0)
+        stats["max_abs_err_entropy"] = float(np.abs(dg[live, 3] - ref["entropy"][live]).max()) if live.any() else 0.0
 
     if check_grad and res.get("grad_logits") is not None:
         V = batch["V"]

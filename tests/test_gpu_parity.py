@@ -26,7 +26,7 @@ def _run_and_compare(w, *, backward=True, in_place=False, flags=0, ld=None, shif
     b = W.make_batch(w, DEV, ld=ld, shift_sampled=shift, **mk)
     rows = np.arange(b["T"]) if rows is None else rows
     ref = P.oracle_rows(b, rows, want_grad=backward and check_grad)   # before an in-place run overwrites the logits
-    res = B.run_batch(b, backward=backward, in_place=in_place, flags=flags)
+    res = B.run_batch(b, backward=backward, in_place=in_place, flags=flags, diagnostics=True)
     torch.cuda.synchronize()
     st = P.compare_rows(b, res, rows, check_grad=backward and check_grad, ref=ref)
     if len(rows) == b["T"]:
@@ -97,7 +97,7 @@ def test_resident_more_rows_than_workgroups_in_place_with_special_rows():
     b["advantages"][5::13] = 0.0
     rows = np.arange(b["T"])
     ref = P.oracle_rows(b, rows)
-    res = B.run_batch(b, in_place=True)
+    res = B.run_batch(b, in_place=True, diagnostics=True)
     torch.cuda.synchronize()
     assert B.last_path() == "resident"
     st = P.compare_rows(b, res, rows, ref=ref)
@@ -117,7 +117,7 @@ def test_resident_saturated_rows():
     b["logits"][10, :] = -1.0e4                    # every logit negative and far from 0
     b["logits"][11, :] = -50.0
     b["logits"][12, :] = 3.0e4
-    res = B.run_batch(b)
+    res = B.run_batch(b, diagnostics=True)
     torch.cuda.synchronize()
     assert B.last_path() == "resident"
     assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["grad_logits"].float()).all()
@@ -188,7 +188,7 @@ def test_ignored_rows_padding_ids_and_zero_advantage():
     b["mu_topk_ids"][:, 4] = -1                   # padding entries
     b["mu_topk_ids"][1::2, 9] = b["V"]
     b["advantages"][2::6] = 0.0
-    res = B.run_batch(b)
+    res = B.run_batch(b, diagnostics=True)
     torch.cuda.synchronize()
     P.compare_rows(b, res, np.arange(b["T"]))
     ign = (b["sampled_ids"] < 0) | (b["sampled_ids"] >= b["V"])
@@ -225,7 +225,7 @@ def test_saturated_and_minus_inf_logits():
     b["logits"][4:8, 100:2000] = float("-inf")     # masked vocabulary entries
     b["logits"][8, :] = -1.0e4                     # flat, far from 0
     b["logits"][9, :] = 3.0e4
-    res = B.run_batch(b)
+    res = B.run_batch(b, diagnostics=True)
     torch.cuda.synchronize()
     assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["loss"]).all()
     assert torch.isfinite(res["grad_logits"].float()).all()
@@ -338,7 +338,7 @@ def test_full_size_headline_configs(name):
     w = W.WORKLOADS[name]
     _say(f"[case] full size {name} T={w.T} V={w.V}")
     b = W.make_batch(w, DEV, rows_per_step=2048)
-    res = B.run_batch(b)
+    res = B.run_batch(b, diagnostics=True)
     torch.cuda.synchronize()
     _say(f"       path={B.last_path()} loss={res['loss'].item():.6e} masked={(res['mask'] == 0).sum().item()}")
     _full_size_properties(b, res)

@@ -409,3 +409,27 @@ def test_ignored_rows_and_loss_scale():
     out2 = _run(h, loss_scale=3.0 * h["loss_scale"])
     assert out2["loss"] == pytest.approx(3.0 * ref["loss"], rel=1e-12)
     np.testing.assert_allclose(out2["grad_logits"], 3.0 * ref["grad_logits"], rtol=1e-12)
+
+
+# ------------------------------------------------------------------ diagnostics (App. F.1, App. B.1)
+def test_diagnostics_entropy_abs_diff_and_covered_mass():
+    for V in (2, 9, 300):
+        pi = _rand_dist(V, True)
+        assert O.entropy(np.log(pi)) == pytest.approx(scipy.stats.entropy(pi), rel=1e-10)
+    assert O.entropy(np.log(np.full(8, 1 / 8))) == pytest.approx(math.log(8))
+    assert O.entropy(np.array([0.0, -np.inf, -np.inf])) == 0.0                  # 0 ln 0 = 0
+    h = _small_batch(O.TOPK_TV, 6, V=200, shift=1.0)
+    out = _run(h)
+    mu_full = np.exp(h["mu_logp_full"].astype(np.float64))
+    for t in range(h["T"]):
+        a = int(h["sampled_ids"][t])
+        pi = np.exp(O.log_softmax(h["logits"][t]))
+        assert out["entropy"][t] == pytest.approx(scipy.stats.entropy(pi), rel=1e-9)
+        assert out["abs_diff"][t] == pytest.approx(abs(mu_full[t, a] - pi[a]), abs=1e-7)   # mu arrives in fp32
+        ids = sorted(set(h["mu_topk_ids"][t].tolist()) | {a})
+        assert out["mass_mu"][t] == pytest.approx(mu_full[t, ids].sum(), abs=1e-6)
+        assert out["mass_pi"][t] == pytest.approx(pi[ids].sum(), rel=1e-9)
+    hb = dict(h)
+    outb = _run(hb, variant=O.BINARY_TV)
+    np.testing.assert_allclose(outb["mass_pi"], np.exp(outb["logp"]), rtol=1e-12)
+    np.testing.assert_allclose(outb["abs_diff"], outb["divergence"], rtol=1e-12)
