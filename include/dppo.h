@@ -18,6 +18,10 @@
  *   grad_logits    = loss_scale * M_t A_t r_t (pi(j|s_t) - 1[j = a_t])   for every j < V
  *                    (Eq. unified_grad with C = infinity; M_t is a constant factor)
  *
+ * The same call also evaluates the paper's baselines, which differ only in M_t and in the cap
+ * C on the ratio (App. C.1): `mask_rule` selects the DPPO mask, the PPO/GRPO ratio-clip mask
+ * or none, and `ratio_cap` replaces r_t by min(r_t, C) in the loss term and the gradient.
+ *
  * All pointers are DEVICE pointers owned by the caller.  Inputs are read-only and, like the
  * outputs and the workspace, must stay valid until the work enqueued on `stream` has finished.
  * The library allocates nothing, never synchronises and never touches another stream; every
@@ -60,6 +64,14 @@ typedef enum {
   DPPO_TOPK_KL   = 3              /* sum over A'' of p_mu ln(p_mu / p_pi)      (Eq. topk_kl)   */
 } dppo_variant_t;
 
+/* Which mask M_t gates the update (unified gradient form, App. C.1, Eq. unified_grad). */
+typedef enum {
+  DPPO_MASK_DIVERGENCE = 0,       /* DPPO: Eq. dppo_obj, on D_t of `variant` and `delta`          */
+  DPPO_MASK_RATIO_CLIP = 1,       /* PPO / GRPO(-ClipHigher): 0 iff (A>0 and r > 1+eps_high) or  */
+                                  /* (A<0 and r < 1-eps_low)                (App. C.1, App. E)  */
+  DPPO_MASK_NONE       = 2        /* M_t = 1: PG-IS, PG-TIS / CISPO                (App. C.1)  */
+} dppo_mask_rule_t;
+
 typedef enum {
   DPPO_OK = 0,
   DPPO_ERR_NULL = 1,              /* a required pointer is NULL                                */
@@ -70,7 +82,8 @@ typedef enum {
   DPPO_ERR_K = 5,                 /* K < 0, K > DPPO_KMAX, or K > 0 without top-K pointers     */
   DPPO_ERR_WORKSPACE = 6,         /* workspace NULL or smaller than dppo_workspace_bytes()     */
   DPPO_ERR_LAUNCH = 7,            /* the HIP runtime refused a launch (see hipGetLastError)    */
-  DPPO_ERR_VALUE = 8              /* delta or loss_scale is NaN                                */
+  DPPO_ERR_VALUE = 8              /* delta, loss_scale, eps_* or ratio_cap is NaN, eps_low not */
+                                  /* in [0, 1), eps_high < 0, or mask_rule unknown             */
 } dppo_status_t;
 
 /* flags */
@@ -98,6 +111,13 @@ typedef struct {
   float          delta;        /* divergence threshold delta of Eq. dppo_obj                   */
   float          loss_scale;   /* multiplies loss and gradient, e.g. 1/T_total (the paper      */
                                /* leaves the minibatch normalisation to the trainer)           */
+  int32_t        mask_rule;    /* dppo_mask_rule_t; 0 = the DPPO divergence mask.  D_t of      */
+                               /* `variant` is computed and stored under every rule            */
+  float          eps_low;      /* DPPO_MASK_RATIO_CLIP only: clip range [1-eps_low, 1+eps_high];*/
+  float          eps_high;     /* "r > 1+eps" is evaluated as log pi - log mu > log(1+eps)     */
+  float          ratio_cap;    /* C of Eq. unified_grad: the gradient weight is M min(r, C) A  */
+                               /* (held constant) and the loss term -M min(r, C) A.            */
+                               /* <= 0 or +inf: no cap (C = infinity, as DPPO uses)            */
   /* ---- outputs (fully overwritten) ---- */
   float*         loss;         /* [1]                                                          */
   float*         loss_tok;     /* [T] -M_t r_t A_t, unscaled; may be NULL                      */

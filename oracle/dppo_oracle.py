@@ -18,6 +18,9 @@ order and notation of the paper:
   * DPPO mask and masked surrogate                (Eq. dppo_obj)
   * gradient wrt the logits, mask held constant   (Eq. unified_grad with C = infinity)
   * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL)
+  * the baselines' masks and the ratio cap         (App. C.1: unified gradient form,
+                                                    Eq. unified_grad; PPO/GRPO clip mask;
+                                                    M = 1 for PG-IS / CISPO; cap C)
   * per-token health metrics the paper monitors   (App. F.1: |pi - mu| of the sampled token,
     (diagnostics)                                   policy entropy; App. B.1: mass covered by
                                                     the top-K set)
@@ -33,17 +36,22 @@ Readings taken where the paper is silent:
   - a top-K id equal to a_t is dropped (a_t's own mu log-prob is used), ids outside [0, V)
     are padding;
   - a row whose sampled id is outside [0, V) is ignored: D = 0, M = 0, loss term 0, zero
-    gradient row.
+    gradient row;
+  - with a finite ratio cap C the gradient is the one Eq. unified_grad states,
+    M min(r, C) A grad log pi (the weight is a constant), and the reported loss term is
+    -M min(r, C) A; "r > 1 + eps" of the clip mask is evaluated as
+    log pi(a) - log mu(a) > log(1 + eps).
 
 All pins for these functions live in tests/test_oracle_*.py.  "parity unpinned": the loss
-normalisation (the paper fixes no minibatch formula; it is the caller's loss_scale) and a finite
-ratio cap C (not implemented; C = infinity as in Eq. dppo_obj).
+normalisation (the paper fixes no minibatch formula; it is the caller's loss_scale) and the
+VALUE reported as loss under a finite ratio cap (the paper defines only the gradient there).
 """
 from __future__ import annotations
 
 import numpy as np
 
 BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
 VARIANT_NAMES = {BINARY_TV: "binary_tv", BINARY_KL: "binary_kl",
                  TOPK_TV: "topk_tv", TOPK_KL: "topk_kl"}
 _TINY = 1e-30
@@ -156,13 +164,26 @@ def dppo_mask(D, delta, adv, lpi_a, lmu_a):
     return 1
 
 
+def ratio_clip_mask(adv, lpi_a, lmu_a, eps_low, eps_high):
+    """PPO / GRPO(-ClipHigher) mask of App. C.1 and App. E: 0 iff (A > 0 and r > 1 + eps_high) or
+    (A < 0 and r < 1 - eps_low), 1 otherwise; r compared in the log domain."""
+    d = lpi_a - lmu_a
+    if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):
+        return 0
+    return 1
+
+
 # --------------------------------------------------------------------------- whole path
 def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
-              mu_topk_ids=None, mu_topk_logp=None, want_grad=True):
+              mu_topk_ids=None, mu_topk_logp=None, want_grad=True,
+              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=None):
     """The whole hot path for T rows.
 
     logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
     mu_logp [T], advantages [T], optional mu_topk_ids / mu_topk_logp [T, K].
+    mask_rule picks M_t: the DPPO divergence mask (default), the PPO/GRPO ratio-clip mask with
+    eps_low / eps_high, or none (M = 1: PG-IS, CISPO).  ratio_cap is C of Eq. unified_grad
+    (None or inf: no cap).
     Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
     ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None, and the
     diagnostics abs_diff [T] = |pi(a_t) - mu(a_t)|, entropy [T], mass_mu [T], mass_pi [T]
@@ -181,6 +202,7 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         "loss_tok": np.zeros(T), "divergence": np.zeros(T), "mask": np.zeros(T, dtype=np.uint8),
         "ratio": np.zeros(T), "logp": np.zeros(T), "lse": np.zeros(T),
         "abs_diff": np.zeros(T), "entropy": np.zeros(T), "mass_mu": np.zeros(T), "mass_pi": np.zeros(T),
+        "weight": np.zeros(T),
         "grad_logits": np.zeros((T, V)) if want_grad else None,
     }
     for t in range(T):
@@ -206,20 +228,29 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
             D = topk_tv(p, q, po, qo) if variant == TOPK_TV else topk_kl(p, q, po, qo)
             mass_mu, mass_pi = p.sum(), q.sum()
         A = float(advantages[t])
-        M = dppo_mask(D, delta, A, lpi, lmu)         # step 4
+        if mask_rule == MASK_DIVERGENCE:             # step 4
+            M = dppo_mask(D, delta, A, lpi, lmu)
+        elif mask_rule == MASK_RATIO_CLIP:
+            M = ratio_clip_mask(A, lpi, lmu, eps_low, eps_high)
+        elif mask_rule == MASK_NONE:
+            M = 1
+        else:
+            raise ValueError("unknown mask rule")
+        w = r if (ratio_cap is None or not np.isfinite(ratio_cap)) else min(r, float(ratio_cap))
         out["divergence"][t] = D
         out["mask"][t] = M
         out["ratio"][t] = r
+        out["weight"][t] = w
         out["logp"][t] = lpi
         out["lse"][t] = z[a] - lpi
         out["abs_diff"][t] = binary_tv(lmu, lpi)
         out["entropy"][t] = entropy(logpi)
         out["mass_mu"][t] = mass_mu
         out["mass_pi"][t] = mass_pi
-        out["loss_tok"][t] = -M * r * A              # step 5
+        out["loss_tok"][t] = -M * w * A              # step 5
         if want_grad:                                # step 6
             g = np.exp(logpi)
             g[a] -= 1.0
-            out["grad_logits"][t] = (loss_scale * M * A * r) * g
+            out["grad_logits"][t] = (loss_scale * M * A * w) * g
     out["loss"] = float(loss_scale * out["loss_tok"].sum())
     return out

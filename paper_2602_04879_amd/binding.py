@@ -12,6 +12,7 @@ import os
 import torch
 
 BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
 NDIAG = 8
 DIAG_RATIO, DIAG_LOGP, DIAG_ABS_DIFF, DIAG_ENTROPY, DIAG_MASS_MU, DIAG_MASS_PI = 0, 1, 2, 3, 4, 5
 FLAG_FORCE_STREAMING = 1
@@ -30,6 +31,7 @@ class DppoArgs(C.Structure):
         ("mu_topk_ids", C.c_void_p), ("mu_topk_logp", C.c_void_p),
         ("K", C.c_int32), ("variant", C.c_int32),
         ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
+        ("mask_rule", C.c_int32), ("eps_low", C.c_float), ("eps_high", C.c_float), ("ratio_cap", C.c_float),
         ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
         ("mask", C.c_void_p), ("grad_logits", C.c_void_p), ("diagnostics", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("flags", C.c_uint32),
@@ -81,7 +83,8 @@ def workspace_bytes(T: int, V: int, K: int) -> int:
 
 
 def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, out,
-              mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None) -> DppoArgs:
+              mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None,
+              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0) -> DppoArgs:
     """Fill a dppo_args_t from torch tensors.  `out` is a dict with loss [1] f32, divergence [T]
     f32, mask [T] u8, workspace (u8), optional loss_tok [T] f32."""
     T, ld = logits.shape[0], (logits.stride(0) if logits.shape[0] > 1 else logits.shape[1])
@@ -92,6 +95,8 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.K = 0 if mu_topk_ids is None else mu_topk_ids.shape[1]
     a.variant = variant
     a.advantages, a.delta, a.loss_scale = _ptr(advantages), delta, loss_scale
+    a.mask_rule, a.eps_low, a.eps_high = mask_rule, eps_low, eps_high
+    a.ratio_cap = 0.0 if ratio_cap is None else ratio_cap
     a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
     a.grad_logits = _ptr(grad_logits)
@@ -160,7 +165,7 @@ def last_path() -> str:
 
 
 def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags: int = 0, out=None,
-              grad=None, stream=None, rows=None, diagnostics: bool = False) -> dict:
+              grad=None, stream=None, rows=None, diagnostics: bool = False, **rule) -> dict:
     """Convenience for tests and benchmarks: run one workload batch (see workloads.make_batch),
     optionally restricted to rows [r0, r1).  Returns the output tensors (device)."""
     r0, r1 = (0, batch["T"]) if rows is None else rows
@@ -175,7 +180,7 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     tk_l = batch["mu_topk_logp"][sl] if batch["mu_topk_logp"] is not None else None
     args = make_args(logits, batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
                      batch["delta"], batch["variant"], batch["loss_scale"], out, tk_i, tk_l,
-                     V=batch["V"], flags=flags, grad_logits=grad if backward else None)
+                     V=batch["V"], flags=flags, grad_logits=grad if backward else None, **rule)
     args.ld = batch["ld"]
     (dppo_loss_fwd_bwd if backward else dppo_loss_fwd)(args, stream)
     res = dict(out)

@@ -37,7 +37,9 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
   if (topk && a->K > 0 && (!a->mu_topk_ids || !a->mu_topk_logp)) return DPPO_ERR_K;
   if (!a->loss) return DPPO_ERR_NULL;
-  if (std::isnan(a->delta) || std::isnan(a->loss_scale)) return DPPO_ERR_VALUE;
+  if (std::isnan(a->delta) || std::isnan(a->loss_scale) || std::isnan(a->ratio_cap)) return DPPO_ERR_VALUE;
+  if (a->mask_rule < DPPO_MASK_DIVERGENCE || a->mask_rule > DPPO_MASK_NONE) return DPPO_ERR_VALUE;
+  if (a->mask_rule == DPPO_MASK_RATIO_CLIP && !(a->eps_low >= 0.f && a->eps_low < 1.f && a->eps_high >= 0.f)) return DPPO_ERR_VALUE;
   if (!a->workspace || a->workspace_bytes < dppo_workspace_bytes(a->T, a->V, a->K)) return DPPO_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
   if (a->T > 0) {
@@ -84,6 +86,10 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     p.variant = a->variant;
     p.delta = a->delta;
     p.loss_scale = a->loss_scale;
+    p.mask_rule = a->mask_rule;
+    p.eps_low = a->eps_low;
+    p.eps_high = a->eps_high;
+    p.ratio_cap = (a->ratio_cap > 0.f && std::isfinite(a->ratio_cap)) ? a->ratio_cap : 0.f;   // 0: no cap
 
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
     // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
@@ -136,7 +142,7 @@ const char* dppo_status_str(dppo_status_t status) {
     case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
     case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes()";
     case DPPO_ERR_LAUNCH: return "HIP kernel launch failed";
-    case DPPO_ERR_VALUE: return "delta or loss_scale is NaN";
+    case DPPO_ERR_VALUE: return "bad value: NaN delta / loss_scale / ratio_cap, unknown mask_rule, or clip range outside 0 <= eps_low < 1, eps_high >= 0";
   }
   return "unknown status";
 }

@@ -28,6 +28,9 @@ struct KParams {
   int64_t ld;
   int32_t T, V, K, variant;
   float delta, loss_scale;
+  int32_t mask_rule;        // 0 divergence (DPPO), 1 ratio clip (PPO/GRPO), 2 none
+  float eps_low, eps_high;  // ratio-clip range
+  float ratio_cap;          // C of the unified gradient form; 0 = no cap
 };
 
 // The subset of the arguments the per-row epilogue needs.  Each kernel makes ONE copy of it at
@@ -42,11 +45,14 @@ struct EpiParams {
   float* diag;
   int32_t V, K, variant;
   float delta, loss_scale;
+  int32_t mask_rule;
+  float eps_low, eps_high, ratio_cap;
 };
 __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   EpiParams e;
   e.tk_ids = p.tk_ids; e.tk_lp = p.tk_lp; e.loss_tok = p.loss_tok; e.divergence = p.divergence; e.mask = p.mask; e.diag = p.diag;
   e.V = p.V; e.K = p.K; e.variant = p.variant; e.delta = p.delta; e.loss_scale = p.loss_scale;
+  e.mask_rule = p.mask_rule; e.eps_low = p.eps_low; e.eps_high = p.eps_high; e.ratio_cap = p.ratio_cap;
   return e;
 }
 
@@ -316,12 +322,22 @@ __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiPara
            : acc + xlogx_over_y(po, log2_fast(fmax(po, 1e-300)) * kLn2, log2_fast(fmax(qo, 1e-300)) * kLn2);
   }
   const double A = static_cast<double>(rs.adv);
-  const bool blocked = (D > static_cast<double>(p.delta)) &&
-                       ((A > 0.0 && lpi > lmu_raw) || (A < 0.0 && lpi < lmu_raw));
+  // mask M_t: DPPO's divergence mask (Eq. dppo_obj), or one of the baselines' (App. C.1)
+  bool blocked;
+  if (p.mask_rule == 0) {
+    blocked = (D > static_cast<double>(p.delta)) && ((A > 0.0 && lpi > lmu_raw) || (A < 0.0 && lpi < lmu_raw));
+  } else if (p.mask_rule == 1) {
+    const double dl = lpi - lmu_raw;     // log r, compared with log(1 + eps_high) and log(1 - eps_low)
+    blocked = (A > 0.0 && dl > log1p(static_cast<double>(p.eps_high))) || (A < 0.0 && dl < log1p(-static_cast<double>(p.eps_low)));
+  } else {
+    blocked = false;
+  }
   const double M = blocked ? 0.0 : 1.0;
   const double r = static_cast<double>(exp2_split((lpi - lmu_raw) * kLog2eD));
-  const double lt = -M * r * A;
-  const double c = static_cast<double>(p.loss_scale) * M * A * r;
+  // weight min(r, C) of the unified gradient form (Eq. unified_grad); no cap for DPPO
+  const double w = (p.ratio_cap > 0.f && r > static_cast<double>(p.ratio_cap)) ? static_cast<double>(p.ratio_cap) : r;
+  const double lt = -M * w * A;
+  const double c = static_cast<double>(p.loss_scale) * M * A * w;
   if (lane == 0) {
     p.divergence[row] = static_cast<float>(D);
     p.mask[row] = blocked ? 0 : 1;

@@ -6,7 +6,8 @@ Tolerances (the absolute terms are what fp32 accumulation of V terms leaves on a
                tokens inside the exemption band)
   loss       : |gpu - ref| <= 1e-4 |ref| + 1e-6 * loss_scale * sum|A|
   mask       : bit-exact, except tokens with |D_ref - delta| < 1e-6 or, where the divergence can
-               exceed delta while r is at 1 (Top-K variants), |log pi(a) - log mu(a)| < 1e-6
+               exceed delta while r is at 1 (Top-K variants), |log pi(a) - log mu(a)| < 1e-6;
+               under the ratio-clip rule, except tokens with log r within 1e-6 of a clip boundary
   diagnostics: ratio 1e-4 rel; log pi(a) 1e-6 rel + 5e-6; |pi - mu| and covered masses 1e-6;
                entropy 1e-4 rel + 1e-5
   grad_logits: |gpu - ref| <= 1e-2 |ref| + 1e-30   (bf16 output, round to nearest even); the
@@ -35,7 +36,7 @@ def oracle_rows(batch: dict, rows, want_grad=True) -> dict:
     tk_l = batch["mu_topk_logp"][sel].cpu().numpy() if batch["mu_topk_logp"] is not None else None
     return O.dppo_loss(z, batch["sampled_ids"][sel].cpu().numpy(), batch["mu_logp"][sel].cpu().numpy(),
                        batch["advantages"][sel].cpu().numpy(), batch["delta"], batch["variant"],
-                       batch["loss_scale"], tk_i, tk_l, want_grad=want_grad)
+                       batch["loss_scale"], tk_i, tk_l, want_grad=want_grad, **batch.get("rule", {}))
 
 
 def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, ref=None) -> dict:
@@ -54,16 +55,24 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
     errD = np.abs(D - ref["divergence"])
     assert np.all(errD <= RTOL_D * np.abs(ref["divergence"]) + ATOL_D), \
         f"divergence: max err {errD.max():.3e} at row {rows[errD.argmax()]}"
-    exempt = np.abs(ref["divergence"] - delta) < BAND
-    if batch["variant"] in (O.TOPK_TV, O.TOPK_KL):
-        exempt |= np.abs(ref["logp"] - lmu) < BAND
+    rule = batch.get("rule", {})
+    mask_rule = rule.get("mask_rule", O.MASK_DIVERGENCE)
+    if mask_rule == O.MASK_DIVERGENCE:
+        exempt = np.abs(ref["divergence"] - delta) < BAND
+        if batch["variant"] in (O.TOPK_TV, O.TOPK_KL):
+            exempt |= np.abs(ref["logp"] - lmu) < BAND
+    elif mask_rule == O.MASK_RATIO_CLIP:      # log r within the band of either clip boundary
+        dl = ref["logp"] - lmu
+        exempt = (np.abs(dl - np.log1p(rule["eps_high"])) < BAND) | (np.abs(dl - np.log1p(-rule["eps_low"])) < BAND)
+    else:
+        exempt = np.zeros(len(rows), dtype=bool)
     bad = (M != ref["mask"]) & ~exempt
     assert not bad.any(), f"mask differs outside the band at rows {rows[bad][:8]}"
     assert np.all((M == 0) | (M == 1))
 
     if res.get("loss_tok") is not None:
         lt = res["loss_tok"][loc].double().cpu().numpy()
-        lt_ref = np.where(M == ref["mask"], ref["loss_tok"], -M * ref["ratio"] * A)
+        lt_ref = np.where(M == ref["mask"], ref["loss_tok"], -M * ref["weight"] * A)
         errL = np.abs(lt - lt_ref)
         assert np.all(errL <= RTOL_D * np.abs(lt_ref) + 1e-6 * np.abs(A)), f"loss_tok: max err {errL.max():.3e}"
     stats = {"max_abs_err_D": float(errD.max()) if len(rows) else 0.0, "masked": int((M == 0).sum()),
@@ -100,7 +109,7 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
         # The oracle forms the sampled token's entry as c*(pi_a - 1) in float64: when pi_a -> 1
         # that difference carries the oracle's own rounding, 2^-52 * |c|.  Allow for it there.
         a_ids = batch["sampled_ids"][torch.as_tensor(rows).to(batch["sampled_ids"].device)].cpu().numpy()
-        c_ref = np.abs(batch["loss_scale"] * M * A * ref["ratio"])
+        c_ref = np.abs(batch["loss_scale"] * M * A * ref["weight"])
         for i, a in enumerate(a_ids):
             if 0 <= a < V:
                 tol[i, a] += 4 * np.finfo(np.float64).eps * c_ref[i]
@@ -113,9 +122,9 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
 
 
 def oracle_single_grad_unmasked(batch: dict, row: int) -> np.ndarray:
-    """Oracle gradient of one row with M forced to 1 (delta = +inf)."""
+    """Oracle gradient of one row with M forced to 1."""
     b = dict(batch)
-    b["delta"] = float("inf")
+    b["rule"] = dict(batch.get("rule", {}), mask_rule=O.MASK_NONE)
     return oracle_rows(b, [row])["grad_logits"][0]
 
 

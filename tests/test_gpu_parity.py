@@ -21,12 +21,14 @@ def _say(msg):
 
 
 def _run_and_compare(w, *, backward=True, in_place=False, flags=0, ld=None, shift=0.0, rows=None,
-                     check_grad=True, **mk):
-    _say(f"[case] {w.name} T={w.T} V={w.V} K={w.K} variant={w.variant} ld={ld} in_place={in_place} flags={flags} shift={shift}")
+                     check_grad=True, rule=None, **mk):
+    _say(f"[case] {w.name} T={w.T} V={w.V} K={w.K} variant={w.variant} ld={ld} in_place={in_place} flags={flags} shift={shift} rule={rule}")
     b = W.make_batch(w, DEV, ld=ld, shift_sampled=shift, **mk)
+    rule = rule or {}
+    b["rule"] = rule
     rows = np.arange(b["T"]) if rows is None else rows
     ref = P.oracle_rows(b, rows, want_grad=backward and check_grad)   # before an in-place run overwrites the logits
-    res = B.run_batch(b, backward=backward, in_place=in_place, flags=flags, diagnostics=True)
+    res = B.run_batch(b, backward=backward, in_place=in_place, flags=flags, diagnostics=True, **rule)
     torch.cuda.synchronize()
     st = P.compare_rows(b, res, rows, check_grad=backward and check_grad, ref=ref)
     if len(rows) == b["T"]:
@@ -123,6 +125,28 @@ def test_resident_saturated_rows():
     assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["grad_logits"].float()).all()
     st = P.compare_rows(b, res, np.arange(b["T"]))
     _say(f"       {st}")
+
+
+# --------------------------------------------------------------------------- baselines' masks, ratio cap
+@pytest.mark.parametrize("rule", [
+    dict(mask_rule=B.MASK_NONE),                                              # PG-IS
+    dict(mask_rule=B.MASK_NONE, ratio_cap=3.0),                               # PG-TIS / CISPO
+    dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28),            # GRPO with Clip-Higher
+    dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.27, ratio_cap=5.0),
+    dict(mask_rule=B.MASK_DIVERGENCE, ratio_cap=5.0),                         # DPPO with the default cap of App. E
+    dict(mask_rule=B.MASK_DIVERGENCE, ratio_cap=float("inf")),
+])
+@pytest.mark.parametrize("V,flags", [(16384, 0), (3001, 0), (16384, B.FLAG_FORCE_STREAMING)])
+def test_mask_rules_and_ratio_cap(rule, V, flags):
+    w = W.Workload("rules", 4, 24, V, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=1.0, adv="normal", seed=43)
+    b, res, st = _run_and_compare(w, shift=2.0, rule=rule, flags=flags)
+    if rule["mask_rule"] == B.MASK_NONE:
+        assert st["masked"] == 0
+    else:
+        assert 0 < st["masked"] < b["T"]
+    if rule.get("ratio_cap", 0) and rule["ratio_cap"] < float("inf"):
+        r = res["diagnostics"][:, B.DIAG_RATIO]
+        assert (r > rule["ratio_cap"]).any()           # the cap bites on some tokens
 
 
 # --------------------------------------------------------------------------- edge cases

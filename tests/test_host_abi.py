@@ -70,6 +70,12 @@ def _valid_args():
     (lambda a: setattr(a, "workspace", None), 6),
     (lambda a: setattr(a, "workspace_bytes", 16), 6),
     (lambda a: setattr(a, "delta", float("nan")), 8),
+    (lambda a: setattr(a, "ratio_cap", float("nan")), 8),
+    (lambda a: setattr(a, "mask_rule", 3), 8),
+    (lambda a: setattr(a, "mask_rule", -1), 8),
+    (lambda a: (setattr(a, "mask_rule", B.MASK_RATIO_CLIP), setattr(a, "eps_low", 1.0), setattr(a, "eps_high", 0.2)), 8),
+    (lambda a: (setattr(a, "mask_rule", B.MASK_RATIO_CLIP), setattr(a, "eps_low", 0.2), setattr(a, "eps_high", -0.1)), 8),
+    (lambda a: setattr(a, "diagnostics", 0x5008), 3),
 ])
 def test_argument_validation_codes(mutate, code):
     a = _valid_args()

@@ -30,11 +30,20 @@ MUTATIONS = [
     ("mask: wrong side for negative advantage", "(adv < 0.0 and lpi_a < lmu_a)", "(adv < 0.0 and lpi_a > lmu_a)"),
     ("mask: symmetric (blocks moves toward r = 1 too)", "if D > delta and ((adv > 0.0 and lpi_a > lmu_a) or (adv < 0.0 and lpi_a < lmu_a)):",
      "if D > delta and adv != 0.0:"),
-    ("loss sign", 'out["loss_tok"][t] = -M * r * A', 'out["loss_tok"][t] = M * r * A'),
-    ("loss ignores mask", 'out["loss_tok"][t] = -M * r * A', 'out["loss_tok"][t] = -r * A'),
+    ("loss sign", 'out["loss_tok"][t] = -M * w * A', 'out["loss_tok"][t] = M * w * A'),
+    ("loss ignores mask", 'out["loss_tok"][t] = -M * w * A', 'out["loss_tok"][t] = -w * A'),
     ("grad: one-hot not subtracted", "g[a] -= 1.0", "g[a] -= 0.0"),
-    ("grad: ratio missing", "(loss_scale * M * A * r) * g", "(loss_scale * M * A) * g"),
-    ("grad: sign", "(loss_scale * M * A * r) * g", "(-loss_scale * M * A * r) * g"),
+    ("grad: ratio missing", "(loss_scale * M * A * w) * g", "(loss_scale * M * A) * g"),
+    ("grad: sign", "(loss_scale * M * A * w) * g", "(-loss_scale * M * A * w) * g"),
+    ("cap: max instead of min", "min(r, float(ratio_cap))", "max(r, float(ratio_cap))"),
+    ("cap ignored in the gradient", "(loss_scale * M * A * w) * g", "(loss_scale * M * A * r) * g"),
+    ("clip mask: eps_low and eps_high swapped", "if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):",
+     "if (adv > 0.0 and d > np.log1p(eps_low)) or (adv < 0.0 and d < np.log1p(-eps_high)):"),
+    ("clip mask: symmetric in the advantage", "if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):",
+     "if d > np.log1p(eps_high) or d < np.log1p(-eps_low):"),
+    ("mask rule none still masks", "            M = 1\n", "            M = dppo_mask(D, delta, A, lpi, lmu)\n"),
+    ("entropy sign", "return float(-(pi[nz] * logpi[nz]).sum())", "return float((pi[nz] * logpi[nz]).sum())"),
+    ("covered mass of pi uses mu", "mass_mu, mass_pi = p.sum(), q.sum()", "mass_mu, mass_pi = p.sum(), p.sum()"),
     ("full TV: half missing", "return 0.5 * np.abs(mu_probs - pi_probs).sum()", "return np.abs(mu_probs - pi_probs).sum()"),
     ("binary KL uses clamped-away 1-q", "one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()", "one_minus_q = pi_row[:a].sum()"),
 ]

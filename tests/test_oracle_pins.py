@@ -433,3 +433,50 @@ def test_diagnostics_entropy_abs_diff_and_covered_mass():
     outb = _run(hb, variant=O.BINARY_TV)
     np.testing.assert_allclose(outb["mass_pi"], np.exp(outb["logp"]), rtol=1e-12)
     np.testing.assert_allclose(outb["abs_diff"], outb["divergence"], rtol=1e-12)
+
+
+# ------------------------------------------------------------------ baselines of App. C.1 / App. E
+def test_ratio_clip_mask_truth_table_and_hyperparameters():
+    """GRPO-ClipHigher: M = 0 iff (A > 0 and r > 1 + eps_high) or (A < 0 and r < 1 - eps_low)."""
+    for eps_low, eps_high in ((0.2, 0.28), (0.2, 0.27), (0.2, 0.2)):
+        for adv in (-1.0, 0.0, 1.0):
+            for r in (0.5, 1 - eps_low - 1e-9, 1 - eps_low + 1e-9, 1.0, 1 + eps_high - 1e-9, 1 + eps_high + 1e-9, 3.0):
+                want = 0 if ((adv > 0 and r > 1 + eps_high) or (adv < 0 and r < 1 - eps_low)) else 1
+                lmu = -2.0
+                assert O.ratio_clip_mask(adv, lmu + math.log(r), lmu, eps_low, eps_high) == want, (adv, r)
+    # the tokens of App. D: "r > 1.28" on positive samples and "r < 0.8" on negative ones are clipped
+    assert O.ratio_clip_mask(1.0, math.log(1.29), 0.0, 0.2, 0.28) == 0
+    assert O.ratio_clip_mask(-1.0, math.log(0.79), 0.0, 0.2, 0.28) == 0
+    assert O.ratio_clip_mask(1.0, math.log(0.5), 0.0, 0.2, 0.28) == 1      # moving back toward r = 1 is never blocked
+    assert O.ratio_clip_mask(-1.0, math.log(2.0), 0.0, 0.2, 0.28) == 1
+
+
+def test_unified_gradient_form_masks_and_cap():
+    h = _small_batch(O.BINARY_TV, 0, V=65, shift=3.0, noise=0.5)
+    base = _run(h)
+    # C = infinity and the divergence mask: nothing changes
+    same = _run(h, ratio_cap=float("inf"), mask_rule=O.MASK_DIVERGENCE)
+    np.testing.assert_array_equal(same["grad_logits"], base["grad_logits"])
+    # PG-IS: M = 1, C = infinity
+    pgis = _run(h, mask_rule=O.MASK_NONE)
+    assert np.all(pgis["mask"] == 1)
+    assert pgis["loss"] == pytest.approx(-h["loss_scale"] * (pgis["ratio"] * h["advantages"]).sum(), rel=1e-12)
+    # CISPO / PG-TIS: M = 1, C = 3; GRPO: clip mask, C = infinity; a capped DPPO
+    for kw in (dict(mask_rule=O.MASK_NONE, ratio_cap=3.0), dict(mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28),
+               dict(mask_rule=O.MASK_DIVERGENCE, ratio_cap=5.0), dict(mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.27, ratio_cap=5.0)):
+        out = _run(h, **kw)
+        C = kw.get("ratio_cap", float("inf"))
+        np.testing.assert_allclose(out["weight"], np.minimum(out["ratio"], C), rtol=1e-12)
+        if C < float("inf"):
+            assert (out["ratio"] > C).any() and (out["ratio"] < C).any()       # the cap bites on some tokens only
+        # Eq. unified_grad: gradient = M * min(r, C) * A * grad log pi(a), weight held constant
+        z = torch.tensor(h["logits"], dtype=torch.float64, requires_grad=True)
+        lp = torch.log_softmax(z, -1).gather(1, torch.tensor(h["sampled_ids"], dtype=torch.int64)[:, None]).squeeze(1)
+        coef = torch.tensor(out["mask"] * out["weight"] * h["advantages"], dtype=torch.float64)
+        (-(coef * lp).sum() * h["loss_scale"]).backward()
+        np.testing.assert_allclose(out["grad_logits"], z.grad.numpy(), rtol=1e-9, atol=1e-15)
+        if kw["mask_rule"] == O.MASK_RATIO_CLIP:
+            want = [O.ratio_clip_mask(float(a), float(lp_), float(lm), kw["eps_low"], kw["eps_high"])
+                    for a, lp_, lm in zip(h["advantages"], out["logp"], h["mu_logp"])]
+            np.testing.assert_array_equal(out["mask"], want)
+            assert 0 < int((out["mask"] == 0).sum()) < h["T"]
