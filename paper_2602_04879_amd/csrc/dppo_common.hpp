@@ -33,9 +33,7 @@ struct KParams {
   float ratio_cap;          // C of the unified gradient form; 0 = no cap
 };
 
-// The subset of the arguments the per-row epilogue needs.  Each kernel makes ONE copy of it at
-// its start and hands the epilogue a reference to that copy: taking the address of the
-// kernel-argument struct itself would move all of it from scalar registers to the stack.
+// The subset of the kernel arguments the per-row epilogue needs.
 struct EpiParams {
   const int32_t* tk_ids;
   const float* tk_lp;
@@ -266,12 +264,9 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
 // mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
 // Lane 0 stores the per-token outputs; every lane returns the same RowResult.
-// Deliberately NOT inlined: as a real call, the registers it needs are saved and restored
-// around it by the one wave that runs it, instead of raising the register pressure of the
-// streaming phases that every wave runs.
-// Everything but the kernel arguments is passed and returned by value, i.e. in registers.
-__device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
-                                                                   const uint16_t* zrow, float b, double S_rest, double T_rest, int lane) {
+// Inlined into its caller; row_epilogue_call below is the same as a real call.
+__device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
+                                                  const uint16_t* zrow, float b, double S_rest, double T_rest, int lane) {
   constexpr double kL = static_cast<double>(kLog2e);
   const double bd = static_cast<double>(b);
   const double xa = static_cast<double>(rs.za) * kL + bd;   // log2 of a_t's own term
@@ -360,6 +355,16 @@ __device__ __attribute__((noinline)) static RowResult row_epilogue(const EpiPara
   // c * pi_j = sgn(c) * 2^(z_j*log2e + kexp)
   res.rc.kexp = (c != 0.0 && fabs(c) < 1e300) ? static_cast<float>(log2_fast(fabs(c)) + bd - log2S) : 0.f;
   return res;
+}
+
+// The same epilogue as a real call.  Its float64 arithmetic needs some 50 registers; where
+// several workgroups share a compute unit, keeping those out of the kernel's register budget
+// (the call saves and restores what it needs, in the one wave that makes it) buys occupancy,
+// and the other workgroups hide the call's latency.
+__device__ __attribute__((noinline)) static RowResult row_epilogue_call(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
+                                                                        const uint16_t* zrow, float b, double S_rest, double T_rest,
+                                                                        int lane) {
+  return row_epilogue(p, row, rs, tk, zrow, b, S_rest, T_rest, lane);
 }
 
 }  // namespace dppo

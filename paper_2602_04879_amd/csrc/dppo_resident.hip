@@ -232,7 +232,17 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
           S_rest += sh_s[w] * sc;
           T_rest += sc * (sh_t[w] + dd * sh_s[w]);
         }
-        const RowResult rr = row_epilogue(ep, row, rs, tk, zrow, bb, S_rest, T_rest, lane);
+        // Shapes whose row data alone leaves room for one workgroup per compute unit: nothing
+        // hides a call there, so the epilogue is inlined.  The shorter shapes keep the call and
+        // with it the second or third workgroup per compute unit.
+        // The row index goes through an empty asm statement first, so that the addresses of the
+        // per-token outputs are formed here and not hoisted to the top of the row, where they
+        // would sit in registers (or be spilled) across the streaming phases.
+        constexpr bool kInlineEpilogue = (THREADS == 512 && NCHUNK >= (GRAD ? 16 : 28));
+        int row_e = row;
+        asm volatile("" : "+s"(row_e));
+        const RowResult rr = kInlineEpilogue ? row_epilogue(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane)
+                                             : row_epilogue_call(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane);
         rc = rr.rc;
         loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
         rs.lmu = p.mu_logp[row];
         rs.adv = p.adv[row];
         const TopkLane tk = load_topk_lane(p, row, a, zrow, lane);
-        const RowResult res = row_epilogue(ep, row, rs, tk, zrow, b, S_rest, T_rest, lane);
+        const RowResult res = row_epilogue_call(ep, row, rs, tk, zrow, b, S_rest, T_rest, lane);
         rc = res.rc;
         loss_acc += res.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;

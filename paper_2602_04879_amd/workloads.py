@@ -36,6 +36,8 @@ class Workload:
     boost_frac: float = 0.0       # fraction of vocabulary ids whose logit gets +boost
     boost: float = 0.0
     temperature: tuple | None = None   # per-token temperature ~ U(lo, hi) applied before the bf16 cast
+    drift_frac: float = 0.0       # fraction of tokens whose sampled-token logit has moved since the
+    drift_std: float = 0.0        # rollout (policy updates in between), by N(0, drift_std)
     adv: str = "pm1"              # "pm1" | "normal" | "group_norm"
     group: int = 8
     chunk_rows: int = 0           # caller-side T-chunking (0 = one call)
@@ -56,14 +58,14 @@ WORKLOADS = {
     "c2_binary_kl": Workload("c2_binary_kl", 16, 512, 32768, BINARY_KL, 0.1, logit_std=3.0,
                              noise_std=0.1, boost_frac=0.01, boost=8.0, adv="normal", seed=1001),
     "c3_qwen3_binary_tv": Workload("c3_qwen3_binary_tv", 16, 2048, 151936, BINARY_TV, 0.2,
-                                   logit_std=3.0, noise_std=0.05, zipf_s=1.1, adv="group_norm",
-                                   group=8, seed=1002),
+                                   logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                   adv="group_norm", group=8, seed=1002),
     "c4_qwen3_topk_tv": Workload("c4_qwen3_topk_tv", 16, 2048, 151936, TOPK_TV, 0.2, K=20,
-                                 logit_std=3.0, noise_std=0.05, zipf_s=1.1, adv="group_norm",
-                                 group=8, seed=1002),
+                                 logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                 adv="group_norm", group=8, seed=1002),
     "c5_long_topk_kl": Workload("c5_long_topk_kl", 32, 4096, 151936, TOPK_KL, 0.05, K=64,
                                 logit_std=3.0, noise_std=0.1, zipf_s=1.1, temperature=(0.6, 1.2),
-                                adv="pm1", chunk_rows=16384, seed=1004),
+                                drift_frac=0.05, drift_std=1.5, adv="pm1", chunk_rows=16384, seed=1004),
 }
 
 
@@ -170,6 +172,13 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
             sgn = torch.where((rows + r0) % 2 == 0, 1.0, -1.0)
             zf = zb.float()
             zf[rows, a] += sgn * shift_sampled
+            zb = zf.to(torch.bfloat16)
+        if w.drift_frac > 0:
+            moved = torch.rand(n, generator=g, device=dev) < w.drift_frac
+            step = w.drift_std * torch.randn(n, generator=g, device=dev)
+            zf = zb.float()
+            rows = torch.arange(n, device=dev)
+            zf[rows, a] += torch.where(moved, step, torch.zeros_like(step))
             zb = zf.to(torch.bfloat16)
         logits[r0:r1, :V] = zb
 
