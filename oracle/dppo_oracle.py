@@ -17,7 +17,8 @@ order and notation of the paper:
                                                    Eq. topk_tv, Eq. topk_kl)
   * DPPO mask and masked surrogate                (Eq. dppo_obj)
   * gradient wrt the logits, mask held constant   (Eq. unified_grad with C = infinity)
-  * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL)
+  * exact full-vocabulary TV / KL (brute force)   (App. B, definitions of D_TV, D_KL); also as
+    the divergence of the trust region itself when the rollout policy's full logits are given
   * the baselines' masks and the ratio cap         (App. C.1: unified gradient form,
                                                     Eq. unified_grad; PPO/GRPO clip mask;
                                                     M = 1 for PG-IS / CISPO; cap C)
@@ -30,7 +31,9 @@ Readings taken where the paper is silent:
     loss_scale is the caller's normalisation (the paper writes an expectation of a sum);
   - KL is D(mu || pi) in nats;
   - comparisons are strict, and "r > 1" is evaluated as log pi(a) > log mu(a);
-  - x*log(x/y) = 0 when x = 0; a vanishing denominator y is floored at 1e-30;
+  - x*log(x/y) = 0 when x = 0; a vanishing denominator y is floored at 1e-30 (the exact
+    full-vocabulary KL used as a trust region has no floor: it is infinite where pi excludes a
+    token that mu can sample);
   - mu probabilities > 1 from rounding are clamped to 1, and the "other" bucket of either
     policy is clamped to >= 0;
   - a top-K id equal to a_t is dropped (a_t's own mu log-prob is used), ids outside [0, V)
@@ -50,10 +53,11 @@ from __future__ import annotations
 
 import numpy as np
 
-BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL, FULL_TV, FULL_KL = 0, 1, 2, 3, 4, 5
 MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
 VARIANT_NAMES = {BINARY_TV: "binary_tv", BINARY_KL: "binary_kl",
-                 TOPK_TV: "topk_tv", TOPK_KL: "topk_kl"}
+                 TOPK_TV: "topk_tv", TOPK_KL: "topk_kl",
+                 FULL_TV: "full_tv", FULL_KL: "full_kl"}
 _TINY = 1e-30
 
 
@@ -147,6 +151,20 @@ def full_kl(mu_probs, pi_probs):
     return d
 
 
+def full_kl_from_logs(lmu, lpi):
+    """Exact D_KL(mu || pi) = sum_a mu(a) (ln mu(a) - ln pi(a)) from the two rows of log-probs
+    (App. B.2), with 0 ln 0 = 0 and no floor: a token pi excludes (ln pi = -inf) that mu can
+    still sample makes the divergence infinite, as the definition does."""
+    lmu = np.asarray(lmu, dtype=np.float64)
+    lpi = np.asarray(lpi, dtype=np.float64)
+    d = 0.0
+    for x, y in zip(lmu.tolist(), lpi.tolist()):
+        if x == -np.inf:
+            continue
+        d += np.exp(x) * (x - y)
+    return d
+
+
 def entropy(logpi):
     """Token entropy -sum_j pi_j ln pi_j in nats, 0 ln 0 = 0  (the "policy entropy" of App. F.1)."""
     logpi = np.asarray(logpi, dtype=np.float64)
@@ -176,14 +194,17 @@ def ratio_clip_mask(adv, lpi_a, lmu_a, eps_low, eps_high):
 # --------------------------------------------------------------------------- whole path
 def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
               mu_topk_ids=None, mu_topk_logp=None, want_grad=True,
-              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=None):
+              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=None,
+              mu_logits=None):
     """The whole hot path for T rows.
 
     logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
     mu_logp [T], advantages [T], optional mu_topk_ids / mu_topk_logp [T, K].
     mask_rule picks M_t: the DPPO divergence mask (default), the PPO/GRPO ratio-clip mask with
     eps_low / eps_high, or none (M = 1: PG-IS, CISPO).  ratio_cap is C of Eq. unified_grad
-    (None or inf: no cap).
+    (None or inf: no cap).  The FULL_TV / FULL_KL variants take the trust region on the exact
+    divergence between the two next-token distributions (App. B) and need mu_logits [T, V], the
+    rollout policy's logits (any shift of a row is immaterial); the ratio still uses mu_logp.
     Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
     ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None, and the
     diagnostics abs_diff [T] = |pi(a_t) - mu(a_t)|, entropy [T], mass_mu [T], mass_pi [T]
@@ -197,6 +218,8 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     topk = variant in (TOPK_TV, TOPK_KL)
     if variant not in VARIANT_NAMES:
         raise ValueError("unknown variant")
+    if variant in (FULL_TV, FULL_KL) and mu_logits is None:
+        raise ValueError("the full-vocabulary variants need mu_logits")
 
     out = {
         "loss_tok": np.zeros(T), "divergence": np.zeros(T), "mask": np.zeros(T, dtype=np.uint8),
@@ -221,6 +244,10 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
             pi_row = np.exp(logpi)
             one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()
             D = binary_kl(lmu, lpi, one_minus_q)
+        elif variant in (FULL_TV, FULL_KL):
+            logmu = log_softmax(np.asarray(mu_logits[t], dtype=np.float64))
+            D = full_tv(np.exp(logmu), np.exp(logpi)) if variant == FULL_TV else full_kl_from_logs(logmu, logpi)
+            mass_mu, mass_pi = 1.0, 1.0              # A' is the whole vocabulary
         else:
             ids = mu_topk_ids[t] if (mu_topk_ids is not None) else None
             lps = mu_topk_logp[t] if (mu_topk_logp is not None) else None

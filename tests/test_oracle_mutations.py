@@ -45,6 +45,12 @@ MUTATIONS = [
     ("entropy sign", "return float(-(pi[nz] * logpi[nz]).sum())", "return float((pi[nz] * logpi[nz]).sum())"),
     ("covered mass of pi uses mu", "mass_mu, mass_pi = p.sum(), q.sum()", "mass_mu, mass_pi = p.sum(), p.sum()"),
     ("full TV: half missing", "return 0.5 * np.abs(mu_probs - pi_probs).sum()", "return np.abs(mu_probs - pi_probs).sum()"),
+    ("full KL as trust region: direction swapped", "d += np.exp(x) * (x - y)", "d += np.exp(y) * (y - x)"),
+    ("full KL as trust region: weight missing", "d += np.exp(x) * (x - y)", "d += (x - y)"),
+    ("full variants: rollout logits not normalised", "logmu = log_softmax(np.asarray(mu_logits[t], dtype=np.float64))",
+     "logmu = np.asarray(mu_logits[t], dtype=np.float64)"),
+    ("full variants: TV and KL swapped", "if variant == FULL_TV else full_kl_from_logs(logmu, logpi)",
+     "if variant == FULL_KL else full_kl_from_logs(logmu, logpi)"),
     ("binary KL uses clamped-away 1-q", "one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()", "one_minus_q = pi_row[:a].sum()"),
 ]
 

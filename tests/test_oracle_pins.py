@@ -480,3 +480,54 @@ def test_unified_gradient_form_masks_and_cap():
                     for a, lp_, lm in zip(h["advantages"], out["logp"], h["mu_logp"])]
             np.testing.assert_array_equal(out["mask"], want)
             assert 0 < int((out["mask"] == 0).sum()) < h["T"]
+
+
+# ------------------------------------------------------------------ exact divergence as the trust region (App. B)
+def test_full_kl_from_logs_is_the_library_relative_entropy():
+    for V in (2, 9, 300):
+        mu, pi = _rand_dist(V, True), _rand_dist(V, True)
+        d = O.full_kl_from_logs(np.log(mu), np.log(pi))
+        assert d == pytest.approx(float(scipy.special.rel_entr(mu, pi).sum()), rel=1e-10)
+        assert d == pytest.approx(O.full_kl(mu, pi), rel=1e-10)
+        assert d != pytest.approx(float(scipy.special.rel_entr(pi, mu).sum()), rel=1e-3)     # the direction is mu || pi
+    # 0 ln 0 = 0: a token mu never samples adds nothing, whatever pi gives it
+    assert O.full_kl_from_logs([math.log(0.5), math.log(0.5), -np.inf], np.log([0.25, 0.25, 0.5])) == pytest.approx(math.log(2))
+    # pi excludes a token mu can sample: infinite, as the definition is
+    assert O.full_kl_from_logs(np.log([0.5, 0.5]), [0.0, -np.inf]) == np.inf
+
+
+@pytest.mark.parametrize("variant", [O.FULL_TV, O.FULL_KL])
+def test_full_variants_use_the_exact_divergence_of_the_two_rows(variant):
+    V, T = 50, 40
+    rng = np.random.default_rng(77)
+    z = rng.normal(0, 2.0, size=(T, V))
+    y = z + rng.normal(0, 0.7, size=(T, V)) + rng.normal(0, 5.0, size=(T, 1))     # a row shift of the logits is immaterial
+    mu = scipy.special.softmax(y, axis=1)
+    pi = scipy.special.softmax(z, axis=1)
+    a = np.array([rng.choice(V, p=mu[t]) for t in range(T)])
+    lmu_a = np.log(mu[np.arange(T), a])
+    adv = rng.choice([-1.0, 1.0], size=T)
+    delta = 0.25 if variant == O.FULL_TV else 0.2
+    out = O.dppo_loss(z, a, lmu_a, adv, delta, variant, mu_logits=y)
+    want = 0.5 * np.abs(mu - pi).sum(1) if variant == O.FULL_TV else scipy.special.rel_entr(mu, pi).sum(1)
+    np.testing.assert_allclose(out["divergence"], want, rtol=1e-10)
+    # the mask is Eq. dppo_obj on that divergence
+    r = pi[np.arange(T), a] / mu[np.arange(T), a]
+    blocked = (want > delta) & (((adv > 0) & (r > 1)) | ((adv < 0) & (r < 1)))
+    np.testing.assert_array_equal(out["mask"], 1 - blocked.astype(np.uint8))
+    assert 0 < blocked.sum() < T
+    np.testing.assert_array_equal(out["mass_mu"], 1.0)
+    np.testing.assert_array_equal(out["mass_pi"], 1.0)
+    # every approximation of Sec. 4.4 lower-bounds it (App. B), token by token
+    ids = np.argsort(-mu, axis=1, kind="stable")[:, :6]
+    lps = np.log(np.take_along_axis(mu, ids, 1))
+    vb, vk = (O.BINARY_TV, O.TOPK_TV) if variant == O.FULL_TV else (O.BINARY_KL, O.TOPK_KL)
+    Db = O.dppo_loss(z, a, lmu_a, adv, delta, vb)["divergence"]
+    Dk = O.dppo_loss(z, a, lmu_a, adv, delta, vk, mu_topk_ids=ids, mu_topk_logp=lps)["divergence"]
+    assert np.all(Db <= Dk + 1e-13) and np.all(Dk <= out["divergence"] + 1e-13)
+    # identical policies: zero divergence, nothing masked
+    same = O.dppo_loss(z, a, np.log(pi[np.arange(T), a]), adv, delta, variant, mu_logits=z + 3.0)
+    np.testing.assert_allclose(same["divergence"], 0.0, atol=1e-14)
+    assert np.all(same["mask"] == 1)
+    with pytest.raises(ValueError):
+        O.dppo_loss(z, a, lmu_a, adv, delta, variant)
