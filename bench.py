@@ -24,7 +24,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c3_qwen3_binary_tv"
-DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_streaming_kernel"}
+DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_streaming_kernel",
+                   "fullvocab": "dppo_fullvocab_kernel"}
 
 
 def kernel_source_hash() -> str:
@@ -52,12 +53,13 @@ def stored_traffic(workload: str, path: str):
     return rec.get("bytes_per_launch")
 
 
-def algorithmic_bytes_per_token(V: int, K: int) -> int:
+def algorithmic_bytes_per_token(V: int, K: int, full: bool = False) -> int:
     """What the method itself must move per token, forward + backward: the bf16 logits row read
-    once, the bf16 gradient row written once, and the per-token side inputs/outputs."""
+    once (and, for the exact full-vocabulary variants, the rollout policy's bf16 row read once),
+    the bf16 gradient row written once, and the per-token side inputs/outputs."""
     side_in = 4 + 4 + 4 + 8 * K          # sampled id, mu log-prob, advantage, top-K ids + log-probs
     side_out = 4 + 4 + 1                 # divergence, per-token loss, mask
-    return 2 * V + 2 * V + side_in + side_out
+    return 2 * V + (2 * V if full else 0) + 2 * V + side_in + side_out
 
 
 def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
@@ -75,7 +77,9 @@ def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
         tk_i = batch["mu_topk_ids"][sl].cpu().numpy() if batch["mu_topk_ids"] is not None else None
         tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
         t0, c0 = time.perf_counter(), time.process_time()
-        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=True)
+        y = batch["mu_logits"][sl, :V].float().cpu().numpy() if batch.get("mu_logits") is not None else None
+        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=True,
+                    mu_logits=y)
         wall += time.perf_counter() - t0
         cpu += time.process_time() - c0
         done += len(ids)
@@ -128,7 +132,8 @@ def main() -> int:
         a = B.make_args(batch["logits"][sl], batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
                         batch["delta"], batch["variant"], batch["loss_scale"], o,
                         batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
-                        V=V, flags=flags, grad_logits=grad[sl])
+                        V=V, flags=flags, grad_logits=grad[sl],
+                        mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None)
         a.ld = batch["ld"]
         calls.append((a, o))
 
@@ -169,7 +174,7 @@ def main() -> int:
             ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
 
     launches = len(calls)
-    alg_bytes_launch = algorithmic_bytes_per_token(V, K) * (T // launches)
+    alg_bytes_launch = algorithmic_bytes_per_token(V, K, batch.get("mu_logits") is not None) * (T // launches)
     kernel_ms = ms_per_step / launches           # the step is the dominant kernel plus a ~3 us reduction
     achieved = alg_bytes_launch / (kernel_ms * 1e-3) / 1e9
     loss = sum(float(o["loss"].item()) for _, o in calls)

@@ -11,6 +11,8 @@
  *   D_t            = Binary-TV | Binary-KL | Top-K-TV | Top-K-KL of (mu || pi)    (Eq. binary_tv,
  *                    over {a_t, rest} or over TopK(mu,K) U {a_t} U {other}         binary_kl,
  *                                                                                  topk_tv, topk_kl)
+ *                    or, given the rollout policy's full logits, the exact full-vocabulary
+ *                    TV / KL those approximate                                     (App. B)
  *   M_t            = 0 iff D_t > delta and ((A_t>0 and r_t>1) or (A_t<0 and r_t<1)), else 1
  *                                                                                  (Eq. dppo_obj)
  *   loss           = loss_scale * sum_t ( - M_t r_t A_t )      (the negated objective of
@@ -40,7 +42,7 @@
 extern "C" {
 #endif
 
-#define DPPO_VERSION 100          /* major*10000 + minor*100 + patch                          */
+#define DPPO_VERSION 200          /* major*10000 + minor*100 + patch                          */
 #define DPPO_KMAX 1024            /* largest accepted K                                        */
 #define DPPO_WORKSPACE_BYTES 65536
 
@@ -61,7 +63,12 @@ typedef enum {
   DPPO_BINARY_TV = 0,             /* |mu(a_t) - pi(a_t)|                       (Eq. binary_tv) */
   DPPO_BINARY_KL = 1,             /* Bernoulli KL on {a_t, not a_t}            (Eq. binary_kl) */
   DPPO_TOPK_TV   = 2,             /* 1/2 sum over A'' of |p_mu - p_pi|         (Eq. topk_tv)   */
-  DPPO_TOPK_KL   = 3              /* sum over A'' of p_mu ln(p_mu / p_pi)      (Eq. topk_kl)   */
+  DPPO_TOPK_KL   = 3,             /* sum over A'' of p_mu ln(p_mu / p_pi)      (Eq. topk_kl)   */
+  /* The exact divergences the four above lower-bound (App. B), over the whole vocabulary;
+   * they need `mu_logits`.  KL has no floor: it is +inf where pi excludes (logit -inf) a token
+   * that mu can sample. */
+  DPPO_FULL_TV   = 4,             /* 1/2 sum_j |mu_j - pi_j|                   (App. B.1)      */
+  DPPO_FULL_KL   = 5              /* sum_j mu_j ln(mu_j / pi_j)                (App. B.2)      */
 } dppo_variant_t;
 
 /* Which mask M_t gates the update (unified gradient form, App. C.1, Eq. unified_grad). */
@@ -74,9 +81,11 @@ typedef enum {
 
 typedef enum {
   DPPO_OK = 0,
-  DPPO_ERR_NULL = 1,              /* a required pointer is NULL                                */
-  DPPO_ERR_SHAPE = 2,             /* T < 0, V < 1, ld < V, or sizes beyond int32 row indexing  */
-  DPPO_ERR_ALIGN = 3,             /* logits / grad_logits not 2-byte aligned, workspace not 8, */
+  DPPO_ERR_NULL = 1,              /* a required pointer is NULL (mu_logits for DPPO_FULL_*)    */
+  DPPO_ERR_SHAPE = 2,             /* T < 0, V < 1, ld < V, mu_ld < V (DPPO_FULL_*), or sizes   */
+                                  /* beyond int32 row indexing                                 */
+  DPPO_ERR_ALIGN = 3,             /* logits / mu_logits / grad_logits not 2-byte aligned,      */
+                                  /* workspace not 8,                                          */
                                   /* diagnostics not 16                                        */
   DPPO_ERR_VARIANT = 4,           /* variant is not a dppo_variant_t                           */
   DPPO_ERR_K = 5,                 /* K < 0, K > DPPO_KMAX, or K > 0 without top-K pointers     */
@@ -118,6 +127,12 @@ typedef struct {
   float          ratio_cap;    /* C of Eq. unified_grad: the gradient weight is M min(r, C) A  */
                                /* (held constant) and the loss term -M min(r, C) A.            */
                                /* <= 0 or +inf: no cap (C = infinity, as DPPO uses)            */
+  const void*    mu_logits;    /* bf16 [T, mu_ld]: the rollout policy's logits over the same   */
+                               /* vocabulary (log-probs are logits too; any per-row shift is   */
+                               /* immaterial).  DPPO_FULL_TV / DPPO_FULL_KL only, else ignored */
+                               /* and may be NULL.  Must not overlap grad_logits.  r_t still   */
+                               /* uses mu_logp                                                 */
+  int64_t        mu_ld;        /* its row pitch in elements, mu_ld >= V                        */
   /* ---- outputs (fully overwritten) ---- */
   float*         loss;         /* [1]                                                          */
   float*         loss_tok;     /* [T] -M_t r_t A_t, unscaled; may be NULL                      */
@@ -159,7 +174,8 @@ int dppo_version(void);
 size_t dppo_args_size(void);
 
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
- * "resident" (row held in registers between the two passes) or "streaming" (row re-read). */
+ * "resident" (row held in registers between the two passes), "streaming" (row re-read) or
+ * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants). */
 const char* dppo_last_path(void);
 
 /* ---- measurement utilities (not part of the loss) ------------------------------------------

@@ -11,7 +11,7 @@ import os
 
 import torch
 
-BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL, FULL_TV, FULL_KL = 0, 1, 2, 3, 4, 5
 MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
 NDIAG = 8
 DIAG_RATIO, DIAG_LOGP, DIAG_ABS_DIFF, DIAG_ENTROPY, DIAG_MASS_MU, DIAG_MASS_PI = 0, 1, 2, 3, 4, 5
@@ -32,6 +32,7 @@ class DppoArgs(C.Structure):
         ("K", C.c_int32), ("variant", C.c_int32),
         ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
         ("mask_rule", C.c_int32), ("eps_low", C.c_float), ("eps_high", C.c_float), ("ratio_cap", C.c_float),
+        ("mu_logits", C.c_void_p), ("mu_ld", C.c_int64),
         ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
         ("mask", C.c_void_p), ("grad_logits", C.c_void_p), ("diagnostics", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("flags", C.c_uint32),
@@ -84,7 +85,7 @@ def workspace_bytes(T: int, V: int, K: int) -> int:
 
 def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, out,
               mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None,
-              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0) -> DppoArgs:
+              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0, mu_logits=None) -> DppoArgs:
     """Fill a dppo_args_t from torch tensors.  `out` is a dict with loss [1] f32, divergence [T]
     f32, mask [T] u8, workspace (u8), optional loss_tok [T] f32."""
     T, ld = logits.shape[0], (logits.stride(0) if logits.shape[0] > 1 else logits.shape[1])
@@ -97,6 +98,8 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.advantages, a.delta, a.loss_scale = _ptr(advantages), delta, loss_scale
     a.mask_rule, a.eps_low, a.eps_high = mask_rule, eps_low, eps_high
     a.ratio_cap = 0.0 if ratio_cap is None else ratio_cap
+    a.mu_logits = _ptr(mu_logits)
+    a.mu_ld = 0 if mu_logits is None else (mu_logits.stride(0) if mu_logits.shape[0] > 1 else mu_logits.shape[1])
     a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
     a.grad_logits = _ptr(grad_logits)
@@ -180,8 +183,11 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     tk_l = batch["mu_topk_logp"][sl] if batch["mu_topk_logp"] is not None else None
     args = make_args(logits, batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
                      batch["delta"], batch["variant"], batch["loss_scale"], out, tk_i, tk_l,
-                     V=batch["V"], flags=flags, grad_logits=grad if backward else None, **rule)
+                     V=batch["V"], flags=flags, grad_logits=grad if backward else None,
+                     mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
     args.ld = batch["ld"]
+    if batch.get("mu_logits") is not None:
+        args.mu_ld = batch["mu_logits"].stride(0)
     (dppo_loss_fwd_bwd if backward else dppo_loss_fwd)(args, stream)
     res = dict(out)
     res["grad_logits"] = grad if backward else None

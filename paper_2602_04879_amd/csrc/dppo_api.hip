@@ -32,7 +32,7 @@ thread_local const char* g_last_path = "none";
 dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   if (!a) return DPPO_ERR_NULL;
   if (a->T < 0 || a->V < 1 || a->ld < a->V || a->V >= (int64_t(1) << 31) || a->T >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
-  if (a->variant < DPPO_BINARY_TV || a->variant > DPPO_TOPK_KL) return DPPO_ERR_VARIANT;
+  if (a->variant < DPPO_BINARY_TV || a->variant > DPPO_FULL_KL) return DPPO_ERR_VARIANT;
   if (a->K < 0 || a->K > DPPO_KMAX) return DPPO_ERR_K;
   const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
   if (topk && a->K > 0 && (!a->mu_topk_ids || !a->mu_topk_logp)) return DPPO_ERR_K;
@@ -45,6 +45,11 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   if (a->T > 0) {
     if (!a->logits || !a->sampled_ids || !a->mu_logp || !a->advantages || !a->divergence || !a->mask) return DPPO_ERR_NULL;
     if (grad && !a->grad_logits) return DPPO_ERR_NULL;
+    if (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL) {
+      if (!a->mu_logits) return DPPO_ERR_NULL;
+      if (a->mu_ld < a->V) return DPPO_ERR_SHAPE;
+      if (reinterpret_cast<uintptr_t>(a->mu_logits) & 1u) return DPPO_ERR_ALIGN;
+    }
     if (reinterpret_cast<uintptr_t>(a->logits) & 1u) return DPPO_ERR_ALIGN;
     if (grad && (reinterpret_cast<uintptr_t>(a->grad_logits) & 1u)) return DPPO_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(a->diagnostics) & 15u) return DPPO_ERR_ALIGN;
@@ -90,13 +95,26 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
     p.eps_low = a->eps_low;
     p.eps_high = a->eps_high;
     p.ratio_cap = (a->ratio_cap > 0.f && std::isfinite(a->ratio_cap)) ? a->ratio_cap : 0.f;   // 0: no cap
+    const bool full = (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL);
+    p.mu_logits = full ? static_cast<const uint16_t*>(a->mu_logits) : nullptr;
+    p.mu_ld = full ? a->mu_ld : 0;
 
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
     // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
     int r_threads = 0, r_chunks = 0;
-    const bool resident = !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
+    const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);
-    if (resident) {
+    if (full) {
+      // Two rows per workgroup in flight: one workgroup of 1024 threads per compute unit keeps the
+      // rows that pass 2 and 3 re-read within reach of the caches.
+      const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
+      int64_t grid = static_cast<int64_t>(cus) * (1024 / threads);
+      if (grid > a->T) grid = a->T;
+      if (grid > max_parts) grid = max_parts;
+      nparts = static_cast<int>(grid);
+      if (dppo::launch_fullvocab(p, a->variant == DPPO_FULL_TV, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      g_last_path = "fullvocab";
+    } else if (resident) {
       int64_t grid = static_cast<int64_t>(cus) * dppo::resident_blocks_per_cu(grad, r_threads, r_chunks);
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
@@ -136,9 +154,9 @@ const char* dppo_status_str(dppo_status_t status) {
   switch (status) {
     case DPPO_OK: return "ok";
     case DPPO_ERR_NULL: return "a required pointer is NULL";
-    case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld, T and V below 2^31";
+    case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld (and <= mu_ld for DPPO_FULL_*), T and V below 2^31";
     case DPPO_ERR_ALIGN: return "misaligned pointer: bf16 buffers need 2-byte, workspace 8-byte, diagnostics 16-byte alignment";
-    case DPPO_ERR_VARIANT: return "variant is not one of DPPO_BINARY_TV/KL, DPPO_TOPK_TV/KL";
+    case DPPO_ERR_VARIANT: return "variant is not one of DPPO_BINARY_TV/KL, DPPO_TOPK_TV/KL, DPPO_FULL_TV/KL";
     case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
     case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes()";
     case DPPO_ERR_LAUNCH: return "HIP kernel launch failed";

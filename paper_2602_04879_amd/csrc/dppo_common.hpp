@@ -9,7 +9,7 @@ constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;   // logits below this are treated as -inf
 
-enum : int { kBinaryTV = 0, kBinaryKL = 1, kTopkTV = 2, kTopkKL = 3 };
+enum : int { kBinaryTV = 0, kBinaryKL = 1, kTopkTV = 2, kTopkKL = 3, kFullTV = 4, kFullKL = 5 };
 
 // Kernel arguments (device pointers; one call).
 struct KParams {
@@ -31,6 +31,8 @@ struct KParams {
   int32_t mask_rule;        // 0 divergence (DPPO), 1 ratio clip (PPO/GRPO), 2 none
   float eps_low, eps_high;  // ratio-clip range
   float ratio_cap;          // C of the unified gradient form; 0 = no cap
+  const uint16_t* mu_logits;  // bf16 bits [T, mu_ld]: the rollout policy's logits (full-vocabulary variants) or nullptr
+  int64_t mu_ld;
 };
 
 // The subset of the kernel arguments the per-row epilogue needs.
@@ -184,6 +186,75 @@ __device__ __forceinline__ double wave_sum(double v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Per-thread running statistics of a row, kept in the base-2 domain:
+//   s = sum_j 2^(z_j*log2e + b)   with b an INTEGER-valued offset, b <= -max_j(z_j*log2e).
+// Because b is an integer, changing it rescales s by an exact power of two, and offsets of
+// different threads combine without any rounding.
+struct OnlineStat {
+  float b = 3.0e38f;   // current offset (starts at "+infinity": nothing seen yet)
+  float s = 0.f;       // sum 2^x,      x = z*log2e + b
+  float t = 0.f;       // sum 2^x * x   (feeds the entropy)
+  __device__ __forceinline__ void cover(float zmax) {   // make the offset cover a logit value
+    const float bn = fminf(b, -ceilf(fmaxf(zmax, kNegBig) * kLog2e));
+    const float d = bn - b, sc = fast_exp2(d);
+    t = sc * fmaf(d, s, t);     // e -> e*2^d, x -> x + d
+    s *= sc;
+    b = bn;
+  }
+  __device__ __forceinline__ void add1(float z) {
+    cover(z);
+    add1_covered(z);
+  }
+  __device__ __forceinline__ void add1_covered(float z) {
+    const float x = fmaf(z, kLog2e, b), e = fast_exp2(x);
+    s += e;
+    t = fma_ex(e, x, t);
+  }
+  __device__ __forceinline__ void add8(const float (&z)[8]) {
+    cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) add1_covered(z[i]);
+  }
+};
+
+__device__ __forceinline__ void unpack8(const u32x4& v, float (&z)[8]) {
+  z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xffff0000u);
+  z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xffff0000u);
+  z[4] = __uint_as_float(v.z << 16); z[5] = __uint_as_float(v.z & 0xffff0000u);
+  z[6] = __uint_as_float(v.w << 16); z[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+// The same for the ROLLOUT policy's row y, with the cross term the exact KL needs:
+//   s = sum_j 2^(y_j*log2e + b),   u = sum_j 2^(y_j*log2e + b) * (y_j - z_j)   (natural units),
+// so that sum_j mu_j (y_j - z_j) = u / s whatever the offset.  A vanished term (y_j = -inf)
+// adds nothing even where z_j = -inf too; a token pi excludes (z_j = -inf) that mu can still
+// sample makes u infinite, as the divergence then is.
+struct CrossStat {
+  float b = 3.0e38f, s = 0.f, u = 0.f;
+  __device__ __forceinline__ void cover(float ymax) {
+    const float bn = fminf(b, -ceilf(fmaxf(ymax, kNegBig) * kLog2e));
+    const float sc = fast_exp2(bn - b);
+    s *= sc;
+    u *= sc;
+    b = bn;
+  }
+  __device__ __forceinline__ void add1_covered(float y, float z) {
+    const float e = fast_exp2(fmaf(y, kLog2e, b));
+    const float d = fminf(fmaxf(y - z, -3.0e38f), 3.0e38f);     // NaN (-inf - -inf) -> -3e38, times e = 0
+    s += e;
+    u = fmaf(e, d, u);
+  }
+  __device__ __forceinline__ void add1(float y, float z) {
+    cover(y);
+    add1_covered(y, z);
+  }
+  __device__ __forceinline__ void add8(const float (&y)[8], const float (&z)[8]) {
+    cover(fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7]))));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) add1_covered(y[i], z[i]);
+  }
+};
+
 // ---- scalar math for the per-row epilogue ----------------------------------------------------
 // The epilogue runs once per row on one wave while the rest of the workgroup waits, so it is
 // built from the hardware's single-instruction exp2/log2 (about 1 ulp in fp32) with the range
@@ -261,12 +332,14 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
 //            sum_j pi_j log2 pi_j = T/S - log2 S).
 // log2e is the fp32 constant kLog2e everywhere (passes and epilogue), so the probabilities
 // are mutually consistent; its rounding (1.3e-8 relative) acts as a temperature of 1+1.3e-8.
+// D_full : the exact full-vocabulary divergence, for the variants that gate on it (App. B).
 // Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
 // mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
 // Lane 0 stores the per-token outputs; every lane returns the same RowResult.
 // Inlined into its caller; row_epilogue_call below is the same as a real call.
 __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
-                                                  const uint16_t* zrow, float b, double S_rest, double T_rest, int lane) {
+                                                  const uint16_t* zrow, float b, double S_rest, double T_rest, int lane,
+                                                  double D_full = 0.0) {
   constexpr double kL = static_cast<double>(kLog2e);
   const double bd = static_cast<double>(b);
   const double xa = static_cast<double>(rs.za) * kL + bd;   // log2 of a_t's own term
@@ -283,7 +356,11 @@ __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, R
   const int variant = p.variant;
   double mass_mu = pa, mass_pi = qa;      // mass on A' (= {a_t} for the Binary variants)
   double D;
-  if (variant == kBinaryTV || (variant == kTopkTV && p.K == 0)) {
+  if (variant == kFullTV || variant == kFullKL) {
+    D = D_full;                           // exact divergence of the two rows (App. B), computed by the caller
+    mass_mu = 1.0;
+    mass_pi = 1.0;
+  } else if (variant == kBinaryTV || (variant == kTopkTV && p.K == 0)) {
     D = fabs(static_cast<double>(pa) - static_cast<double>(qa));
   } else if (variant == kBinaryKL || (variant == kTopkKL && p.K == 0)) {
     const double omp = one_minus_exp(lmu, pa);
@@ -363,8 +440,8 @@ __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, R
 // and the other workgroups hide the call's latency.
 __device__ __attribute__((noinline)) static RowResult row_epilogue_call(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
                                                                         const uint16_t* zrow, float b, double S_rest, double T_rest,
-                                                                        int lane) {
-  return row_epilogue(p, row, rs, tk, zrow, b, S_rest, T_rest, lane);
+                                                                        int lane, double D_full = 0.0) {
+  return row_epilogue(p, row, rs, tk, zrow, b, S_rest, T_rest, lane, D_full);
 }
 
 }  // namespace dppo

@@ -17,6 +17,9 @@ bool resident_shape(int64_t V, int* threads, int* chunks);
 hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s);
 int resident_blocks_per_cu(bool grad, int threads, int chunks);
 
+// Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
+hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);
+
 // loss[0] = loss_scale * sum(partial[0..n)) in a fixed order.
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s);
 

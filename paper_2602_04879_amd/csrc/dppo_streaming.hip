@@ -11,44 +11,6 @@
 namespace dppo {
 namespace {
 
-// Per-thread running statistics of a row, kept in the base-2 domain:
-//   s = sum_j 2^(z_j*log2e + b)   with b an INTEGER-valued offset, b <= -max_j(z_j*log2e).
-// Because b is an integer, changing it rescales s by an exact power of two, and offsets of
-// different threads combine without any rounding.
-struct OnlineStat {
-  float b = 3.0e38f;   // current offset (starts at "+infinity": nothing seen yet)
-  float s = 0.f;       // sum 2^x,      x = z*log2e + b
-  float t = 0.f;       // sum 2^x * x   (feeds the entropy)
-  __device__ __forceinline__ void cover(float zmax) {   // make the offset cover a logit value
-    const float bn = fminf(b, -ceilf(fmaxf(zmax, kNegBig) * kLog2e));
-    const float d = bn - b, sc = fast_exp2(d);
-    t = sc * fmaf(d, s, t);     // e -> e*2^d, x -> x + d
-    s *= sc;
-    b = bn;
-  }
-  __device__ __forceinline__ void add1(float z) {
-    cover(z);
-    add1_covered(z);
-  }
-  __device__ __forceinline__ void add1_covered(float z) {
-    const float x = fmaf(z, kLog2e, b), e = fast_exp2(x);
-    s += e;
-    t = fma_ex(e, x, t);
-  }
-  __device__ __forceinline__ void add8(const float (&z)[8]) {
-    cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) add1_covered(z[i]);
-  }
-};
-
-__device__ __forceinline__ void unpack8(const u32x4& v, float (&z)[8]) {
-  z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xffff0000u);
-  z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xffff0000u);
-  z[4] = __uint_as_float(v.z << 16); z[5] = __uint_as_float(v.z & 0xffff0000u);
-  z[6] = __uint_as_float(v.w << 16); z[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-
 template <int THREADS, bool VEC, bool GRAD>
 __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p) {
   constexpr int NW = THREADS / kWave;

@@ -18,7 +18,7 @@ from dataclasses import dataclass, field
 
 import torch
 
-BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL = 0, 1, 2, 3
+BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL, FULL_TV, FULL_KL = 0, 1, 2, 3, 4, 5
 
 
 @dataclass
@@ -38,6 +38,7 @@ class Workload:
     temperature: tuple | None = None   # per-token temperature ~ U(lo, hi) applied before the bf16 cast
     drift_frac: float = 0.0       # fraction of tokens whose sampled-token logit has moved since the
     drift_std: float = 0.0        # rollout (policy updates in between), by N(0, drift_std)
+    mu_full: bool = False         # also hand over the rollout policy's full logits, rounded to bf16
     adv: str = "pm1"              # "pm1" | "normal" | "group_norm"
     group: int = 8
     chunk_rows: int = 0           # caller-side T-chunking (0 = one call)
@@ -66,6 +67,14 @@ WORKLOADS = {
     "c5_long_topk_kl": Workload("c5_long_topk_kl", 32, 4096, 151936, TOPK_KL, 0.05, K=64,
                                 logit_std=3.0, noise_std=0.1, zipf_s=1.1, temperature=(0.6, 1.2),
                                 drift_frac=0.05, drift_std=1.5, adv="pm1", chunk_rows=16384, seed=1004),
+    # The headline shape with the trust region on the exact divergence between the two rows
+    # (the rollout policy's full logits are given as a second bf16 matrix).
+    "c6_qwen3_full_tv": Workload("c6_qwen3_full_tv", 16, 2048, 151936, FULL_TV, 0.2, mu_full=True,
+                                 logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                 adv="group_norm", group=8, seed=1002),
+    "c6_qwen3_full_kl": Workload("c6_qwen3_full_kl", 16, 2048, 151936, FULL_KL, 0.05, mu_full=True,
+                                 logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                 adv="group_norm", group=8, seed=1002),
 }
 
 
@@ -110,7 +119,7 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
     Returns a dict of tensors on `device`:
       logits [T, ld] bf16 (columns V..ld-1, if any, hold a poison value the path must ignore),
       sampled_ids [T] int32, mu_logp [T] f32, mu_topk_ids / mu_topk_logp [T, K] (or None),
-      advantages [T] f32, plus python scalars delta, variant, K, loss_scale, T, V, ld.
+      advantages [T] f32, mu_logits [T, ld] bf16 (workloads with mu_full, else None), plus python scalars delta, variant, K, loss_scale, T, V, ld.
     With keep_mu_full the rollout policy's full log-probs [T, V] (f32) are kept as
     "mu_logp_full" so exact divergences can be brute-forced on small V.
     shift_sampled != 0 adds +/-shift to the trainer's logit of the sampled token on
@@ -132,6 +141,11 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
     tk_ids = torch.empty((T, K), dtype=torch.int32, device=dev) if K > 0 else None
     tk_lp = torch.empty((T, K), dtype=torch.float32, device=dev) if K > 0 else None
     mu_full = torch.empty((T, V), dtype=torch.float32, device=dev) if keep_mu_full else None
+    mu_logits = None
+    if w.mu_full:
+        mu_logits = torch.empty((T, ld), dtype=torch.bfloat16, device=dev)
+        if ld > V:
+            mu_logits[:, V:] = 1.0e4
 
     prior = None
     if w.zipf_s > 0:
@@ -157,6 +171,9 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
         zb = x.to(torch.bfloat16)                      # what the trainer hands over
         # rollout engine: same logits seen through inference-side numerical mismatch
         y = zb.float() + w.noise_std * torch.randn((n, V), generator=g, device=dev)
+        if w.mu_full:                                  # the rollout logits as handed over: bf16
+            mu_logits[r0:r1, :V] = y.to(torch.bfloat16)
+            y = mu_logits[r0:r1, :V].float()
         lmu = torch.log_softmax(y, dim=-1)
         a = torch.multinomial(lmu.exp(), 1, generator=g).squeeze(1)
         sampled[r0:r1] = a.to(torch.int32)
@@ -185,7 +202,7 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
     return {
         "logits": logits, "sampled_ids": sampled, "mu_logp": mu_logp,
         "mu_topk_ids": tk_ids, "mu_topk_logp": tk_lp, "advantages": _advantages(w, g, dev),
-        "mu_logp_full": mu_full, "delta": float(w.delta), "variant": int(w.variant), "K": int(K),
+        "mu_logp_full": mu_full, "mu_logits": mu_logits, "delta": float(w.delta), "variant": int(w.variant), "K": int(K),
         "loss_scale": 1.0 / float(T), "T": T, "V": V, "ld": ld, "name": w.name,
     }
 

@@ -1,0 +1,173 @@
+"""GPU parity of the exact full-vocabulary variants (trust region on the true TV / KL between the
+rollout policy's and the trainer's rows, App. B) against the float64 oracle, through the C ABI."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_04879_amd import binding as B
+from paper_2602_04879_amd import workloads as W
+from tests import parity as P
+from tests.test_gpu_parity import DEV, _run_and_compare, _say
+
+pytestmark = pytest.mark.gpu
+
+FULL = [(W.FULL_TV, 0.2), (W.FULL_KL, 0.05)]
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+@pytest.mark.parametrize("shift", [0.0, 2.0])
+def test_c1_shape_all_rows(variant, delta, shift):
+    w = W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], variant=variant, delta=delta, mu_full=True,
+                 noise_std=1.0 if shift else 0.05)
+    b, res, st = _run_and_compare(w, shift=shift)
+    assert B.last_path() == "fullvocab"
+    if shift:
+        assert 0 < st["masked"] < b["T"]
+    _run_and_compare(w, shift=shift, backward=False)
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+@pytest.mark.parametrize("V,ld", [(1, 1), (7, 7), (8, 8), (1000, 1000), (5003, 5003), (5003, 5011), (32768, 32768),
+                                  (40004, 40010), (151936, 151936)])
+def test_ragged_rows_pitches_and_workgroup_sizes(variant, delta, V, ld):
+    # V = 1 .. 151936 covers the three workgroup sizes, rows with head / vector / tail parts, odd
+    # pitches (rows that change their 16-byte misalignment from one to the next) and a poisoned pad
+    w = W.Workload("ragged_full", 3, 5, V, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.7, zipf_s=1.1,
+                   adv="normal", seed=53)
+    _run_and_compare(w, ld=ld, shift=1.0 if V > 1 else 0.0)
+    _run_and_compare(w, ld=ld, in_place=True)
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+def test_rows_of_the_two_matrices_misaligned_against_each_other(variant, delta):
+    """mu_logits with a pitch of its own and a start 2 bytes off: the vector path cannot apply."""
+    w = W.Workload("misfull", 2, 9, 4104, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.7, adv="pm1", seed=59)
+    b = W.make_batch(w, DEV)
+    T, V = b["T"], b["V"]
+    store = torch.full((T * (V + 24) + 8,), 1.0e4, dtype=torch.bfloat16, device=DEV)
+    mu2 = store[1:1 + T * (V + 24)].view(T, V + 24)[:, :V]
+    mu2.copy_(b["mu_logits"][:, :V])
+    b["mu_logits"] = mu2
+    rows = np.arange(T)
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    assert res["args"].mu_ld == V + 24
+    st = P.compare_rows(b, res, rows, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    _say(f"       {st}")
+
+
+def test_excluded_tokens_and_infinite_kl():
+    """-inf logits: a token both policies exclude adds nothing; one only mu excludes adds nothing to
+    KL(mu || pi); one only pi excludes while mu can sample it makes KL infinite (TV stays finite)."""
+    for variant, delta in FULL:
+        w = W.Workload("inf_full", 2, 6, 8192, variant, delta, mu_full=True, logit_std=2.0, noise_std=0.3, adv="pm1", seed=61)
+        b = W.make_batch(w, DEV)
+        a = b["sampled_ids"].long()
+        cols = torch.arange(100, 2000, device=DEV)
+        keep = [(int(a[r]) < 100 or int(a[r]) >= 2000) for r in range(b["T"])]    # rows whose sampled token stays
+        r_both, r_mu, r_pi = [r for r in range(b["T"]) if keep[r]][:3]
+        b["logits"][r_both, cols] = float("-inf"); b["mu_logits"][r_both, cols] = float("-inf")
+        b["mu_logits"][r_mu, cols] = float("-inf")
+        b["logits"][r_pi, cols] = float("-inf")
+        rows = np.arange(b["T"])
+        ref = P.oracle_rows(b, rows)
+        res = B.run_batch(b, diagnostics=True)
+        torch.cuda.synchronize()
+        st = P.compare_rows(b, res, rows, ref=ref)
+        D = res["divergence"].cpu().numpy()
+        if variant == W.FULL_KL:
+            assert np.isinf(ref["divergence"][r_pi]) and np.isinf(D[r_pi]) and D[r_pi] > 0
+        assert np.isfinite(np.delete(D, r_pi)).all()
+        assert torch.isfinite(res["grad_logits"].float()).all()
+        _say(f"       variant={variant} {st}")
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+def test_identical_rows_give_zero_and_special_rows(variant, delta):
+    w = W.Workload("same_full", 4, 20, 16384, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.5, zipf_s=1.1,
+                   adv="normal", seed=67)
+    b = W.make_batch(w, DEV, shift_sampled=1.5)
+    b["mu_logits"][:10] = b["logits"][:10]                   # identical policies
+    b["sampled_ids"][::7] = -1
+    b["advantages"][3::9] = 0.0
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    st = P.compare_rows(b, res, rows, ref=ref)
+    D = res["divergence"].cpu().numpy()
+    live = (b["sampled_ids"][:10] >= 0).cpu().numpy()
+    assert np.all(np.abs(D[:10][live]) <= 1e-6)
+    assert st["masked"] > 0
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    _say(f"       {st}")
+
+
+def test_every_approximation_lower_bounds_the_exact_divergence_on_the_gpu():
+    """App. B at the headline vocabulary: Binary <= Top-K <= exact, token by token, all computed by
+    the library on the same batch."""
+    w = W.scaled(W.WORKLOADS["c6_qwen3_full_tv"], n_seq=4, seq_len=64, K=20)
+    b = W.make_batch(w, DEV, shift_sampled=1.0)
+    mu = torch.log_softmax(b["mu_logits"][:, :b["V"]].float(), -1)
+    v, i = torch.topk(mu, 20, dim=-1)
+    b["mu_topk_ids"], b["mu_topk_logp"], b["K"] = i.to(torch.int32), v.contiguous(), 20
+    for chain in ((W.BINARY_TV, W.TOPK_TV, W.FULL_TV), (W.BINARY_KL, W.TOPK_KL, W.FULL_KL)):
+        Ds = []
+        for variant in chain:
+            bb = dict(b, variant=variant)
+            res = B.run_batch(bb, backward=False)
+            torch.cuda.synchronize()
+            Ds.append(res["divergence"].double().cpu().numpy())
+        assert np.all(Ds[0] <= Ds[1] + 2e-6) and np.all(Ds[1] <= Ds[2] + 2e-6)
+        assert (Ds[2] - Ds[1]).max() > 1e-4          # and the bound is not vacuous on this batch
+        _say(f"       chain {chain}: mean D {[float(d.mean()) for d in Ds]}")
+
+
+def test_error_codes():
+    w = W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], variant=W.FULL_TV, mu_full=True)
+    b = W.make_batch(w, DEV)
+    out = B.alloc_outputs(b["T"], DEV)
+    grad = torch.empty_like(b["logits"])
+
+    def status(**kw):
+        a = B.make_args(b["logits"], b["sampled_ids"], b["mu_logp"], b["advantages"], b["delta"], W.FULL_TV, 1.0, out,
+                        grad_logits=grad, mu_logits=b["mu_logits"])
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return B.lib().dppo_loss_fwd_bwd(C.byref(a), None)
+
+    assert status() == 0
+    assert status(mu_logits=None) == 1
+    assert status(mu_ld=b["V"] - 1) == 2
+    assert status(mu_logits=b["mu_logits"].data_ptr() + 1) == 3
+    assert status(variant=6) == 4
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["c6_qwen3_full_tv", "c6_qwen3_full_kl"])
+def test_full_size_sampled_rows(name):
+    """T = 32768, V = 151936 in the launch configuration bench.py times: a sample of rows against
+    the oracle (first, last, masked, zero-advantage, random), the loss against the per-token terms."""
+    w = W.WORKLOADS[name]
+    _say(f"[case] {name} full size")
+    b = W.make_batch(w, DEV, rows_per_step=2048)
+    grad = torch.empty_like(b["logits"])
+    res = B.run_batch(b, grad=grad, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab"
+    mask = res["mask"].cpu().numpy()
+    adv = b["advantages"].cpu().numpy()
+    rng = np.random.default_rng(5)
+    pick = {0, b["T"] - 1}
+    pick.update(np.nonzero(mask == 0)[0][:6].tolist())
+    pick.update(np.nonzero(adv == 0)[0][:2].tolist())
+    pick.update(rng.integers(0, b["T"], 20).tolist())
+    rows = np.array(sorted(pick))
+    st = P.compare_rows(b, res, rows)
+    P.check_loss_scalar(b, res)
+    assert 0 < (mask == 0).sum() < b["T"] // 10
+    _say(f"       masked={(mask == 0).sum()} {st}")

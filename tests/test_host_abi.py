@@ -55,7 +55,10 @@ def _valid_args():
     (lambda a: setattr(a, "ld", 8), 2),
     (lambda a: setattr(a, "T", -1), 2),
     (lambda a: setattr(a, "V", 1 << 31), 2),
-    (lambda a: setattr(a, "variant", 4), 4),
+    (lambda a: setattr(a, "variant", 6), 4),
+    (lambda a: setattr(a, "variant", B.FULL_TV), 1),                                                    # no mu_logits
+    (lambda a: (setattr(a, "variant", B.FULL_KL), setattr(a, "mu_logits", 0x6000), setattr(a, "mu_ld", 8)), 2),
+    (lambda a: (setattr(a, "variant", B.FULL_KL), setattr(a, "mu_logits", 0x6001), setattr(a, "mu_ld", 16)), 3),
     (lambda a: setattr(a, "variant", -1), 4),
     (lambda a: setattr(a, "K", -1), 5),
     (lambda a: setattr(a, "K", 1025), 5),
