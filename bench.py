@@ -28,13 +28,13 @@ DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_stream
                    "fullvocab": "dppo_fullvocab_kernel"}
 
 
-def kernel_source_hash() -> str:
-    """Hash of the HIP sources: the stored HBM-traffic counters are only valid for it."""
+def kernel_source_hash(path: str) -> str:
+    """Hash of the HIP sources behind one kernel path (its kernel, the shared device helpers and
+    the host code that picks the launch shape): stored HBM-traffic counters hold only for it."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
-    for fn in sorted(os.listdir(src)):
-        if fn.endswith((".hip", ".hpp")):
-            h.update(open(os.path.join(src, fn), "rb").read())
+    for fn in ("dppo_common.hpp", "dppo_launch.hpp", "dppo_api.hip", f"dppo_{path}.hip"):
+        h.update(open(os.path.join(src, fn), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -48,7 +48,7 @@ def stored_traffic(workload: str, path: str):
         rec = json.load(open(fn)).get(f"{workload}:{path}")
     except Exception:
         return None
-    if not rec or rec.get("kernel_source_hash") != kernel_source_hash():
+    if not rec or rec.get("kernel_source_hash") != kernel_source_hash(path):
         return None
     return rec.get("bytes_per_launch")
 

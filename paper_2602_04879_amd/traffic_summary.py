@@ -21,12 +21,13 @@ import os
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def kernel_source_hash() -> str:
+def kernel_source_hash(path: str) -> str:
+    """Hash of the HIP sources behind one kernel path (its kernel, the shared device helpers and
+    the host code that picks the launch shape): stored HBM-traffic counters hold only for it."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
-    for fn in sorted(os.listdir(src)):
-        if fn.endswith((".hip", ".hpp")):
-            h.update(open(os.path.join(src, fn), "rb").read())
+    for fn in ("dppo_common.hpp", "dppo_launch.hpp", "dppo_api.hip", f"dppo_{path}.hip"):
+        h.update(open(os.path.join(src, fn), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -44,7 +45,7 @@ def counter_avg(directory: str, kernel_substr: str, counter: str) -> float:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--path", required=True, choices=["resident", "streaming"])
+    ap.add_argument("--path", required=True, choices=["resident", "streaming", "fullvocab"])
     ap.add_argument("--probe-fetch", required=True)
     ap.add_argument("--probe-write", required=True)
     ap.add_argument("--fetch", required=True)
@@ -55,11 +56,11 @@ def main():
     kib = a.probe_bytes / 1024.0
     f_read = kib / counter_avg(a.probe_fetch, "dppo_probe_copy_kernel", "FETCH_SIZE")
     f_write = kib / counter_avg(a.probe_write, "dppo_probe_copy_kernel", "WRITE_SIZE")
-    kern = "dppo_resident_kernel" if a.path == "resident" else "dppo_streaming_kernel"
+    kern = f"dppo_{a.path}_kernel"
     rd = counter_avg(a.fetch, kern, "FETCH_SIZE") * f_read * 1024.0
     wr = counter_avg(a.write, kern, "WRITE_SIZE") * f_write * 1024.0
     rec = {"bytes_per_launch": rd + wr, "read_bytes": rd, "write_bytes": wr, "fetch_size_factor": f_read,
-           "write_size_factor": f_write, "kernel": kern, "kernel_source_hash": kernel_source_hash()}
+           "write_size_factor": f_write, "kernel": kern, "kernel_source_hash": kernel_source_hash(a.path)}
     allrec = json.load(open(a.out)) if os.path.exists(a.out) else {}
     allrec[f"{a.workload}:{a.path}"] = rec
     json.dump(allrec, open(a.out, "w"), indent=1, sort_keys=True)
