@@ -44,16 +44,25 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
       OnlineStat st;
       st.cover(fmaxf(kNegBig, bf16_bits_to_float(zrow[a])));   // the offset must cover z[a_t]
       const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
-      for (int v = tid; v < nvec; v += THREADS) {
+      auto add_vec = [&](const u32x4& q, int v) {
         float z[8];
-        unpack8(zv[v], z);
+        unpack8(q, z);
         if (v == av) {
           const int sub = (a - head) & 7;
 #pragma unroll
           for (int i = 0; i < 8; ++i) z[i] = (i == sub) ? -INFINITY : z[i];
         }
         st.add8(z);
+      };
+      int v = tid;
+      for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {     // four 16-byte loads in flight per thread
+        const u32x4 q0 = zv[v], q1 = zv[v + THREADS], q2 = zv[v + 2 * THREADS], q3 = zv[v + 3 * THREADS];
+        add_vec(q0, v);
+        add_vec(q1, v + THREADS);
+        add_vec(q2, v + 2 * THREADS);
+        add_vec(q3, v + 3 * THREADS);
       }
+      for (; v < nvec; v += THREADS) add_vec(zv[v], v);
       for (int e = tid; e < nscalar; e += THREADS) {
         const int j = (e < head) ? e : tail0 + (e - head);
         if (j != a) st.add1(bf16_bits_to_float(zrow[j]));
