@@ -185,9 +185,9 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
         const float kexp = rc.kexp;
         const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
-        for (int v = tid; v < nvec; v += THREADS) {
+        auto grad_vec = [&](const u32x4& q, int v) {
           float z[8];
-          unpack8(zv[v], z);
+          unpack8(q, z);
 #pragma unroll
           for (int i = 0; i < 8; ++i) z[i] = fast_exp2(fmaf(z[i], kLog2e, kexp));
           uint32_t w[4];
@@ -201,7 +201,16 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
           }
           const u32x4 o = {w[0], w[1], w[2], w[3]};
           __builtin_nontemporal_store(o, gv + v);
+        };
+        int v = tid;
+        for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {     // four loads in flight, then four stores
+          const u32x4 q0 = zv[v], q1 = zv[v + THREADS], q2 = zv[v + 2 * THREADS], q3 = zv[v + 3 * THREADS];
+          grad_vec(q0, v);
+          grad_vec(q1, v + THREADS);
+          grad_vec(q2, v + 2 * THREADS);
+          grad_vec(q3, v + 3 * THREADS);
         }
+        for (; v < nvec; v += THREADS) grad_vec(zv[v], v);
         for (int e = tid; e < nscalar; e += THREADS) {
           const int j = (e < head) ? e : tail0 + (e - head);
           float g = fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, kexp));
