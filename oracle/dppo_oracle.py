@@ -22,6 +22,8 @@ order and notation of the paper:
   * the baselines' masks and the ratio cap         (App. C.1: unified gradient form,
                                                     Eq. unified_grad; PPO/GRPO clip mask;
                                                     M = 1 for PG-IS / CISPO; cap C)
+  * the same path from the final hidden states and the lm_head weight (logits formed inside,
+    gradient with respect to the hidden states), Sec. 4.4's memory concern
   * per-token health metrics the paper monitors   (App. F.1: |pi - mu| of the sampled token,
     (diagnostics)                                   policy entropy; App. B.1: mass covered by
                                                     the top-K set)
@@ -44,6 +46,9 @@ Readings taken where the paper is silent:
     M min(r, C) A grad log pi (the weight is a constant), and the reported loss term is
     -M min(r, C) A; "r > 1 + eps" of the clip mask is evaluated as
     log pi(a) - log mu(a) > log(1 + eps).
+
+  - from hidden states: the logits are the exact product h W^T rounded ONCE to bfloat16 (what a
+    bf16 lm_head with wide accumulation hands over), and that rounding passes gradients through.
 
 All pins for these functions live in tests/test_oracle_*.py.  "parity unpinned": the loss
 normalisation (the paper fixes no minibatch formula; it is the caller's loss_scale) and the
@@ -280,4 +285,36 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
             g[a] -= 1.0
             out["grad_logits"][t] = (loss_scale * M * A * w) * g
     out["loss"] = float(loss_scale * out["loss_tok"].sum())
+    return out
+
+
+# --------------------------------------------------------------------------- from the hidden states
+def bf16_round(x):
+    """Round float64 values to the nearest bfloat16 (8 significant bits, ties to even), returned
+    as float64.  Normal range only (no subnormals, no overflow): what logits need."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m * 2^e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def lmhead_logits(hidden, weight):
+    """The trainer's bf16 logits z = h W^T: the exact product, rounded once to bfloat16."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    return bf16_round(hidden @ weight.T)
+
+
+def lmhead_dppo_loss(hidden, weight, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
+                     mu_topk_ids=None, mu_topk_logp=None, want_grad=True, **rule):
+    """The whole path from the final hidden states h [T, d] and the lm_head weight W [V, d]
+    (the memory-saving form of Sec. 4.4's concern: no [T, V] array is needed outside this oracle):
+    logits as the trainer's lm_head produces them, dppo_loss on them, and the gradient with respect
+    to the hidden states by the chain rule, d loss / d h = (d loss / d z) W, the rounding of the
+    logits passing gradients through unchanged.  Returns dppo_loss's dict plus logits and
+    grad_hidden [T, d] (None without want_grad)."""
+    z = lmhead_logits(hidden, weight)
+    out = dppo_loss(z, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, mu_topk_ids, mu_topk_logp,
+                    want_grad=want_grad, **rule)
+    out["logits"] = z
+    out["grad_hidden"] = out["grad_logits"] @ np.asarray(weight, dtype=np.float64) if want_grad else None
     return out

@@ -531,3 +531,51 @@ def test_full_variants_use_the_exact_divergence_of_the_two_rows(variant):
     assert np.all(same["mask"] == 1)
     with pytest.raises(ValueError):
         O.dppo_loss(z, a, lmu_a, adv, delta, variant)
+
+
+# ------------------------------------------------------------------ from the hidden states
+def test_bf16_round_matches_the_library_cast_and_ties_go_to_even():
+    x = np.concatenate([RNG.normal(0, 30.0, 5000), RNG.normal(0, 1e-3, 1000), [0.0, 1.0, -1.0, 255.0, 256.0, 3.0e4]]).astype(np.float32)
+    want = torch.tensor(x).to(torch.bfloat16).double().numpy()          # float32 -> bf16, nearest even
+    np.testing.assert_array_equal(O.bf16_round(x.astype(np.float64)), want)
+    assert O.bf16_round(1.0 + 2.0 ** -8) == 1.0                          # halfway: to the even neighbour
+    assert O.bf16_round(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert O.bf16_round(-(1.0 + 2.0 ** -8 + 2.0 ** -30)) == -(1.0 + 2.0 ** -7)
+    assert O.bf16_round(1.0 + 2.0 ** -8 + 2.0 ** -40) == 1.0 + 2.0 ** -7  # no double rounding through float32
+
+
+def test_lmhead_path_is_the_chain_rule_through_the_logits():
+    rng = np.random.default_rng(9)
+    T, d, V = 40, 16, 40
+    # small integers: every logit is an integer below 256, so the bf16 rounding is the identity and
+    # the whole path must equal float64 autograd of the masked surrogate through h W^T
+    h = rng.integers(-2, 3, size=(T, d)).astype(np.float64)
+    W = rng.integers(-2, 3, size=(V, d)).astype(np.float64)
+    z = h @ W.T
+    assert np.abs(z).max() < 256
+    np.testing.assert_array_equal(O.lmhead_logits(h, W), z)
+    y = z / 8 + rng.normal(0, 1.5, size=z.shape)
+    mu = scipy.special.softmax(y, axis=1)
+    a = np.array([rng.choice(V, p=mu[t]) for t in range(T)])
+    lmu = np.log(mu[np.arange(T), a])
+    adv = rng.normal(size=T)
+    ids = np.argsort(-mu, axis=1, kind="stable")[:, :5]
+    lps = np.log(np.take_along_axis(mu, ids, 1))
+    hs, Ws = h / 8, W                    # logits z / 8: exact in bf16 as well
+    for variant, kw in ((O.BINARY_TV, {}), (O.TOPK_KL, dict(mu_topk_ids=ids, mu_topk_logp=lps))):
+        out = O.lmhead_dppo_loss(hs, Ws, a, lmu, adv, 0.05, variant, loss_scale=0.25, **kw)
+        ref = O.dppo_loss(z / 8, a, lmu, adv, 0.05, variant, loss_scale=0.25, **kw)
+        for k in ("loss_tok", "divergence", "mask", "grad_logits"):
+            np.testing.assert_array_equal(out[k], ref[k])
+        assert 0 < (out["mask"] == 0).sum() < T
+        ht = torch.tensor(hs, dtype=torch.float64, requires_grad=True)
+        lp = torch.log_softmax(ht @ torch.tensor(Ws, dtype=torch.float64).T, -1).gather(1, torch.tensor(a)[:, None]).squeeze(1)
+        coef = torch.tensor(out["mask"] * out["ratio"] * adv, dtype=torch.float64)
+        (-(coef * lp).sum() * 0.25).backward()
+        np.testing.assert_allclose(out["grad_hidden"], ht.grad.numpy(), rtol=1e-9, atol=1e-14)
+    # logits that do need rounding: rounded once, to 8 significant bits
+    h2, W2 = rng.normal(size=(3, 8)), rng.normal(size=(5, 8))
+    z2 = O.lmhead_logits(h2, W2)
+    exact = h2 @ W2.T
+    assert np.all(np.abs(z2 - exact) <= np.abs(exact) * 2.0 ** -8) and np.any(z2 != exact)
+    np.testing.assert_array_equal(z2, torch.tensor(z2).to(torch.bfloat16).double().numpy())
