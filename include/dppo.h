@@ -175,8 +175,59 @@ size_t dppo_args_size(void);
 
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
  * "resident" (row held in registers between the two passes), "streaming" (row re-read) or
- * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants). */
+ * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants); "lmhead" after a dppo_lmhead_* call. */
 const char* dppo_last_path(void);
+
+/* ---- the same loss from the hidden states: the [T, V] logits never exist in full -------------
+ * The full divergence and even the log-probabilities over a 150k vocabulary are what makes the
+ * trust region expensive in memory (Sec. 4.4).  Here the caller hands over the final hidden
+ * states h[T, d] and the lm_head weight W[V, d] (bf16, row-major, as an nn.Linear keeps it);
+ * the library walks T in chunks of `chunk_rows` tokens:
+ *     z_c = h_c W^T           bf16 logits of the chunk, fp32 accumulation, round to nearest even
+ *     loss, D, M, and g_c = d loss / d z_c in place            (exactly dppo_loss_fwd_bwd on z_c)
+ *     d loss / d h_c = g_c W  bf16, fp32 accumulation
+ * so device memory holds one chunk of logits, not [T, V].  `loss` carries every per-token
+ * input and output with the meaning it has in dppo_loss_fwd_bwd (its logits, ld, grad_logits,
+ * mu_logits, workspace and flags fields are ignored); the DPPO_FULL_* variants are not
+ * available here.  Needs V and d multiples of 64.  Outputs: those of `loss`, and grad_hidden. */
+typedef struct {
+  dppo_args_t    loss;          /* T, V, per-token inputs/outputs, variant, delta, loss_scale, ...  */
+  const void*    hidden;        /* bf16 [T, ld_hidden], 16-byte aligned                            */
+  int64_t        ld_hidden;     /* >= d, multiple of 8                                             */
+  int64_t        d;             /* hidden size, multiple of 64                                     */
+  const void*    weight;        /* bf16 [V, ld_weight]: lm_head weight, 16-byte aligned            */
+  int64_t        ld_weight;     /* >= d, multiple of 8                                             */
+  const void*    weight_t;      /* optional bf16 [d, ld_weight_t] = weight transposed (a caller    */
+                                /* that keeps one saves the transposition per call); may be NULL   */
+  int64_t        ld_weight_t;   /* >= V, multiple of 8                                             */
+  int64_t        chunk_rows;    /* tokens per chunk; <= 0: 4096                                    */
+  void*          grad_hidden;   /* bf16 [T, ld_grad_hidden]; dppo_lmhead_loss_fwd_bwd only         */
+  int64_t        ld_grad_hidden;/* >= d                                                            */
+  void*          workspace;     /* >= dppo_lmhead_workspace_bytes(...) bytes, 256-byte aligned:    */
+                                /* loss partial sums, the chunk of logits, and W^T unless given    */
+  size_t         workspace_bytes;
+} dppo_lmhead_args_t;
+
+size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t);
+
+/* Forward only (loss, loss_tok, divergence, mask, diagnostics). */
+dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream);
+
+/* Forward and backward: also grad_hidden = d loss / d hidden. */
+dppo_status_t dppo_lmhead_loss_fwd_bwd(const dppo_lmhead_args_t* args, void* stream);
+
+/* sizeof(dppo_lmhead_args_t) as the library was compiled. */
+size_t dppo_lmhead_args_size(void);
+
+/* C[M, N] = A[M, K] * B[N, K]^T on the matrix cores: bf16 operands, both row-major with the
+ * contraction index contiguous (activations [T, d] times an lm_head weight [V, d] transposed),
+ * fp32 accumulation, C bf16 row-major rounded to nearest even.  The building block of the
+ * logits-free path (the logits of a chunk of tokens, and the gradient with respect to the
+ * hidden states from the gradient with respect to those logits).  K a multiple of 64; A and B
+ * 16-byte aligned with lda, ldb multiples of 8 and below 2^22; C 2-byte aligned; buffers must not
+ * overlap.  M = 0 or N = 0 is valid and does nothing. */
+dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                           int64_t M, int64_t N, int64_t K, void* stream);
 
 /* ---- measurement utilities (not part of the loss) ------------------------------------------
  * Plain device-to-device copy of `bytes` bytes with 16-byte vector loads/stores (dst, src and

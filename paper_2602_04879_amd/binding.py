@@ -39,6 +39,19 @@ class DppoArgs(C.Structure):
     ]
 
 
+class DppoLmheadArgs(C.Structure):
+    """Mirror of dppo_lmhead_args_t."""
+    _fields_ = [
+        ("loss", DppoArgs),
+        ("hidden", C.c_void_p), ("ld_hidden", C.c_int64), ("d", C.c_int64),
+        ("weight", C.c_void_p), ("ld_weight", C.c_int64),
+        ("weight_t", C.c_void_p), ("ld_weight_t", C.c_int64),
+        ("chunk_rows", C.c_int64),
+        ("grad_hidden", C.c_void_p), ("ld_grad_hidden", C.c_int64),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 class DppoError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -69,6 +82,17 @@ def lib() -> C.CDLL:
         l.dppo_probe_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         l.dppo_probe_read.restype = C.c_int
         l.dppo_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        l.dppo_gemm_nt.restype = C.c_int
+        l.dppo_gemm_nt.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                   C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+        l.dppo_lmhead_workspace_bytes.restype = C.c_size_t
+        l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int]
+        for f in (l.dppo_lmhead_loss_fwd, l.dppo_lmhead_loss_fwd_bwd):
+            f.restype = C.c_int
+            f.argtypes = [C.POINTER(DppoLmheadArgs), C.c_void_p]
+        l.dppo_lmhead_args_size.restype = C.c_size_t
+        if l.dppo_lmhead_args_size() != C.sizeof(DppoLmheadArgs):
+            raise ImportError("dppo_lmhead_args_t layout differs between libdppo.so and this binding")
         if l.dppo_args_size() != C.sizeof(DppoArgs):
             raise ImportError("dppo_args_t layout differs between libdppo.so and this binding")
         _lib = l
@@ -163,6 +187,20 @@ def probe_read(src, sink, stream=None) -> None:
         raise DppoError(st)
 
 
+def gemm_nt(a, b, c=None, stream=None):
+    """dppo_gemm_nt: c[M, N] = a[M, K] @ b[N, K]^T for bf16 tensors with unit inner stride."""
+    M, K = a.shape
+    N = b.shape[0]
+    assert b.shape[1] == K and a.stride(1) == 1 and b.stride(1) == 1
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    st = lib().dppo_gemm_nt(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0),
+                            M, N, K, C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    return c
+
+
 def last_path() -> str:
     return lib().dppo_last_path().decode()
 
@@ -192,4 +230,42 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     res = dict(out)
     res["grad_logits"] = grad if backward else None
     res["args"] = args
+    return res
+
+
+def lmhead_workspace_bytes(T: int, V: int, d: int, chunk_rows: int = 0, have_weight_t: bool = False) -> int:
+    return lib().dppo_lmhead_workspace_bytes(T, V, d, chunk_rows, int(have_weight_t))
+
+
+def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t=None, out=None, grad_hidden=None,
+               workspace=None, stream=None, diagnostics: bool = False, **rule) -> dict:
+    """Run one hidden-state batch (workloads.make_lmhead_batch) through dppo_lmhead_loss_fwd[_bwd].
+    Returns the output tensors (device), grad_hidden among them."""
+    h, w = batch["hidden"], batch["weight"]
+    T, d, V = h.shape[0], batch["d"], batch["V"]
+    dev = h.device
+    if out is None:
+        out = alloc_outputs(T, dev, want_diagnostics=diagnostics)
+    if backward and grad_hidden is None:
+        grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        workspace = torch.empty(lmhead_workspace_bytes(T, V, d, chunk_rows, weight_t is not None), dtype=torch.uint8, device=dev)
+    a = DppoLmheadArgs()
+    a.loss = make_args(torch.empty((0, V), dtype=torch.bfloat16, device=dev), batch["sampled_ids"], batch["mu_logp"],
+                       batch["advantages"], batch["delta"], batch["variant"], batch["loss_scale"], out,
+                       batch["mu_topk_ids"], batch["mu_topk_logp"], V=V, **rule)
+    a.loss.T, a.loss.logits = T, None
+    a.hidden, a.ld_hidden, a.d = h.data_ptr(), h.stride(0), d
+    a.weight, a.ld_weight = w.data_ptr(), w.stride(0)
+    a.weight_t, a.ld_weight_t = _ptr(weight_t), (0 if weight_t is None else weight_t.stride(0))
+    a.chunk_rows = chunk_rows
+    a.grad_hidden, a.ld_grad_hidden = _ptr(grad_hidden if backward else None), (grad_hidden.stride(0) if backward else 0)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    fn = lib().dppo_lmhead_loss_fwd_bwd if backward else lib().dppo_lmhead_loss_fwd
+    st = fn(C.byref(a), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    res = dict(out)
+    res["grad_hidden"] = grad_hidden if backward else None
+    res["args"], res["workspace_buf"] = a, workspace
     return res

@@ -57,13 +57,9 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   return DPPO_OK;
 }
 
-dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
-  const dppo_status_t st = check_args(a, grad);
-  if (st != DPPO_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  double* partial = static_cast<double*>(a->workspace);
-  const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
-
+// Launch the loss kernel of one (already validated) call; its per-workgroup partial loss sums
+// go to partial[0 .. *nparts), *nparts <= max_parts.
+dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int max_parts, int* nparts_out, hipStream_t s) {
   int nparts = 0;
   if (a->T > 0) {
     int dev = 0;
@@ -136,7 +132,120 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
       g_last_path = "streaming";
     }
   }
+  *nparts_out = nparts;
+  return DPPO_OK;
+}
+
+dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
+  dppo_status_t st = check_args(a, grad);
+  if (st != DPPO_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  double* partial = static_cast<double*>(a->workspace);
+  int nparts = 0;
+  st = launch_loss(a, grad, partial, static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double)), &nparts, s);
+  if (st != DPPO_OK) return st;
   if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  return DPPO_OK;
+}
+
+// ---- the logits-free path: hidden states and lm_head weight in, gradient of the hidden states out
+
+constexpr int64_t kLmheadDefaultChunk = 4096;
+
+int64_t lmhead_chunk_rows(const dppo_lmhead_args_t* a) {
+  int64_t c = a->chunk_rows > 0 ? a->chunk_rows : kLmheadDefaultChunk;
+  if (c > a->loss.T) c = a->loss.T;
+  return c < 1 ? 1 : c;
+}
+
+size_t lmhead_workspace(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, bool have_weight_t) {
+  int64_t c = chunk_rows > 0 ? chunk_rows : kLmheadDefaultChunk;
+  if (c > T) c = T;
+  if (c < 1) c = 1;
+  size_t b = DPPO_WORKSPACE_BYTES;
+  b += static_cast<size_t>(c) * static_cast<size_t>(V) * 2;
+  if (!have_weight_t) b += static_cast<size_t>(d) * static_cast<size_t>(V) * 2;
+  return b;
+}
+
+dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
+  if (!a) return DPPO_ERR_NULL;
+  const int64_t T = a->loss.T, V = a->loss.V, d = a->d;
+  if (T < 0 || V < 64 || V % 64 != 0 || d < 64 || d % 64 != 0 || a->ld_hidden < d || a->ld_weight < d ||
+      a->ld_hidden % 8 != 0 || a->ld_weight % 8 != 0 || V >= (int64_t(1) << 22) || d >= (int64_t(1) << 22))
+    return DPPO_ERR_SHAPE;
+  if (a->loss.variant == DPPO_FULL_TV || a->loss.variant == DPPO_FULL_KL) return DPPO_ERR_VARIANT;
+  if (grad && (a->ld_grad_hidden < d)) return DPPO_ERR_SHAPE;
+  if (a->weight_t && (a->ld_weight_t < V || a->ld_weight_t % 8 != 0)) return DPPO_ERR_SHAPE;
+  const int64_t chunk = lmhead_chunk_rows(a);
+  if (!a->workspace || a->workspace_bytes < lmhead_workspace(T, V, d, a->chunk_rows, a->weight_t != nullptr)) return DPPO_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DPPO_ERR_ALIGN;
+  if (T > 0) {
+    if (!a->hidden || !a->weight || (grad && !a->grad_hidden)) return DPPO_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(a->hidden) | reinterpret_cast<uintptr_t>(a->weight) | reinterpret_cast<uintptr_t>(a->weight_t)) & 15u)
+      return DPPO_ERR_ALIGN;
+    if (grad && (reinterpret_cast<uintptr_t>(a->grad_hidden) & 1u)) return DPPO_ERR_ALIGN;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(a->workspace);
+  double* partial = reinterpret_cast<double*>(ws);
+  uint16_t* zbuf = reinterpret_cast<uint16_t*>(ws + DPPO_WORKSPACE_BYTES);
+  const uint16_t* wt = static_cast<const uint16_t*>(a->weight_t);
+  int64_t ldwt = a->ld_weight_t;
+
+  // validate the loss arguments on the first chunk's view before anything is launched
+  dppo_args_t c = a->loss;
+  c.logits = zbuf;
+  c.grad_logits = zbuf;
+  c.ld = V;
+  c.workspace = ws;
+  c.workspace_bytes = DPPO_WORKSPACE_BYTES;
+  const dppo_status_t st0 = check_args(&c, grad);
+  if (st0 != DPPO_OK) return st0;
+
+  if (grad && T > 0 && !wt) {
+    uint16_t* wt_own = zbuf + static_cast<size_t>(chunk) * static_cast<size_t>(V);
+    if (dppo::launch_transpose(static_cast<const uint16_t*>(a->weight), a->ld_weight, wt_own, V, static_cast<int>(V), static_cast<int>(d), s) != hipSuccess)
+      return DPPO_ERR_LAUNCH;
+    wt = wt_own;
+    ldwt = V;
+  }
+  const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
+  const int64_t nchunks = T > 0 ? (T + chunk - 1) / chunk : 0;
+  const int parts_per_chunk = nchunks > 0 ? static_cast<int>(max_parts / nchunks) : max_parts;
+  if (nchunks > 0 && parts_per_chunk < 1) return DPPO_ERR_SHAPE;
+  int used = 0;
+  for (int64_t r0 = 0; r0 < T; r0 += chunk) {
+    const int64_t rows = (T - r0 < chunk) ? (T - r0) : chunk;
+    const uint16_t* h = static_cast<const uint16_t*>(a->hidden) + r0 * a->ld_hidden;
+    // logits of the chunk (bf16, as a trainer's lm_head produces them)
+    if (dppo::launch_gemm_nt(h, a->ld_hidden, static_cast<const uint16_t*>(a->weight), a->ld_weight, zbuf, V,
+                             static_cast<int>(rows), static_cast<int>(V), static_cast<int>(d), s) != hipSuccess)
+      return DPPO_ERR_LAUNCH;
+    c.T = rows;
+    c.sampled_ids = a->loss.sampled_ids + r0;
+    c.mu_logp = a->loss.mu_logp + r0;
+    c.advantages = a->loss.advantages + r0;
+    c.mu_topk_ids = a->loss.mu_topk_ids ? a->loss.mu_topk_ids + r0 * a->loss.K : nullptr;
+    c.mu_topk_logp = a->loss.mu_topk_logp ? a->loss.mu_topk_logp + r0 * a->loss.K : nullptr;
+    c.loss_tok = a->loss.loss_tok ? a->loss.loss_tok + r0 : nullptr;
+    c.divergence = a->loss.divergence + r0;
+    c.mask = a->loss.mask + r0;
+    c.diagnostics = a->loss.diagnostics ? a->loss.diagnostics + r0 * DPPO_NDIAG : nullptr;
+    int np = 0;
+    const dppo_status_t st = launch_loss(&c, grad, partial + used, parts_per_chunk, &np, s);   // gradient in place
+    if (st != DPPO_OK) return st;
+    used += np;
+    if (grad) {
+      // gradient of the chunk's hidden states: g [rows, V] times W [V, d] = g times (W^T)^T
+      uint16_t* gh = static_cast<uint16_t*>(a->grad_hidden) + r0 * a->ld_grad_hidden;
+      if (dppo::launch_gemm_nt(zbuf, V, wt, ldwt, gh, a->ld_grad_hidden, static_cast<int>(rows), static_cast<int>(d),
+                               static_cast<int>(V), s) != hipSuccess)
+        return DPPO_ERR_LAUNCH;
+    }
+  }
+  if (dppo::launch_finalize(partial, used, a->loss.loss_scale, a->loss.loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  if (T > 0) g_last_path = "lmhead";
   return DPPO_OK;
 }
 
@@ -170,5 +279,29 @@ int dppo_version(void) { return DPPO_VERSION; }
 size_t dppo_args_size(void) { return sizeof(dppo_args_t); }
 
 const char* dppo_last_path(void) { return g_last_path; }
+
+size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t) {
+  return lmhead_workspace(T, V, d, chunk_rows, have_weight_t != 0);
+}
+
+dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream) { return run_lmhead(args, stream, false); }
+
+dppo_status_t dppo_lmhead_loss_fwd_bwd(const dppo_lmhead_args_t* args, void* stream) { return run_lmhead(args, stream, true); }
+
+size_t dppo_lmhead_args_size(void) { return sizeof(dppo_lmhead_args_t); }
+
+dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                           int64_t M, int64_t N, int64_t K, void* stream) {
+  if (M < 0 || N < 0 || K < 64 || K % 64 != 0 || M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
+  if (lda < K || ldb < K || ldc < N || lda % 8 != 0 || ldb % 8 != 0 || lda >= (int64_t(1) << 22) || ldb >= (int64_t(1) << 22)) return DPPO_ERR_SHAPE;
+  if (M == 0 || N == 0) return DPPO_OK;
+  if (!A || !B || !C) return DPPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) return DPPO_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(C) & 1u) return DPPO_ERR_ALIGN;
+  const hipError_t e = dppo::launch_gemm_nt(static_cast<const uint16_t*>(A), lda, static_cast<const uint16_t*>(B), ldb,
+                                            static_cast<uint16_t*>(C), ldc, static_cast<int>(M), static_cast<int>(N),
+                                            static_cast<int>(K), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
 
 }  // extern "C"

@@ -207,6 +207,58 @@ def make_batch(w: Workload, device="cpu", ld: int | None = None, keep_mu_full: b
     }
 
 
+@torch.no_grad()
+def make_lmhead_batch(w: Workload, d: int, device="cpu", exact: bool = False, rows_per_step: int = 1024,
+                      shift_sampled: float = 0.0) -> dict:
+    """One batch for the path that starts from the final hidden states: hidden [T, d] and lm_head
+    weight [V, d] in bf16 whose product has logits of standard deviation about w.logit_std, and a
+    rollout drawn from those logits (rounded to bf16, plus the mismatch noise) as in make_batch.
+
+    exact=True draws both matrices from small integers over a power of two, so that every product
+    and every partial sum of a logit is exact in fp32: the bf16 logits are then the same
+    whatever the order of accumulation.  shift_sampled moves the ROLLOUT's logit of the sampled
+    token on alternating rows after sampling (so mu_logp changes, not the hidden states)."""
+    dev = torch.device(device)
+    T, V, K = w.T, w.V, w.K
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    if exact:
+        # integers -8..8 have variance 24: a logit is a sum of d products of variance (24/64 / s)^2
+        s = 2.0 ** round(0.5 * torch.log2(torch.tensor(d / 64.0)).item() + torch.log2(torch.tensor(3.0 / w.logit_std)).item())
+        hidden = (torch.randint(-8, 9, (T, d), generator=g, device=dev).float() / (8.0 * s)).to(torch.bfloat16)
+        weight = (torch.randint(-8, 9, (V, d), generator=g, device=dev).float() / 8.0).to(torch.bfloat16)
+    else:
+        hidden = torch.randn((T, d), generator=g, device=dev).to(torch.bfloat16)
+        weight = (torch.randn((V, d), generator=g, device=dev) * (w.logit_std / d ** 0.5)).to(torch.bfloat16)
+    sampled = torch.empty(T, dtype=torch.int32, device=dev)
+    mu_logp = torch.empty(T, dtype=torch.float32, device=dev)
+    tk_ids = torch.empty((T, K), dtype=torch.int32, device=dev) if K > 0 else None
+    tk_lp = torch.empty((T, K), dtype=torch.float32, device=dev) if K > 0 else None
+    wf = weight.float()
+    for r0 in range(0, T, rows_per_step):
+        r1 = min(T, r0 + rows_per_step)
+        n = r1 - r0
+        zb = (hidden[r0:r1].float() @ wf.T).to(torch.bfloat16)      # the rollout engine's own forward
+        y = zb.float() + w.noise_std * torch.randn((n, V), generator=g, device=dev)
+        a = torch.multinomial(torch.softmax(y, -1), 1, generator=g).squeeze(1)
+        if shift_sampled != 0.0:
+            rows = torch.arange(n, device=dev)
+            y[rows, a] += torch.where((rows + r0) % 2 == 0, 1.0, -1.0) * shift_sampled
+        lmu = torch.log_softmax(y, dim=-1)
+        sampled[r0:r1] = a.to(torch.int32)
+        mu_logp[r0:r1] = lmu.gather(1, a[:, None]).squeeze(1)
+        if K > 0:
+            v, i = torch.topk(lmu, K, dim=-1)
+            tk_ids[r0:r1] = i.to(torch.int32)
+            tk_lp[r0:r1] = v
+    return {
+        "hidden": hidden, "weight": weight, "d": int(d), "sampled_ids": sampled, "mu_logp": mu_logp,
+        "mu_topk_ids": tk_ids, "mu_topk_logp": tk_lp, "advantages": _advantages(w, g, dev),
+        "delta": float(w.delta), "variant": int(w.variant), "K": int(K), "loss_scale": 1.0 / float(T),
+        "T": T, "V": V, "name": w.name,
+    }
+
+
 def to_host(batch: dict) -> dict:
     """Host copies for the oracle: bf16 logits widened exactly to float32 numpy, rest as numpy."""
     out = {}

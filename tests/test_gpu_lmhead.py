@@ -1,0 +1,251 @@
+"""GPU parity of the path that starts from the final hidden states (logits formed chunk by chunk on
+the matrix cores, never [T, V] at once; gradient with respect to the hidden states) against the
+float64 oracle, through the C ABI.
+
+Strict cases use inputs whose logits are exact in fp32 whatever the order of accumulation, so the
+bf16 logits of both sides are the same numbers and the per-token bar of the logits path applies
+unchanged.  With ordinary inputs an fp32-accumulated logit can fall on the other side of a bf16
+rounding boundary than the exact product does; those cases compare the rows where no token that
+matters sits that close to a boundary (decided on the oracle side alone)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dppo_oracle as O
+from paper_2602_04879_amd import binding as B
+from paper_2602_04879_amd import workloads as W
+from tests import parity as P
+from tests.test_gpu_parity import DEV, _say
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(b, rows, **rule):
+    sel = torch.as_tensor(np.asarray(rows, dtype=np.int64)).to(b["hidden"].device)
+    tk_i = b["mu_topk_ids"][sel].cpu().numpy() if b["mu_topk_ids"] is not None else None
+    tk_l = b["mu_topk_logp"][sel].cpu().numpy() if b["mu_topk_logp"] is not None else None
+    return O.lmhead_dppo_loss(b["hidden"][sel].float().cpu().numpy(), b["weight"].float().cpu().numpy(),
+                              b["sampled_ids"][sel].cpu().numpy(), b["mu_logp"][sel].cpu().numpy(),
+                              b["advantages"][sel].cpu().numpy(), b["delta"], b["variant"], b["loss_scale"], tk_i, tk_l, **rule)
+
+
+def _check_grad_hidden(b, res, rows, ref, skip=None):
+    """|gpu - ref| <= 1e-2 |ref| + 6 sigma, sigma the standard deviation of what rounding each
+    logit-gradient entry to bf16 (uniform within 2^-9 relative, independent over the vocabulary)
+    leaves on the sum over the vocabulary; 6 sigma because a test looks at up to 10^6 entries."""
+    g = res["grad_hidden"][torch.as_tensor(rows).to(DEV)].double().cpu().numpy()
+    Wd = b["weight"].double().cpu().numpy()
+    sigma = np.sqrt((ref["grad_logits"] ** 2) @ (Wd ** 2)) * (2.0 ** -9 / np.sqrt(3.0))
+    tol = 1e-2 * np.abs(ref["grad_hidden"]) + 6.0 * sigma + 1e-30
+    err = np.abs(g - ref["grad_hidden"])
+    if skip is not None:
+        err[skip] = 0.0
+    if not np.all(err <= tol):
+        i, j = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"grad_hidden row {rows[i]} col {j}: gpu {g[i, j]:.6e} ref {ref['grad_hidden'][i, j]:.6e} tol {tol[i, j]:.3e}")
+    nz = np.abs(ref["grad_hidden"]) > 0
+    return float(np.median(err[nz] / np.abs(ref["grad_hidden"][nz]))) if nz.any() else 0.0
+
+
+def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0, rows=None, rule=None, weight_t=None):
+    _say(f"[case] lmhead {w.name} T={w.T} V={w.V} d={d} K={w.K} variant={w.variant} exact={exact} chunk={chunk_rows} shift={shift} rule={rule}")
+    b = W.make_lmhead_batch(w, d, DEV, exact=exact, shift_sampled=shift)
+    rule = rule or {}
+    b["rule"] = rule
+    rows = np.arange(b["T"]) if rows is None else rows
+    res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, weight_t=weight_t, **rule)
+    torch.cuda.synchronize()
+    ref = _oracle(b, rows, **rule)
+    cmp_batch = dict(b, logits=None)
+    st = P.compare_rows(cmp_batch, res, rows, check_grad=False, ref=ref)
+    if len(rows) == b["T"]:
+        P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    if backward:
+        st["median_rel_err_grad_hidden"] = _check_grad_hidden(b, res, rows, ref)
+    _say(f"       {st}")
+    return b, res, st, ref
+
+
+# --------------------------------------------------------------------------- the matrix product alone
+@pytest.mark.parametrize("M,N,K,lda,ldb,ldc", [
+    (256, 256, 64, 64, 64, 256), (1, 1, 64, 64, 64, 1), (300, 520, 128, 136, 128, 528), (1000, 777, 192, 192, 200, 777),
+    (257, 4160, 4096, 4096, 4096, 4160), (513, 64, 8192, 8192, 8192, 64)])
+def test_gemm_exact_inputs_bitwise(M, N, K, lda, ldb, ldc):
+    _say(f"[case] gemm M={M} N={N} K={K}")
+    g = torch.Generator(device=DEV); g.manual_seed(M * 7 + N)
+    a = torch.zeros((M, lda), dtype=torch.bfloat16, device=DEV); b = torch.zeros((N, ldb), dtype=torch.bfloat16, device=DEV)
+    a[:, :K] = (torch.randint(-8, 9, (M, K), generator=g, device=DEV).float() / 64).bfloat16()
+    b[:, :K] = (torch.randint(-8, 9, (N, K), generator=g, device=DEV).float() / 8).bfloat16()
+    a[:, K:] = 7.0; b[:, K:] = -5.0                                # pitch padding must never be read
+    c = torch.full((M, ldc), 123.0, dtype=torch.bfloat16, device=DEV)
+    B.gemm_nt(a[:, :K], b[:, :K], c[:, :N])
+    torch.cuda.synchronize()
+    ref = O.lmhead_logits(a[:, :K].float().cpu().numpy(), b[:, :K].float().cpu().numpy())
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), ref)
+    assert (c[:, N:] == 123.0).all()
+
+
+def test_gemm_ordinary_inputs_within_one_rounding():
+    M, N, K = 384, 1000, 1024
+    g = torch.Generator(device=DEV); g.manual_seed(3)
+    a = torch.randn((M, K), generator=g, device=DEV).bfloat16(); b = (torch.randn((N, K), generator=g, device=DEV) / 8).bfloat16()
+    c = B.gemm_nt(a, b)
+    torch.cuda.synchronize()
+    exact = a.double().cpu().numpy() @ b.double().cpu().numpy().T
+    got = c.double().cpu().numpy()
+    # fp32 accumulation error (<= K eps32 sum|a||b|) plus one rounding to 8 significant bits
+    bound = 2.0 ** -8 * np.abs(exact) + K * 2.0 ** -24 * (np.abs(a.double().cpu().numpy()) @ np.abs(b.double().cpu().numpy()).T)
+    assert np.all(np.abs(got - exact) <= bound)
+    assert np.mean(got == O.bf16_round(exact)) > 0.99          # and almost always THE nearest bf16
+
+
+def test_gemm_error_codes():
+    a = torch.zeros((64, 128), dtype=torch.bfloat16, device=DEV); b = torch.zeros((64, 128), dtype=torch.bfloat16, device=DEV)
+    c = torch.zeros((64, 64), dtype=torch.bfloat16, device=DEV)
+    f = B.lib().dppo_gemm_nt
+    assert f(a.data_ptr(), 128, b.data_ptr(), 128, c.data_ptr(), 64, 64, 64, 128, None) == 0
+    assert f(a.data_ptr(), 128, b.data_ptr(), 128, c.data_ptr(), 64, 64, 64, 96, None) == 2       # K not a multiple of 64
+    assert f(a.data_ptr(), 100, b.data_ptr(), 128, c.data_ptr(), 64, 64, 64, 128, None) == 2      # lda < K
+    assert f(a.data_ptr(), 128, b.data_ptr(), 128, c.data_ptr(), 32, 64, 64, 128, None) == 2      # ldc < N
+    assert f(a.data_ptr() + 2, 128, b.data_ptr(), 128, c.data_ptr(), 64, 64, 64, 128, None) == 3
+    assert f(None, 128, b.data_ptr(), 128, c.data_ptr(), 64, 64, 64, 128, None) == 1
+    assert f(None, 128, None, 128, None, 64, 0, 64, 128, None) == 0                               # empty
+    torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------------- the whole path, every row
+@pytest.mark.parametrize("variant,K,delta", [(W.BINARY_TV, 0, 0.2), (W.BINARY_KL, 0, 0.05), (W.TOPK_TV, 20, 0.2), (W.TOPK_KL, 64, 0.05)])
+@pytest.mark.parametrize("shift", [0.0, 2.0])
+def test_small_all_rows_several_chunks(variant, K, delta, shift):
+    # T = 300 in chunks of 128 (two full chunks and a ragged one), V = 4160 = 16 tiles + a quarter tile
+    w = W.Workload("lm_small", 3, 100, 4160, variant, delta, K=K, logit_std=3.0, noise_std=1.0 if shift else 0.05, adv="normal", seed=71)
+    b, res, st, ref = _run_and_compare(w, 128, chunk_rows=128, shift=shift)
+    if shift:
+        assert 0 < st["masked"] < b["T"]
+
+
+@pytest.mark.parametrize("V,d,chunk", [(8192, 64, 0), (16384, 256, 1000), (64, 64, 7)])
+def test_shapes_resident_loss_kernel_inside_and_tiny(V, d, chunk):
+    w = W.Workload("lm_shape", 2, 150, V, W.TOPK_TV, 0.1, K=8, logit_std=3.0, noise_std=1.0, adv="pm1", seed=73)
+    _run_and_compare(w, d, chunk_rows=chunk, shift=2.0)
+    _run_and_compare(w, d, chunk_rows=chunk, shift=2.0, backward=False)
+
+
+def test_ignored_rows_baseline_rule_and_given_transpose():
+    w = W.Workload("lm_rule", 2, 130, 4096, W.BINARY_TV, 0.1, logit_std=3.0, noise_std=1.0, adv="normal", seed=79)
+    b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
+    b["sampled_ids"][::9] = -1
+    b["advantages"][4::11] = 0.0
+    rule = dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, ratio_cap=3.0)
+    b["rule"] = rule
+    rows = np.arange(b["T"])
+    ref = _oracle(b, rows, **rule)
+    wt = b["weight"].T.contiguous()
+    outs = []
+    for weight_t in (None, wt):
+        res = B.run_lmhead(b, chunk_rows=64, diagnostics=True, weight_t=weight_t, **rule)
+        torch.cuda.synchronize()
+        st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
+        _check_grad_hidden(b, res, rows, ref)
+        P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+        outs.append(res)
+        _say(f"       {st}")
+    assert torch.equal(outs[0]["grad_hidden"], outs[1]["grad_hidden"])
+    assert (outs[0]["grad_hidden"][::9] == 0).all()
+    assert st["masked"] > 0
+
+
+def test_ordinary_inputs_rows_clear_of_rounding_boundaries():
+    w = W.Workload("lm_real", 2, 128, 4096, W.TOPK_TV, 0.1, K=20, logit_std=3.0, noise_std=0.5, adv="pm1", seed=83)
+    d = 512
+    b = W.make_lmhead_batch(w, d, DEV, exact=False, shift_sampled=1.0)
+    rows = np.arange(b["T"])
+    res = B.run_lmhead(b, chunk_rows=100, diagnostics=True)
+    torch.cuda.synchronize()
+    ref = _oracle(b, rows)
+    # oracle side only: which logits lie within fp32-accumulation reach of a bf16 rounding boundary
+    h, Wm = b["hidden"].double().cpu().numpy(), b["weight"].double().cpu().numpy()
+    exact = h @ Wm.T
+    _, e = np.frexp(exact)
+    half_ulp = np.ldexp(1.0, e - 9)
+    margin = half_ulp - np.abs(exact - ref["logits"])
+    # d/8 fp32 roundings along an accumulator, each of at most 2^-24 of a partial sum, whose size is that
+    # of a random walk over the products: |final| + 4 standard deviations
+    reach = (d / 8) * 2.0 ** -24 * (np.abs(exact) + 4.0 * np.sqrt((h ** 2) @ (Wm ** 2).T))
+    near = margin <= reach
+    pi = np.exp(ref["logits"] - ref["logits"].max(1, keepdims=True)); pi /= pi.sum(1, keepdims=True)
+    matters = pi > 1e-3
+    a = b["sampled_ids"].cpu().numpy()
+    matters[np.arange(len(a)), a] = True
+    np.put_along_axis(matters, b["mu_topk_ids"].cpu().numpy().astype(np.int64), True, axis=1)
+    clear = ~(near & matters).any(1)
+    assert clear.sum() > 0.4 * b["T"]
+    # rows clear of boundaries: a flipped logit of a token below 1e-3 moves the log-normaliser by at most
+    # pi_j * ulp(z_j) < 1e-3 * 0.03, and every probability with it: an absolute 2e-5 on D covers those (measured 6e-6)
+    D = res["divergence"].double().cpu().numpy()
+    M = res["mask"].cpu().numpy()
+    errD = np.abs(D - ref["divergence"])[clear]
+    assert np.all(errD <= 1e-4 * np.abs(ref["divergence"][clear]) + 2e-5), errD.max()
+    exempt = (np.abs(ref["divergence"] - b["delta"]) < 2e-4) | (np.abs(ref["logp"] - b["mu_logp"].double().cpu().numpy()) < 2e-4)
+    assert np.all((M == ref["mask"])[clear & ~exempt])
+    same = clear & (M == ref["mask"])
+    lt = res["loss_tok"].double().cpu().numpy()
+    assert np.all(np.abs(lt - ref["loss_tok"])[same] <= 1e-3 * np.abs(ref["loss_tok"][same]) + 1e-4)
+    _check_grad_hidden(b, res, rows, ref, skip=~same)
+    _say(f"       clear rows {clear.sum()} of {b['T']}, max |dD| on them {errD.max():.2e}, masked {(M == 0).sum()}")
+
+
+def test_error_codes():
+    w = W.Workload("lm_err", 1, 16, 256, W.BINARY_TV, 0.2, logit_std=3.0, adv="pm1", seed=89)
+    b = W.make_lmhead_batch(w, 64, DEV, exact=True)
+    res = B.run_lmhead(b)
+    torch.cuda.synchronize()
+    a = res["args"]
+
+    def status(**kw):
+        saved = {k: getattr(a, k) for k in kw}
+        for k, v in kw.items():
+            setattr(a, k, v)
+        st = B.lib().dppo_lmhead_loss_fwd_bwd(C.byref(a), None)
+        for k, v in saved.items():
+            setattr(a, k, v)
+        return st
+
+    assert status() == 0
+    assert status(d=96) == 2
+    assert status(ld_hidden=32) == 2
+    assert status(hidden=None) == 1
+    assert status(grad_hidden=None) == 1
+    assert status(workspace_bytes=1024) == 6
+    assert status(workspace=a.workspace + 8) == 3
+    assert status(hidden=a.hidden + 2) == 3
+    a.loss.variant = W.FULL_TV
+    assert status() == 4
+    a.loss.variant = W.BINARY_TV
+    a.loss.V = 200
+    assert status() == 2                      # V not a multiple of 64
+    a.loss.V = 256
+    assert status() == 0
+    torch.cuda.synchronize()
+
+
+def test_headline_vocabulary_sampled_rows():
+    """V = 151936, d = 4096, T = 4608 in chunks of 2048 (two full chunks and a ragged one): sampled
+    rows against the oracle on inputs whose logits are exact in fp32."""
+    w = W.Workload("lm_qwen3", 9, 512, 151936, W.TOPK_TV, 0.2, K=20, logit_std=3.0, noise_std=0.3, adv="pm1", seed=97)
+    _say(f"[case] lmhead {w.name} T={w.T} V={w.V} d=4096 exact inputs, chunks of 2048")
+    b = W.make_lmhead_batch(w, 4096, DEV, exact=True, shift_sampled=1.0)
+    res = B.run_lmhead(b, chunk_rows=2048, diagnostics=True)
+    torch.cuda.synchronize()
+    mask = res["mask"].cpu().numpy()
+    rng = np.random.default_rng(11)
+    pick = {0, w.T - 1, 2047, 2048, 4095, 4096} | set(rng.integers(0, w.T, 8).tolist()) | set(np.nonzero(mask == 0)[0][:4].tolist())
+    rows = np.array(sorted(pick))
+    ref = _oracle(b, rows)
+    st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
+    st["median_rel_err_grad_hidden"] = _check_grad_hidden(b, res, rows, ref)
+    P.check_loss_scalar(b, res)
+    assert 0 < (mask == 0).sum() < w.T and st["masked"] > 0
+    _say(f"       masked={(mask == 0).sum()} {st}")
