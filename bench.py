@@ -87,6 +87,78 @@ def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
             "sample": f"first {done} of {T} rows of the same batch, fwd+bwd, float64 numpy, {wall:.1f} s"}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core peak
+
+
+def bench_lmhead(args, w, dev) -> int:
+    """The path from the final hidden states: one step = logits chunk by chunk on the matrix cores,
+    the loss kernel in place on each chunk, and the gradient of the hidden states."""
+    import torch
+    from paper_2602_04879_amd import binding as B
+    from paper_2602_04879_amd import workloads as W
+    batch = W.make_lmhead_batch(w, w.d_model, dev, rows_per_step=2048)
+    T, V, d = batch["T"], batch["V"], batch["d"]
+    out = B.alloc_outputs(T, dev)
+    grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, args.chunk_rows), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        return B.run_lmhead(batch, chunk_rows=args.chunk_rows, out=out, grad_hidden=grad_hidden, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / args.steps
+    # the two products (logits, gradient of the hidden states): 2 T V d multiply-adds each
+    flops = 4.0 * T * V * d
+    achieved = flops / (ms * 1e-3) / 1e12
+    chunk = args.chunk_rows if args.chunk_rows > 0 else 4096
+    rec = {
+        "metric": "dppo_lmhead_loss_fwd_bwd_tokens_per_s", "value": T / (ms * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "V": V, "d": d, "K": batch["K"], "variant": int(batch["variant"]),
+                   "delta": batch["delta"], "chunk_rows": chunk, "kernel_path": B.last_path(),
+                   "logits_bytes_resident": min(chunk, T) * V * 2, "logits_bytes_if_materialised": T * V * 2},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "dppo_gemm_nt_kernel",
+                     "algorithmic_flops_per_step": flops},
+        "loss": float(out["loss"].item()), "masked_tokens": int((out["mask"] == 0).sum().item()),
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline_lmhead(batch, args.cpu_seconds)
+    print(json.dumps(rec), flush=True)
+    return 0
+
+
+def cpu_baseline_lmhead(batch, budget_s: float, chunk_rows: int = 16) -> dict:
+    """Time the float64 oracle of the hidden-state path on leading rows of the same batch."""
+    from oracle import dppo_oracle as O
+    T = batch["T"]
+    Wd = batch["weight"].float().cpu().numpy()
+    done, wall, cpu = 0, 0.0, 0.0
+    while done < T and wall < budget_s:
+        sl = slice(done, min(T, done + chunk_rows))
+        h = batch["hidden"][sl].float().cpu().numpy()
+        tk_i = batch["mu_topk_ids"][sl].cpu().numpy() if batch["mu_topk_ids"] is not None else None
+        tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
+        t0, c0 = time.perf_counter(), time.process_time()
+        O.lmhead_dppo_loss(h, Wd, batch["sampled_ids"][sl].cpu().numpy(), batch["mu_logp"][sl].cpu().numpy(),
+                           batch["advantages"][sl].cpu().numpy(), batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l)
+        wall += time.perf_counter() - t0
+        cpu += time.process_time() - c0
+        done += sl.stop - sl.start
+    return {"value": done / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)), "kind": "oracle",
+            "sample": f"first {done} of {T} rows of the same batch, logits + fwd+bwd + hidden-state gradient, float64 numpy, {wall:.1f} s"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +168,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
+    ap.add_argument("--chunk-rows", type=int, default=0, help="tokens per chunk of the hidden-state workloads (0: library default)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures ONE GPU: the path is data-parallel over tokens with no exchange "
@@ -112,6 +185,8 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = W.WORKLOADS[args.workload]
+    if w.d_model:
+        return bench_lmhead(args, w, dev)
     batch = W.make_batch(w, dev, rows_per_step=2048)
     T, V, K = batch["T"], batch["V"], batch["K"]
     chunk = w.chunk_rows or T

@@ -5,9 +5,9 @@
 // One workgroup of 256 threads (4 waves, one per SIMD) per 256 x 256 tile of C, each wave a
 // 128 x 128 quadrant as 4 x 4 products of v_mfma_f32_32x32x16_bf16 (256 fp32 accumulators per
 // lane).  The contraction runs in steps of 64: the A and B panels of a step (256 x 64 each,
-// 32 KiB) go from global memory to registers while the previous step is multiplied, then into
-// LDS, 16 bytes per lane, in a layout swizzled so that the matrix-core fragment reads (one
-// 16-byte read per lane: 8 consecutive k of one row) spread over all banks.
+// 32 KiB) are loaded from global memory straight into one of two LDS stages a step ahead,
+// 16 bytes per lane, in a layout swizzled so that the matrix-core fragment reads (one 16-byte
+// read per lane: 8 consecutive k of one row) spread over all banks.
 // Panel rows past M or N re-read the last valid row (their products are never stored); all
 // loads go through range-checked buffer resources over exactly the rows a tile owns.  K must be
 // a multiple of 64, rows 16-byte aligned (checked by the host).
@@ -22,6 +22,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kRowBytes = kBK * 2;                    // one panel row in LDS: 128 bytes = 8 vectors
+constexpr int kPanelBytes = kBM * kRowBytes;          // 32 KiB (kBM == kBN)
+constexpr int kStageBytes = 2 * kPanelBytes;          // A panel then B panel
 
 // LDS byte offset of the 16-byte vector `kvec` (0..7) of panel row `row`: the vector index is
 // XOR-ed with bits 1..3 of the row, so 16 consecutive rows at one kvec cover all 64 banks once.
@@ -29,45 +31,26 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
   return static_cast<uint32_t>(row) * kRowBytes + static_cast<uint32_t>((kvec ^ ((row >> 1) & 7)) << 4);
 }
 
-__global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                           const uint16_t* __restrict__ B, int64_t ldb,
-                                                           uint16_t* __restrict__ C, int64_t ldc, int M, int N, int K,
-                                                           int tiles_m, int tiles_n) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[(kBM + kBN) * kRowBytes];   // 64 KiB
-  unsigned char* ldsA = lds;
-  unsigned char* ldsB = lds + kBM * kRowBytes;
-  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+// One 256 x 256 tile.  FULL: all 256 rows of both panels exist, so the eight rows a loader thread
+// moves per panel differ by a uniform stride (carried in the scalar offset of the load).
+// Otherwise a panel row past the matrix re-reads the last valid row: its products are never stored.
+template <bool FULL>
+__device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* lds1, const uint16_t* __restrict__ A, int64_t lda,
+                                          const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
+                                          int M, int N, int K, int m0, int n0) {
+  const int tid = threadIdx.x, lane = tid & 63, wid = uniform_i(tid >> 6);
   const int wm = wid >> 1, wn = wid & 1;
-
-  // Workgroup ids go round-robin over the 8 accelerator dies, each with its own L2: give each
-  // die a contiguous range of tiles, ordered with the M index fastest, so that the workgroups
-  // running together on a die share their B panels (and all of them the A panels).
-  const int ntiles = tiles_m * tiles_n;
-  const int per_xcd = (ntiles + 7) / 8;
-  const int logical = (static_cast<int>(blockIdx.x) & 7) * per_xcd + (static_cast<int>(blockIdx.x) >> 3);
-  if (logical >= ntiles) return;
-  const int tn = logical / tiles_m, tm = logical - tn * tiles_m;
-  const int m0 = tm * kBM, n0 = tn * kBN;
-
-  // range-checked views of the two panels
   const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);
-  const uint64_t bytes_a = static_cast<uint64_t>(rows_a - 1) * lda * 2 + static_cast<uint64_t>(K) * 2;
-  const uint64_t bytes_b = static_cast<uint64_t>(rows_b - 1) * ldb * 2 + static_cast<uint64_t>(K) * 2;
-  const row_rsrc_t ra = make_row_rsrc(A + static_cast<int64_t>(m0) * lda, static_cast<uint32_t>(bytes_a));
-  const row_rsrc_t rb = make_row_rsrc(B + static_cast<int64_t>(n0) * ldb, static_cast<uint32_t>(bytes_b));
+  const uint32_t pitch_a = static_cast<uint32_t>(lda) * 2u, pitch_b = static_cast<uint32_t>(ldb) * 2u;
+  // range-checked views of exactly the rows this tile owns
+  const row_rsrc_t ra = make_row_rsrc(A + static_cast<int64_t>(m0) * lda, static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u);
+  const row_rsrc_t rb = make_row_rsrc(B + static_cast<int64_t>(n0) * ldb, static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u);
 
-  // Loader role: thread t moves vector slot (t % 8) of rows t/8 + 32 i, i = 0..7, of each panel.
+  // Loader role: thread t moves LDS vector slot (t % 8) of rows t/8 + 32 i, i = 0..7, of each panel;
+  // the slot holds global k-vector slot ^ ((row >> 1) & 7), the same for all eight rows.
   const int lrow = tid >> 3, lslot = tid & 7;
-  uint32_t goff_a[8], goff_b[8], loff[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = lrow + 32 * i;
-    const int kvec = lslot ^ ((row >> 1) & 7);          // which global vector lands in this LDS slot
-    // a panel row past the matrix re-reads the last valid row: its products are never stored
-    goff_a[i] = static_cast<uint32_t>(static_cast<uint64_t>(min(row, rows_a - 1)) * lda * 2 + kvec * 16);
-    goff_b[i] = static_cast<uint32_t>(static_cast<uint64_t>(min(row, rows_b - 1)) * ldb * 2 + kvec * 16);
-    loff[i] = static_cast<uint32_t>(row) * kRowBytes + static_cast<uint32_t>(lslot << 4);
-  }
+  const uint32_t lkv = static_cast<uint32_t>((lslot ^ ((lrow >> 1) & 7)) << 4);
+  const uint32_t voff_a = static_cast<uint32_t>(lrow) * pitch_a + lkv, voff_b = static_cast<uint32_t>(lrow) * pitch_b + lkv;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -77,59 +60,143 @@ __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __res
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 sa[8], sb[8];
+  // Fragment role: lane holds 8 consecutive k (k half `fk` of a 16-wide step) of row `frow` of a
+  // 32-row block.  The swizzle depends on the row only through frow, so one offset per k-vector
+  // serves every block of both panels.
+  const int frow = lane & 31, fk = lane >> 5;
+  // 8-byte stores need C rows that keep 8-byte alignment (uniform over the launch)
+  const bool pair_aligned = ((reinterpret_cast<uintptr_t>(C) & 7u) == 0) && (ldc % 4 == 0);
+  uint32_t foff[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    sa[i] = row_load16(ra, goff_a[i], 0);
-    sb[i] = row_load16(rb, goff_b[i], 0);
-  }
-  const int frow = lane & 31, fk = lane >> 5;           // fragment role: row within a 32-row block, k half
+  for (int ks = 0; ks < 4; ++ks) foff[ks] = lds_off(frow, ks * 2 + fk);
+  const uint32_t fbase_a = static_cast<uint32_t>(wm * 128) * kRowBytes;
+  const uint32_t fbase_b = kPanelBytes + static_cast<uint32_t>(wn * 128) * kRowBytes;
+  auto read_frags = [&](const unsigned char* stage, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[4]) {
+    const uint32_t o = foff[ks];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      fa[t] = *reinterpret_cast<const bf16x8*>(stage + fbase_a + t * 32 * kRowBytes + o);
+      fb[t] = *reinterpret_cast<const bf16x8*>(stage + fbase_b + t * 32 * kRowBytes + o);
+    }
+  };
+  auto mma16 = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+
+  // Pipeline over the contraction: while step kt is multiplied out of LDS stage kt % 2, the
+  // panels of step kt+1 are loaded into the other stage; the fragments of each 16-wide sub-step
+  // are read from LDS one sub-step ahead of the matrix-core instructions that consume them.
+  // One barrier per step, before the first fragments of the next stage are read.
   const int nk = K / kBK;
-  for (int kt = 0; kt < nk; ++kt) {
-    __syncthreads();                                     // everyone is done reading the previous step
+  // Global memory -> LDS directly (buffer_load ... lds): lane l of a wave-level load deposits its
+  // 16 bytes at (LDS base of the instruction) + 16 l, which is exactly the loader layout above for
+  // the base stage + panel + i * 4096 + wave * 1024.  No staging registers, no LDS store
+  // instructions; completion is counted with the other vector-memory loads.
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  auto dma_panel = [&](unsigned char* stage, int step, bool b_panel) {
+    const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
+    unsigned char* dst = stage + (b_panel ? kPanelBytes : 0) + wid * 1024;
+    const row_rsrc_t r = b_panel ? rb : ra;
+    const uint32_t pitch = b_panel ? pitch_b : pitch_a;
+    const uint32_t voff = (b_panel ? voff_b : voff_a) + koff;
+    const int rows = b_panel ? rows_b : rows_a;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4*>(ldsA + loff[i]) = sa[i];
-      *reinterpret_cast<u32x4*>(ldsB + loff[i]) = sb[i];
+      if (FULL) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(dst + i * 4096), 16, voff, static_cast<uint32_t>(i * 32) * pitch, 0, 0);
+      } else {
+        const uint32_t row = static_cast<uint32_t>(min(lrow + 32 * i, rows - 1));
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(dst + i * 4096), 16, row * pitch + lkv + koff, 0, 0, 0);
+      }
     }
+  };
+  dma_panel(lds0, 0, false);
+  dma_panel(lds0, 0, true);
+  __syncthreads();                       // waits for this wave's loads, then for everyone's
+  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+  read_frags(lds0, 0, fa0, fb0);
+  // The two stages are two separate arrays and the loop takes two steps per trip, so that every
+  // LDS access names its array: the compiler then knows that fragment reads of one stage need not
+  // wait for the loads in flight into the other.
+  auto step = [&](const unsigned char* cur, unsigned char* nxt, int kt) {
+    const bool more = kt + 1 < nk;
+    read_frags(cur, 1, fa1, fb1);
+    if (more) dma_panel(nxt, kt + 1, false);
+    __builtin_amdgcn_sched_barrier(0);
+    mma16(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 2, fa0, fb0);
+    if (more) dma_panel(nxt, kt + 1, true);
+    __builtin_amdgcn_sched_barrier(0);
+    mma16(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(cur, 3, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma16(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    // the next stage is complete (own loads waited for, then everyone's) and this one fully read
     __syncthreads();
-    if (kt + 1 < nk) {
-      const uint32_t koff = static_cast<uint32_t>(kt + 1) * (kBK * 2);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        sa[i] = row_load16(ra, goff_a[i], koff);
-        sb[i] = row_load16(rb, goff_b[i], koff);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[4], fb[4];
-      const int kvec = ks * 2 + fk;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        fa[t] = *reinterpret_cast<const bf16x8*>(ldsA + lds_off(wm * 128 + t * 32 + frow, kvec));
-        fb[t] = *reinterpret_cast<const bf16x8*>(ldsB + lds_off(wn * 128 + t * 32 + frow, kvec));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
+    if (more) read_frags(nxt, 0, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma16(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    step(lds0, lds1, kt);
+    step(lds1, lds0, kt + 1);
   }
+  if (kt < nk) step(lds0, lds1, kt);      // odd number of steps: the last one reads stage 0 again
 
-  // Store: accumulator r of a 32 x 32 block is row (r/4)*8 + (lane/32)*4 + r%4, column lane%32.
+  // Store.  The products were formed with the operands swapped (B fragment first), so a lane's
+  // accumulators r = 4q .. 4q+3 of a 32 x 32 block are four consecutive COLUMNS
+  // q*8 + (lane/32)*4 + 0..3 of row lane%32: one 8-byte store of four bf16 each.
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    const int row = m0 + wm * 128 + i * 32 + frow;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int col = n0 + wn * 128 + j * 32 + frow;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
-        if (row < M && col < N) C[static_cast<int64_t>(row) * ldc + col] = float_to_bf16_bits(acc[i][j][r]);
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * 128 + j * 32 + q * 8 + fk * 4;
+        const uint32_t lo = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]), hi = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        uint16_t* dst = C + static_cast<int64_t>(row) * ldc + col;
+        if (FULL && pair_aligned) {
+          typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+          const u32x2 v = {lo, hi};
+          *reinterpret_cast<u32x2*>(dst) = v;
+        } else if (row < M) {
+          if (col < N) dst[0] = static_cast<uint16_t>(lo & 0xffffu);
+          if (col + 1 < N) dst[1] = static_cast<uint16_t>(lo >> 16);
+          if (col + 2 < N) dst[2] = static_cast<uint16_t>(hi & 0xffffu);
+          if (col + 3 < N) dst[3] = static_cast<uint16_t>(hi >> 16);
+        }
       }
     }
   }
+}
+
+__global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                           const uint16_t* __restrict__ B, int64_t ldb,
+                                                           uint16_t* __restrict__ C, int64_t ldc, int M, int N, int K,
+                                                           int tiles_m, int tiles_n) {
+  // two stages of (A panel | B panel): 2 x 64 KiB of the compute unit's 160 KiB
+  __shared__ __attribute__((aligned(16))) unsigned char lds0[kStageBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char lds1[kStageBytes];
+  // Workgroup ids go round-robin over the 8 accelerator dies, each with its own L2: give each
+  // die a contiguous range of tiles, ordered with the M index fastest, so that the workgroups
+  // running together on a die share their B panels (and all of them the A panels).
+  const int ntiles = tiles_m * tiles_n;
+  const int per_xcd = (ntiles + 7) / 8;
+  const int logical = (static_cast<int>(blockIdx.x) & 7) * per_xcd + (static_cast<int>(blockIdx.x) >> 3);
+  if (logical >= ntiles) return;
+  const int tn = logical / tiles_m, tm = logical - tn * tiles_m;
+  const int m0 = tm * kBM, n0 = tn * kBN;
+  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  else                                gemm_tile<false>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
 }
 
 // dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS (one padding column keeps

@@ -39,6 +39,7 @@ class Workload:
     drift_frac: float = 0.0       # fraction of tokens whose sampled-token logit has moved since the
     drift_std: float = 0.0        # rollout (policy updates in between), by N(0, drift_std)
     mu_full: bool = False         # also hand over the rollout policy's full logits, rounded to bf16
+    d_model: int = 0              # > 0: the batch starts from hidden states [T, d_model] and an lm_head weight
     adv: str = "pm1"              # "pm1" | "normal" | "group_norm"
     group: int = 8
     chunk_rows: int = 0           # caller-side T-chunking (0 = one call)
@@ -75,6 +76,11 @@ WORKLOADS = {
     "c6_qwen3_full_kl": Workload("c6_qwen3_full_kl", 16, 2048, 151936, FULL_KL, 0.05, mu_full=True,
                                  logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
                                  adv="group_norm", group=8, seed=1002),
+    # The headline shape entered one step earlier: final hidden states of a d = 4096 model (the
+    # Qwen3-8B size) and its lm_head weight; the logits exist one chunk of tokens at a time.
+    "c7_qwen3_lmhead_binary_tv": Workload("c7_qwen3_lmhead_binary_tv", 16, 2048, 151936, BINARY_TV, 0.2, d_model=4096,
+                                          logit_std=3.0, noise_std=0.05, drift_frac=0.05, drift_std=1.5,
+                                          adv="group_norm", group=8, seed=1007),
 }
 
 
@@ -244,6 +250,10 @@ def make_lmhead_batch(w: Workload, d: int, device="cpu", exact: bool = False, ro
         if shift_sampled != 0.0:
             rows = torch.arange(n, device=dev)
             y[rows, a] += torch.where((rows + r0) % 2 == 0, 1.0, -1.0) * shift_sampled
+        if w.drift_frac > 0:     # the trainer has moved since the rollout: seen from the trainer, mu is what is off
+            moved = torch.rand(n, generator=g, device=dev) < w.drift_frac
+            stepv = w.drift_std * torch.randn(n, generator=g, device=dev)
+            y[torch.arange(n, device=dev), a] -= torch.where(moved, stepv, torch.zeros_like(stepv))
         lmu = torch.log_softmax(y, dim=-1)
         sampled[r0:r1] = a.to(torch.int32)
         mu_logp[r0:r1] = lmu.gather(1, a[:, None]).squeeze(1)
