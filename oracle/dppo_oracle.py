@@ -310,11 +310,13 @@ def lmhead_dppo_loss(hidden, weight, sampled_ids, mu_logp, advantages, delta, va
     (the memory-saving form of Sec. 4.4's concern: no [T, V] array is needed outside this oracle):
     logits as the trainer's lm_head produces them, dppo_loss on them, and the gradient with respect
     to the hidden states by the chain rule, d loss / d h = (d loss / d z) W, the rounding of the
-    logits passing gradients through unchanged.  Returns dppo_loss's dict plus logits and
-    grad_hidden [T, d] (None without want_grad)."""
+    logits passing gradients through unchanged; likewise d loss / d W = (d loss / d z)^T h for the
+    lm_head weight.  Returns dppo_loss's dict plus logits, grad_hidden [T, d] and grad_weight [V, d]
+    (None without want_grad)."""
     z = lmhead_logits(hidden, weight)
     out = dppo_loss(z, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, mu_topk_ids, mu_topk_logp,
                     want_grad=want_grad, **rule)
     out["logits"] = z
     out["grad_hidden"] = out["grad_logits"] @ np.asarray(weight, dtype=np.float64) if want_grad else None
+    out["grad_weight"] = out["grad_logits"].T @ np.asarray(hidden, dtype=np.float64) if want_grad else None
     return out

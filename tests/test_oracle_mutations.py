@@ -55,6 +55,8 @@ MUTATIONS = [
     ("bf16 rounding keeps 9 bits", "return np.ldexp(np.rint(m * 256.0) / 256.0, e)", "return np.ldexp(np.rint(m * 512.0) / 512.0, e)"),
     ("lm_head: weight not transposed in the gradient", 'out["grad_logits"] @ np.asarray(weight, dtype=np.float64) if want_grad',
      'out["grad_logits"] @ np.asarray(weight, dtype=np.float64)[::-1] if want_grad'),
+    ("lm_head: weight gradient contracts the wrong index", 'out["grad_logits"].T @ np.asarray(hidden, dtype=np.float64) if want_grad',
+     'out["grad_logits"].T[:, ::-1] @ np.asarray(hidden, dtype=np.float64) if want_grad'),
     ("lm_head: logits not rounded", "return bf16_round(hidden @ weight.T)", "return hidden @ weight.T"),
     ("binary KL uses clamped-away 1-q", "one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()", "one_minus_q = pi_row[:a].sum()"),
 ]

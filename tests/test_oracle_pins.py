@@ -569,10 +569,13 @@ def test_lmhead_path_is_the_chain_rule_through_the_logits():
             np.testing.assert_array_equal(out[k], ref[k])
         assert 0 < (out["mask"] == 0).sum() < T
         ht = torch.tensor(hs, dtype=torch.float64, requires_grad=True)
-        lp = torch.log_softmax(ht @ torch.tensor(Ws, dtype=torch.float64).T, -1).gather(1, torch.tensor(a)[:, None]).squeeze(1)
+        wt = torch.tensor(Ws, dtype=torch.float64, requires_grad=True)
+        lp = torch.log_softmax(ht @ wt.T, -1).gather(1, torch.tensor(a)[:, None]).squeeze(1)
         coef = torch.tensor(out["mask"] * out["ratio"] * adv, dtype=torch.float64)
         (-(coef * lp).sum() * 0.25).backward()
         np.testing.assert_allclose(out["grad_hidden"], ht.grad.numpy(), rtol=1e-9, atol=1e-14)
+        np.testing.assert_allclose(out["grad_weight"], wt.grad.numpy(), rtol=1e-9, atol=1e-14)
+        assert out["grad_weight"].shape == (V, d) and np.abs(out["grad_weight"].sum(0)).max() < 1e-12    # rows of g sum to 0
     # logits that do need rounding: rounded once, to 8 significant bits
     h2, W2 = rng.normal(size=(3, 8)), rng.normal(size=(5, 8))
     z2 = O.lmhead_logits(h2, W2)
