@@ -92,7 +92,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core peak
 
 def bench_lmhead(args, w, dev) -> int:
     """The path from the final hidden states: one step = logits chunk by chunk on the matrix cores,
-    the loss kernel in place on each chunk, and the gradient of the hidden states."""
+    the loss kernel in place on each chunk, and the gradients of the hidden states and of the
+    lm_head weight."""
     import torch
     from paper_2602_04879_amd import binding as B
     from paper_2602_04879_amd import workloads as W
@@ -100,11 +101,13 @@ def bench_lmhead(args, w, dev) -> int:
     T, V, d = batch["T"], batch["V"], batch["d"]
     out = B.alloc_outputs(T, dev)
     grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, args.chunk_rows), dtype=torch.uint8, device=dev)
+    grad_weight = torch.empty((V, d), dtype=torch.float32, device=dev)
+    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, args.chunk_rows, False, True), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step():
-        return B.run_lmhead(batch, chunk_rows=args.chunk_rows, out=out, grad_hidden=grad_hidden, workspace=ws, stream=stream)
+        return B.run_lmhead(batch, chunk_rows=args.chunk_rows, out=out, grad_hidden=grad_hidden, grad_weight=grad_weight,
+                            workspace=ws, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -116,8 +119,8 @@ def bench_lmhead(args, w, dev) -> int:
     ev1.record(stream)
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / args.steps
-    # the two products (logits, gradient of the hidden states): 2 T V d multiply-adds each
-    flops = 4.0 * T * V * d
+    # the three products (logits, gradient of the hidden states, gradient of the weight): 2 T V d flops each
+    flops = 6.0 * T * V * d
     achieved = flops / (ms * 1e-3) / 1e12
     chunk = args.chunk_rows if args.chunk_rows > 0 else 4096
     rec = {
@@ -126,6 +129,7 @@ def bench_lmhead(args, w, dev) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "d": d, "K": batch["K"], "variant": int(batch["variant"]),
                    "delta": batch["delta"], "chunk_rows": chunk, "kernel_path": B.last_path(),
+                   "outputs": "loss, per-token, grad_hidden bf16, grad_weight fp32",
                    "logits_bytes_resident": min(chunk, T) * V * 2, "logits_bytes_if_materialised": T * V * 2},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "dppo_gemm_nt_kernel",

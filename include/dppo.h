@@ -186,6 +186,7 @@ const char* dppo_last_path(void);
  *     z_c = h_c W^T           bf16 logits of the chunk, fp32 accumulation, round to nearest even
  *     loss, D, M, and g_c = d loss / d z_c in place            (exactly dppo_loss_fwd_bwd on z_c)
  *     d loss / d h_c = g_c W  bf16, fp32 accumulation
+ *     d loss / d W  += g_c^T h_c   (optional) fp32
  * so device memory holds one chunk of logits, not [T, V].  `loss` carries every per-token
  * input and output with the meaning it has in dppo_loss_fwd_bwd (its logits, ld, grad_logits,
  * mu_logits, workspace and flags fields are ignored); the DPPO_FULL_* variants are not
@@ -203,17 +204,24 @@ typedef struct {
   int64_t        chunk_rows;    /* tokens per chunk; <= 0: 4096                                    */
   void*          grad_hidden;   /* bf16 [T, ld_grad_hidden]; dppo_lmhead_loss_fwd_bwd only         */
   int64_t        ld_grad_hidden;/* >= d                                                            */
+  float*         grad_weight;   /* optional fp32 [V, ld_grad_weight], 16-byte aligned:             */
+                                /* d loss / d W = g^T h summed over all T tokens; NULL = not wanted */
+  int64_t        ld_grad_weight;/* >= d, multiple of 4                                             */
+  int32_t        grad_weight_accumulate; /* 0: overwrite grad_weight; 1: add to what it holds (a   */
+                                /* trainer accumulating micro-batches into an fp32 main gradient) */
   void*          workspace;     /* >= dppo_lmhead_workspace_bytes(...) bytes, 256-byte aligned:    */
-                                /* loss partial sums, the chunk of logits, and W^T unless given    */
+                                /* loss partial sums, the chunk of logits, W^T unless given, and   */
+                                /* for the weight gradient the transposed chunk of g and of h      */
   size_t         workspace_bytes;
 } dppo_lmhead_args_t;
 
-size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t);
+size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t,
+                                   int want_grad_weight);
 
 /* Forward only (loss, loss_tok, divergence, mask, diagnostics). */
 dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream);
 
-/* Forward and backward: also grad_hidden = d loss / d hidden. */
+/* Forward and backward: also grad_hidden = d loss / d hidden and, if asked for, grad_weight. */
 dppo_status_t dppo_lmhead_loss_fwd_bwd(const dppo_lmhead_args_t* args, void* stream);
 
 /* sizeof(dppo_lmhead_args_t) as the library was compiled. */
@@ -228,6 +236,12 @@ size_t dppo_lmhead_args_size(void);
  * overlap.  M = 0 or N = 0 is valid and does nothing. */
 dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
                            int64_t M, int64_t N, int64_t K, void* stream);
+
+/* The same product with an fp32 result, C (+)= A B^T: C fp32 [M, ldc], 16-byte aligned with ldc a
+ * multiple of 4; accumulate != 0 adds the product to what C holds.  (The weight gradient of the
+ * path above sums its chunks this way.) */
+dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
+                               int64_t M, int64_t N, int64_t K, int accumulate, void* stream);
 
 /* ---- measurement utilities (not part of the loss) ------------------------------------------
  * Plain device-to-device copy of `bytes` bytes with 16-byte vector loads/stores (dst, src and

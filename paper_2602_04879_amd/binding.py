@@ -48,6 +48,7 @@ class DppoLmheadArgs(C.Structure):
         ("weight_t", C.c_void_p), ("ld_weight_t", C.c_int64),
         ("chunk_rows", C.c_int64),
         ("grad_hidden", C.c_void_p), ("ld_grad_hidden", C.c_int64),
+        ("grad_weight", C.c_void_p), ("ld_grad_weight", C.c_int64), ("grad_weight_accumulate", C.c_int32),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -86,7 +87,10 @@ def lib() -> C.CDLL:
         l.dppo_gemm_nt.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                    C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
         l.dppo_lmhead_workspace_bytes.restype = C.c_size_t
-        l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int]
+        l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int]
+        l.dppo_gemm_nt_f32.restype = C.c_int
+        l.dppo_gemm_nt_f32.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                       C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p]
         for f in (l.dppo_lmhead_loss_fwd, l.dppo_lmhead_loss_fwd_bwd):
             f.restype = C.c_int
             f.argtypes = [C.POINTER(DppoLmheadArgs), C.c_void_p]
@@ -201,6 +205,17 @@ def gemm_nt(a, b, c=None, stream=None):
     return c
 
 
+def gemm_nt_f32(a, b, c, accumulate: bool = False, stream=None):
+    """dppo_gemm_nt_f32: c[M, N] (+)= a[M, K] @ b[N, K]^T, c fp32."""
+    M, K = a.shape
+    N = b.shape[0]
+    st = lib().dppo_gemm_nt_f32(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0),
+                                M, N, K, int(accumulate), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    return c
+
+
 def last_path() -> str:
     return lib().dppo_last_path().decode()
 
@@ -233,12 +248,14 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     return res
 
 
-def lmhead_workspace_bytes(T: int, V: int, d: int, chunk_rows: int = 0, have_weight_t: bool = False) -> int:
-    return lib().dppo_lmhead_workspace_bytes(T, V, d, chunk_rows, int(have_weight_t))
+def lmhead_workspace_bytes(T: int, V: int, d: int, chunk_rows: int = 0, have_weight_t: bool = False,
+                           want_grad_weight: bool = False) -> int:
+    return lib().dppo_lmhead_workspace_bytes(T, V, d, chunk_rows, int(have_weight_t), int(want_grad_weight))
 
 
 def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t=None, out=None, grad_hidden=None,
-               workspace=None, stream=None, diagnostics: bool = False, **rule) -> dict:
+               workspace=None, stream=None, diagnostics: bool = False, grad_weight=None, accumulate: bool = False,
+               **rule) -> dict:
     """Run one hidden-state batch (workloads.make_lmhead_batch) through dppo_lmhead_loss_fwd[_bwd].
     Returns the output tensors (device), grad_hidden among them."""
     h, w = batch["hidden"], batch["weight"]
@@ -249,7 +266,8 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t
     if backward and grad_hidden is None:
         grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
     if workspace is None:
-        workspace = torch.empty(lmhead_workspace_bytes(T, V, d, chunk_rows, weight_t is not None), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(lmhead_workspace_bytes(T, V, d, chunk_rows, weight_t is not None, grad_weight is not None),
+                                dtype=torch.uint8, device=dev)
     a = DppoLmheadArgs()
     a.loss = make_args(torch.empty((0, V), dtype=torch.bfloat16, device=dev), batch["sampled_ids"], batch["mu_logp"],
                        batch["advantages"], batch["delta"], batch["variant"], batch["loss_scale"], out,
@@ -260,6 +278,8 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t
     a.weight_t, a.ld_weight_t = _ptr(weight_t), (0 if weight_t is None else weight_t.stride(0))
     a.chunk_rows = chunk_rows
     a.grad_hidden, a.ld_grad_hidden = _ptr(grad_hidden if backward else None), (grad_hidden.stride(0) if backward else 0)
+    a.grad_weight, a.ld_grad_weight = _ptr(grad_weight), (0 if grad_weight is None else grad_weight.stride(0))
+    a.grad_weight_accumulate = int(accumulate)
     a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     fn = lib().dppo_lmhead_loss_fwd_bwd if backward else lib().dppo_lmhead_loss_fwd
     st = fn(C.byref(a), C.c_void_p(_stream_handle(stream)))
@@ -267,5 +287,6 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t
         raise DppoError(st)
     res = dict(out)
     res["grad_hidden"] = grad_hidden if backward else None
+    res["grad_weight"] = grad_weight if backward else None
     res["args"], res["workspace_buf"] = a, workspace
     return res

@@ -34,9 +34,12 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
 // One 256 x 256 tile.  FULL: all 256 rows of both panels exist, so the eight rows a loader thread
 // moves per panel differ by a uniform stride (carried in the scalar offset of the load).
 // Otherwise a panel row past the matrix re-reads the last valid row: its products are never stored.
-template <bool FULL>
+// OUT selects what leaves the tile: bf16 (rounded to nearest even), fp32, or fp32 added to what C holds.
+enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
+
+template <bool FULL, int OUT>
 __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* lds1, const uint16_t* __restrict__ A, int64_t lda,
-                                          const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
+                                          const uint16_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv, int64_t ldc,
                                           int M, int N, int K, int m0, int n0) {
   const int tid = threadIdx.x, lane = tid & 63, wid = uniform_i(tid >> 6);
   const int wm = wid >> 1, wn = wid & 1;
@@ -65,7 +68,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // serves every block of both panels.
   const int frow = lane & 31, fk = lane >> 5;
   // 8-byte stores need C rows that keep 8-byte alignment (uniform over the launch)
-  const bool pair_aligned = ((reinterpret_cast<uintptr_t>(C) & 7u) == 0) && (ldc % 4 == 0);
+  const bool pair_aligned = ((reinterpret_cast<uintptr_t>(Cv) & 7u) == 0) && (ldc % 4 == 0);
   uint32_t foff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) foff[ks] = lds_off(frow, ks * 2 + fk);
@@ -153,7 +156,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
 
   // Store.  The products were formed with the operands swapped (B fragment first), so a lane's
   // accumulators r = 4q .. 4q+3 of a 32 x 32 block are four consecutive COLUMNS
-  // q*8 + (lane/32)*4 + 0..3 of row lane%32: one 8-byte store of four bf16 each.
+  // q*8 + (lane/32)*4 + 0..3 of row lane%32: one 8-byte store of four bf16 (16 bytes of fp32) each.
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = m0 + wm * 128 + i * 32 + frow;
@@ -162,47 +165,67 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int col = n0 + wn * 128 + j * 32 + q * 8 + fk * 4;
-        const uint32_t lo = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]), hi = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-        uint16_t* dst = C + static_cast<int64_t>(row) * ldc + col;
-        if (FULL && pair_aligned) {
-          typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-          const u32x2 v = {lo, hi};
-          *reinterpret_cast<u32x2*>(dst) = v;
-        } else if (row < M) {
-          if (col < N) dst[0] = static_cast<uint16_t>(lo & 0xffffu);
-          if (col + 1 < N) dst[1] = static_cast<uint16_t>(lo >> 16);
-          if (col + 2 < N) dst[2] = static_cast<uint16_t>(hi & 0xffffu);
-          if (col + 3 < N) dst[3] = static_cast<uint16_t>(hi >> 16);
+        if (OUT == kOutBf16) {
+          const uint32_t lo = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]), hi = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          uint16_t* dst = static_cast<uint16_t*>(Cv) + static_cast<int64_t>(row) * ldc + col;
+          if (FULL && pair_aligned) {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 v = {lo, hi};
+            *reinterpret_cast<u32x2*>(dst) = v;
+          } else if (row < M) {
+            if (col < N) dst[0] = static_cast<uint16_t>(lo & 0xffffu);
+            if (col + 1 < N) dst[1] = static_cast<uint16_t>(lo >> 16);
+            if (col + 2 < N) dst[2] = static_cast<uint16_t>(hi & 0xffffu);
+            if (col + 3 < N) dst[3] = static_cast<uint16_t>(hi >> 16);
+          }
+        } else {
+          // fp32 out (the host requires 16-byte aligned rows for these forms)
+          typedef float f32x4 __attribute__((ext_vector_type(4)));
+          float* dst = static_cast<float*>(Cv) + static_cast<int64_t>(row) * ldc + col;
+          f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          if (FULL || (row < M && col + 3 < N)) {
+            if (OUT == kOutF32Add) v += *reinterpret_cast<const f32x4*>(dst);
+            *reinterpret_cast<f32x4*>(dst) = v;
+          } else if (row < M) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (col + e < N) dst[e] = (OUT == kOutF32Add ? dst[e] : 0.f) + v[e];
+          }
         }
       }
     }
   }
 }
 
+// Workgroup ids go round-robin over the 8 accelerator dies, each with its own L2.  Tiles are
+// grouped in blocks of 8 (M) x 4 (N) = 32, the number of workgroups that run together on a die, and
+// each die gets a contiguous range of blocks: the workgroups sharing an L2 at any time then share
+// 8 A panels and 4 B panels (12 panel streams for 32 tiles).  Positions of a block that fall
+// outside the matrix exit at once.
+constexpr int kGroupM = 8, kGroupN = 4;
+
+template <int OUT>
 __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                            const uint16_t* __restrict__ B, int64_t ldb,
-                                                           uint16_t* __restrict__ C, int64_t ldc, int M, int N, int K,
-                                                           int tiles_m, int tiles_n) {
+                                                           void* __restrict__ C, int64_t ldc, int M, int N, int K,
+                                                           int tiles_m, int tiles_n, int blocks_m, int blocks_per_die) {
   // two stages of (A panel | B panel): 2 x 64 KiB of the compute unit's 160 KiB
   __shared__ __attribute__((aligned(16))) unsigned char lds0[kStageBytes];
   __shared__ __attribute__((aligned(16))) unsigned char lds1[kStageBytes];
-  // Workgroup ids go round-robin over the 8 accelerator dies, each with its own L2: give each
-  // die a contiguous range of tiles, ordered with the M index fastest, so that the workgroups
-  // running together on a die share their B panels (and all of them the A panels).
-  const int ntiles = tiles_m * tiles_n;
-  const int per_xcd = (ntiles + 7) / 8;
-  const int logical = (static_cast<int>(blockIdx.x) & 7) * per_xcd + (static_cast<int>(blockIdx.x) >> 3);
-  if (logical >= ntiles) return;
-  const int tn = logical / tiles_m, tm = logical - tn * tiles_m;
+  const int die = static_cast<int>(blockIdx.x) & 7, slot = static_cast<int>(blockIdx.x) >> 3;      // slot-th workgroup of its die
+  const int block = die * blocks_per_die + slot / (kGroupM * kGroupN), within = slot % (kGroupM * kGroupN);
+  const int bn = block / blocks_m, bm = block - bn * blocks_m;
+  const int tm = bm * kGroupM + (within % kGroupM), tn = bn * kGroupN + (within / kGroupM);
+  if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * kBM, n0 = tn * kBN;
-  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
-  else                                gemm_tile<false>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  else                                gemm_tile<false, OUT>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
 }
 
-// dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS (one padding column keeps
-// the transposed reads off a single bank).
+// dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS (two padding columns keep
+// the transposed reads off a single bank).  Columns R .. R_pad-1 of dst are written as zeros.
 __global__ __launch_bounds__(256) void dppo_transpose_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
-                                                             uint16_t* __restrict__ dst, int64_t ld_dst, int R, int Cn) {
+                                                             uint16_t* __restrict__ dst, int64_t ld_dst, int R, int Cn, int R_pad) {
   __shared__ uint16_t tile[64][66];
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -213,25 +236,29 @@ __global__ __launch_bounds__(256) void dppo_transpose_kernel(const uint16_t* __r
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
     const int c = c0 + i, r = r0 + tx;
-    if (c < Cn && r < R) dst[static_cast<int64_t>(c) * ld_dst + r] = tile[tx][i];
+    if (c < Cn && r < R_pad) dst[static_cast<int64_t>(c) * ld_dst + r] = tile[tx][i];
   }
 }
 
 }  // namespace
 
-hipError_t launch_transpose(const uint16_t* src, int64_t ld_src, uint16_t* dst, int64_t ld_dst, int R, int Cn, hipStream_t s) {
-  if (R <= 0 || Cn <= 0) return hipSuccess;
-  hipLaunchKernelGGL(dppo_transpose_kernel, dim3((Cn + 63) / 64, (R + 63) / 64), dim3(256), 0, s, src, ld_src, dst, ld_dst, R, Cn);
+hipError_t launch_transpose(const uint16_t* src, int64_t ld_src, uint16_t* dst, int64_t ld_dst, int R, int Cn, int R_pad, hipStream_t s) {
+  if (R_pad < R) R_pad = R;
+  if (R_pad <= 0 || Cn <= 0) return hipSuccess;
+  hipLaunchKernelGGL(dppo_transpose_kernel, dim3((Cn + 63) / 64, (R_pad + 63) / 64), dim3(256), 0, s, src, ld_src, dst, ld_dst, R, Cn, R_pad);
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, uint16_t* C, int64_t ldc,
-                          int M, int N, int K, hipStream_t s) {
+hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, int out, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
   const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
-  const int ntiles = tiles_m * tiles_n;
-  const int grid = ((ntiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(dppo_gemm_nt_kernel, dim3(grid), dim3(256), 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n);
+  const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
+  const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
+  const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
+  if (out == 0)      hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutBf16>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else if (out == 1) hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutF32>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else               hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutF32Add>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
   return hipGetLastError();
 }
 

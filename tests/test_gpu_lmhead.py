@@ -49,13 +49,31 @@ def _check_grad_hidden(b, res, rows, ref, skip=None):
     return float(np.median(err[nz] / np.abs(ref["grad_hidden"][nz]))) if nz.any() else 0.0
 
 
+def _check_grad_weight(b, res, ref, M):
+    """All T rows were run and compared: the summed weight gradient against the oracle's, within
+    1e-3 |ref| + 6 sigma of the bf16 rounding of g (as for grad_hidden; the result itself is fp32)."""
+    if not np.array_equal(M, ref["mask"]):
+        return None                                 # a token inside the exemption band took the other mask value
+    gw = res["grad_weight"].double().cpu().numpy()
+    h = b["hidden"].double().cpu().numpy()
+    sigma = np.sqrt((ref["grad_logits"] ** 2).T @ (h ** 2)) * (2.0 ** -9 / np.sqrt(3.0))
+    tol = 1e-3 * np.abs(ref["grad_weight"]) + 6.0 * sigma + 1e-30
+    err = np.abs(gw - ref["grad_weight"])
+    if not np.all(err <= tol):
+        i, j = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"grad_weight [{i}, {j}]: gpu {gw[i, j]:.6e} ref {ref['grad_weight'][i, j]:.6e} tol {tol[i, j]:.3e}")
+    return float(err.max())
+
+
 def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0, rows=None, rule=None, weight_t=None):
     _say(f"[case] lmhead {w.name} T={w.T} V={w.V} d={d} K={w.K} variant={w.variant} exact={exact} chunk={chunk_rows} shift={shift} rule={rule}")
     b = W.make_lmhead_batch(w, d, DEV, exact=exact, shift_sampled=shift)
     rule = rule or {}
     b["rule"] = rule
+    all_rows = rows is None
     rows = np.arange(b["T"]) if rows is None else rows
-    res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, weight_t=weight_t, **rule)
+    gw = torch.full((b["V"], d + 4), 7.0, dtype=torch.float32, device=DEV)[:, :d] if (backward and all_rows) else None
+    res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, weight_t=weight_t, grad_weight=gw, **rule)
     torch.cuda.synchronize()
     ref = _oracle(b, rows, **rule)
     cmp_batch = dict(b, logits=None)
@@ -64,6 +82,8 @@ def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0
         P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
     if backward:
         st["median_rel_err_grad_hidden"] = _check_grad_hidden(b, res, rows, ref)
+        if all_rows:
+            st["max_abs_err_grad_weight"] = _check_grad_weight(b, res, ref, res["mask"].cpu().numpy())
     _say(f"       {st}")
     return b, res, st, ref
 
@@ -85,6 +105,23 @@ def test_gemm_exact_inputs_bitwise(M, N, K, lda, ldb, ldc):
     ref = O.lmhead_logits(a[:, :K].float().cpu().numpy(), b[:, :K].float().cpu().numpy())
     np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), ref)
     assert (c[:, N:] == 123.0).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (1000, 260, 192), (4160, 128, 320)])
+def test_gemm_fp32_result_exact_inputs_bitwise_and_accumulation(M, N, K):
+    _say(f"[case] gemm fp32 M={M} N={N} K={K}")
+    g = torch.Generator(device=DEV); g.manual_seed(M + N)
+    a = (torch.randint(-8, 9, (M, K), generator=g, device=DEV).float() / 64).bfloat16()
+    b = (torch.randint(-8, 9, (N, K), generator=g, device=DEV).float() / 8).bfloat16()
+    c = torch.full((M, N + 4), 3.0, dtype=torch.float32, device=DEV)
+    B.gemm_nt_f32(a, b, c[:, :N])
+    torch.cuda.synchronize()
+    ref = a.double().cpu().numpy() @ b.double().cpu().numpy().T          # exact, and exactly representable in fp32
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), ref)
+    B.gemm_nt_f32(a, b, c[:, :N], accumulate=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), 2 * ref)
+    assert (c[:, N:] == 3.0).all()
 
 
 def test_gemm_ordinary_inputs_within_one_rounding():
@@ -197,6 +234,21 @@ def test_ordinary_inputs_rows_clear_of_rounding_boundaries():
     _say(f"       clear rows {clear.sum()} of {b['T']}, max |dD| on them {errD.max():.2e}, masked {(M == 0).sum()}")
 
 
+def test_weight_gradient_accumulates_onto_the_callers_buffer():
+    w = W.Workload("lm_acc", 2, 100, 4096, W.BINARY_KL, 0.05, logit_std=3.0, noise_std=1.0, adv="normal", seed=101)
+    b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
+    g1 = torch.empty((b["V"], 128), dtype=torch.float32, device=DEV)
+    B.run_lmhead(b, chunk_rows=64, grad_weight=g1)
+    g2 = torch.full((b["V"], 128), 0.5, dtype=torch.float32, device=DEV)
+    B.run_lmhead(b, chunk_rows=64, grad_weight=g2, accumulate=True)
+    torch.cuda.synchronize()
+    assert (g2 - (g1 + 0.5)).abs().max().item() <= 5e-7          # four chunk sums, each rounded at the size of 0.5
+    g3 = torch.empty((b["V"], 128), dtype=torch.float32, device=DEV)
+    B.run_lmhead(b, chunk_rows=200, grad_weight=g3)                    # one chunk: same sum, another order
+    torch.cuda.synchronize()
+    assert (g3 - g1).abs().max().item() <= 1e-6 * g1.abs().max().item() + 1e-12
+
+
 def test_error_codes():
     w = W.Workload("lm_err", 1, 16, 256, W.BINARY_TV, 0.2, logit_std=3.0, adv="pm1", seed=89)
     b = W.make_lmhead_batch(w, 64, DEV, exact=True)
@@ -237,8 +289,13 @@ def test_headline_vocabulary_sampled_rows():
     w = W.Workload("lm_qwen3", 9, 512, 151936, W.TOPK_TV, 0.2, K=20, logit_std=3.0, noise_std=0.3, adv="pm1", seed=97)
     _say(f"[case] lmhead {w.name} T={w.T} V={w.V} d=4096 exact inputs, chunks of 2048")
     b = W.make_lmhead_batch(w, 4096, DEV, exact=True, shift_sampled=1.0)
-    res = B.run_lmhead(b, chunk_rows=2048, diagnostics=True)
+    gw = torch.empty((w.V, 4096), dtype=torch.float32, device=DEV)
+    res = B.run_lmhead(b, chunk_rows=2048, diagnostics=True, grad_weight=gw)
     torch.cuda.synchronize()
+    # every row of d loss / d z sums to zero, so the columns of the weight gradient do (up to the bf16 rounding of g)
+    col_sum, col_abs = gw.double().sum(0), gw.double().abs().sum(0)
+    assert torch.isfinite(gw).all() and (col_sum.abs() <= 1e-2 * col_abs + 1e-30).all() and col_abs.min().item() > 0
+    del gw
     mask = res["mask"].cpu().numpy()
     rng = np.random.default_rng(11)
     pick = {0, w.T - 1, 2047, 2048, 4095, 4096} | set(rng.integers(0, w.T, 8).tolist()) | set(np.nonzero(mask == 0)[0][:4].tolist())
