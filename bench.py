@@ -122,7 +122,7 @@ def bench_lmhead(args, w, dev) -> int:
     # the three products (logits, gradient of the hidden states, gradient of the weight): 2 T V d flops each
     flops = 6.0 * T * V * d
     achieved = flops / (ms * 1e-3) / 1e12
-    chunk = args.chunk_rows if args.chunk_rows > 0 else 4096
+    chunk = args.chunk_rows if args.chunk_rows > 0 else 8192
     rec = {
         "metric": "dppo_lmhead_loss_fwd_bwd_tokens_per_s", "value": T / (ms * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -273,6 +273,9 @@ def main() -> int:
                      "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},
         "loss": loss, "masked_tokens": int((out["mask"] == 0).sum().item()),
     }
+    if rec["roofline"]["traffic"]:
+        # what the counters say went over the HBM interface per second of this run's kernel time
+        rec["roofline"]["traffic_GBs"] = rec["roofline"]["traffic"] / (kernel_ms * 1e-3) / 1e9
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(batch, args.cpu_seconds)
     print(json.dumps(rec), flush=True)

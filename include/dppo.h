@@ -201,7 +201,9 @@ typedef struct {
   const void*    weight_t;      /* optional bf16 [d, ld_weight_t] = weight transposed (a caller    */
                                 /* that keeps one saves the transposition per call); may be NULL   */
   int64_t        ld_weight_t;   /* >= V, multiple of 8                                             */
-  int64_t        chunk_rows;    /* tokens per chunk; <= 0: 4096                                    */
+  int64_t        chunk_rows;    /* tokens per chunk; <= 0: 8192.  The second and third products have  */
+                                /* chunk_rows/256 x d/256 tiles: keep that at or above the number  */
+                                /* of compute units (256)                                          */
   void*          grad_hidden;   /* bf16 [T, ld_grad_hidden]; dppo_lmhead_loss_fwd_bwd only         */
   int64_t        ld_grad_hidden;/* >= d                                                            */
   float*         grad_weight;   /* optional fp32 [V, ld_grad_weight], 16-byte aligned:             */

@@ -150,7 +150,7 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
 
 // ---- the logits-free path: hidden states and lm_head weight in, gradient of the hidden states out
 
-constexpr int64_t kLmheadDefaultChunk = 4096;
+constexpr int64_t kLmheadDefaultChunk = 8192;
 
 int64_t lmhead_chunk_rows(const dppo_lmhead_args_t* a) {
   int64_t c = a->chunk_rows > 0 ? a->chunk_rows : kLmheadDefaultChunk;
