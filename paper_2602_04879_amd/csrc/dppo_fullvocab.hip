@@ -8,9 +8,11 @@
 //           token left out, as in the other kernels), of the rollout row y, and the cross term
 //           sum_j 2^(y_j..) (y_j - z_j).  With both normalisers known this already gives
 //           KL = E_mu[y - z] - lse(y) + lse(z).
-//   pass 2  (TV only) re-reads both rows and sums |pi_j - mu_j|.
+//   pass 2  (TV only) re-reads both rows and sums min(pi_j, mu_j): TV = 1 - that sum; with the
+//           backward it also writes the gradient row, as if the divergence did not mask it.
 //   epilogue on one wave: mask, loss term, gradient coefficient.
-//   pass 3  (backward only) re-reads z and writes the bf16 gradient row.
+//   pass 3  (backward, KL form) re-reads z and writes the bf16 gradient row; in the TV form
+//           only the rows the divergence masked are zero-filled.
 // The re-reads come right after the first read of the same row and are normally served by the
 // L2 / Infinity Cache.
 #include "dppo_common.hpp"
@@ -52,6 +54,40 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
 
     RowCoef rc;
     rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
+    u32x4* gv = reinterpret_cast<u32x4*>(grow + head);
+    // gradient of the eight entries of vector v of the row, given the row's coefficient
+    auto grad_vec = [&](const u32x4& q, int v, const RowCoef& c) {
+      float z[8];
+      unpack8(q, z);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) z[i] = fast_exp2(fmaf(z[i], kLog2e, c.kexp));
+      const uint32_t sgn = (c.coef < 0.f) ? 0x80008000u : 0u;
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(z[2 * i], z[2 * i + 1]) ^ sgn;
+      if (v == av) {   // the vector holding a_t: overwrite that one entry
+        const uint32_t ga = float_to_bf16_bits(c.g_a);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if ((sub >> 1) == i) w[i] = (sub & 1) ? ((w[i] & 0x0000ffffu) | (ga << 16)) : ((w[i] & 0xffff0000u) | ga);
+      }
+      const u32x4 o = {w[0], w[1], w[2], w[3]};
+      __builtin_nontemporal_store(o, gv + v);
+    };
+    auto grad_scalar = [&](int j, const RowCoef& c) {
+      float g = fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, c.kexp));
+      g = (c.coef < 0.f) ? -g : g;
+      if (j == a) g = c.g_a;
+      grow[j] = float_to_bf16_bits(g);
+    };
+    auto zero_row = [&]() {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      for (int v = tid; v < nvec; v += THREADS) __builtin_nontemporal_store(zero, gv + v);
+      for (int e = tid; e < nscalar; e += THREADS) grow[(e < head) ? e : tail0 + (e - head)] = 0;
+    };
+    bool grad_written = false;      // the TV form writes the gradient during its second pass ...
+    RowCoef rc1;                    // ... with this coefficient: the row's if the divergence does not mask it
+    rc1.coef = 0.f; rc1.kexp = 0.f; rc1.g_a = 0.f;
     if (live) {
       const float z_a = bf16_bits_to_float(zrow[a]);
       // ---- pass 1 --------------------------------------------------------------------------
@@ -109,30 +145,63 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
       const double S = S_rest + static_cast<double>(exp2_split(xa));
       double D;
       if (TV) {
-        // ---- pass 2: sum |pi_j - mu_j|, the same exponentials as pass 1 times 1/S ------------
-        const float cz = 1.0f / static_cast<float>(S), cy = 1.0f / static_cast<float>(Sy);
+        // ---- pass 2: TV = 1/2 sum |pi_j - mu_j| = 1 - sum_j min(pi_j, mu_j) -------------------
+        // One exponential per entry: the minimum is taken on the base-2 log-probabilities
+        // z_j*log2e + b - log2 S.  The integer part of log2 S goes into the (integer) offset, which
+        // stays exact, and only the fraction in [0, 1) is subtracted in fp32, so a probability
+        // keeps a relative error of about 1e-7 however large the offset is.
+        const double l2z = log2_fast(S), l2y = log2_fast(Sy);
+        const double nz = floor(l2z), ny = floor(l2y);
+        const float bz2 = bz - static_cast<float>(nz), by2 = by - static_cast<float>(ny);
+        const float fz = static_cast<float>(l2z - nz), fy = static_cast<float>(l2y - ny);
+        // Backward: the row's gradient is written in this same pass, with the coefficient the row
+        // has if the divergence does not mask it (everything else that decides it is known); the
+        // few rows the exact divergence then masks are zero-filled afterwards.  That saves the
+        // third read of z for all the others.
+        if (GRAD) {
+          if (wid == 0) {
+            RowScalars rs;
+            rs.a = a; rs.za = z_a; rs.lmu = p.mu_logp[row]; rs.adv = p.adv[row];
+            TopkLane tk;
+            tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
+            const RowResult res = row_epilogue_call(ep, row, rs, tk, zrow, bz, S_rest, T_rest, lane, 0.0);   // D = 0: not masked by it
+            if (lane == 0) sh_rc = res.rc;
+          }
+          __syncthreads();
+          rc1 = sh_rc;
+        }
         float acc0 = 0.f, acc1 = 0.f;
-        auto diff8 = [&](const u32x4& zq, const u32x4& yq, float& acc) {
+        auto min8 = [&](const u32x4& zq, const u32x4& yq, float& acc) {
           float z[8], y[8];
           unpack8(zq, z);
           unpack8(yq, y);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const float m = fast_exp2(fmaf(y[i], kLog2e, by)) * cy;
-            acc += fabsf(fmaf(fast_exp2(fmaf(z[i], kLog2e, bz)), cz, -m));
-          }
+          for (int i = 0; i < 8; ++i) acc += fast_exp2(fminf(fmaf(z[i], kLog2e, bz2) - fz, fmaf(y[i], kLog2e, by2) - fy));
         };
+        const bool write_grad = GRAD && rc1.coef != 0.f;
         int v2 = tid;
         for (; v2 + THREADS < nvec; v2 += 2 * THREADS) {
           const u32x4 z0 = zv[v2], y0 = yv[v2], z1 = zv[v2 + THREADS], y1 = yv[v2 + THREADS];
-          diff8(z0, y0, acc0);
-          diff8(z1, y1, acc1);
+          min8(z0, y0, acc0);
+          min8(z1, y1, acc1);
+          if (write_grad) {
+            grad_vec(z0, v2, rc1);
+            grad_vec(z1, v2 + THREADS, rc1);
+          }
         }
-        if (v2 < nvec) diff8(zv[v2], yv[v2], acc0);
+        if (v2 < nvec) {
+          const u32x4 z0 = zv[v2];
+          min8(z0, yv[v2], acc0);
+          if (write_grad) grad_vec(z0, v2, rc1);
+        }
         for (int e = tid; e < nscalar; e += THREADS) {
           const int j = (e < head) ? e : tail0 + (e - head);
-          const float m = fast_exp2(fmaf(bf16_bits_to_float(yrow[j]), kLog2e, by)) * cy;
-          acc1 += fabsf(fmaf(fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, bz)), cz, -m));
+          acc1 += fast_exp2(fminf(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, bz2) - fz, fmaf(bf16_bits_to_float(yrow[j]), kLog2e, by2) - fy));
+          if (write_grad) grad_scalar(j, rc1);
+        }
+        if (GRAD) {
+          if (!write_grad) zero_row();
+          grad_written = true;
         }
         const double wa = wave_sum(static_cast<double>(acc0) + static_cast<double>(acc1));
         if (lane == 0) sh_acc[wid] = wa;
@@ -140,7 +209,8 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         double tot = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) tot += sh_acc[w];
-        D = 0.5 * tot;
+        D = fmax(1.0 - tot, 0.0);
+        if (tot != tot) D = tot;                  // NaN logits propagate
       } else {
         // KL = E_mu[y - z] - lse(y) + lse(z), the log-sum-exps in base 2 against their offsets
         const double lse2_z = log2_fast(S) - static_cast<double>(bz), lse2_y = log2_fast(Sy) - static_cast<double>(by);
@@ -164,6 +234,8 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
       if (GRAD) {
         __syncthreads();
         rc = sh_rc;
+        // TV form: the row was written as if unmasked; the exact divergence has now masked it
+        if (TV && grad_written && rc1.coef != 0.f && rc.coef == 0.f) zero_row();
       }
     } else if (tid == 0) {
       p.divergence[row] = 0.f;
@@ -174,50 +246,22 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
       }
     }
 
-    if (GRAD) {
-      // ---- pass 3: gradient ------------------------------------------------------------------
-      u32x4* gv = reinterpret_cast<u32x4*>(grow + head);
+    if (GRAD && !grad_written) {
+      // ---- pass 3: gradient (KL form, and rows that were never live) ---------------------------
       if (rc.coef == 0.f) {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (int v = tid; v < nvec; v += THREADS) __builtin_nontemporal_store(zero, gv + v);
-        for (int e = tid; e < nscalar; e += THREADS) grow[(e < head) ? e : tail0 + (e - head)] = 0;
+        zero_row();
       } else {
-        const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
-        const float kexp = rc.kexp;
         const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
-        auto grad_vec = [&](const u32x4& q, int v) {
-          float z[8];
-          unpack8(q, z);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) z[i] = fast_exp2(fmaf(z[i], kLog2e, kexp));
-          uint32_t w[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(z[2 * i], z[2 * i + 1]) ^ sgn;
-          if (v == av) {   // the vector holding a_t: overwrite that one entry
-            const uint32_t ga = float_to_bf16_bits(rc.g_a);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if ((sub >> 1) == i) w[i] = (sub & 1) ? ((w[i] & 0x0000ffffu) | (ga << 16)) : ((w[i] & 0xffff0000u) | ga);
-          }
-          const u32x4 o = {w[0], w[1], w[2], w[3]};
-          __builtin_nontemporal_store(o, gv + v);
-        };
         int v = tid;
         for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {     // four loads in flight, then four stores
           const u32x4 q0 = zv[v], q1 = zv[v + THREADS], q2 = zv[v + 2 * THREADS], q3 = zv[v + 3 * THREADS];
-          grad_vec(q0, v);
-          grad_vec(q1, v + THREADS);
-          grad_vec(q2, v + 2 * THREADS);
-          grad_vec(q3, v + 3 * THREADS);
+          grad_vec(q0, v, rc);
+          grad_vec(q1, v + THREADS, rc);
+          grad_vec(q2, v + 2 * THREADS, rc);
+          grad_vec(q3, v + 3 * THREADS, rc);
         }
-        for (; v < nvec; v += THREADS) grad_vec(zv[v], v);
-        for (int e = tid; e < nscalar; e += THREADS) {
-          const int j = (e < head) ? e : tail0 + (e - head);
-          float g = fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, kexp));
-          g = (rc.coef < 0.f) ? -g : g;
-          if (j == a) g = rc.g_a;
-          grow[j] = float_to_bf16_bits(g);
-        }
+        for (; v < nvec; v += THREADS) grad_vec(zv[v], v, rc);
+        for (int e = tid; e < nscalar; e += THREADS) grad_scalar((e < head) ? e : tail0 + (e - head), rc);
       }
     }
     // The shared statistics are rewritten by the next row: make sure everyone has read them.
