@@ -73,6 +73,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   constexpr int NW = THREADS / kWave;
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
   constexpr int GC = 2;                          // chunks per group of the online row statistics
+  constexpr int kSplit = ((NCHUNK / 2 + GC - 1) / GC) * GC;   // forward only: chunks refilled mid-row
   __shared__ float sh_b[NW];
   __shared__ double sh_s[NW], sh_t[NW];
   __shared__ RowCoef sh_rc;
@@ -120,6 +121,9 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     }
     const bool live = (a >= 0 && a < p.V);
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
+    // The workgroup's next row; without one the refills go through a resource of zero bytes:
+    // their loads touch no memory.
+    const row_rsrc_t zn = make_row_rsrc(logits + (more ? next : row) * pitch, more ? row_bytes : 0u);
     const int avec = a >> 3;
     const int ia = live ? avec / THREADS : -1;               // chunk holding a_t (uniform)
     const bool owner = live && (avec - ia * THREADS == tid);
@@ -210,6 +214,15 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
           }
         }
         __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
+        // Forward only: nothing needs the row after its statistics, so the first part of the
+        // registers is refilled from the next row as soon as it has been consumed.  Those loads
+        // are in flight during the rest of this row and its epilogue; the rest is refilled after
+        // the epilogue and is in flight during the first part of the next row's statistics.
+        if (!GRAD && g0 + GC == kSplit) {
+#pragma unroll
+          for (int i = 0; i < kSplit; ++i) buf[i] = row_load16(zn, voff, i * kStride);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       // wave-level combine: common offset = the smallest one, rescaling is exact
       const float bw = -wave_max(-b);
@@ -264,9 +277,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 
     // ---- phase C: gradient out, next row in -------------------------------------------------
     // Every chunk: store its gradient, then refill it with the same chunk of the workgroup's
-    // next row, in the order the next row's arithmetic will consume them.  Without a next row
-    // the refill goes through a resource of zero bytes: its loads touch no memory.
-    const row_rsrc_t zn = make_row_rsrc(logits + (more ? next : row) * pitch, more ? row_bytes : 0u);
+    // next row, in the order the next row's arithmetic will consume them.
     if (GRAD) {
       char* gr = grad + row * pitch;
       const row_desc_t gout = make_row_desc(gr, row_bytes);
@@ -292,8 +303,10 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         reinterpret_cast<uint16_t*>(gr)[a] = float_to_bf16_bits(rc.g_a);
       }
     } else {
+      // rows whose statistics ran refilled the first part there
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zn, voff, i * kStride);
+      for (int i = 0; i < NCHUNK; ++i)
+        if (i >= kSplit || !live) buf[i] = row_load16(zn, voff, i * kStride);
     }
   }
   if (tid == 0) p.partial[blockIdx.x] = loss_acc;
