@@ -222,21 +222,34 @@ __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __res
   else                                gemm_tile<false, OUT>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
 }
 
-// dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS (two padding columns keep
-// the transposed reads off a single bank).  Columns R .. R_pad-1 of dst are written as zeros.
+// dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS, 16-byte accesses (8 elements
+// per lane) on both sides; the LDS rows are 66 elements long, which spreads the transposed 2-byte
+// reads over the banks.  Columns R .. R_pad-1 of dst are written as zeros.  Needs Cn, R_pad, both
+// pitches multiples of 8 and 16-byte aligned bases (checked by the launcher).
 __global__ __launch_bounds__(256) void dppo_transpose_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
                                                              uint16_t* __restrict__ dst, int64_t ld_dst, int R, int Cn, int R_pad) {
-  __shared__ uint16_t tile[64][66];
+  __shared__ __attribute__((aligned(4))) uint16_t tile[64][66];
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
-    const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < R && c < Cn) ? src[static_cast<int64_t>(r) * ld_src + c] : uint16_t(0);
+  const int sub = threadIdx.x & 7, line = threadIdx.x >> 3;      // 8 lanes x 16 bytes per 64-element line
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = r0 + line + 32 * i, c = c0 + sub * 8;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r < R && c < Cn) v = *reinterpret_cast<const u32x4*>(src + static_cast<int64_t>(r) * ld_src + c);   // Cn % 8 == 0: all 8 in range
+    uint32_t* t = reinterpret_cast<uint32_t*>(&tile[line + 32 * i][sub * 8]);
+    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
   }
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int c = c0 + i, r = r0 + tx;
-    if (c < Cn && r < R_pad) dst[static_cast<int64_t>(c) * ld_dst + r] = tile[tx][i];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int cl = line + 32 * i, c = c0 + cl, r = r0 + sub * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = static_cast<uint32_t>(tile[sub * 8 + 2 * k][cl]) | (static_cast<uint32_t>(tile[sub * 8 + 2 * k + 1][cl]) << 16);
+    if (c < Cn && r < R_pad) {                                   // R_pad % 8 == 0: all 8 in range
+      const u32x4 v = {w[0], w[1], w[2], w[3]};
+      *reinterpret_cast<u32x4*>(dst + static_cast<int64_t>(c) * ld_dst + r) = v;
+    }
   }
 }
 
@@ -245,6 +258,8 @@ __global__ __launch_bounds__(256) void dppo_transpose_kernel(const uint16_t* __r
 hipError_t launch_transpose(const uint16_t* src, int64_t ld_src, uint16_t* dst, int64_t ld_dst, int R, int Cn, int R_pad, hipStream_t s) {
   if (R_pad < R) R_pad = R;
   if (R_pad <= 0 || Cn <= 0) return hipSuccess;
+  if ((Cn % 8) || (R_pad % 8) || (ld_src % 8) || (ld_dst % 8) || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u))
+    return hipErrorInvalidValue;
   hipLaunchKernelGGL(dppo_transpose_kernel, dim3((Cn + 63) / 64, (R_pad + 63) / 64), dim3(256), 0, s, src, ld_src, dst, ld_dst, R, Cn, R_pad);
   return hipGetLastError();
 }
