@@ -132,6 +132,22 @@ __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t vof
   asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
+// 16 bytes per lane from global memory straight into LDS, issued from inline assembly: lane l of
+// the wave deposits its vector at LDS byte address `lds_addr` (uniform) + 16 l.  Like the store
+// above the compiler does not count it; the caller waits with s_waitcnt vmcnt before anything
+// reads that LDS range.  (The instruction takes its LDS base from M0, which is saved and restored.)
+__device__ __forceinline__ void row_load16_to_lds_untracked(row_desc_t d, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
+  uint32_t saved;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved)
+               : "s"(lds_addr), "v"(voff), "s"(d), "s"(soff)
+               : "memory");
+}
+// LDS byte address of a __shared__ object (uniform).
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
+}
+
 // A value every lane of the wave holds identically, moved to a scalar register.
 __device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ float uniform_f(float v) {
