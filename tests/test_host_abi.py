@@ -106,3 +106,21 @@ def test_product_package_never_reaches_the_oracle():
             for f in files:
                 if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                     assert not pat.search(open(os.path.join(dirpath, f)).read()), os.path.join(dirpath, f)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/dppo.h is the boundary for callers in any language: it must compile as C99 and as C++
+    on its own, with nothing but the standard headers it names."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use_dppo.c"
+    src.write_text('#include "dppo.h"\n'
+                   'int probe(void) { dppo_args_t a; dppo_lmhead_args_t l; (void)a; (void)l;\n'
+                   '  return (int)sizeof(a) + (int)sizeof(l) + DPPO_KMAX + DPPO_NDIAG + (int)DPPO_FULL_KL + (int)DPPO_MASK_NONE; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not available")
+        r = subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c" if cc == "gcc" else "c++",
+                            "-I", inc, str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
