@@ -1,6 +1,7 @@
 // bf16 matrix product on the matrix cores, C[M, N] = A[M, K] * B[N, K]^T with fp32 accumulation:
 // both operands row-major with the contraction index contiguous (what an nn.Linear forward is:
-// activations [T, d] times weight [V, d] transposed), C row-major bf16, rounded to nearest even.
+// activations [T, d] times weight [V, d] transposed), C row-major: bf16 rounded to nearest even,
+// or fp32, optionally added to what C holds.
 //
 // One workgroup of 256 threads (4 waves, one per SIMD) per 256 x 256 tile of C, each wave a
 // 128 x 128 quadrant as 4 x 4 products of v_mfma_f32_32x32x16_bf16 (256 fp32 accumulators per
