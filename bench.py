@@ -53,16 +53,16 @@ def stored_traffic(workload: str, path: str):
     return rec.get("bytes_per_launch")
 
 
-def algorithmic_bytes_per_token(V: int, K: int, full: bool = False) -> int:
+def algorithmic_bytes_per_token(V: int, K: int, full: bool = False, backward: bool = True) -> int:
     """What the method itself must move per token, forward + backward: the bf16 logits row read
     once (and, for the exact full-vocabulary variants, the rollout policy's bf16 row read once),
     the bf16 gradient row written once, and the per-token side inputs/outputs."""
     side_in = 4 + 4 + 4 + 8 * K          # sampled id, mu log-prob, advantage, top-K ids + log-probs
     side_out = 4 + 4 + 1                 # divergence, per-token loss, mask
-    return 2 * V + (2 * V if full else 0) + 2 * V + side_in + side_out
+    return 2 * V + (2 * V if full else 0) + (2 * V if backward else 0) + side_in + side_out
 
 
-def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
+def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256, backward: bool = True) -> dict:
     """Time the float64 oracle, as it stands, on leading rows of the same batch: chunks of
     chunk_rows rows until about budget_s seconds of CPU work are spent (or the batch ends)."""
     from oracle import dppo_oracle as O
@@ -78,13 +78,13 @@ def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256) -> dict:
         tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
         t0, c0 = time.perf_counter(), time.process_time()
         y = batch["mu_logits"][sl, :V].float().cpu().numpy() if batch.get("mu_logits") is not None else None
-        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=True,
+        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=backward,
                     mu_logits=y)
         wall += time.perf_counter() - t0
         cpu += time.process_time() - c0
         done += len(ids)
     return {"value": done / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)), "kind": "oracle",
-            "sample": f"first {done} of {T} rows of the same batch, fwd+bwd, float64 numpy, {wall:.1f} s"}
+            "sample": f"first {done} of {T} rows of the same batch, {'fwd+bwd' if backward else 'fwd'}, float64 numpy, {wall:.1f} s"}
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core peak
@@ -172,6 +172,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
+    ap.add_argument("--forward-only", action="store_true", help="time dppo_loss_fwd (no gradient) instead of forward+backward")
     ap.add_argument("--chunk-rows", type=int, default=0, help="tokens per chunk of the hidden-state workloads (0: library default)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -218,9 +219,11 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
 
+    run = B.dppo_loss_fwd if args.forward_only else B.dppo_loss_fwd_bwd
+
     def step():
         for a, _ in calls:
-            B.dppo_loss_fwd_bwd(a, stream)
+            run(a, stream)
 
     for _ in range(args.warmup):
         step()
@@ -253,21 +256,22 @@ def main() -> int:
             ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
 
     launches = len(calls)
-    alg_bytes_launch = algorithmic_bytes_per_token(V, K, batch.get("mu_logits") is not None) * (T // launches)
+    alg_bytes_launch = algorithmic_bytes_per_token(V, K, batch.get("mu_logits") is not None, not args.forward_only) * (T // launches)
     kernel_ms = ms_per_step / launches           # the step is the dominant kernel plus a ~3 us reduction
     achieved = alg_bytes_launch / (kernel_ms * 1e-3) / 1e9
     loss = sum(float(o["loss"].item()) for _, o in calls)
 
     rec = {
-        "metric": "dppo_loss_fwd_bwd_tokens_per_s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "metric": "dppo_loss_fwd_tokens_per_s" if args.forward_only else "dppo_loss_fwd_bwd_tokens_per_s",
+        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
                    "delta": batch["delta"], "logits_dtype": "bf16", "launches_per_step": launches,
-                   "kernel_path": path, "grad": "separate buffer"},
+                   "kernel_path": path, "grad": "none (forward only)" if args.forward_only else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(args.workload, path),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.forward_only else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
                      "kernel_ms": kernel_ms, "device_ceilings": ceilings,
                      "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},
@@ -277,7 +281,7 @@ def main() -> int:
         # what the counters say went over the HBM interface per second of this run's kernel time
         rec["roofline"]["traffic_GBs"] = rec["roofline"]["traffic"] / (kernel_ms * 1e-3) / 1e9
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(batch, args.cpu_seconds)
+        rec["cpu_baseline"] = cpu_baseline(batch, args.cpu_seconds, backward=not args.forward_only)
     print(json.dumps(rec), flush=True)
     return 0
 
