@@ -237,14 +237,19 @@ def main() -> int:
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     path = B.last_path()
 
-    # the device's streaming ceilings, measured with the library's plain copy / read kernels
-    ceil_src = batch["logits"].view(-1)[: (2 << 30)].view(torch.uint8) if batch["logits"].numel() * 2 >= (4 << 30) else None
+    # the device's streaming ceilings on THESE buffers (the rate depends on the footprint), measured
+    # with the library's plain copy kernels (grid-stride, and one workgroup per row like the loss
+    # kernels) and its read kernel
     ceilings = {}
-    if ceil_src is not None:
-        ceil_dst = grad.view(-1)[: (2 << 30)].view(torch.uint8)
+    src2d, dst2d = batch["logits"], grad
+    nbytes = src2d.numel() * 2
+    if nbytes % 16 == 0 and nbytes >= (1 << 30):
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
-        for name, fn, moved in (("copy", lambda: B.probe_copy(ceil_dst, ceil_src, stream), 2 * ceil_src.numel()),
-                                ("read", lambda: B.probe_read(ceil_src, sink, stream), ceil_src.numel())):
+        probes = [("copy", lambda: B.probe_copy(dst2d.view(-1).view(torch.uint8), src2d.view(-1).view(torch.uint8), stream), 2 * nbytes),
+                  ("read", lambda: B.probe_read(src2d.view(-1).view(torch.uint8), sink, stream), nbytes)]
+        if (V * 2) % 16 == 0 and (batch["ld"] * 2) % 16 == 0:
+            probes.append(("copy_rows", lambda: B.probe_copy_rows(dst2d[:, :V], src2d[:, :V], stream), 2 * T * V * 2))
+        for name, fn, moved in probes:
             fn()
             torch.cuda.synchronize()
             c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

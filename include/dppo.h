@@ -253,6 +253,9 @@ dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_
  * counter-calibration probe use them: a copy of known size scales the HBM byte counters, and
  * their bandwidth is the device's streaming ceiling the loss kernels are compared with. */
 dppo_status_t dppo_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+/* The same copy with the loss kernels' address pattern: one workgroup per row of `row_bytes` bytes
+ * (rows `pitch_bytes` apart; both multiples of 16), as many workgroups as compute units. */
+dppo_status_t dppo_probe_copy_rows(void* dst, const void* src, int64_t rows, size_t row_bytes, size_t pitch_bytes, void* stream);
 dppo_status_t dppo_probe_fill(void* dst, size_t bytes, uint32_t value, void* stream);
 dppo_status_t dppo_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 

@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         l.dppo_args_size.restype = C.c_size_t
         l.dppo_probe_copy.restype = C.c_int
         l.dppo_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.dppo_probe_copy_rows.restype = C.c_int
+        l.dppo_probe_copy_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_size_t, C.c_size_t, C.c_void_p]
         l.dppo_probe_fill.restype = C.c_int
         l.dppo_probe_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         l.dppo_probe_read.restype = C.c_int
@@ -172,6 +174,16 @@ def probe_copy(dst, src, stream=None) -> None:
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     st = lib().dppo_probe_copy(dst.data_ptr(), src.data_ptr(), n, C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def probe_copy_rows(dst, src, stream=None) -> None:
+    """dppo_probe_copy_rows: copy a 2-D tensor row by row, one workgroup per row."""
+    assert dst.shape == src.shape and dst.stride() == src.stride() and src.stride(1) == 1
+    es = src.element_size()
+    st = lib().dppo_probe_copy_rows(dst.data_ptr(), src.data_ptr(), src.shape[0], src.shape[1] * es, src.stride(0) * es,
+                                    C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
 

@@ -38,6 +38,25 @@ __global__ __launch_bounds__(256) void dppo_probe_fill_kernel(dppo::u32x4* __res
   for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += stride) dst[i] = v;
 }
 
+// The same copy with the address pattern of the loss kernels: each workgroup copies whole rows,
+// one after the other, four 16-byte vectors per thread in flight.
+__global__ __launch_bounds__(512) void dppo_probe_copy_rows_kernel(const dppo::u32x4* __restrict__ src, dppo::u32x4* __restrict__ dst,
+                                                                   int rows, int row_vecs, size_t pitch_vecs) {
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    const dppo::u32x4* s = src + static_cast<size_t>(row) * pitch_vecs;
+    dppo::u32x4* d = dst + static_cast<size_t>(row) * pitch_vecs;
+    int i = threadIdx.x;
+    for (; i + 3 * 512 < row_vecs; i += 4 * 512) {
+      dppo::u32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = s[i + u * 512];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) d[i + u * 512] = v[u];
+    }
+    for (; i < row_vecs; i += 512) d[i] = s[i];
+  }
+}
+
 int probe_cus() {
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
@@ -55,6 +74,18 @@ dppo_status_t dppo_probe_copy(void* dst, const void* src, size_t bytes, void* st
   if (bytes == 0) return DPPO_OK;
   hipLaunchKernelGGL(dppo_probe_copy_kernel, dim3(probe_cus()), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const dppo::u32x4*>(src), static_cast<dppo::u32x4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
+
+dppo_status_t dppo_probe_copy_rows(void* dst, const void* src, int64_t rows, size_t row_bytes, size_t pitch_bytes, void* stream) {
+  if (!dst || !src) return DPPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | row_bytes | pitch_bytes) & 15u) return DPPO_ERR_ALIGN;
+  if (rows < 0 || rows >= (int64_t(1) << 31) || pitch_bytes < row_bytes || row_bytes / 16 >= (size_t(1) << 31)) return DPPO_ERR_SHAPE;
+  if (rows == 0 || row_bytes == 0) return DPPO_OK;
+  const int grid = static_cast<int>(rows < probe_cus() ? rows : probe_cus());
+  hipLaunchKernelGGL(dppo_probe_copy_rows_kernel, dim3(grid), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const dppo::u32x4*>(src), static_cast<dppo::u32x4*>(dst), static_cast<int>(rows),
+                     static_cast<int>(row_bytes / 16), pitch_bytes / 16);
   return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
 }
 

@@ -446,3 +446,30 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
                 assert torch.equal(e[k], o[k]), (rep, k)
             assert torch.equal(e["grad_logits"], gr), rep
     _say(f"       graph with both kernel paths replayed 3 times, bitwise equal to eager")
+
+
+# --------------------------------------------------------------------------- measurement utilities
+def test_probe_kernels_copy_fill_read():
+    """The plain copy / fill / read kernels that the benchmark compares the loss kernels with do what
+    they say, byte for byte, and leave everything else alone."""
+    g = torch.Generator(device=DEV); g.manual_seed(7)
+    n = (1 << 20) + 48
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, generator=g, device=DEV)
+    dst = torch.zeros(n + 32, dtype=torch.uint8, device=DEV)
+    B.probe_copy(dst[:n], src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and (dst[n:] == 0).all()
+    B.probe_fill(dst[:n], 0x3c003c00)
+    torch.cuda.synchronize()
+    assert (dst[:n].view(torch.int32) == 0x3c003c00).all() and (dst[n:] == 0).all()
+    sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.probe_read(src, sink)
+    torch.cuda.synchronize()
+    assert sink.item() == 0
+    # row by row, with a pitch: columns past the row stay untouched; more rows than workgroups
+    rows, cols, ld = 700, 4104, 4112
+    a = torch.randn((rows, ld), generator=g, device=DEV).bfloat16()
+    b = torch.full((rows, ld), -7.0, dtype=torch.bfloat16, device=DEV)
+    B.probe_copy_rows(b[:, :cols], a[:, :cols])
+    torch.cuda.synchronize()
+    assert torch.equal(b[:, :cols], a[:, :cols]) and (b[:, cols:] == -7.0).all()
