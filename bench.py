@@ -172,6 +172,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
+    ap.add_argument("--ld", type=int, default=0, help="row pitch of logits / gradient in elements (0: V)")
     ap.add_argument("--forward-only", action="store_true", help="time dppo_loss_fwd (no gradient) instead of forward+backward")
     ap.add_argument("--chunk-rows", type=int, default=0, help="tokens per chunk of the hidden-state workloads (0: library default)")
     args = ap.parse_args()
@@ -192,7 +193,7 @@ def main() -> int:
     w = W.WORKLOADS[args.workload]
     if w.d_model:
         return bench_lmhead(args, w, dev)
-    batch = W.make_batch(w, dev, rows_per_step=2048)
+    batch = W.make_batch(w, dev, rows_per_step=2048, ld=(args.ld or None))
     T, V, K = batch["T"], batch["V"], batch["K"]
     chunk = w.chunk_rows or T
     flags = B.FLAG_FORCE_STREAMING if args.force_streaming else 0
@@ -273,7 +274,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
-                   "delta": batch["delta"], "logits_dtype": "bf16", "launches_per_step": launches,
+                   "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
                    "kernel_path": path, "grad": "none (forward only)" if args.forward_only else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.forward_only else stored_traffic(args.workload, path),
