@@ -1,15 +1,19 @@
-// Register-resident fused forward+backward kernel.
+// Register-resident kernel: fused forward+backward, or forward only.
 //
 // One persistent workgroup per compute unit owns one row at a time and keeps the whole bf16
 // row packed in its vector registers (V = 151936 is 297 KiB; a CU's register file is 512 KiB),
 // so the logits are read from HBM exactly once and the gradient written exactly once:
 //
-//   phase A  packed-integer maximum over the resident row            (no unpacking)
-//   phase B  sum of 2^(z*log2e + b) in fp32 with a per-wave integer offset b
-//            -> one LDS exchange + barrier -> per-token epilogue on wave 0 -> barrier
-//   phase C  gradient of every resident element, 16-byte non-temporal stores; as each
-//            register chunk is consumed it is refilled with the same chunk of the workgroup's
-//            NEXT row, so HBM reads of row r+1 overlap the arithmetic and writes of row r.
+//   phases A+B  online over groups of chunks: packed-integer maximum (no unpacking), then
+//               sum of 2^(z*log2e + b) in fp32 with an integer offset b
+//               -> one LDS exchange + barrier -> per-token epilogue on wave 0 -> barrier
+//   phase C     gradient of every resident element, 16-byte stores; as each register chunk is
+//               consumed it is refilled with the same chunk of the workgroup's NEXT row, so HBM
+//               reads of row r+1 overlap the arithmetic and writes of row r.  The head of the
+//               next row is requested into LDS just before the epilogue, so that the compute
+//               unit has memory requests in flight while one wave does the per-token arithmetic.
+//   forward only: no phase C; the first half of the registers is refilled mid-row, the second
+//               after the epilogue, so at least half a row is in flight at any time.
 //
 // Preconditions (checked by the host): V % 8 == 0, V/8 <= THREADS*NCHUNK, logits and
 // grad_logits 16-byte aligned with ld % 8 == 0.
@@ -68,7 +72,7 @@ constexpr int kChunkStep = 4;
 // All row traffic goes through range-checked buffer resources, so the phases are straight-line
 // code with a fixed sequence of memory instructions: loads past the row return 0 (turned into
 // -inf where the row statistics consume them) and stores past it are dropped.
-// GRAD = false is the forward-only form: phase C only refills (no gradient, no stores).
+// GRAD = false is the forward-only form: no gradient, no stores, refills in two halves.
 // DIAG = true also accumulates sum e*x for the entropy diagnostic (two more instructions per
 // element in the statistics loop), selected when the caller passes a diagnostics buffer.
 template <int THREADS, int NCHUNK, bool GRAD, bool DIAG>
