@@ -89,6 +89,7 @@ typedef enum {
                                   /* diagnostics not 16                                        */
   DPPO_ERR_VARIANT = 4,           /* variant is not a dppo_variant_t                           */
   DPPO_ERR_K = 5,                 /* K < 0, K > DPPO_KMAX, or K > 0 without top-K pointers     */
+                                  /* (with T > 0)                                              */
   DPPO_ERR_WORKSPACE = 6,         /* workspace NULL or smaller than dppo_workspace_bytes()     */
   DPPO_ERR_LAUNCH = 7,            /* the HIP runtime refused a launch (see hipGetLastError)    */
   DPPO_ERR_VALUE = 8              /* delta, loss_scale, eps_* or ratio_cap is NaN, eps_low not */

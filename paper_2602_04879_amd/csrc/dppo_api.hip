@@ -35,7 +35,7 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   if (a->variant < DPPO_BINARY_TV || a->variant > DPPO_FULL_KL) return DPPO_ERR_VARIANT;
   if (a->K < 0 || a->K > DPPO_KMAX) return DPPO_ERR_K;
   const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
-  if (topk && a->K > 0 && (!a->mu_topk_ids || !a->mu_topk_logp)) return DPPO_ERR_K;
+  if (topk && a->K > 0 && a->T > 0 && (!a->mu_topk_ids || !a->mu_topk_logp)) return DPPO_ERR_K;
   if (!a->loss) return DPPO_ERR_NULL;
   if (std::isnan(a->delta) || std::isnan(a->loss_scale) || std::isnan(a->ratio_cap)) return DPPO_ERR_VALUE;
   if (a->mask_rule < DPPO_MASK_DIVERGENCE || a->mask_rule > DPPO_MASK_NONE) return DPPO_ERR_VALUE;

@@ -306,3 +306,15 @@ def test_headline_vocabulary_sampled_rows():
     P.check_loss_scalar(b, res)
     assert 0 < (mask == 0).sum() < w.T and st["masked"] > 0
     _say(f"       masked={(mask == 0).sum()} {st}")
+
+
+def test_empty_batch_and_single_token():
+    w = W.Workload("lm_one", 1, 1, 256, W.TOPK_KL, 0.05, K=4, logit_std=3.0, noise_std=0.5, adv="pm1", seed=103)
+    _run_and_compare(w, 64, shift=1.0)
+    b = W.make_lmhead_batch(w, 64, DEV, exact=True)
+    empty = dict(b, hidden=b["hidden"][:0], sampled_ids=b["sampled_ids"][:0], mu_logp=b["mu_logp"][:0],
+                 advantages=b["advantages"][:0], mu_topk_ids=b["mu_topk_ids"][:0], mu_topk_logp=b["mu_topk_logp"][:0], T=0)
+    gw = torch.full((b["V"], 64), 2.0, dtype=torch.float32, device=DEV)
+    res = B.run_lmhead(empty, grad_weight=gw)
+    torch.cuda.synchronize()
+    assert res["loss"].item() == 0.0 and (gw == 2.0).all()          # nothing to add, nothing touched
