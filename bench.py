@@ -29,11 +29,11 @@ DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_stream
 
 
 def kernel_source_hash(path: str) -> str:
-    """Hash of the HIP sources behind one kernel path (its kernel, the shared device helpers and
-    the host code that picks the launch shape): stored HBM-traffic counters hold only for it."""
+    """Hash of the device code behind one kernel path (its kernel file and the shared device
+    helpers): stored HBM-traffic counters hold only for it."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
-    for fn in ("dppo_common.hpp", "dppo_launch.hpp", "dppo_api.hip", f"dppo_{path}.hip"):
+    for fn in ("dppo_common.hpp", f"dppo_{path}.hip"):
         h.update(open(os.path.join(src, fn), "rb").read())
     return h.hexdigest()[:16]
 
