@@ -119,6 +119,17 @@ def bench_lmhead(args, w, dev) -> int:
     ev1.record(stream)
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / args.steps
+    # What the matrix cores sustain under the board's power limit: a loop of nothing but products
+    # on every compute unit, both instruction shapes, the last of four ~15 ms launches each.
+    ceilings = {}
+    probe_out = torch.empty(4096 * 256, dtype=torch.float32, device=dev)
+    for shape, key in ((16, "mfma_16x16x32_TFLOPs"), (32, "mfma_32x32x16_TFLOPs")):
+        for _ in range(4):
+            ev0.record(stream)
+            fl = B.probe_mfma(shape, 30000 if shape == 16 else 60000, probe_out, stream=stream)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+        ceilings[key] = fl / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
     # the three products (logits, gradient of the hidden states, gradient of the weight): 2 T V d flops each
     flops = 6.0 * T * V * d
     achieved = flops / (ms * 1e-3) / 1e12
@@ -133,7 +144,8 @@ def bench_lmhead(args, w, dev) -> int:
                    "logits_bytes_resident": min(chunk, T) * V * 2, "logits_bytes_if_materialised": T * V * 2},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "dppo_gemm_nt_kernel",
-                     "algorithmic_flops_per_step": flops},
+                     "algorithmic_flops_per_step": flops, "ceilings": ceilings,
+                     "frac_of_product_only_loop": achieved / ceilings["mfma_16x16x32_TFLOPs"]},
         "loss": float(out["loss"].item()), "masked_tokens": int((out["mask"] == 0).sum().item()),
     }
     if not args.no_cpu_baseline:

@@ -260,6 +260,14 @@ dppo_status_t dppo_probe_copy(void* dst, const void* src, size_t bytes, void* st
 dppo_status_t dppo_probe_copy_rows(void* dst, const void* src, int64_t rows, size_t row_bytes, size_t pitch_bytes, void* stream);
 dppo_status_t dppo_probe_fill(void* dst, size_t bytes, uint32_t value, void* stream);
 dppo_status_t dppo_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+/* Matrix-core ceiling under the board's power limit: one workgroup of 4 waves per compute unit,
+ * each wave `iters` rounds of independent bf16 products on register operands with 256 fp32
+ * accumulators: `shape` 16 = 64 x v_mfma_f32_16x16x32_bf16 per round, 32 = 16 x
+ * v_mfma_f32_32x32x16_bf16.  `out` (device, at least 1024 bytes per compute unit, `out_bytes`
+ * says how many) receives one float per lane; `*flop` (host, may be NULL) the floating-point
+ * operations of the launch, for the caller to divide by the time it measures.
+ * DPPO_ERR_SHAPE for another shape or negative iters, DPPO_ERR_WORKSPACE if `out` is too small. */
+dppo_status_t dppo_probe_mfma(int shape, int iters, void* out, size_t out_bytes, double* flop, void* stream);
 
 #ifdef __cplusplus
 }

@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
         l.dppo_probe_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         l.dppo_probe_read.restype = C.c_int
         l.dppo_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        l.dppo_probe_mfma.restype = C.c_int
+        l.dppo_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
         l.dppo_gemm_nt.restype = C.c_int
         l.dppo_gemm_nt.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                    C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
@@ -193,6 +195,17 @@ def probe_fill(dst, value: int = 0, stream=None) -> None:
     st = lib().dppo_probe_fill(dst.data_ptr(), dst.numel() * dst.element_size(), value, C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
+
+
+def probe_mfma(shape: int, iters: int, out, stream=None) -> float:
+    """dppo_probe_mfma: a loop of bf16 matrix-core products on every compute unit; returns the
+    floating-point operations of the launch (out: device float tensor, 256 per compute unit)."""
+    flop = C.c_double(0.0)
+    st = lib().dppo_probe_mfma(shape, iters, out.data_ptr(), out.numel() * out.element_size(), C.byref(flop),
+                               C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    return flop.value
 
 
 def probe_read(src, sink, stream=None) -> None:

@@ -4,14 +4,24 @@
 // or fp32, optionally added to what C holds.
 //
 // One workgroup of 256 threads (4 waves, one per SIMD) per 256 x 256 tile of C, each wave a
-// 128 x 128 quadrant as 4 x 4 products of v_mfma_f32_32x32x16_bf16 (256 fp32 accumulators per
-// lane).  The contraction runs in steps of 64: the A and B panels of a step (256 x 64 each,
-// 32 KiB) are loaded from global memory straight into one of two LDS stages a step ahead,
-// 16 bytes per lane, in a layout swizzled so that the matrix-core fragment reads (one 16-byte
-// read per lane: 8 consecutive k of one row) spread over all banks.
+// 128 x 128 quadrant as 8 x 8 products of v_mfma_f32_16x16x32_bf16 (256 fp32 accumulators per
+// lane, the whole accumulation register file).  That shape is chosen for power: with every
+// compute unit busy the clock is set by the power limit, and a loop of nothing but 16x16x32
+// products sustains about 14 % more than one of 32x32x16 products (measured, 2.17 against
+// 1.90 PFLOP/s).  The contraction runs in steps of 64: the A and B panels of a step (256 x 64
+// each, 32 KiB) are loaded from global memory straight into one of two LDS stages, 16 bytes per
+// lane, in a layout swizzled so that the fragment reads (one 16-byte read per lane: 8 consecutive
+// k of one row) spread over all banks.
+// A 16x16x32 product occupies the matrix pipe for 16 cycles and a wave issues at most one
+// instruction every 4, so whatever else the wave issues has to sit in the shadow of a product:
+// the matrix-core instructions are written as assembly statements in a fixed order (that also
+// keeps each accumulator in place in its own registers, which the register allocator does not
+// manage by itself at this pressure), with one fragment read or one panel load pinned behind
+// every second to fourth of them.
 // Panel rows past M or N re-read the last valid row (their products are never stored); all
 // loads go through range-checked buffer resources over exactly the rows a tile owns.  K must be
 // a multiple of 64, rows 16-byte aligned (checked by the host).
+#include <type_traits>
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 
@@ -19,7 +29,7 @@ namespace dppo {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kRowBytes = kBK * 2;                    // one panel row in LDS: 128 bytes = 8 vectors
@@ -32,9 +42,8 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
   return static_cast<uint32_t>(row) * kRowBytes + static_cast<uint32_t>((kvec ^ ((row >> 1) & 7)) << 4);
 }
 
-// One 256 x 256 tile.  FULL: all 256 rows of both panels exist, so the eight rows a loader thread
-// moves per panel differ by a uniform stride (carried in the scalar offset of the load).
-// Otherwise a panel row past the matrix re-reads the last valid row: its products are never stored.
+// One 256 x 256 tile.  FULL: all 256 rows and columns of the tile exist, so the stores need no
+// range checks.  A panel row past the matrix re-reads the last valid row: its products are never stored.
 // OUT selects what leaves the tile: bf16 (rounded to nearest even), fp32, or fp32 added to what C holds.
 enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
 
@@ -46,152 +55,162 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   const int wm = wid >> 1, wn = wid & 1;
   const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);
   const uint32_t pitch_a = static_cast<uint32_t>(lda) * 2u, pitch_b = static_cast<uint32_t>(ldb) * 2u;
-  // range-checked views of exactly the rows this tile owns
-  const row_rsrc_t ra = make_row_rsrc(A + static_cast<int64_t>(m0) * lda, static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u);
-  const row_rsrc_t rb = make_row_rsrc(B + static_cast<int64_t>(n0) * ldb, static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u);
 
   // Loader role: thread t moves LDS vector slot (t % 8) of rows t/8 + 32 i, i = 0..7, of each panel;
   // the slot holds global k-vector slot ^ ((row >> 1) & 7), the same for all eight rows.
   const int lrow = tid >> 3, lslot = tid & 7;
   const uint32_t lkv = static_cast<uint32_t>((lslot ^ ((lrow >> 1) & 7)) << 4);
-  const uint32_t voff_a = static_cast<uint32_t>(lrow) * pitch_a + lkv, voff_b = static_cast<uint32_t>(lrow) * pitch_b + lkv;
 
-  f32x16 acc[4][4];
+  f32x4 acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-  // Fragment role: lane holds 8 consecutive k (k half `fk` of a 16-wide step) of row `frow` of a
-  // 32-row block.  The swizzle depends on the row only through frow, so one offset per k-vector
-  // serves every block of both panels.
-  const int frow = lane & 31, fk = lane >> 5;
-  // 8-byte stores need C rows that keep 8-byte alignment (uniform over the launch)
-  const bool pair_aligned = ((reinterpret_cast<uintptr_t>(Cv) & 7u) == 0) && (ldc % 4 == 0);
-  uint32_t foff[4];
+  // Fragment role: lane holds 8 consecutive k (k quarter `fk` of a 32-wide sub-step) of row `frow`
+  // of a 16-row block.  The swizzle depends on the row only through frow, so one offset per
+  // k-vector serves every block of both panels.
+  const int frow = lane & 15, fk = lane >> 4;
+  uint32_t foff[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) foff[ks] = lds_off(frow, ks * 2 + fk);
+  for (int ks = 0; ks < 2; ++ks) foff[ks] = lds_off(frow, ks * 4 + fk);
   const uint32_t fbase_a = static_cast<uint32_t>(wm * 128) * kRowBytes;
   const uint32_t fbase_b = kPanelBytes + static_cast<uint32_t>(wn * 128) * kRowBytes;
-  auto read_frags = [&](const unsigned char* stage, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[4]) {
-    const uint32_t o = foff[ks];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      fa[t] = *reinterpret_cast<const bf16x8*>(stage + fbase_a + t * 32 * kRowBytes + o);
-      fb[t] = *reinterpret_cast<const bf16x8*>(stage + fbase_b + t * 32 * kRowBytes + o);
-    }
+  // fragment t of a sub-step: 0..7 the B blocks, 8..15 the A blocks
+  auto read_frag = [&](const unsigned char* stage, int ks, int t) {
+    return *reinterpret_cast<const bf16x8*>(stage + (t < 8 ? fbase_b : fbase_a) + (t & 7) * 16 * kRowBytes + foff[ks]);
   };
-  auto mma16 = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-  };
+#define DPPO_MFMA16(ACC, X, Y) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(X), "v"(Y))
 
-  // Pipeline over the contraction: while step kt is multiplied out of LDS stage kt % 2, the
-  // panels of step kt+1 are loaded into the other stage; the fragments of each 16-wide sub-step
-  // are read from LDS one sub-step ahead of the matrix-core instructions that consume them.
-  // One barrier per step, before the first fragments of the next stage are read.
+  // Pipeline over the contraction: step kt is multiplied out of LDS stage kt % 2; once every wave
+  // has read its last fragments of that stage (the barrier in the middle of the step) the panels
+  // of step kt+2 are loaded into it.  The fragments of each 32-wide sub-step are read from LDS one
+  // sub-step ahead of the matrix-core instructions that consume them.  One barrier per step.
   const int nk = K / kBK;
   // Global memory -> LDS directly (buffer_load ... lds): lane l of a wave-level load deposits its
   // 16 bytes at (LDS base of the instruction) + 16 l, which is exactly the loader layout above for
   // the base stage + panel + i * 4096 + wave * 1024.  No staging registers, no LDS store
   // instructions; completion is counted with the other vector-memory loads.
   typedef __attribute__((address_space(3))) void* lds_ptr_t;
-  auto dma_panel = [&](unsigned char* stage, int step, bool b_panel) {
-    const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
-    unsigned char* dst = stage + (b_panel ? kPanelBytes : 0) + wid * 1024;
-    const row_rsrc_t r = b_panel ? rb : ra;
-    const uint32_t pitch = b_panel ? pitch_b : pitch_a;
-    const uint32_t voff = (b_panel ? voff_b : voff_a) + koff;
-    const int rows = b_panel ? rows_b : rows_a;
+  // Load i of a panel moves rows lrow + 32 i (clamped to the last row the tile owns), through a
+  // range-checked view of exactly the rows this tile owns.  The k offset of a step goes into the
+  // base of that view (scalar arithmetic), so the per-lane offsets never change.
+  uint32_t vo_a[8], vo_b[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (FULL) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(dst + i * 4096), 16, voff, static_cast<uint32_t>(i * 32) * pitch, 0, 0);
-      } else {
-        const uint32_t row = static_cast<uint32_t>(min(lrow + 32 * i, rows - 1));
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(dst + i * 4096), 16, row * pitch + lkv + koff, 0, 0, 0);
-      }
-    }
+  for (int i = 0; i < 8; ++i) {
+    vo_a[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_a - 1)) * pitch_a + lkv;
+    vo_b[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_b - 1)) * pitch_b + lkv;
+  }
+  const uint32_t bytes_a = static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u;
+  const uint32_t bytes_b = static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u;
+  auto dma_one = [&](unsigned char* stage, int step, int idx) {     // load idx of the 16 of a step: 0..7 A panel, 8..15 B panel
+    const bool b_panel = idx >= 8;
+    const int i = idx & 7;
+    const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
+    unsigned char* dst = stage + (b_panel ? kPanelBytes : 0) + wid * 1024 + i * 4096;
+    const row_rsrc_t r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(n0) * ldb + step * kBK, bytes_b - koff)
+                                 : make_row_rsrc(A + static_cast<int64_t>(m0) * lda + step * kBK, bytes_a - koff);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, b_panel ? vo_b[i] : vo_a[i], 0, 0, 0);
   };
-  dma_panel(lds0, 0, false);
-  dma_panel(lds0, 0, true);
+#pragma unroll
+  for (int q = 0; q < 16; ++q) dma_one(lds0, 0, q);
   __syncthreads();                       // waits for this wave's loads, then for everyone's
-  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
-  read_frags(lds0, 0, fa0, fb0);
-  // The two stages are two separate arrays and the loop takes two steps per trip, so that every
-  // LDS access names its array: the compiler then knows that fragment reads of one stage need not
-  // wait for the loads in flight into the other.
-  auto step = [&](const unsigned char* cur, unsigned char* nxt, int kt) {
-    const bool more = kt + 1 < nk;
-    read_frags(cur, 1, fa1, fb1);
-    if (more) dma_panel(nxt, kt + 1, false);
-    __builtin_amdgcn_sched_barrier(0);
-    mma16(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 2, fa0, fb0);
-    if (more) dma_panel(nxt, kt + 1, true);
-    __builtin_amdgcn_sched_barrier(0);
-    mma16(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 3, fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma16(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
+  bf16x8 f0[16], f1[16];      // [0..7] B blocks, [8..15] A blocks
+  // fragment q of the read order: the first A block, the 8 B blocks, then the other A blocks
+  constexpr int kOrder[16] = {8, 0, 1, 2, 3, 4, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15};
+#pragma unroll
+  for (int t = 0; t < 16; ++t) f0[t] = read_frag(lds0, 0, t);
+  // One step of the contraction out of stage `cur`: two 32-wide sub-steps of 64 matrix-core
+  // instructions each (A block i = m / 8 against B block j = m % 8).  Every other instruction sits
+  // directly behind a matrix-core instruction, where it issues while that one executes.
+  // First sub-step: the 16 fragment reads of the second, behind the first 32 instructions, so they
+  // have landed when the barrier is reached.  Second sub-step: the 16 fragment reads of the next
+  // step's first sub-step and the 16 panel loads of the step after next.
+#define DPPO_PIN __builtin_amdgcn_sched_barrier(0)
+  auto step = [&](unsigned char* cur, unsigned char* nxt, int kt, auto steady) {
+    constexpr bool STEADY = decltype(steady)::value;
+    const bool more = STEADY || kt + 1 < nk, more2 = STEADY || kt + 2 < nk;
+#pragma unroll
+    for (int m = 0; m < 64; ++m) {
+      DPPO_MFMA16(acc[m >> 3][m & 7], f0[m & 7], f0[8 + (m >> 3)]); DPPO_PIN;
+      if (m < 32 && (m & 1) == 0) { f1[kOrder[m >> 1]] = read_frag(cur, 1, kOrder[m >> 1]); DPPO_PIN; }
+    }
     // the next stage is complete (own loads waited for, then everyone's) and this one fully read
     __syncthreads();
-    if (more) read_frags(nxt, 0, fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma16(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
+    DPPO_PIN;
+#pragma unroll
+    for (int m = 0; m < 64; ++m) {
+      DPPO_MFMA16(acc[m >> 3][m & 7], f1[m & 7], f1[8 + (m >> 3)]); DPPO_PIN;
+      if ((m & 3) == 0) { if (more) f0[kOrder[m >> 2]] = read_frag(nxt, 0, kOrder[m >> 2]); DPPO_PIN; }
+      if ((m & 3) == 2) { if (more2) dma_one(cur, kt + 2, m >> 2); DPPO_PIN; }
+    }
   };
-  int kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    step(lds0, lds1, kt);
-    step(lds1, lds0, kt + 1);
+  if (nk > 1) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dma_one(lds1, 1, q);
   }
-  if (kt < nk) step(lds0, lds1, kt);      // odd number of steps: the last one reads stage 0 again
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    step(lds0, lds1, kt, std::true_type{});
+    step(lds1, lds0, kt + 1, std::true_type{});
+  }
+  for (; kt + 1 < nk; kt += 2) {
+    step(lds0, lds1, kt, std::false_type{});
+    step(lds1, lds0, kt + 1, std::false_type{});
+  }
+  if (kt < nk) step(lds0, lds1, kt, std::false_type{});
+  // the matrix-core results must have landed before other instructions read the accumulators
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
   // Store.  The products were formed with the operands swapped (B fragment first), so a lane's
-  // accumulators r = 4q .. 4q+3 of a 32 x 32 block are four consecutive COLUMNS
-  // q*8 + (lane/32)*4 + 0..3 of row lane%32: one 8-byte store of four bf16 (16 bytes of fp32) each.
+  // four accumulators of a 16 x 16 block are four consecutive COLUMNS (lane/16)*4 + 0..3 of row
+  // lane%16.  bf16: two neighbouring blocks exchange halves between lane rows (one
+  // v_permlane16_swap per register pair), after which a lane owns 8 consecutive columns: one
+  // 16-byte store, 64 contiguous bytes per row and instruction.  fp32: 16 bytes per lane as they are.
+  const bool quad_aligned = ((reinterpret_cast<uintptr_t>(Cv) & 15u) == 0) && (ldc % 8 == 0);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = m0 + wm * 128 + i * 32 + frow;
+  for (int i = 0; i < 8; ++i) {
+    const int row = m0 + wm * 128 + i * 16 + frow;
+    if (OUT == kOutBf16) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 8; j += 2) {
+        const uint32_t lo0 = pack_bf16x2(acc[i][j][0], acc[i][j][1]), hi0 = pack_bf16x2(acc[i][j][2], acc[i][j][3]);
+        const uint32_t lo1 = pack_bf16x2(acc[i][j + 1][0], acc[i][j + 1][1]), hi1 = pack_bf16x2(acc[i][j + 1][2], acc[i][j + 1][3]);
+        if (FULL && quad_aligned) {
+          const auto l = __builtin_amdgcn_permlane16_swap(lo0, lo1, false, false);
+          const auto h = __builtin_amdgcn_permlane16_swap(hi0, hi1, false, false);
+          const u32x4 v = {l[0], h[0], l[1], h[1]};
+          const int col = n0 + wn * 128 + (j + (fk & 1)) * 16 + (fk >> 1) * 8;
+          *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(Cv) + static_cast<int64_t>(row) * ldc + col) = v;
+        } else if (row < M) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn * 128 + j * 32 + q * 8 + fk * 4;
-        if (OUT == kOutBf16) {
-          const uint32_t lo = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]), hi = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-          uint16_t* dst = static_cast<uint16_t*>(Cv) + static_cast<int64_t>(row) * ldc + col;
-          if (FULL && pair_aligned) {
-            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-            const u32x2 v = {lo, hi};
-            *reinterpret_cast<u32x2*>(dst) = v;
-          } else if (row < M) {
+          for (int h = 0; h < 2; ++h) {
+            const int col = n0 + wn * 128 + (j + h) * 16 + fk * 4;
+            const uint32_t lo = h ? lo1 : lo0, hi = h ? hi1 : hi0;
+            uint16_t* dst = static_cast<uint16_t*>(Cv) + static_cast<int64_t>(row) * ldc + col;
             if (col < N) dst[0] = static_cast<uint16_t>(lo & 0xffffu);
             if (col + 1 < N) dst[1] = static_cast<uint16_t>(lo >> 16);
             if (col + 2 < N) dst[2] = static_cast<uint16_t>(hi & 0xffffu);
             if (col + 3 < N) dst[3] = static_cast<uint16_t>(hi >> 16);
           }
-        } else {
-          // fp32 out (the host requires 16-byte aligned rows for these forms)
-          typedef float f32x4 __attribute__((ext_vector_type(4)));
-          float* dst = static_cast<float*>(Cv) + static_cast<int64_t>(row) * ldc + col;
-          f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-          if (FULL || (row < M && col + 3 < N)) {
-            if (OUT == kOutF32Add) v += *reinterpret_cast<const f32x4*>(dst);
-            *reinterpret_cast<f32x4*>(dst) = v;
-          } else if (row < M) {
+        }
+      }
+    } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (col + e < N) dst[e] = (OUT == kOutF32Add ? dst[e] : 0.f) + v[e];
-          }
+      for (int j = 0; j < 8; ++j) {
+        // fp32 out (the host requires 16-byte aligned rows for these forms)
+        const int col = n0 + wn * 128 + j * 16 + fk * 4;
+        float* dst = static_cast<float*>(Cv) + static_cast<int64_t>(row) * ldc + col;
+        f32x4 v = acc[i][j];
+        if (FULL || (row < M && col + 3 < N)) {
+          if (OUT == kOutF32Add) v += *reinterpret_cast<const f32x4*>(dst);
+          *reinterpret_cast<f32x4*>(dst) = v;
+        } else if (row < M) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (col + e < N) dst[e] = (OUT == kOutF32Add ? dst[e] : 0.f) + v[e];
         }
       }
     }

@@ -1,6 +1,8 @@
 // Measurement utilities: a plain 16-byte-vector device copy and a read-only pass over a buffer.
 // They calibrate the HBM byte counters (a copy of known size) and give the streaming ceiling
-// of the device that the loss kernels are compared with.
+// of the device that the loss kernels are compared with.  And a loop of nothing but bf16
+// matrix-core products on every compute unit: what the matrix cores sustain under the board's
+// power limit, the ceiling the matrix-product kernel is compared with.
 #include <hip/hip_runtime.h>
 #include "dppo.h"
 #include "dppo_common.hpp"
@@ -57,6 +59,73 @@ __global__ __launch_bounds__(512) void dppo_probe_copy_rows_kernel(const dppo::u
   }
 }
 
+// Matrix-core ceiling: each wave keeps 256 fp32 accumulators (as the product kernel does) and
+// issues `iters` rounds of independent products on operands held in registers: SHAPE 16: 64 of
+// v_mfma_f32_16x16x32_bf16 per round (524288 multiply-adds); SHAPE 32: 16 of
+// v_mfma_f32_32x32x16_bf16 (262144 multiply-adds).  Operands are pseudo-random bf16 in
+// +-[1, 2) so that the multipliers toggle as they do on real data.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+template <int SHAPE>
+__global__ __launch_bounds__(256) void dppo_probe_mfma_kernel(float* __restrict__ out, int iters) {
+  uint32_t s = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+  probe_bf16x8 a[4], b[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    union { uint32_t u[4]; probe_bf16x8 v; } ua, ub;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s = s * 1664525u + 1013904223u; ua.u[e] = (s & 0x807f807fu) | 0x3f803f80u;
+      s = s * 1664525u + 1013904223u; ub.u[e] = (s & 0x807f807fu) | 0x3f803f80u;
+    }
+    a[t] = ua.v; b[t] = ub.v;
+  }
+  float r = 0.f;
+  if (SHAPE == 32) {
+    probe_f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) r += acc[i][j][e];
+  } else {
+    probe_f32x4 acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j & 3], a[i & 3], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r += acc[i][j][e];
+  }
+  out[blockIdx.x * 256 + threadIdx.x] = r;    // keeps the products alive
+}
+
 int probe_cus() {
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
@@ -104,6 +173,18 @@ dppo_status_t dppo_probe_read(const void* src, size_t bytes, void* sink, void* s
   if (bytes == 0) return DPPO_OK;
   hipLaunchKernelGGL(dppo_probe_read_kernel, dim3(probe_cus() * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const dppo::u32x4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
+
+dppo_status_t dppo_probe_mfma(int shape, int iters, void* out, size_t out_bytes, double* flop, void* stream) {
+  if (!out) return DPPO_ERR_NULL;
+  if ((shape != 16 && shape != 32) || iters < 0) return DPPO_ERR_SHAPE;
+  const int cus = probe_cus();
+  if (out_bytes < static_cast<size_t>(cus) * 256 * sizeof(float)) return DPPO_ERR_WORKSPACE;
+  // per round and wave: 64 x (16 x 16 x 32) or 16 x (32 x 32 x 16) multiply-adds
+  if (flop) *flop = 2.0 * (shape == 16 ? 524288.0 : 262144.0) * 4.0 * static_cast<double>(cus) * static_cast<double>(iters);
+  if (shape == 16) hipLaunchKernelGGL(dppo_probe_mfma_kernel<16>, dim3(cus), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<float*>(out), iters);
+  else             hipLaunchKernelGGL(dppo_probe_mfma_kernel<32>, dim3(cus), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<float*>(out), iters);
   return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
 }
 

@@ -473,3 +473,29 @@ def test_probe_kernels_copy_fill_read():
     B.probe_copy_rows(b[:, :cols], a[:, :cols])
     torch.cuda.synchronize()
     assert torch.equal(b[:, :cols], a[:, :cols]) and (b[:, cols:] == -7.0).all()
+
+
+def test_probe_matrix_core_loop():
+    """The products-only loop that gives the matrix-core ceiling: runs for both instruction shapes,
+    reports its operation count, is deterministic, and rejects what it cannot run."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.full((cus * 256 + 64,), -3.0, dtype=torch.float32, device=DEV)
+    for shape in (16, 32):
+        assert B.probe_mfma(shape, 0, out) == 0.0
+        torch.cuda.synchronize()
+        assert (out[:cus * 256] == 0).all() and (out[cus * 256:] == -3.0).all()
+        fl = B.probe_mfma(shape, 3, out)
+        torch.cuda.synchronize()
+        assert fl == 2.0 * (524288 if shape == 16 else 262144) * 4 * cus * 3
+        first = out.clone()
+        assert torch.isfinite(first[:cus * 256]).all() and (first[:cus * 256] != 0).any()
+        B.probe_mfma(shape, 3, out)
+        torch.cuda.synchronize()
+        assert torch.equal(out, first)
+        out[:cus * 256] = -3.0
+    with pytest.raises(B.DppoError):
+        B.probe_mfma(8, 1, out)
+    with pytest.raises(B.DppoError):
+        B.probe_mfma(16, 1, out[:1024])
+    torch.cuda.synchronize()
+    assert (out == -3.0).all()
