@@ -249,6 +249,42 @@ def test_weight_gradient_accumulates_onto_the_callers_buffer():
     assert (g3 - g1).abs().max().item() <= 1e-6 * g1.abs().max().item() + 1e-12
 
 
+def test_hidden_state_path_can_be_captured_in_a_hip_graph_and_replayed():
+    """The chunk loop (products, loss in place, transpositions, accumulation) allocates nothing and never
+    synchronises: with the workspace and every output preallocated one call is a capturable chain of
+    kernels.  Replayed three times with eager work in between, every replay bit for bit the eager result."""
+    w = W.Workload("lm_graph", 3, 100, 4096, W.BINARY_TV, 0.1, logit_std=3.0, noise_std=1.0, adv="normal", seed=103)
+    b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
+    T, V, d = b["T"], b["V"], 128
+    gw_e = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    e = B.run_lmhead(b, chunk_rows=128, diagnostics=True, grad_weight=gw_e)
+    torch.cuda.synchronize()
+    eager = {k: e[k].clone() for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics", "grad_hidden")}
+    out = B.alloc_outputs(T, DEV, want_diagnostics=True)
+    gh = torch.empty((T, d), dtype=torch.bfloat16, device=DEV)
+    gw = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, 128, False, True), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            B.run_lmhead(b, chunk_rows=128, out=out, grad_hidden=gh, grad_weight=gw, workspace=ws)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for rep in range(3):
+        for k in ("loss", "loss_tok", "divergence", "diagnostics"):
+            out[k].fill_(float("nan"))
+        out["mask"].fill_(7)
+        gh.fill_(float("nan")); gw.fill_(float("nan")); ws.fill_(0xff)
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics"):
+            assert torch.equal(eager[k], out[k]), (rep, k)
+        assert torch.equal(eager["grad_hidden"], gh) and torch.equal(gw_e, gw), rep
+    _say("       hidden-state path captured and replayed 3 times, bitwise equal to eager")
+
+
 def test_error_codes():
     w = W.Workload("lm_err", 1, 16, 256, W.BINARY_TV, 0.2, logit_std=3.0, adv="pm1", seed=89)
     b = W.make_lmhead_batch(w, 64, DEV, exact=True)
