@@ -329,7 +329,7 @@ def test_error_codes_on_device():
 
 
 # --------------------------------------------------------------------------- full size
-def _sample_rows(b, res, n=40, seed=0):
+def _sample_rows(b, res, n=64, seed=0):
     """First, last, masked rows, zero-advantage rows, the largest |coefficient| row, random rows."""
     T = b["T"]
     rng = np.random.default_rng(seed)
@@ -370,8 +370,8 @@ def test_full_size_headline_configs(name):
     rows = _sample_rows(b, res)
     st = P.compare_rows(b, res, rows)
     _say(f"       {st}")
-    # every row's per-token scalars on a larger sample (no gradient): 512 rows
-    rows2 = np.random.default_rng(1).choice(b["T"], 512, replace=False)
+    # every row's per-token scalars on a larger sample (no gradient): 2048 rows
+    rows2 = np.random.default_rng(1).choice(b["T"], 2048, replace=False)
     st2 = P.compare_rows(b, res, np.sort(rows2), check_grad=False)
     _say(f"       {st2}")
 
