@@ -116,8 +116,11 @@ __device__ __forceinline__ void row_store16(row_rsrc_t r, uint32_t voff, uint32_
 // loads issued around such stores are waited for one by one: with stores and loads both
 // pending the compiler falls back to waiting for everything (s_waitcnt vmcnt(0)), whereas loads
 // alone complete in order and it waits for exactly the one it needs (vmcnt = number of loads
-// issued after it, which stays correct however many stores are in flight).  The hardware reads
-// the store data when the instruction issues, so the data registers may be reused at once.
+// issued after it, which stays correct however many stores are in flight).
+// A store of more than 8 bytes whose offset comes from a scalar register needs one wait state
+// before a vector-ALU instruction may overwrite its data registers (the compiler inserts that
+// for the stores it sees; it does not see this one), so the statement carries an s_nop.  A later
+// vector-memory load into the same registers queues behind the store and needs nothing.
 typedef int row_desc_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t bytes) {
   const uint64_t a = reinterpret_cast<uint64_t>(base);
@@ -129,23 +132,7 @@ __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t b
   return d;
 }
 __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t voff, uint32_t soff, u32x4 v) {
-  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
-}
-
-// 16 bytes per lane from global memory straight into LDS, issued from inline assembly: lane l of
-// the wave deposits its vector at LDS byte address `lds_addr` (uniform) + 16 l.  Like the store
-// above the compiler does not count it; the caller waits with s_waitcnt vmcnt before anything
-// reads that LDS range.  (The instruction takes its LDS base from M0, which is saved and restored.)
-__device__ __forceinline__ void row_load16_to_lds_untracked(row_desc_t d, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
-  uint32_t saved;
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
-               : "=&s"(saved)
-               : "s"(lds_addr), "v"(voff), "s"(d), "s"(soff)
-               : "memory");
-}
-// LDS byte address of a __shared__ object (uniform).
-__device__ __forceinline__ uint32_t lds_address(const void* p) {
-  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
+  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen\n\ts_nop 0" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
 // A value every lane of the wave holds identically, moved to a scalar register.

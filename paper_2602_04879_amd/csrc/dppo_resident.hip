@@ -7,11 +7,11 @@
 //   phases A+B  online over groups of chunks: packed-integer maximum (no unpacking), then
 //               sum of 2^(z*log2e + b) in fp32 with an integer offset b
 //               -> one LDS exchange + barrier -> per-token epilogue on wave 0 -> barrier
-//   phase C     gradient of every resident element, 16-byte stores; as each register chunk is
-//               consumed it is refilled with the same chunk of the workgroup's NEXT row, so HBM
-//               reads of row r+1 overlap the arithmetic and writes of row r.  The head of the
-//               next row is requested into LDS just before the epilogue, so that the compute
-//               unit has memory requests in flight while one wave does the per-token arithmetic.
+//   phase C     gradient of every resident element, 16-byte stores, the whole row in one run of
+//               stores; then the workgroup's NEXT row is requested into the same registers in one
+//               run of loads, which travel while the statistics of that row start.  (Refilling
+//               each chunk right behind its store, so that reads and writes alternate one by one,
+//               measured 3.5 % slower: the memory system prefers them in bursts.)
 //   forward only: no phase C; the first half of the registers is refilled mid-row, the second
 //               after the epilogue, so at least half a row is in flight at any time.
 //
@@ -19,10 +19,6 @@
 // grad_logits 16-byte aligned with ld % 8 == 0.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
-
-#ifndef DPPO_STAGE_CHUNKS
-#define DPPO_STAGE_CHUNKS 8
-#endif
 
 namespace dppo {
 namespace {
@@ -82,10 +78,6 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
   constexpr int GC = 2;                          // chunks per group of the online row statistics
   constexpr int kSplit = ((NCHUNK / 2 + GC - 1) / GC) * GC;   // forward only: chunks refilled mid-row
-  // Backward, one workgroup per compute unit: the head of the next row is staged in LDS during the
-  // epilogue (see below): 8 chunks of 8 KiB = 64 of the compute unit's 160 KiB (16 chunks measure the same).
-  constexpr int kStage = (GRAD && THREADS == 512 && NCHUNK >= 16) ? DPPO_STAGE_CHUNKS : 0;
-  __shared__ __attribute__((aligned(16))) u32x4 sh_stage[kStage > 0 ? kStage * THREADS : 1];
   __shared__ float sh_b[NW];
   __shared__ double sh_s[NW], sh_t[NW];
   __shared__ RowCoef sh_rc;
@@ -143,7 +135,6 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 
     RowCoef rc;
     rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
-    bool staged = false;            // the head of the next row is on its way into LDS
     if (live) {
       // Inputs of the epilogue, requested now so that they have arrived when it runs.
       RowScalars rs;
@@ -237,22 +228,6 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // The epilogue below would leave this compute unit without a memory request in flight: the
-      // row has arrived, and the next one cannot be requested into the registers before the
-      // gradient has been formed from them.  A compute unit's share of the HBM bandwidth is
-      // bounded by what it keeps in flight, so request the head of the next row NOW, into LDS
-      // (which this kernel hardly uses otherwise): it travels during the epilogue, and phase C
-      // refills those chunks from LDS.  Everything this wave has in flight is waited for first, so
-      // that the epilogue's own inputs never wait behind these loads.
-      if (kStage > 0 && more) {
-        asm volatile("" ::"v"(rs.za), "v"(rs.lmu), "v"(rs.adv), "v"(tk.z), "v"(tk.lp), "v"(tk.id));
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const row_desc_t zd = make_row_desc(logits + next * pitch, row_bytes);
-        const uint32_t base = lds_address(sh_stage) + static_cast<uint32_t>(wid) * (kWave * 16);
-#pragma unroll
-        for (int i = 0; i < kStage; ++i) row_load16_to_lds_untracked(zd, voff, i * kStride, base + i * (THREADS * 16));
-        staged = true;
-      }
       // wave-level combine: common offset = the smallest one, rescaling is exact
       const float bw = -wave_max(-b);
       const double dw = static_cast<double>(bw - b), scw = static_cast<double>(fast_exp2(bw - b));
@@ -305,8 +280,8 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     }
 
     // ---- phase C: gradient out, next row in -------------------------------------------------
-    // Every chunk: store its gradient, then refill it with the same chunk of the workgroup's
-    // next row, in the order the next row's arithmetic will consume them.
+    // Store the gradient of every chunk, then refill the chunks with the workgroup's next row,
+    // in the order the next row's arithmetic will consume them.
     if (GRAD) {
       char* gr = grad + row * pitch;
       const row_desc_t gout = make_row_desc(gr, row_bytes);
@@ -317,31 +292,15 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 #pragma unroll
         for (int i = 0; i < NCHUNK; ++i) buf[i] = neg_inf;
       }
-      if (kStage > 0) {
-        if (more && !staged) {
-          // an ignored row (no statistics, no epilogue): stage the head of the next row here
-          const row_desc_t zd = make_row_desc(logits + next * pitch, row_bytes);
-          const uint32_t base = lds_address(sh_stage) + static_cast<uint32_t>(wid) * (kWave * 16);
 #pragma unroll
-          for (int i = 0; i < kStage; ++i) row_load16_to_lds_untracked(zd, voff, i * kStride, base + i * (THREADS * 16));
-        }
-        // the staged chunks have landed (nothing else of this wave is in flight yet); every lane
-        // reads back exactly what its own wave's loads deposited, so no barrier is needed.  Without
-        // a next row nothing was staged and what is read here is never used.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
+      for (int i = 0; i < NCHUNK; ++i) row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
+      // Keep the instruction scheduler from hoisting the refills above the stores: a refill can
+      // only reuse its chunk's registers once the store has been given them (a vector-memory load
+      // into those registers then queues behind that store).
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) {
-        row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
-        // A vector-memory load into the registers a store has just been given queues behind that
-        // store; an LDS read does not, and could land before the store has fetched its data: wait
-        // until it has (the export counter counts store data not yet read from the registers).
-        if (i < kStage) asm volatile("s_waitcnt expcnt(0)" ::: "memory");
-        buf[i] = (i < kStage) ? sh_stage[i * THREADS + tid] : row_load16(zn, voff, i * kStride);
-        // Keep the instruction scheduler from hoisting the refills above the stores they follow:
-        // a refill can only reuse its chunk's registers once the chunk has been consumed.
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zn, voff, i * kStride);
+      __builtin_amdgcn_sched_barrier(0);
       if (rc.coef != 0.f && owner) {
         // The resident copy held -inf at a_t, so the vector store above wrote 0 there.  Once
         // that store has completed, the owning thread writes the sampled token's entry.
