@@ -121,6 +121,8 @@ __device__ __forceinline__ void row_store16(row_rsrc_t r, uint32_t voff, uint32_
 // before a vector-ALU instruction may overwrite its data registers (the compiler inserts that
 // for the stores it sees; it does not see this one), so the statement carries an s_nop.  A later
 // vector-memory load into the same registers queues behind the store and needs nothing.
+// The store is marked non-temporal (a gradient row is not read again by this kernel): measured
+// 2.5 % faster on the headline shape; the same mark on the row loads measured slower.
 typedef int row_desc_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t bytes) {
   const uint64_t a = reinterpret_cast<uint64_t>(base);
@@ -132,7 +134,7 @@ __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t b
   return d;
 }
 __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t voff, uint32_t soff, u32x4 v) {
-  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen\n\ts_nop 0" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
+  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 0" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
 // A value every lane of the wave holds identically, moved to a scalar register.
