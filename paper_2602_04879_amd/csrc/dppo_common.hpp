@@ -104,8 +104,10 @@ typedef __amdgpu_buffer_rsrc_t row_rsrc_t;
 __device__ __forceinline__ row_rsrc_t make_row_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
 }
+// NT: marked non-temporal (the third bit pair of the cache policy: 2 = nt).
+template <bool NT = false>
 __device__ __forceinline__ u32x4 row_load16(row_rsrc_t r, uint32_t voff, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, NT ? 2 : 0);
 }
 __device__ __forceinline__ void row_store16(row_rsrc_t r, uint32_t voff, uint32_t soff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 0);

@@ -75,6 +75,9 @@ template <int THREADS, int NCHUNK, bool GRAD, bool DIAG>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
+  // Forward only, the row loads are marked non-temporal (measured 3.5 % faster on the headline shape);
+  // with the gradient stores in the mix the same mark measured 4 % slower, so there they are plain.
+  constexpr bool kNtLoads = !GRAD;
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
   constexpr int GC = 2;                          // chunks per group of the online row statistics
   constexpr int kSplit = ((NCHUNK / 2 + GC - 1) / GC) * GC;   // forward only: chunks refilled mid-row
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   {
     const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
 #pragma unroll
-    for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zr, voff, i * kStride);
+    for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<kNtLoads>(zr, voff, i * kStride);
   }
   // Fetched one row ahead, so that neither the row loop nor wave 0's gathers ever wait on a load
   // that queues behind the row's own refills: the sampled id, and (wave 0, lane k < K) the id
@@ -224,7 +227,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         // the epilogue and is in flight during the first part of the next row's statistics.
         if (!GRAD && g0 + GC == kSplit) {
 #pragma unroll
-          for (int i = 0; i < kSplit; ++i) buf[i] = row_load16(zn, voff, i * kStride);
+          for (int i = 0; i < kSplit; ++i) buf[i] = row_load16<kNtLoads>(zn, voff, i * kStride);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // into those registers then queues behind that store).
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16(zn, voff, i * kStride);
+      for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<kNtLoads>(zn, voff, i * kStride);
       __builtin_amdgcn_sched_barrier(0);
       if (rc.coef != 0.f && owner) {
         // The resident copy held -inf at a_t, so the vector store above wrote 0 there.  Once
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // rows whose statistics ran refilled the first part there
 #pragma unroll
       for (int i = 0; i < NCHUNK; ++i)
-        if (i >= kSplit || !live) buf[i] = row_load16(zn, voff, i * kStride);
+        if (i >= kSplit || !live) buf[i] = row_load16<kNtLoads>(zn, voff, i * kStride);
     }
   }
   if (tid == 0) p.partial[blockIdx.x] = loss_acc;
