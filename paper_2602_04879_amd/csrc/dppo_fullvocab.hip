@@ -183,7 +183,9 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         const bool write_grad = GRAD && rc1.coef != 0.f;
         int v2 = tid;
         for (; v2 + THREADS < nvec; v2 += 2 * THREADS) {
-          const u32x4 z0 = zv[v2], y0 = yv[v2], z1 = zv[v2 + THREADS], y1 = yv[v2 + THREADS];
+          // last use of both rows: non-temporal loads (7 % faster on the headline shape)
+          const u32x4 z0 = __builtin_nontemporal_load(zv + v2), y0 = __builtin_nontemporal_load(yv + v2);
+          const u32x4 z1 = __builtin_nontemporal_load(zv + v2 + THREADS), y1 = __builtin_nontemporal_load(yv + v2 + THREADS);
           min8(z0, y0, acc0);
           min8(z1, y1, acc1);
           if (write_grad) {
@@ -256,7 +258,8 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         const u32x4* zv = reinterpret_cast<const u32x4*>(zrow + head);
         int v = tid;
         for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {     // four loads in flight, then four stores
-          const u32x4 q0 = zv[v], q1 = zv[v + THREADS], q2 = zv[v + 2 * THREADS], q3 = zv[v + 3 * THREADS];
+          const u32x4 q0 = __builtin_nontemporal_load(zv + v), q1 = __builtin_nontemporal_load(zv + v + THREADS);   // last use of the row
+          const u32x4 q2 = __builtin_nontemporal_load(zv + v + 2 * THREADS), q3 = __builtin_nontemporal_load(zv + v + 3 * THREADS);
           grad_vec(q0, v, rc);
           grad_vec(q1, v + THREADS, rc);
           grad_vec(q2, v + 2 * THREADS, rc);
