@@ -139,6 +139,13 @@ __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t vof
   asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 0" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
+// First row of a workgroup in a row-per-workgroup kernel whose rows advance by gridDim.x: a
+// permutation of 0 .. gridDim.x-1 that gives the workgroups of one die (id % 8) neighbouring rows.
+__device__ __forceinline__ int first_row_of_workgroup() {
+  const unsigned g = gridDim.x, b = blockIdx.x;
+  return static_cast<int>((g & 7u) == 0 ? (b & 7u) * (g >> 3) + (b >> 3) : b);
+}
+
 // A value every lane of the wave holds identically, moved to a scalar register.
 __device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ float uniform_f(float v) {
