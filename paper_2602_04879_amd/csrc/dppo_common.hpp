@@ -75,27 +75,6 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte vector = 8 bf16
-// Pointers known to be in global memory (address space 1): lets the compiler emit global_*
-// instructions with a scalar base instead of flat_* ones.
-typedef const __attribute__((address_space(1))) u32x4* gvec_cptr;
-typedef __attribute__((address_space(1))) u32x4* gvec_ptr;
-typedef const __attribute__((address_space(1))) uint16_t* gu16_cptr;
-typedef __attribute__((address_space(1))) uint16_t* gu16_ptr;
-typedef const __attribute__((address_space(1))) char* gbyte_cptr;
-typedef __attribute__((address_space(1))) char* gbyte_ptr;
-
-// 16-byte access at (uniform base) + (per-lane unsigned 32-bit byte offset): the form that maps
-// to a global_load/store with a scalar base register and one vector offset register.
-__device__ __forceinline__ u32x4 gload16(gbyte_cptr base, uint32_t voff) {
-  return *reinterpret_cast<gvec_cptr>(base + voff);
-}
-__device__ __forceinline__ void gstore16(gbyte_ptr base, uint32_t voff, u32x4 v) {
-  *reinterpret_cast<gvec_ptr>(base + voff) = v;
-}
-__device__ __forceinline__ void gstore16_nt(gbyte_ptr base, uint32_t voff, u32x4 v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<gvec_ptr>(base + voff));
-}
-
 // Buffer resource over one row: base address in scalar registers, byte range checked by the
 // hardware (a load past `bytes` returns 0, a store past it is dropped), so a 16-byte access is
 // addressed by one per-lane 32-bit offset plus a scalar offset and needs no address arithmetic
@@ -109,11 +88,8 @@ template <bool NT = false>
 __device__ __forceinline__ u32x4 row_load16(row_rsrc_t r, uint32_t voff, uint32_t soff) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, NT ? 2 : 0);
 }
-__device__ __forceinline__ void row_store16(row_rsrc_t r, uint32_t voff, uint32_t soff, u32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 0);
-}
 
-// The same store issued from inline assembly, over a descriptor built by hand.  The compiler
+// A 16-byte store to such a row issued from inline assembly, over a descriptor built by hand.  The compiler
 // then does not count it among the pending vector-memory operations.  That matters where
 // loads issued around such stores are waited for one by one: with stores and loads both
 // pending the compiler falls back to waiting for everything (s_waitcnt vmcnt(0)), whereas loads
