@@ -188,7 +188,7 @@ const char* dppo_last_path(void);
  *     z_c = h_c W^T           bf16 logits of the chunk, fp32 accumulation, round to nearest even
  *     loss, D, M, and g_c = d loss / d z_c in place            (exactly dppo_loss_fwd_bwd on z_c)
  *     d loss / d h_c = g_c W  bf16, fp32 accumulation
- *     d loss / d W  += g_c^T h_c   (optional) fp32
+ *     d loss / d W  += g_c^T h_c   (optional) fp32, from g_c and h_c as they lie (no transposed copies)
  * so device memory holds one chunk of logits, not [T, V].  `loss` carries every per-token
  * input and output with the meaning it has in dppo_loss_fwd_bwd (its logits, ld, grad_logits,
  * mu_logits, workspace and flags fields are ignored); the DPPO_FULL_* variants are not
@@ -214,11 +214,11 @@ typedef struct {
   int32_t        grad_weight_accumulate; /* 0: overwrite grad_weight; 1: add to what it holds (a   */
                                 /* trainer accumulating micro-batches into an fp32 main gradient) */
   void*          workspace;     /* >= dppo_lmhead_workspace_bytes(...) bytes, 256-byte aligned:    */
-                                /* loss partial sums, the chunk of logits, W^T unless given, and   */
-                                /* for the weight gradient the transposed chunk of g and of h      */
+                                /* loss partial sums, the chunk of logits, W^T unless given        */
   size_t         workspace_bytes;
 } dppo_lmhead_args_t;
 
+/* (want_grad_weight no longer changes the size: the weight gradient needs no buffer of its own.) */
 size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t,
                                    int want_grad_weight);
 
@@ -245,6 +245,16 @@ dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ld
  * multiple of 4; accumulate != 0 adds the product to what C holds.  (The weight gradient of the
  * path above sums its chunks this way.) */
 dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
+                               int64_t M, int64_t N, int64_t K, int accumulate, void* stream);
+
+/* C[M, N] (+)= A[K, M]^T * B[K, N]: both bf16 operands row-major with the contraction index as
+ * the ROW index (what the gradient of a weight is: logit gradients [T, V] transposed times
+ * activations [T, d]), read as they lie, fp32 accumulation, C fp32 [M, ldc].  Any K >= 1 (rows
+ * past K count as zeros); A and B 16-byte aligned with lda >= M, ldb >= N multiples of 8 and
+ * below 2^22; C 16-byte aligned with ldc >= N a multiple of 4; accumulate != 0 adds the product to
+ * what C holds.  Device pointers, caller-owned; buffers must not overlap.  M = 0 or N = 0 is valid
+ * and does nothing.  DPPO_ERR_SHAPE / _NULL / _ALIGN / _LAUNCH as for dppo_gemm_nt. */
+dppo_status_t dppo_gemm_tn_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
                                int64_t M, int64_t N, int64_t K, int accumulate, void* stream);
 
 /* ---- measurement utilities (not part of the loss) ------------------------------------------

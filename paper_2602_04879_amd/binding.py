@@ -92,9 +92,10 @@ def lib() -> C.CDLL:
                                    C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
         l.dppo_lmhead_workspace_bytes.restype = C.c_size_t
         l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int]
-        l.dppo_gemm_nt_f32.restype = C.c_int
-        l.dppo_gemm_nt_f32.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                                       C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p]
+        for f in (l.dppo_gemm_nt_f32, l.dppo_gemm_tn_f32):
+            f.restype = C.c_int
+            f.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                          C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p]
         for f in (l.dppo_lmhead_loss_fwd, l.dppo_lmhead_loss_fwd_bwd):
             f.restype = C.c_int
             f.argtypes = [C.POINTER(DppoLmheadArgs), C.c_void_p]
@@ -235,6 +236,17 @@ def gemm_nt_f32(a, b, c, accumulate: bool = False, stream=None):
     M, K = a.shape
     N = b.shape[0]
     st = lib().dppo_gemm_nt_f32(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0),
+                                M, N, K, int(accumulate), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    return c
+
+
+def gemm_tn_f32(a, b, c, accumulate: bool = False, stream=None):
+    """dppo_gemm_tn_f32: c[M, N] (+)= a[K, M]^T @ b[K, N], c fp32."""
+    K, M = a.shape
+    N = b.shape[1]
+    st = lib().dppo_gemm_tn_f32(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0),
                                 M, N, K, int(accumulate), C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)

@@ -168,7 +168,7 @@ size_t lmhead_workspace(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, boo
   size_t b = DPPO_WORKSPACE_BYTES;
   b += static_cast<size_t>(c) * static_cast<size_t>(V) * 2;
   if (!have_weight_t) b += static_cast<size_t>(d) * static_cast<size_t>(V) * 2;
-  if (want_grad_weight) b += static_cast<size_t>(round_up64(c)) * static_cast<size_t>(V + d) * 2;
+  (void)want_grad_weight;     // the weight gradient needs no buffer of its own
   return b;
 }
 
@@ -221,9 +221,6 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
     }
     next_free += static_cast<size_t>(d) * static_cast<size_t>(V);
   }
-  const int64_t kp_max = round_up64(chunk);
-  uint16_t* gT = next_free;                                               // [V, kp_max]
-  uint16_t* hT = next_free + static_cast<size_t>(kp_max) * static_cast<size_t>(V);   // [d, kp_max]
   const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
   const int64_t nchunks = T > 0 ? (T + chunk - 1) / chunk : 0;
   const int parts_per_chunk = nchunks > 0 ? static_cast<int>(max_parts / nchunks) : max_parts;
@@ -258,14 +255,12 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
         return DPPO_ERR_LAUNCH;
     }
     if (want_gw) {
-      // gradient of the lm_head weight: g_c^T [V, rows] times h_c [rows, d], the token index padded
-      // with zeros to a multiple of 64; fp32, summed over the chunks (and onto the caller's buffer
-      // if asked to accumulate)
-      const int kp = static_cast<int>(round_up64(rows));
-      if (dppo::launch_transpose(zbuf, V, gT, kp_max, static_cast<int>(rows), static_cast<int>(V), kp, s) != hipSuccess) return DPPO_ERR_LAUNCH;
-      if (dppo::launch_transpose(h, a->ld_hidden, hT, kp_max, static_cast<int>(rows), static_cast<int>(d), kp, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      // gradient of the lm_head weight: g_c^T h_c with g_c [rows, V] and h_c [rows, d] as they lie
+      // (the token index is the row index of both); fp32, summed over the chunks (and onto the
+      // caller's buffer if asked to accumulate)
       const int out = (r0 == 0 && !a->grad_weight_accumulate) ? 1 : 2;
-      if (dppo::launch_gemm_nt(gT, kp_max, hT, kp_max, a->grad_weight, a->ld_grad_weight, static_cast<int>(V), static_cast<int>(d), kp, out, s) != hipSuccess)
+      if (dppo::launch_gemm_tn(zbuf, V, h, a->ld_hidden, a->grad_weight, a->ld_grad_weight, static_cast<int>(V), static_cast<int>(d),
+                               static_cast<int>(rows), out, s) != hipSuccess)
         return DPPO_ERR_LAUNCH;
     }
   }
@@ -337,6 +332,19 @@ dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_
   if (!A || !B || !C) return DPPO_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15u) return DPPO_ERR_ALIGN;
   const hipError_t e = dppo::launch_gemm_nt(static_cast<const uint16_t*>(A), lda, static_cast<const uint16_t*>(B), ldb,
+                                            C, ldc, static_cast<int>(M), static_cast<int>(N), static_cast<int>(K),
+                                            accumulate ? 2 : 1, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
+
+dppo_status_t dppo_gemm_tn_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
+                               int64_t M, int64_t N, int64_t K, int accumulate, void* stream) {
+  if (M < 0 || N < 0 || K < 1 || M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
+  if (lda < M || ldb < N || ldc < N || lda % 8 != 0 || ldb % 8 != 0 || ldc % 4 != 0 || lda >= (int64_t(1) << 22) || ldb >= (int64_t(1) << 22)) return DPPO_ERR_SHAPE;
+  if (M == 0 || N == 0) return DPPO_OK;
+  if (!A || !B || !C) return DPPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15u) return DPPO_ERR_ALIGN;
+  const hipError_t e = dppo::launch_gemm_tn(static_cast<const uint16_t*>(A), lda, static_cast<const uint16_t*>(B), ldb,
                                             C, ldc, static_cast<int>(M), static_cast<int>(N), static_cast<int>(K),
                                             accumulate ? 2 : 1, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;

@@ -21,6 +21,12 @@
 // Panel rows past M or N re-read the last valid row (their products are never stored); all
 // loads go through range-checked buffer resources over exactly the rows a tile owns.  K must be
 // a multiple of 64, rows 16-byte aligned (checked by the host).
+//
+// A second form of the same kernel takes both operands with the contraction index as the ROW
+// index, C[M, N] = A[K, M]^T * B[K, N] (what the gradient of a weight is: logit gradients [T, V]
+// transposed times activations [T, d]), with no transposed copies: the panels of a step are 64
+// rows of 512 bytes, and the LDS transpose read (ds_read_b64_tr_b16) hands every lane the
+// consecutive k of one column.  There K is arbitrary: rows past it read as zeros.
 #include <type_traits>
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
@@ -47,13 +53,18 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
 // OUT selects what leaves the tile: bf16 (rounded to nearest even), fp32, or fp32 added to what C holds.
 enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
 
-template <bool FULL, int OUT>
+// TN: A is [K, M] and B is [K, N] (the contraction index is the ROW index; C = A^T B).  The panels
+// of a step are then 64 rows of 512 bytes, and the fragment reads use the LDS transpose read
+// (ds_read_b64_tr_b16: out of a 16-lane group's sixteen 8-byte blocks, lane i gets element i%4 of
+// the blocks i/4, i/4 + 4, i/4 + 8, i/4 + 12), which turns four k rows of four neighbouring m
+// into the four consecutive k of one m that a matrix-core operand wants.
+template <bool FULL, int OUT, bool TN>
 __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* lds1, const uint16_t* __restrict__ A, int64_t lda,
                                           const uint16_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv, int64_t ldc,
                                           int M, int N, int K, int m0, int n0) {
   const int tid = threadIdx.x, lane = tid & 63, wid = uniform_i(tid >> 6);
   const int wm = wid >> 1, wn = wid & 1;
-  const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);
+  const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);     // (TN: columns of A and of B)
   const uint32_t pitch_a = static_cast<uint32_t>(lda) * 2u, pitch_b = static_cast<uint32_t>(ldb) * 2u;
 
   // Loader role: thread t moves LDS vector slot (t % 8) of rows t/8 + 32 i, i = 0..7, of each panel;
@@ -78,8 +89,34 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   for (int ks = 0; ks < 2; ++ks) foff[ks] = lds_off(frow, ks * 4 + fk);
   const uint32_t fbase_a = static_cast<uint32_t>(wm * 128) * kRowBytes;
   const uint32_t fbase_b = kPanelBytes + static_cast<uint32_t>(wn * 128) * kRowBytes;
+  // TN panels: LDS row k (512 bytes = 32 slots of 16 bytes) holds in slot s the 8 columns of
+  // global slot s ^ (2 g(k)), g(k) = (k & 3) | ((k >> 3) & 1) << 2: the sixteen k rows one transpose
+  // read touches (k = 8 kg + j, kg = lane / 16, j = (lane % 16) / 4) then spread their 32-byte pieces
+  // over all banks.  Lane (kg, j, q = lane % 4) reads the 8 bytes of columns 4 q .. 4 q + 3 of block t
+  // in row 8 kg + j (+ 4 for the second half of the fragment, + 32 for the second sub-step).
+  uint32_t toff_a[8], toff_b[8];
+  if (TN) {
+    const int kg = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
+    const uint32_t g2 = static_cast<uint32_t>(2 * (j | ((kg & 1) << 2)));
+    const uint32_t rowoff = static_cast<uint32_t>(8 * kg + j) * 512u + static_cast<uint32_t>(q & 1) * 8u;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      toff_a[t] = rowoff + ((static_cast<uint32_t>(wm * 16 + 2 * t + (q >> 1)) ^ g2) << 4);
+      toff_b[t] = kPanelBytes + rowoff + ((static_cast<uint32_t>(wn * 16 + 2 * t + (q >> 1)) ^ g2) << 4);
+    }
+  }
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
   // fragment t of a sub-step: 0..7 the B blocks, 8..15 the A blocks
-  auto read_frag = [&](const unsigned char* stage, int ks, int t) {
+  auto read_frag = [&](const unsigned char* stage, int ks, int t) -> bf16x8 {
+    if (TN) {
+      const unsigned char* p = stage + (t < 8 ? toff_b[t & 7] : toff_a[t & 7]) + ks * (32 * 512);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 512));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
     return *reinterpret_cast<const bf16x8*>(stage + (t < 8 ? fbase_b : fbase_a) + (t & 7) * 16 * kRowBytes + foff[ks]);
   };
 #define DPPO_MFMA16(ACC, X, Y) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(X), "v"(Y))
@@ -88,7 +125,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // has read its last fragments of that stage (the barrier in the middle of the step) the panels
   // of step kt+2 are loaded into it.  The fragments of each 32-wide sub-step are read from LDS one
   // sub-step ahead of the matrix-core instructions that consume them.  One barrier per step.
-  const int nk = K / kBK;
+  const int nk = TN ? (K + kBK - 1) / kBK : K / kBK;     // TN: rows past K read as zeros (range check)
   // Global memory -> LDS directly (buffer_load ... lds): lane l of a wave-level load deposits its
   // 16 bytes at (LDS base of the instruction) + 16 l, which is exactly the loader layout above for
   // the base stage + panel + i * 4096 + wave * 1024.  No staging registers, no LDS store
@@ -98,20 +135,44 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // range-checked view of exactly the rows this tile owns.  The k offset of a step goes into the
   // base of that view (scalar arithmetic), so the per-lane offsets never change.
   uint32_t vo_a[8], vo_b[8];
+  uint32_t bytes_a, bytes_b;
+  if (TN) {
+    // load i of a panel (one KiB: two LDS rows) moves k rows 8 i + 2 wave + lane / 32, LDS slot lane % 32
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    vo_a[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_a - 1)) * pitch_a + lkv;
-    vo_b[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_b - 1)) * pitch_b + lkv;
+    for (int i = 0; i < 8; ++i) {
+      const int k = 8 * i + 2 * wid + (lane >> 5);
+      const uint32_t gs = static_cast<uint32_t>(lane & 31) ^ static_cast<uint32_t>(2 * ((k & 3) | (((k >> 3) & 1) << 2)));
+      vo_a[i] = static_cast<uint32_t>(k) * pitch_a + (gs << 4);
+      vo_b[i] = static_cast<uint32_t>(k) * pitch_b + (gs << 4);
+    }
+    bytes_a = static_cast<uint32_t>(M - m0) * 2u;     // bytes of a row from the tile's first column on
+    bytes_b = static_cast<uint32_t>(N - n0) * 2u;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      vo_a[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_a - 1)) * pitch_a + lkv;
+      vo_b[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_b - 1)) * pitch_b + lkv;
+    }
+    bytes_a = static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u;
+    bytes_b = static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u;
   }
-  const uint32_t bytes_a = static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u;
-  const uint32_t bytes_b = static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u;
   auto dma_one = [&](unsigned char* stage, int step, int idx) {     // load idx of the 16 of a step: 0..7 A panel, 8..15 B panel
     const bool b_panel = idx >= 8;
     const int i = idx & 7;
-    const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
     unsigned char* dst = stage + (b_panel ? kPanelBytes : 0) + wid * 1024 + i * 4096;
-    const row_rsrc_t r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(n0) * ldb + step * kBK, bytes_b - koff)
-                                 : make_row_rsrc(A + static_cast<int64_t>(m0) * lda + step * kBK, bytes_a - koff);
+    row_rsrc_t r;
+    if (TN) {
+      // view of the step's k rows (those that exist) from the tile's first column on: what lies past
+      // the last row's end reads as zero, what lies past a row's M (N) columns belongs to C rows
+      // (columns) that are never stored
+      const int kr = min(kBK, K - step * kBK);
+      r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(step) * kBK * ldb + n0, static_cast<uint32_t>(kr - 1) * pitch_b + bytes_b)
+                  : make_row_rsrc(A + static_cast<int64_t>(step) * kBK * lda + m0, static_cast<uint32_t>(kr - 1) * pitch_a + bytes_a);
+    } else {
+      const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
+      r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(n0) * ldb + step * kBK, bytes_b - koff)
+                  : make_row_rsrc(A + static_cast<int64_t>(m0) * lda + step * kBK, bytes_a - koff);
+    }
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, b_panel ? vo_b[i] : vo_a[i], 0, 0, 0);
   };
 #pragma unroll
@@ -224,7 +285,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
 // outside the matrix exit at once.
 constexpr int kGroupM = 8, kGroupN = 4;
 
-template <int OUT>
+template <int OUT, bool TN>
 __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                            const uint16_t* __restrict__ B, int64_t ldb,
                                                            void* __restrict__ C, int64_t ldc, int M, int N, int K,
@@ -238,8 +299,8 @@ __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __res
   const int tm = bm * kGroupM + (within % kGroupM), tn = bn * kGroupN + (within / kGroupM);
   if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * kBM, n0 = tn * kBN;
-  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
-  else                                gemm_tile<false, OUT>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT, TN>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  else                                gemm_tile<false, OUT, TN>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
 }
 
 // dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS, 16-byte accesses (8 elements
@@ -291,9 +352,22 @@ hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  if (out == 0)      hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutBf16>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else if (out == 1) hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutF32>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else               hipLaunchKernelGGL(dppo_gemm_nt_kernel<kOutF32Add>, grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  if (out == 0)      hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else               hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  return hipGetLastError();
+}
+
+// C[M, N] (fp32; out 1: written, 2: added to) = A^T B with A [K, M], B [K, N] (row-major, the contraction index the row index)
+hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, int out, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
+  const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
+  const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
+  const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
+  if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else          hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
   return hipGetLastError();
 }
 

@@ -24,6 +24,9 @@ hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, i
 // 1: C fp32; 2: C fp32, the product added to what it holds (the fp32 forms need 16-byte aligned
 // rows of C).  Needs K % 64 == 0, 16-byte aligned A and B with lda, ldb multiples of 8, and
 // 256 * ld * 2 < 2^32.
+// C[M, N] fp32 (out 1: written, 2: added to) = A^T B, A [K, M], B [K, N]; any K >= 1
+hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, int out, hipStream_t s);
 hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
                           int M, int N, int K, int out, hipStream_t s);
 

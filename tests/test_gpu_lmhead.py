@@ -124,6 +124,51 @@ def test_gemm_fp32_result_exact_inputs_bitwise_and_accumulation(M, N, K):
     assert (c[:, N:] == 3.0).all()
 
 
+@pytest.mark.parametrize("M,N,K,lda,ldb,ldc", [
+    (256, 256, 64, 256, 256, 256), (8, 8, 1, 8, 8, 8), (300, 520, 100, 304, 520, 520), (1000, 776, 193, 1008, 784, 780),
+    (4160, 128, 321, 4160, 128, 128), (130, 4100, 4096, 136, 4104, 4100), (151936, 64, 130, 151936, 64, 64)])
+def test_gemm_tn_exact_inputs_bitwise_and_accumulation(M, N, K, lda, ldb, ldc):
+    """C = A^T B with both operands stored with the contraction index as the row index (the form of
+    the weight gradient), any K, ragged M and N, pitches of their own, then once more accumulating."""
+    _say(f"[case] gemm tn M={M} N={N} K={K}")
+    g = torch.Generator(device=DEV); g.manual_seed(M * 3 + N + K)
+    a = torch.full((K, lda), 7.0, dtype=torch.bfloat16, device=DEV); b = torch.full((K, ldb), -5.0, dtype=torch.bfloat16, device=DEV)
+    a[:, :M] = (torch.randint(-8, 9, (K, M), generator=g, device=DEV).float() / 64).bfloat16()
+    b[:, :N] = (torch.randint(-8, 9, (K, N), generator=g, device=DEV).float() / 8).bfloat16()
+    c = torch.full((M, ldc), 3.0, dtype=torch.float32, device=DEV)
+    B.gemm_tn_f32(a[:, :M], b[:, :N], c[:, :N])
+    torch.cuda.synchronize()
+    ref = (a[:, :M].double().T @ b[:, :N].double()).cpu().numpy()       # exact, and exactly representable in fp32
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), ref)
+    B.gemm_tn_f32(a[:, :M], b[:, :N], c[:, :N], accumulate=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), 2 * ref)
+    assert (c[:, N:] == 3.0).all()
+
+
+def test_gemm_tn_poisoned_neighbourhood_and_error_codes():
+    """What lies next to the operands (pitch padding, rows past K in a larger buffer) holds NaN and
+    infinities and must not reach any result; bad arguments are refused."""
+    g = torch.Generator(device=DEV); g.manual_seed(11)
+    K, M, N = 70, 264, 72
+    big_a = torch.full((K + 64, M + 8), float("nan"), dtype=torch.bfloat16, device=DEV)
+    big_b = torch.full((K + 64, N + 8), float("inf"), dtype=torch.bfloat16, device=DEV)
+    big_a[:K, :M] = (torch.randint(-8, 9, (K, M), generator=g, device=DEV).float() / 8).bfloat16()
+    big_b[:K, :N] = (torch.randint(-8, 9, (K, N), generator=g, device=DEV).float() / 8).bfloat16()
+    c = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    B.gemm_tn_f32(big_a[:K, :M], big_b[:K, :N], c)
+    torch.cuda.synchronize()
+    ref = (big_a[:K, :M].double().T @ big_b[:K, :N].double()).cpu().numpy()
+    np.testing.assert_array_equal(c.double().cpu().numpy(), ref)
+    a, b = big_a[:K, :M], big_b[:K, :N]
+    for bad in (lambda: B.gemm_tn_f32(a[:, 1:], b, c[1:]),                      # misaligned A
+                lambda: B.gemm_tn_f32(a[:0], b[:0], c),                          # K = 0
+                lambda: B.gemm_tn_f32(a, b, c.view(-1)[: M * N - M].view(M, N - 1)[:, :N - 1])):   # ldc not a multiple of 4
+        with pytest.raises(B.DppoError):
+            bad()
+    torch.cuda.synchronize()
+
+
 def test_gemm_ordinary_inputs_within_one_rounding():
     M, N, K = 384, 1000, 1024
     g = torch.Generator(device=DEV); g.manual_seed(3)
