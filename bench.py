@@ -102,7 +102,7 @@ def bench_lmhead(args, w, dev) -> int:
     out = B.alloc_outputs(T, dev)
     grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
     grad_weight = torch.empty((V, d), dtype=torch.float32, device=dev)
-    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, args.chunk_rows, False, True), dtype=torch.uint8, device=dev)
+    ws = torch.empty(B.lmhead_workspace_bytes(T, V, args.chunk_rows), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step():

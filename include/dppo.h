@@ -42,7 +42,7 @@
 extern "C" {
 #endif
 
-#define DPPO_VERSION 200          /* major*10000 + minor*100 + patch                          */
+#define DPPO_VERSION 300          /* major*10000 + minor*100 + patch                          */
 #define DPPO_KMAX 1024            /* largest accepted K                                        */
 #define DPPO_WORKSPACE_BYTES 65536
 
@@ -187,7 +187,7 @@ const char* dppo_last_path(void);
  * the library walks T in chunks of `chunk_rows` tokens:
  *     z_c = h_c W^T           bf16 logits of the chunk, fp32 accumulation, round to nearest even
  *     loss, D, M, and g_c = d loss / d z_c in place            (exactly dppo_loss_fwd_bwd on z_c)
- *     d loss / d h_c = g_c W  bf16, fp32 accumulation
+ *     d loss / d h_c = g_c W  bf16, fp32 accumulation, W read as it lies
  *     d loss / d W  += g_c^T h_c   (optional) fp32, from g_c and h_c as they lie (no transposed copies)
  * so device memory holds one chunk of logits, not [T, V].  `loss` carries every per-token
  * input and output with the meaning it has in dppo_loss_fwd_bwd (its logits, ld, grad_logits,
@@ -200,9 +200,6 @@ typedef struct {
   int64_t        d;             /* hidden size, multiple of 64                                     */
   const void*    weight;        /* bf16 [V, ld_weight]: lm_head weight, 16-byte aligned            */
   int64_t        ld_weight;     /* >= d, multiple of 8                                             */
-  const void*    weight_t;      /* optional bf16 [d, ld_weight_t] = weight transposed (a caller    */
-                                /* that keeps one saves the transposition per call); may be NULL   */
-  int64_t        ld_weight_t;   /* >= V, multiple of 8                                             */
   int64_t        chunk_rows;    /* tokens per chunk; <= 0: 8192.  The second and third products have  */
                                 /* chunk_rows/256 x d/256 tiles: keep that at or above the number  */
                                 /* of compute units (256)                                          */
@@ -214,13 +211,12 @@ typedef struct {
   int32_t        grad_weight_accumulate; /* 0: overwrite grad_weight; 1: add to what it holds (a   */
                                 /* trainer accumulating micro-batches into an fp32 main gradient) */
   void*          workspace;     /* >= dppo_lmhead_workspace_bytes(...) bytes, 256-byte aligned:    */
-                                /* loss partial sums, the chunk of logits, W^T unless given        */
+                                /* loss partial sums and the chunk of logits                       */
   size_t         workspace_bytes;
 } dppo_lmhead_args_t;
 
-/* (want_grad_weight no longer changes the size: the weight gradient needs no buffer of its own.) */
-size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t,
-                                   int want_grad_weight);
+/* 64 KiB + min(chunk_rows, T) * V * 2 bytes (chunk_rows <= 0: the default). */
+size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t chunk_rows);
 
 /* Forward only (loss, loss_tok, divergence, mask, diagnostics). */
 dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream);
@@ -246,6 +242,14 @@ dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ld
  * path above sums its chunks this way.) */
 dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
                                int64_t M, int64_t N, int64_t K, int accumulate, void* stream);
+
+/* C[M, N] = A[M, K] * B[K, N]: A with the contraction index contiguous, B with the contraction
+ * index as the ROW index (a gradient with respect to the logits [T, V] times the lm_head weight
+ * [V, d] as it lies), bf16 in, fp32 accumulation, C bf16 rounded to nearest even.  K a multiple of
+ * 64; A and B 16-byte aligned with lda >= K, ldb >= N multiples of 8 and below 2^22; C 2-byte
+ * aligned, ldc >= N; buffers must not overlap.  Errors as for dppo_gemm_nt. */
+dppo_status_t dppo_gemm_nn(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                           int64_t M, int64_t N, int64_t K, void* stream);
 
 /* C[M, N] (+)= A[K, M]^T * B[K, N]: both bf16 operands row-major with the contraction index as
  * the ROW index (what the gradient of a weight is: logit gradients [T, V] transposed times

@@ -45,7 +45,6 @@ class DppoLmheadArgs(C.Structure):
         ("loss", DppoArgs),
         ("hidden", C.c_void_p), ("ld_hidden", C.c_int64), ("d", C.c_int64),
         ("weight", C.c_void_p), ("ld_weight", C.c_int64),
-        ("weight_t", C.c_void_p), ("ld_weight_t", C.c_int64),
         ("chunk_rows", C.c_int64),
         ("grad_hidden", C.c_void_p), ("ld_grad_hidden", C.c_int64),
         ("grad_weight", C.c_void_p), ("ld_grad_weight", C.c_int64), ("grad_weight_accumulate", C.c_int32),
@@ -87,11 +86,12 @@ def lib() -> C.CDLL:
         l.dppo_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.dppo_probe_mfma.restype = C.c_int
         l.dppo_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
-        l.dppo_gemm_nt.restype = C.c_int
-        l.dppo_gemm_nt.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                                   C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+        for f in (l.dppo_gemm_nt, l.dppo_gemm_nn):
+            f.restype = C.c_int
+            f.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                          C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
         l.dppo_lmhead_workspace_bytes.restype = C.c_size_t
-        l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int]
+        l.dppo_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
         for f in (l.dppo_gemm_nt_f32, l.dppo_gemm_tn_f32):
             f.restype = C.c_int
             f.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
@@ -231,6 +231,20 @@ def gemm_nt(a, b, c=None, stream=None):
     return c
 
 
+def gemm_nn(a, b, c=None, stream=None):
+    """dppo_gemm_nn: c[M, N] = a[M, K] @ b[K, N] for bf16 tensors with unit inner stride."""
+    M, K = a.shape
+    N = b.shape[1]
+    assert b.shape[0] == K and a.stride(1) == 1 and b.stride(1) == 1
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    st = lib().dppo_gemm_nn(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0),
+                            M, N, K, C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+    return c
+
+
 def gemm_nt_f32(a, b, c, accumulate: bool = False, stream=None):
     """dppo_gemm_nt_f32: c[M, N] (+)= a[M, K] @ b[N, K]^T, c fp32."""
     M, K = a.shape
@@ -285,12 +299,11 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     return res
 
 
-def lmhead_workspace_bytes(T: int, V: int, d: int, chunk_rows: int = 0, have_weight_t: bool = False,
-                           want_grad_weight: bool = False) -> int:
-    return lib().dppo_lmhead_workspace_bytes(T, V, d, chunk_rows, int(have_weight_t), int(want_grad_weight))
+def lmhead_workspace_bytes(T: int, V: int, chunk_rows: int = 0) -> int:
+    return lib().dppo_lmhead_workspace_bytes(T, V, chunk_rows)
 
 
-def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t=None, out=None, grad_hidden=None,
+def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, out=None, grad_hidden=None,
                workspace=None, stream=None, diagnostics: bool = False, grad_weight=None, accumulate: bool = False,
                **rule) -> dict:
     """Run one hidden-state batch (workloads.make_lmhead_batch) through dppo_lmhead_loss_fwd[_bwd].
@@ -303,7 +316,7 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t
     if backward and grad_hidden is None:
         grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
     if workspace is None:
-        workspace = torch.empty(lmhead_workspace_bytes(T, V, d, chunk_rows, weight_t is not None, grad_weight is not None),
+        workspace = torch.empty(lmhead_workspace_bytes(T, V, chunk_rows),
                                 dtype=torch.uint8, device=dev)
     a = DppoLmheadArgs()
     a.loss = make_args(torch.empty((0, V), dtype=torch.bfloat16, device=dev), batch["sampled_ids"], batch["mu_logp"],
@@ -312,7 +325,6 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, weight_t
     a.loss.T, a.loss.logits = T, None
     a.hidden, a.ld_hidden, a.d = h.data_ptr(), h.stride(0), d
     a.weight, a.ld_weight = w.data_ptr(), w.stride(0)
-    a.weight_t, a.ld_weight_t = _ptr(weight_t), (0 if weight_t is None else weight_t.stride(0))
     a.chunk_rows = chunk_rows
     a.grad_hidden, a.ld_grad_hidden = _ptr(grad_hidden if backward else None), (grad_hidden.stride(0) if backward else 0)
     a.grad_weight, a.ld_grad_weight = _ptr(grad_weight), (0 if grad_weight is None else grad_weight.stride(0))

@@ -161,14 +161,12 @@ int64_t lmhead_chunk_rows(const dppo_lmhead_args_t* a) {
 int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
 
 // [partial sums | chunk of logits | W^T unless given | g_c^T and h_c^T if the weight gradient is wanted]
-size_t lmhead_workspace(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, bool have_weight_t, bool want_grad_weight) {
+size_t lmhead_workspace(int64_t T, int64_t V, int64_t chunk_rows) {
   int64_t c = chunk_rows > 0 ? chunk_rows : kLmheadDefaultChunk;
   if (c > T) c = T;
   if (c < 1) c = 1;
   size_t b = DPPO_WORKSPACE_BYTES;
   b += static_cast<size_t>(c) * static_cast<size_t>(V) * 2;
-  if (!have_weight_t) b += static_cast<size_t>(d) * static_cast<size_t>(V) * 2;
-  (void)want_grad_weight;     // the weight gradient needs no buffer of its own
   return b;
 }
 
@@ -180,16 +178,15 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
     return DPPO_ERR_SHAPE;
   if (a->loss.variant == DPPO_FULL_TV || a->loss.variant == DPPO_FULL_KL) return DPPO_ERR_VARIANT;
   if (grad && (a->ld_grad_hidden < d)) return DPPO_ERR_SHAPE;
-  if (a->weight_t && (a->ld_weight_t < V || a->ld_weight_t % 8 != 0)) return DPPO_ERR_SHAPE;
   const int64_t chunk = lmhead_chunk_rows(a);
   const bool want_gw = grad && a->grad_weight != nullptr;
   if (want_gw && (a->ld_grad_weight < d || a->ld_grad_weight % 4 != 0)) return DPPO_ERR_SHAPE;
   if (want_gw && (reinterpret_cast<uintptr_t>(a->grad_weight) & 15u)) return DPPO_ERR_ALIGN;
-  if (!a->workspace || a->workspace_bytes < lmhead_workspace(T, V, d, a->chunk_rows, a->weight_t != nullptr, want_gw)) return DPPO_ERR_WORKSPACE;
+  if (!a->workspace || a->workspace_bytes < lmhead_workspace(T, V, a->chunk_rows)) return DPPO_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DPPO_ERR_ALIGN;
   if (T > 0) {
     if (!a->hidden || !a->weight || (grad && !a->grad_hidden)) return DPPO_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(a->hidden) | reinterpret_cast<uintptr_t>(a->weight) | reinterpret_cast<uintptr_t>(a->weight_t)) & 15u)
+    if ((reinterpret_cast<uintptr_t>(a->hidden) | reinterpret_cast<uintptr_t>(a->weight)) & 15u)
       return DPPO_ERR_ALIGN;
     if (grad && (reinterpret_cast<uintptr_t>(a->grad_hidden) & 1u)) return DPPO_ERR_ALIGN;
   }
@@ -197,8 +194,6 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
   char* ws = static_cast<char*>(a->workspace);
   double* partial = reinterpret_cast<double*>(ws);
   uint16_t* zbuf = reinterpret_cast<uint16_t*>(ws + DPPO_WORKSPACE_BYTES);
-  const uint16_t* wt = static_cast<const uint16_t*>(a->weight_t);
-  int64_t ldwt = a->ld_weight_t;
 
   // validate the loss arguments on the first chunk's view before anything is launched
   dppo_args_t c = a->loss;
@@ -210,17 +205,6 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
   const dppo_status_t st0 = check_args(&c, grad);
   if (st0 != DPPO_OK) return st0;
 
-  uint16_t* next_free = zbuf + static_cast<size_t>(chunk) * static_cast<size_t>(V);
-  if (!a->weight_t) {
-    if (grad && T > 0) {
-      if (dppo::launch_transpose(static_cast<const uint16_t*>(a->weight), a->ld_weight, next_free, V, static_cast<int>(V), static_cast<int>(d),
-                                 static_cast<int>(V), s) != hipSuccess)
-        return DPPO_ERR_LAUNCH;
-      wt = next_free;
-      ldwt = V;
-    }
-    next_free += static_cast<size_t>(d) * static_cast<size_t>(V);
-  }
   const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
   const int64_t nchunks = T > 0 ? (T + chunk - 1) / chunk : 0;
   const int parts_per_chunk = nchunks > 0 ? static_cast<int>(max_parts / nchunks) : max_parts;
@@ -248,10 +232,10 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
     if (st != DPPO_OK) return st;
     used += np;
     if (grad) {
-      // gradient of the chunk's hidden states: g [rows, V] times W [V, d] = g times (W^T)^T
+      // gradient of the chunk's hidden states: g [rows, V] times W [V, d], the weight as it lies
       uint16_t* gh = static_cast<uint16_t*>(a->grad_hidden) + r0 * a->ld_grad_hidden;
-      if (dppo::launch_gemm_nt(zbuf, V, wt, ldwt, gh, a->ld_grad_hidden, static_cast<int>(rows), static_cast<int>(d),
-                               static_cast<int>(V), 0, s) != hipSuccess)
+      if (dppo::launch_gemm_nn(zbuf, V, static_cast<const uint16_t*>(a->weight), a->ld_weight, gh, a->ld_grad_hidden, static_cast<int>(rows),
+                               static_cast<int>(d), static_cast<int>(V), s) != hipSuccess)
         return DPPO_ERR_LAUNCH;
     }
     if (want_gw) {
@@ -300,8 +284,8 @@ size_t dppo_args_size(void) { return sizeof(dppo_args_t); }
 
 const char* dppo_last_path(void) { return g_last_path; }
 
-size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d, int64_t chunk_rows, int have_weight_t, int want_grad_weight) {
-  return lmhead_workspace(T, V, d, chunk_rows, have_weight_t != 0, want_grad_weight != 0);
+size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t chunk_rows) {
+  return lmhead_workspace(T, V, chunk_rows);
 }
 
 dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream) { return run_lmhead(args, stream, false); }
@@ -334,6 +318,19 @@ dppo_status_t dppo_gemm_nt_f32(const void* A, int64_t lda, const void* B, int64_
   const hipError_t e = dppo::launch_gemm_nt(static_cast<const uint16_t*>(A), lda, static_cast<const uint16_t*>(B), ldb,
                                             C, ldc, static_cast<int>(M), static_cast<int>(N), static_cast<int>(K),
                                             accumulate ? 2 : 1, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
+
+dppo_status_t dppo_gemm_nn(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                           int64_t M, int64_t N, int64_t K, void* stream) {
+  if (M < 0 || N < 0 || K < 64 || K % 64 != 0 || M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
+  if (lda < K || ldb < N || ldc < N || lda % 8 != 0 || ldb % 8 != 0 || lda >= (int64_t(1) << 22) || ldb >= (int64_t(1) << 22)) return DPPO_ERR_SHAPE;
+  if (M == 0 || N == 0) return DPPO_OK;
+  if (!A || !B || !C) return DPPO_ERR_NULL;
+  if (((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) || (reinterpret_cast<uintptr_t>(C) & 1u)) return DPPO_ERR_ALIGN;
+  const hipError_t e = dppo::launch_gemm_nn(static_cast<const uint16_t*>(A), lda, static_cast<const uint16_t*>(B), ldb,
+                                            C, ldc, static_cast<int>(M), static_cast<int>(N), static_cast<int>(K),
+                                            static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
 }
 

@@ -53,18 +53,19 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
 // OUT selects what leaves the tile: bf16 (rounded to nearest even), fp32, or fp32 added to what C holds.
 enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
 
-// TN: A is [K, M] and B is [K, N] (the contraction index is the ROW index; C = A^T B).  The panels
-// of a step are then 64 rows of 512 bytes, and the fragment reads use the LDS transpose read
+// TA: A is [K, M]; TB: B is [K, N] (the contraction index is the ROW index of that operand; with
+// both, C = A^T B; with TB alone, C = A B).  The panel of such an operand
+// is then 64 rows of 512 bytes per step, and its fragment reads use the LDS transpose read
 // (ds_read_b64_tr_b16: out of a 16-lane group's sixteen 8-byte blocks, lane i gets element i%4 of
 // the blocks i/4, i/4 + 4, i/4 + 8, i/4 + 12), which turns four k rows of four neighbouring m
 // into the four consecutive k of one m that a matrix-core operand wants.
-template <bool FULL, int OUT, bool TN>
+template <bool FULL, int OUT, bool TA, bool TB>
 __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* lds1, const uint16_t* __restrict__ A, int64_t lda,
                                           const uint16_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv, int64_t ldc,
                                           int M, int N, int K, int m0, int n0) {
   const int tid = threadIdx.x, lane = tid & 63, wid = uniform_i(tid >> 6);
   const int wm = wid >> 1, wn = wid & 1;
-  const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);     // (TN: columns of A and of B)
+  const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);     // (TA / TB: columns of A / of B)
   const uint32_t pitch_a = static_cast<uint32_t>(lda) * 2u, pitch_b = static_cast<uint32_t>(ldb) * 2u;
 
   // Loader role: thread t moves LDS vector slot (t % 8) of rows t/8 + 32 i, i = 0..7, of each panel;
@@ -95,7 +96,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // over all banks.  Lane (kg, j, q = lane % 4) reads the 8 bytes of columns 4 q .. 4 q + 3 of block t
   // in row 8 kg + j (+ 4 for the second half of the fragment, + 32 for the second sub-step).
   uint32_t toff_a[8], toff_b[8];
-  if (TN) {
+  if (TA || TB) {
     const int kg = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
     const uint32_t g2 = static_cast<uint32_t>(2 * (j | ((kg & 1) << 2)));
     const uint32_t rowoff = static_cast<uint32_t>(8 * kg + j) * 512u + static_cast<uint32_t>(q & 1) * 8u;
@@ -109,7 +110,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
   // fragment t of a sub-step: 0..7 the B blocks, 8..15 the A blocks
   auto read_frag = [&](const unsigned char* stage, int ks, int t) -> bf16x8 {
-    if (TN) {
+    if (t < 8 ? TB : TA) {
       const unsigned char* p = stage + (t < 8 ? toff_b[t & 7] : toff_a[t & 7]) + ks * (32 * 512);
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 512));
@@ -125,7 +126,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // has read its last fragments of that stage (the barrier in the middle of the step) the panels
   // of step kt+2 are loaded into it.  The fragments of each 32-wide sub-step are read from LDS one
   // sub-step ahead of the matrix-core instructions that consume them.  One barrier per step.
-  const int nk = TN ? (K + kBK - 1) / kBK : K / kBK;     // TN: rows past K read as zeros (range check)
+  const int nk = (TA && TB) ? (K + kBK - 1) / kBK : K / kBK;     // both by rows: rows past K read as zeros (range check)
   // Global memory -> LDS directly (buffer_load ... lds): lane l of a wave-level load deposits its
   // 16 bytes at (LDS base of the instruction) + 16 l, which is exactly the loader layout above for
   // the base stage + panel + i * 4096 + wave * 1024.  No staging registers, no LDS store
@@ -136,43 +137,32 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // base of that view (scalar arithmetic), so the per-lane offsets never change.
   uint32_t vo_a[8], vo_b[8];
   uint32_t bytes_a, bytes_b;
-  if (TN) {
-    // load i of a panel (one KiB: two LDS rows) moves k rows 8 i + 2 wave + lane / 32, LDS slot lane % 32
+  // by rows: load i of a panel (one KiB: two LDS rows) moves k rows 8 i + 2 wave + lane / 32, LDS slot lane % 32
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int k = 8 * i + 2 * wid + (lane >> 5);
-      const uint32_t gs = static_cast<uint32_t>(lane & 31) ^ static_cast<uint32_t>(2 * ((k & 3) | (((k >> 3) & 1) << 2)));
-      vo_a[i] = static_cast<uint32_t>(k) * pitch_a + (gs << 4);
-      vo_b[i] = static_cast<uint32_t>(k) * pitch_b + (gs << 4);
-    }
-    bytes_a = static_cast<uint32_t>(M - m0) * 2u;     // bytes of a row from the tile's first column on
-    bytes_b = static_cast<uint32_t>(N - n0) * 2u;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      vo_a[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_a - 1)) * pitch_a + lkv;
-      vo_b[i] = static_cast<uint32_t>(min(lrow + 32 * i, rows_b - 1)) * pitch_b + lkv;
-    }
-    bytes_a = static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u;
-    bytes_b = static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u;
+  for (int i = 0; i < 8; ++i) {
+    const int k = 8 * i + 2 * wid + (lane >> 5);
+    const uint32_t gs = static_cast<uint32_t>(lane & 31) ^ static_cast<uint32_t>(2 * ((k & 3) | (((k >> 3) & 1) << 2)));
+    vo_a[i] = TA ? static_cast<uint32_t>(k) * pitch_a + (gs << 4) : static_cast<uint32_t>(min(lrow + 32 * i, rows_a - 1)) * pitch_a + lkv;
+    vo_b[i] = TB ? static_cast<uint32_t>(k) * pitch_b + (gs << 4) : static_cast<uint32_t>(min(lrow + 32 * i, rows_b - 1)) * pitch_b + lkv;
   }
+  // by rows: bytes of a row from the tile's first column on, in whole 16-byte vectors (the range
+  // check works per 4 bytes, and the pitch, a multiple of 8 entries, covers them); else: bytes of the tile's rows
+  bytes_a = TA ? ((static_cast<uint32_t>(M - m0) * 2u + 15u) & ~15u) : static_cast<uint32_t>(rows_a - 1) * pitch_a + static_cast<uint32_t>(K) * 2u;
+  bytes_b = TB ? ((static_cast<uint32_t>(N - n0) * 2u + 15u) & ~15u) : static_cast<uint32_t>(rows_b - 1) * pitch_b + static_cast<uint32_t>(K) * 2u;
   auto dma_one = [&](unsigned char* stage, int step, int idx) {     // load idx of the 16 of a step: 0..7 A panel, 8..15 B panel
     const bool b_panel = idx >= 8;
     const int i = idx & 7;
     unsigned char* dst = stage + (b_panel ? kPanelBytes : 0) + wid * 1024 + i * 4096;
     row_rsrc_t r;
-    if (TN) {
-      // view of the step's k rows (those that exist) from the tile's first column on: what lies past
-      // the last row's end reads as zero, what lies past a row's M (N) columns belongs to C rows
-      // (columns) that are never stored
-      const int kr = min(kBK, K - step * kBK);
-      r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(step) * kBK * ldb + n0, static_cast<uint32_t>(kr - 1) * pitch_b + bytes_b)
-                  : make_row_rsrc(A + static_cast<int64_t>(step) * kBK * lda + m0, static_cast<uint32_t>(kr - 1) * pitch_a + bytes_a);
-    } else {
-      const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
-      r = b_panel ? make_row_rsrc(B + static_cast<int64_t>(n0) * ldb + step * kBK, bytes_b - koff)
-                  : make_row_rsrc(A + static_cast<int64_t>(m0) * lda + step * kBK, bytes_a - koff);
-    }
+    // By rows: view of the step's k rows (those that exist) from the tile's first column on: what
+    // lies past the last row's end reads as zero, what lies past a row's M (N) columns belongs to
+    // C rows (columns) that are never stored.  Else: the tile's rows, from the step's k on.
+    const int kr = min(kBK, K - step * kBK);
+    const uint32_t koff = static_cast<uint32_t>(step) * (kBK * 2);
+    if (b_panel) r = TB ? make_row_rsrc(B + static_cast<int64_t>(step) * kBK * ldb + n0, static_cast<uint32_t>(kr - 1) * pitch_b + bytes_b)
+                        : make_row_rsrc(B + static_cast<int64_t>(n0) * ldb + step * kBK, bytes_b - koff);
+    else         r = TA ? make_row_rsrc(A + static_cast<int64_t>(step) * kBK * lda + m0, static_cast<uint32_t>(kr - 1) * pitch_a + bytes_a)
+                        : make_row_rsrc(A + static_cast<int64_t>(m0) * lda + step * kBK, bytes_a - koff);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, b_panel ? vo_b[i] : vo_a[i], 0, 0, 0);
   };
 #pragma unroll
@@ -285,7 +275,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
 // outside the matrix exit at once.
 constexpr int kGroupM = 8, kGroupN = 4;
 
-template <int OUT, bool TN>
+template <int OUT, bool TA, bool TB>
 __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                            const uint16_t* __restrict__ B, int64_t ldb,
                                                            void* __restrict__ C, int64_t ldc, int M, int N, int K,
@@ -299,51 +289,11 @@ __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __res
   const int tm = bm * kGroupM + (within % kGroupM), tn = bn * kGroupN + (within / kGroupM);
   if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * kBM, n0 = tn * kBN;
-  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT, TN>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
-  else                                gemm_tile<false, OUT, TN>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
-}
-
-// dst[c, r] = src[r, c] for 2-byte elements, 64 x 64 tiles through LDS, 16-byte accesses (8 elements
-// per lane) on both sides; the LDS rows are 66 elements long, which spreads the transposed 2-byte
-// reads over the banks.  Columns R .. R_pad-1 of dst are written as zeros.  Needs Cn, R_pad, both
-// pitches multiples of 8 and 16-byte aligned bases (checked by the launcher).
-__global__ __launch_bounds__(256) void dppo_transpose_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
-                                                             uint16_t* __restrict__ dst, int64_t ld_dst, int R, int Cn, int R_pad) {
-  __shared__ __attribute__((aligned(4))) uint16_t tile[64][66];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int sub = threadIdx.x & 7, line = threadIdx.x >> 3;      // 8 lanes x 16 bytes per 64-element line
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = r0 + line + 32 * i, c = c0 + sub * 8;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (r < R && c < Cn) v = *reinterpret_cast<const u32x4*>(src + static_cast<int64_t>(r) * ld_src + c);   // Cn % 8 == 0: all 8 in range
-    uint32_t* t = reinterpret_cast<uint32_t*>(&tile[line + 32 * i][sub * 8]);
-    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int cl = line + 32 * i, c = c0 + cl, r = r0 + sub * 8;
-    uint32_t w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = static_cast<uint32_t>(tile[sub * 8 + 2 * k][cl]) | (static_cast<uint32_t>(tile[sub * 8 + 2 * k + 1][cl]) << 16);
-    if (c < Cn && r < R_pad) {                                   // R_pad % 8 == 0: all 8 in range
-      const u32x4 v = {w[0], w[1], w[2], w[3]};
-      *reinterpret_cast<u32x4*>(dst + static_cast<int64_t>(c) * ld_dst + r) = v;
-    }
-  }
+  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  else                                gemm_tile<false, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
 }
 
 }  // namespace
-
-hipError_t launch_transpose(const uint16_t* src, int64_t ld_src, uint16_t* dst, int64_t ld_dst, int R, int Cn, int R_pad, hipStream_t s) {
-  if (R_pad < R) R_pad = R;
-  if (R_pad <= 0 || Cn <= 0) return hipSuccess;
-  if ((Cn % 8) || (R_pad % 8) || (ld_src % 8) || (ld_dst % 8) || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u))
-    return hipErrorInvalidValue;
-  hipLaunchKernelGGL(dppo_transpose_kernel, dim3((Cn + 63) / 64, (R_pad + 63) / 64), dim3(256), 0, s, src, ld_src, dst, ld_dst, R, Cn, R_pad);
-  return hipGetLastError();
-}
 
 hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
                           int M, int N, int K, int out, hipStream_t s) {
@@ -352,9 +302,9 @@ hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  if (out == 0)      hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else               hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  if (out == 0)      hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else               hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
   return hipGetLastError();
 }
 
@@ -366,8 +316,20 @@ hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else          hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  else          hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  return hipGetLastError();
+}
+
+// C[M, N] bf16 = A B with A [M, K] (contraction index contiguous) and B [K, N] (contraction index the row index); K % 64 == 0
+hipError_t launch_gemm_nn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
+  const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
+  const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
+  const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
+  hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
   return hipGetLastError();
 }
 

@@ -20,18 +20,17 @@ int resident_blocks_per_cu(bool grad, int threads, int chunks);
 // Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
 hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);
 
-// C[M, N] = A[M, K] * B[N, K]^T on the matrix cores, bf16 in, fp32 accumulation.  out = 0: C bf16;
-// 1: C fp32; 2: C fp32, the product added to what it holds (the fp32 forms need 16-byte aligned
-// rows of C).  Needs K % 64 == 0, 16-byte aligned A and B with lda, ldb multiples of 8, and
-// 256 * ld * 2 < 2^32.
+// bf16 matrix products on the matrix cores (fp32 accumulation).  A, B 16-byte aligned with lda, ldb
+// multiples of 8 and 256 * ld * 2 < 2^32; the fp32 forms need 16-byte aligned rows of C.
+// C[M, N] = A B^T, A [M, K], B [N, K]; K % 64 == 0; out 0: C bf16; 1: C fp32; 2: C fp32, added to what it holds
+hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, int out, hipStream_t s);
+// C[M, N] bf16 = A B, A [M, K], B [K, N]; K % 64 == 0
+hipError_t launch_gemm_nn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
+                          int M, int N, int K, hipStream_t s);
 // C[M, N] fp32 (out 1: written, 2: added to) = A^T B, A [K, M], B [K, N]; any K >= 1
 hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
                           int M, int N, int K, int out, hipStream_t s);
-hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
-                          int M, int N, int K, int out, hipStream_t s);
-
-// dst[c, r] = src[r, c] for an R x Cn matrix of 2-byte elements; columns R .. R_pad-1 of dst are zeroed.
-hipError_t launch_transpose(const uint16_t* src, int64_t ld_src, uint16_t* dst, int64_t ld_dst, int R, int Cn, int R_pad, hipStream_t s);
 
 // loss[0] = loss_scale * sum(partial[0..n)) in a fixed order.
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s);

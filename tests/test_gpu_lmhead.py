@@ -65,7 +65,7 @@ def _check_grad_weight(b, res, ref, M):
     return float(err.max())
 
 
-def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0, rows=None, rule=None, weight_t=None):
+def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0, rows=None, rule=None):
     _say(f"[case] lmhead {w.name} T={w.T} V={w.V} d={d} K={w.K} variant={w.variant} exact={exact} chunk={chunk_rows} shift={shift} rule={rule}")
     b = W.make_lmhead_batch(w, d, DEV, exact=exact, shift_sampled=shift)
     rule = rule or {}
@@ -73,7 +73,7 @@ def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0
     all_rows = rows is None
     rows = np.arange(b["T"]) if rows is None else rows
     gw = torch.full((b["V"], d + 4), 7.0, dtype=torch.float32, device=DEV)[:, :d] if (backward and all_rows) else None
-    res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, weight_t=weight_t, grad_weight=gw, **rule)
+    res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, grad_weight=gw, **rule)
     torch.cuda.synchronize()
     ref = _oracle(b, rows, **rule)
     cmp_batch = dict(b, logits=None)
@@ -107,6 +107,24 @@ def test_gemm_exact_inputs_bitwise(M, N, K, lda, ldb, ldc):
     assert (c[:, N:] == 123.0).all()
 
 
+@pytest.mark.parametrize("M,N,K,lda,ldb,ldc", [
+    (256, 256, 64, 64, 256, 256), (1, 1, 64, 64, 8, 1), (300, 520, 128, 136, 520, 528), (1000, 777, 192, 192, 784, 777),
+    (257, 4160, 4096, 4096, 4160, 4160), (513, 64, 8192, 8192, 64, 64)])
+def test_gemm_nn_exact_inputs_bitwise(M, N, K, lda, ldb, ldc):
+    """C = A B with B stored with the contraction index as its row index (a weight [V, d] as it lies)."""
+    _say(f"[case] gemm nn M={M} N={N} K={K}")
+    g = torch.Generator(device=DEV); g.manual_seed(M * 5 + N)
+    a = torch.full((M, lda), 7.0, dtype=torch.bfloat16, device=DEV); b = torch.full((K, ldb), -5.0, dtype=torch.bfloat16, device=DEV)
+    a[:, :K] = (torch.randint(-8, 9, (M, K), generator=g, device=DEV).float() / 64).bfloat16()
+    b[:, :N] = (torch.randint(-8, 9, (K, N), generator=g, device=DEV).float() / 8).bfloat16()
+    c = torch.full((M, ldc), 123.0, dtype=torch.bfloat16, device=DEV)
+    B.gemm_nn(a[:, :K], b[:, :N], c[:, :N])
+    torch.cuda.synchronize()
+    ref = O.bf16_round(a[:, :K].double().cpu().numpy() @ b[:, :N].double().cpu().numpy())
+    np.testing.assert_array_equal(c[:, :N].double().cpu().numpy(), ref)
+    assert (c[:, N:] == 123.0).all()
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (1000, 260, 192), (4160, 128, 320)])
 def test_gemm_fp32_result_exact_inputs_bitwise_and_accumulation(M, N, K):
     _say(f"[case] gemm fp32 M={M} N={N} K={K}")
@@ -126,7 +144,8 @@ def test_gemm_fp32_result_exact_inputs_bitwise_and_accumulation(M, N, K):
 
 @pytest.mark.parametrize("M,N,K,lda,ldb,ldc", [
     (256, 256, 64, 256, 256, 256), (8, 8, 1, 8, 8, 8), (300, 520, 100, 304, 520, 520), (1000, 776, 193, 1008, 784, 780),
-    (4160, 128, 321, 4160, 128, 128), (130, 4100, 4096, 136, 4104, 4100), (151936, 64, 130, 151936, 64, 64)])
+    (4160, 128, 321, 4160, 128, 128), (130, 4100, 4096, 136, 4104, 4100), (151936, 64, 130, 151936, 64, 64),
+    (777, 261, 129, 784, 264, 264)])
 def test_gemm_tn_exact_inputs_bitwise_and_accumulation(M, N, K, lda, ldb, ldc):
     """C = A^T B with both operands stored with the contraction index as the row index (the form of
     the weight gradient), any K, ragged M and N, pitches of their own, then once more accumulating."""
@@ -215,7 +234,7 @@ def test_shapes_resident_loss_kernel_inside_and_tiny(V, d, chunk):
     _run_and_compare(w, d, chunk_rows=chunk, shift=2.0, backward=False)
 
 
-def test_ignored_rows_baseline_rule_and_given_transpose():
+def test_ignored_rows_and_baseline_rule_run_to_run():
     w = W.Workload("lm_rule", 2, 130, 4096, W.BINARY_TV, 0.1, logit_std=3.0, noise_std=1.0, adv="normal", seed=79)
     b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
     b["sampled_ids"][::9] = -1
@@ -224,10 +243,9 @@ def test_ignored_rows_baseline_rule_and_given_transpose():
     b["rule"] = rule
     rows = np.arange(b["T"])
     ref = _oracle(b, rows, **rule)
-    wt = b["weight"].T.contiguous()
     outs = []
-    for weight_t in (None, wt):
-        res = B.run_lmhead(b, chunk_rows=64, diagnostics=True, weight_t=weight_t, **rule)
+    for _ in range(2):                          # twice: the path is bitwise reproducible run to run
+        res = B.run_lmhead(b, chunk_rows=64, diagnostics=True, **rule)
         torch.cuda.synchronize()
         st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
         _check_grad_hidden(b, res, rows, ref)
@@ -308,7 +326,7 @@ def test_hidden_state_path_can_be_captured_in_a_hip_graph_and_replayed():
     out = B.alloc_outputs(T, DEV, want_diagnostics=True)
     gh = torch.empty((T, d), dtype=torch.bfloat16, device=DEV)
     gw = torch.empty((V, d), dtype=torch.float32, device=DEV)
-    ws = torch.empty(B.lmhead_workspace_bytes(T, V, d, 128, False, True), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.lmhead_workspace_bytes(T, V, 128), dtype=torch.uint8, device=DEV)
     side = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
