@@ -313,7 +313,7 @@ def test_weight_gradient_accumulates_onto_the_callers_buffer():
 
 
 def test_hidden_state_path_can_be_captured_in_a_hip_graph_and_replayed():
-    """The chunk loop (products, loss in place, transpositions, accumulation) allocates nothing and never
+    """The chunk loop (products, loss in place, accumulation) allocates nothing and never
     synchronises: with the workspace and every output preallocated one call is a capturable chain of
     kernels.  Replayed three times with eager work in between, every replay bit for bit the eager result."""
     w = W.Workload("lm_graph", 3, 100, 4096, W.BINARY_TV, 0.1, logit_std=3.0, noise_std=1.0, adv="normal", seed=103)
