@@ -2,7 +2,7 @@
 """Benchmark of the DPPO loss hot path (forward + backward over the full vocabulary) on ONE
 MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--in-place]
 
 A step is one pass of the whole path (log-softmax statistics, gathers, divergence, mask,
 loss, gradient over all V logits) over one synthetic batch that is already resident in HBM.
@@ -183,6 +183,7 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits (the boundary allows it); the logits are restored, untimed, before every step")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
     ap.add_argument("--ld", type=int, default=0, help="row pitch of logits / gradient in elements (0: V)")
     ap.add_argument("--forward-only", action="store_true", help="time dppo_loss_fwd (no gradient) instead of forward+backward")
@@ -212,7 +213,9 @@ def main() -> int:
 
     # caller-side buffers, allocated once: gradient (separate from the logits so that every
     # step sees the same input), per-token outputs, one loss scalar per T-chunk
-    grad = torch.empty_like(batch["logits"])
+    in_place = args.in_place and not args.forward_only
+    pristine = batch["logits"].clone() if in_place else None
+    grad = batch["logits"] if in_place else torch.empty_like(batch["logits"])
     out = B.alloc_outputs(T, dev)
     calls = []
     for c0 in range(0, T, chunk):
@@ -238,23 +241,39 @@ def main() -> int:
         for a, _ in calls:
             run(a, stream)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record(stream)
-    for _ in range(args.steps):
-        step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    if in_place:
+        # every step overwrites its input, so the logits are restored before each one (untimed)
+        # and each step is timed by an event pair of its own
+        def timed(n):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for e0, e1 in evs:
+                batch["logits"].copy_(pristine)
+                e0.record(stream)
+                step()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            return sum(e0.elapsed_time(e1) for e0, e1 in evs) / max(n, 1)
+        timed(args.warmup)
+        ms_per_step = timed(args.steps)
+        batch["logits"].copy_(pristine)
+    else:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(args.steps):
+            step()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms_per_step = ev0.elapsed_time(ev1) / args.steps
     path = B.last_path()
 
     # the device's streaming ceilings on THESE buffers (the rate depends on the footprint), measured
     # with the library's plain copy kernels (grid-stride, and one workgroup per row like the loss
     # kernels) and its read kernel
     ceilings = {}
-    src2d, dst2d = batch["logits"], grad
+    src2d, dst2d = (pristine if in_place else batch["logits"]), grad
     nbytes = src2d.numel() * 2
     if nbytes % 16 == 0 and nbytes >= (1 << 30):
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -287,9 +306,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
-                   "kernel_path": path, "grad": "none (forward only)" if args.forward_only else "separate buffer"},
+                   "kernel_path": path, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.forward_only else stored_traffic(args.workload, path),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
                      "kernel_ms": kernel_ms, "device_ceilings": ceilings,
                      "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},

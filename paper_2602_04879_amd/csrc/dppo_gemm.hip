@@ -7,8 +7,8 @@
 // 128 x 128 quadrant as 8 x 8 products of v_mfma_f32_16x16x32_bf16 (256 fp32 accumulators per
 // lane, the whole accumulation register file).  That shape is chosen for power: with every
 // compute unit busy the clock is set by the power limit, and a loop of nothing but 16x16x32
-// products sustains about 14 % more than one of 32x32x16 products (measured, 2.17 against
-// 1.90 PFLOP/s).  The contraction runs in steps of 64: the A and B panels of a step (256 x 64
+// products sustains about 13 % more than one of 32x32x16 products (measured, 2.2-2.3 against
+// 1.9-2.0 PFLOP/s).  The contraction runs in steps of 64: the A and B panels of a step (256 x 64
 // each, 32 KiB) are loaded from global memory straight into one of two LDS stages, 16 bytes per
 // lane, in a layout swizzled so that the fragment reads (one 16-byte read per lane: 8 consecutive
 // k of one row) spread over all banks.
@@ -213,7 +213,10 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   }
   if (kt < nk) step(lds0, lds1, kt, std::false_type{});
   // the matrix-core results must have landed before other instructions read the accumulators
+  // (the products are assembly statements, so the compiler does not keep that distance by itself;
+  // the scheduling barrier keeps the accumulator reads of the store behind the wait)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  DPPO_PIN;
 
   // Store.  The products were formed with the operands swapped (B fragment first), so a lane's
   // four accumulators of a 16 x 16 block are four consecutive COLUMNS (lane/16)*4 + 0..3 of row
