@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c3_qwen3_binary_tv"
 DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_streaming_kernel",
-                   "fullvocab": "dppo_fullvocab_kernel"}
+                   "fullvocab": "dppo_fullvocab_kernel", "fullvocab_resident": "dppo_fullvocab_resident_kernel"}
 
 
 def kernel_source_hash(path: str) -> str:

@@ -97,8 +97,8 @@ typedef enum {
 } dppo_status_t;
 
 /* flags */
-#define DPPO_FLAG_FORCE_STREAMING 1u /* use the general two-pass kernel even where the
-                                        register-resident one applies (testing / comparison)  */
+#define DPPO_FLAG_FORCE_STREAMING 1u /* use the general kernels even where a register-resident
+                                        one applies (testing / comparison)                     */
 
 typedef struct {
   /* ---- inputs ---- */
@@ -176,8 +176,10 @@ int dppo_version(void);
 size_t dppo_args_size(void);
 
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
- * "resident" (row held in registers between the two passes), "streaming" (row re-read) or
- * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants); "lmhead" after a dppo_lmhead_* call. */
+ * "resident" (row held in registers between the two passes), "streaming" (row re-read),
+ * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
+ * backward on long aligned rows: the trainer's row held in registers, the rollout row streamed
+ * past it); "lmhead" after a dppo_lmhead_* call. */
 const char* dppo_last_path(void);
 
 /* ---- the same loss from the hidden states: the [T, V] logits never exist in full -------------

@@ -100,7 +100,16 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
     int r_threads = 0, r_chunks = 0;
     const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);
-    if (full) {
+    const int fr_chunks = (full && grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING)) ? dppo::fullvocab_resident_chunks(p) : 0;
+    if (fr_chunks) {
+      // long aligned rows, backward: the trainer's row stays in registers, one workgroup per compute unit
+      int64_t grid = cus;
+      if (grid > a->T) grid = a->T;
+      if (grid > max_parts) grid = max_parts;
+      nparts = static_cast<int>(grid);
+      if (dppo::launch_fullvocab_resident(p, a->variant == DPPO_FULL_TV, fr_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      g_last_path = "fullvocab_resident";
+    } else if (full) {
       // Two rows per workgroup in flight: one workgroup of 1024 threads per compute unit keeps the
       // rows that pass 2 and 3 re-read within reach of the caches.
       const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
@@ -158,9 +167,7 @@ int64_t lmhead_chunk_rows(const dppo_lmhead_args_t* a) {
   return c < 1 ? 1 : c;
 }
 
-int64_t round_up64(int64_t x) { return (x + 63) / 64 * 64; }
-
-// [partial sums | chunk of logits | W^T unless given | g_c^T and h_c^T if the weight gradient is wanted]
+// [partial sums | one chunk of logits, which becomes the chunk's logit gradient in place]
 size_t lmhead_workspace(int64_t T, int64_t V, int64_t chunk_rows) {
   int64_t c = chunk_rows > 0 ? chunk_rows : kLmheadDefaultChunk;
   if (c > T) c = T;

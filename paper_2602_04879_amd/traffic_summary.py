@@ -45,7 +45,7 @@ def counter_avg(directory: str, kernel_substr: str, counter: str) -> float:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--path", required=True, choices=["resident", "streaming", "fullvocab"])
+    ap.add_argument("--path", required=True, choices=["resident", "streaming", "fullvocab", "fullvocab_resident"])
     ap.add_argument("--probe-fetch", required=True)
     ap.add_argument("--probe-write", required=True)
     ap.add_argument("--fetch", required=True)

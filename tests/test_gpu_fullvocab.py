@@ -158,7 +158,7 @@ def test_full_size_sampled_rows(name):
     grad = torch.empty_like(b["logits"])
     res = B.run_batch(b, grad=grad, diagnostics=True)
     torch.cuda.synchronize()
-    assert B.last_path() == "fullvocab"
+    assert B.last_path() == "fullvocab_resident"
     mask = res["mask"].cpu().numpy()
     adv = b["advantages"].cpu().numpy()
     rng = np.random.default_rng(5)
@@ -171,3 +171,75 @@ def test_full_size_sampled_rows(name):
     P.check_loss_scalar(b, res)
     assert 0 < (mask == 0).sum() < b["T"] // 10
     _say(f"       masked={(mask == 0).sum()} {st}")
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+@pytest.mark.parametrize("V,ld", [(98312, 98312), (128256, 128264), (131072, 131072), (131080, 131080), (150008, 150016),
+                                  (155648, 155648)])
+def test_resident_form_against_the_oracle_and_the_general_kernel(variant, delta, V, ld):
+    """Backward on long aligned rows: the trainer's row is held in registers (both chunk counts, the
+    shortest and the longest row of each, rows that end inside a chunk, a pitch with a poisoned pad),
+    with ignored, zero-advantage and identical rows, separate and in place, with and without the
+    diagnostics; and the general kernel on the same input gives the same masks and divergences."""
+    w = W.Workload("fv_resident", 3, 7, V, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.7, zipf_s=1.1,
+                   adv="normal", seed=71)
+    b = W.make_batch(w, DEV, shift_sampled=1.0, ld=ld)
+    b["mu_logits"][:3, :V] = b["logits"][:3, :V]             # identical policies
+    b["sampled_ids"][5] = -1
+    b["sampled_ids"][6] = V - 1                              # the sampled token in the row's last vector
+    b["advantages"][8] = 0.0
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    _say(f"[case] resident full-vocabulary form V={V} ld={ld} variant={variant}")
+    res = B.run_batch(b, diagnostics=True, grad=torch.full_like(b["logits"], 77.0))
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab_resident"
+    st = P.compare_rows(b, res, rows, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    assert st["masked"] > 0
+    assert (res["grad_logits"][:, V:] == 77.0).all()         # the pad between rows is the caller's
+    gen = B.run_batch(b, diagnostics=True, flags=B.FLAG_FORCE_STREAMING)
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab"
+    assert torch.equal(gen["mask"], res["mask"])
+    assert (gen["divergence"] - res["divergence"]).abs().max().item() <= 2e-6
+    plain = B.run_batch(b)                                   # no diagnostics: the other instantiation
+    torch.cuda.synchronize()
+    assert torch.equal(plain["mask"], res["mask"]) and torch.equal(plain["divergence"], res["divergence"])
+    assert torch.equal(plain["grad_logits"][:, :V], res["grad_logits"][:, :V])
+    keep = res["grad_logits"][:, :V].clone()
+    inp = B.run_batch(b, in_place=True)
+    torch.cuda.synchronize()
+    assert torch.equal(inp["grad_logits"][:, :V], keep)
+    _say(f"       {st}")
+
+
+def test_resident_form_more_rows_than_workgroups_and_fallbacks():
+    """Several rows per persistent workgroup, sampled rows against the oracle; a rollout matrix that
+    starts 2 bytes off, a forward-only call and a short row stay with the general kernel."""
+    w = W.Workload("fv_many", 20, 30, 98816, W.FULL_KL, 0.05, mu_full=True, logit_std=3.0, noise_std=0.7, zipf_s=1.1,
+                   adv="normal", seed=73)
+    b = W.make_batch(w, DEV, shift_sampled=1.0)
+    b["sampled_ids"][::11] = -1
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab_resident"
+    rows = np.array(sorted(set([0, 1, 255, 256, 257, 511, 512, b["T"] - 1] + np.random.default_rng(3).integers(0, b["T"], 12).tolist())))
+    st = P.compare_rows(b, res, rows)
+    P.check_loss_scalar(b, res)
+    _say(f"       {st}")
+    B.run_batch(b, backward=False)
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab"
+    T, V = b["T"], b["V"]
+    store = torch.zeros(T * V + 8, dtype=torch.bfloat16, device=DEV)
+    mu2 = store[1:1 + T * V].view(T, V)
+    mu2.copy_(b["mu_logits"])
+    off = B.run_batch(dict(b, mu_logits=mu2))
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab"
+    assert torch.equal(off["mask"], res["mask"]) and (off["divergence"] - res["divergence"]).abs().max().item() <= 2e-6
+    short = W.Workload("fv_short", 2, 5, 65536, W.FULL_TV, 0.2, mu_full=True, logit_std=3.0, noise_std=0.7, adv="pm1", seed=79)
+    B.run_batch(W.make_batch(short, DEV))
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab"
