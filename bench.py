@@ -3,6 +3,7 @@
 MI355X.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--in-place]
+                  [--diagnostics] [--mask-rule dppo|ratio_clip|none] [--eps-low E] [--eps-high E] [--ratio-cap C]
 
 A step is one pass of the whole path (log-softmax statistics, gathers, divergence, mask,
 loss, gradient over all V logits) over one synthetic batch that is already resident in HBM.
@@ -183,6 +184,12 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--diagnostics", action="store_true", help="also write the per-token diagnostics [T, 8] (entropy, |pi - mu|, covered mass, ...)")
+    ap.add_argument("--mask-rule", choices=["dppo", "ratio_clip", "none"], default="dppo",
+                    help="dppo: divergence mask (default); ratio_clip: PPO / GRPO(-ClipHigher) with --eps-low/--eps-high; none: PG-IS, CISPO / PG-TIS")
+    ap.add_argument("--eps-low", type=float, default=0.2)
+    ap.add_argument("--eps-high", type=float, default=0.28)
+    ap.add_argument("--ratio-cap", type=float, default=0.0, help="C of the unified gradient form (0: no cap)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits (the boundary allows it); the logits are restored, untimed, before every step")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
     ap.add_argument("--ld", type=int, default=0, help="row pitch of logits / gradient in elements (0: V)")
@@ -216,20 +223,22 @@ def main() -> int:
     in_place = args.in_place and not args.forward_only
     pristine = batch["logits"].clone() if in_place else None
     grad = batch["logits"] if in_place else torch.empty_like(batch["logits"])
-    out = B.alloc_outputs(T, dev)
+    out = B.alloc_outputs(T, dev, want_diagnostics=args.diagnostics)
+    rule = {"mask_rule": {"dppo": B.MASK_DIVERGENCE, "ratio_clip": B.MASK_RATIO_CLIP, "none": B.MASK_NONE}[args.mask_rule],
+            "eps_low": args.eps_low, "eps_high": args.eps_high, "ratio_cap": args.ratio_cap}
     calls = []
     for c0 in range(0, T, chunk):
         c1 = min(T, c0 + chunk)
         o = dict(out)
         o["loss"] = torch.empty(1, dtype=torch.float32, device=dev)
-        for k in ("loss_tok", "divergence", "mask"):
+        for k in ("loss_tok", "divergence", "mask") + (("diagnostics",) if args.diagnostics else ()):
             o[k] = out[k][c0:c1]
         sl = slice(c0, c1)
         a = B.make_args(batch["logits"][sl], batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
                         batch["delta"], batch["variant"], batch["loss_scale"], o,
                         batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
                         V=V, flags=flags, grad_logits=grad[sl],
-                        mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None)
+                        mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
         a.ld = batch["ld"]
         calls.append((a, o))
 
@@ -306,9 +315,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
-                   "kernel_path": path, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
+                   "kernel_path": path, "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place) else stored_traffic(args.workload, path),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
                      "kernel_ms": kernel_ms, "device_ceilings": ceilings,
                      "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},

@@ -42,7 +42,7 @@
 extern "C" {
 #endif
 
-#define DPPO_VERSION 300          /* major*10000 + minor*100 + patch                          */
+#define DPPO_VERSION 301          /* major*10000 + minor*100 + patch                          */
 #define DPPO_KMAX 1024            /* largest accepted K                                        */
 #define DPPO_WORKSPACE_BYTES 65536
 
