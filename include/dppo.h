@@ -178,8 +178,8 @@ size_t dppo_args_size(void);
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
  * "resident" (row held in registers between the two passes), "streaming" (row re-read),
  * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
- * backward on long aligned rows: the trainer's row held in registers, the rollout row streamed
- * past it); "lmhead" after a dppo_lmhead_* call. */
+ * backward, and the forward-only TV form, on long aligned rows: the trainer's row held in
+ * registers, the rollout row streamed past it); "lmhead" after a dppo_lmhead_* call. */
 const char* dppo_last_path(void);
 
 /* ---- the same loss from the hidden states: the [T, V] logits never exist in full -------------

@@ -100,14 +100,15 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
     int r_threads = 0, r_chunks = 0;
     const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);
-    const int fr_chunks = (full && grad && !(a->flags & DPPO_FLAG_FORCE_STREAMING)) ? dppo::fullvocab_resident_chunks(p) : 0;
+    const bool tv_full = a->variant == DPPO_FULL_TV;
+    const int fr_chunks = (full && !(a->flags & DPPO_FLAG_FORCE_STREAMING)) ? dppo::fullvocab_resident_chunks(p, tv_full, grad) : 0;
     if (fr_chunks) {
-      // long aligned rows, backward: the trainer's row stays in registers, one workgroup per compute unit
+      // long aligned rows (backward, or the TV form): the trainer's row stays in registers, one workgroup per compute unit
       int64_t grid = cus;
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
-      if (dppo::launch_fullvocab_resident(p, a->variant == DPPO_FULL_TV, fr_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      if (dppo::launch_fullvocab_resident(p, tv_full, grad, fr_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab_resident";
     } else if (full) {
       // Two rows per workgroup in flight: one workgroup of 1024 threads per compute unit keeps the

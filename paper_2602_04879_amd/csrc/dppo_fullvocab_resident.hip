@@ -1,5 +1,5 @@
-// Trust region on the EXACT full-vocabulary divergence (App. B), register-resident form of the
-// backward: total variation 1/2 sum_j |mu_j - pi_j| or KL(mu || pi) = sum_j mu_j ln(mu_j / pi_j)
+// Trust region on the EXACT full-vocabulary divergence (App. B), register-resident form (the
+// backward of both variants, and the forward-only TV form): total variation 1/2 sum_j |mu_j - pi_j| or KL(mu || pi) = sum_j mu_j ln(mu_j / pi_j)
 // between the rollout policy's and the trainer's next-token distributions, both given as rows of
 // bf16 logits, and the gradient of the masked surrogate over the trainer's row.
 //
@@ -57,8 +57,9 @@ struct RowStat {
   }
 };
 
-template <int NCHUNK, bool TV, bool DIAG>
+template <int NCHUNK, bool TV, bool DIAG, bool GRAD>
 __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const KParams p) {
+  static_assert(GRAD || TV, "forward only, the KL form reads each row once anyway: the general kernel serves it");
   static_assert(NCHUNK == 32 || NCHUNK == 38, "the forms the host selects: rows of more than 24 and up to 32, more than 32 and up to 38 chunks");
   constexpr int THREADS = kThreads, NW = THREADS / kWave;
   constexpr uint32_t kStride = THREADS * 16u;      // bytes between a thread's consecutive chunks
@@ -212,6 +213,14 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
           asm volatile("" : "+v"(acc0), "+v"(acc1));
           __builtin_amdgcn_sched_barrier(0);
         }
+        if (!GRAD) {
+          // forward only: nothing needs the rows any more, the next ones start to travel now
+#pragma unroll
+          for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<false>(zn, voff, i * kStride);
+#pragma unroll
+          for (int i = 0; i < kWindow; ++i) yb[i] = row_load16<kY1Nt>(yn, voff, i * kStride);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         const double wa = wave_sum(static_cast<double>(acc0) + static_cast<double>(acc1));
         if (lane == 0) sh_acc[wid] = wa;
         __syncthreads();
@@ -242,12 +251,16 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         const RowResult res = row_epilogue(ep, row_e, rs, tk, zrow, bz, S_rest, T_rest, lane, D);
         rc = res.rc;
         loss_acc += res.loss_term;
-        if (lane == 0) sh_rc = rc;
+        if (GRAD && lane == 0) sh_rc = rc;
       }
+      // (forward only, this barrier also keeps the next row's statistics from overwriting the
+      // shared sums while a slower wave still reads them)
       __syncthreads();
-      rc.coef = uniform_f(sh_rc.coef);
-      rc.kexp = uniform_f(sh_rc.kexp);
-      rc.g_a = uniform_f(sh_rc.g_a);
+      if (GRAD) {
+        rc.coef = uniform_f(sh_rc.coef);
+        rc.kexp = uniform_f(sh_rc.kexp);
+        rc.g_a = uniform_f(sh_rc.g_a);
+      }
     } else if (tid == 0) {
       p.divergence[row] = 0.f;
       p.mask[row] = 0;
@@ -258,7 +271,14 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
     }
 
     // ---- gradient out, next rows in -----------------------------------------------------------
-    {
+    if (!GRAD) {
+      if (!live) {       // an ignored row skipped the passes and with them the refill
+#pragma unroll
+        for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<false>(zn, voff, i * kStride);
+#pragma unroll
+        for (int i = 0; i < kWindow; ++i) yb[i] = row_load16<kY1Nt>(yn, voff, i * kStride);
+      }
+    } else {
       char* gr = gbase + row * pitch;
       const row_desc_t gout = make_row_desc(gr, row_bytes);
       const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
@@ -298,24 +318,32 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
 }
 
 template <int NCHUNK>
-hipError_t launch_chunks(const KParams& p, bool tv, int grid, hipStream_t s) {
+hipError_t launch_chunks(const KParams& p, bool tv, bool grad, int grid, hipStream_t s) {
   const bool diag = p.diag != nullptr;
   const dim3 g(grid), b(kThreads);
-  if (tv && diag)  hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, true>), g, b, 0, s, p);
-  else if (tv)     hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, false>), g, b, 0, s, p);
-  else if (diag)   hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, true>), g, b, 0, s, p);
-  else             hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, false>), g, b, 0, s, p);
+  if (!grad) {
+    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, true, false>), g, b, 0, s, p);
+    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, false, false>), g, b, 0, s, p);
+  } else if (tv) {
+    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, true, true>), g, b, 0, s, p);
+    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, false, true>), g, b, 0, s, p);
+  } else {
+    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, true, true>), g, b, 0, s, p);
+    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, false, true>), g, b, 0, s, p);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Chunks of 512 x 16 bytes that cover a row in this form, 0 where it does not apply: rows of
-// 98312 .. 155648 entries (shorter rows stay with the general kernel, several of whose rows fit the
-// caches together), a multiple of 8, all three matrices 16-byte aligned with pitches in multiples of 8.
-int fullvocab_resident_chunks(const KParams& p) {
-  if (!p.grad || !p.mu_logits || p.V % 8 != 0 || p.ld % 8 != 0 || p.mu_ld % 8 != 0) return 0;
-  if ((reinterpret_cast<uintptr_t>(p.logits) | reinterpret_cast<uintptr_t>(p.mu_logits) | reinterpret_cast<uintptr_t>(p.grad)) & 15u) return 0;
+// Chunks of 512 x 16 bytes that cover a row in this form, 0 where it does not apply.  It applies to
+// the backward of both variants and to the forward-only TV form (which reads both rows twice; the
+// forward-only KL form reads each row once in the general kernel too), on rows of 98312 .. 155648
+// entries (shorter rows stay with the general kernel, several of whose rows fit the caches
+// together), a multiple of 8, every matrix 16-byte aligned with a pitch that is a multiple of 8.
+int fullvocab_resident_chunks(const KParams& p, bool tv, bool grad) {
+  if (!(grad || tv) || !p.mu_logits || p.V % 8 != 0 || p.ld % 8 != 0 || p.mu_ld % 8 != 0) return 0;
+  if ((reinterpret_cast<uintptr_t>(p.logits) | reinterpret_cast<uintptr_t>(p.mu_logits) | (grad ? reinterpret_cast<uintptr_t>(p.grad) : 0)) & 15u) return 0;
   const int64_t nvec = p.V / 8;
   if (nvec <= kThreads * 24) return 0;
   if (nvec <= kThreads * 32) return 32;
@@ -323,9 +351,9 @@ int fullvocab_resident_chunks(const KParams& p) {
   return 0;
 }
 
-hipError_t launch_fullvocab_resident(const KParams& p, bool tv, int chunks, int grid, hipStream_t s) {
-  if (chunks == 32) return launch_chunks<32>(p, tv, grid, s);
-  if (chunks == 38) return launch_chunks<38>(p, tv, grid, s);
+hipError_t launch_fullvocab_resident(const KParams& p, bool tv, bool grad, int chunks, int grid, hipStream_t s) {
+  if (chunks == 32) return launch_chunks<32>(p, tv, grad, grid, s);
+  if (chunks == 38) return launch_chunks<38>(p, tv, grad, grid, s);
   return hipErrorInvalidValue;
 }
 

@@ -20,12 +20,12 @@ int resident_blocks_per_cu(bool grad, int threads, int chunks);
 // Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
 hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);
 
-// Register-resident backward of the same variants: the trainer's row in the registers of one
-// workgroup of 512 threads per compute unit, the rollout row streamed past it.
-// fullvocab_resident_chunks() says whether a call qualifies (0: no) and with how many 16-byte
-// chunks per thread.
-int fullvocab_resident_chunks(const KParams& p);
-hipError_t launch_fullvocab_resident(const KParams& p, bool tv, int chunks, int grid, hipStream_t s);
+// Register-resident form of the same variants (backward, and the forward-only TV form): the
+// trainer's row in the registers of one workgroup of 512 threads per compute unit, the rollout row
+// streamed past it.  fullvocab_resident_chunks() says whether a call qualifies (0: no) and with
+// how many 16-byte chunks per thread.
+int fullvocab_resident_chunks(const KParams& p, bool tv, bool grad);
+hipError_t launch_fullvocab_resident(const KParams& p, bool tv, bool grad, int chunks, int grid, hipStream_t s);
 
 // bf16 matrix products on the matrix cores (fp32 accumulation).  A, B 16-byte aligned with lda, ldb
 // multiples of 8 and 256 * ld * 2 < 2^32; the fp32 forms need 16-byte aligned rows of C.

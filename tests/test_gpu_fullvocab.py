@@ -207,6 +207,12 @@ def test_resident_form_against_the_oracle_and_the_general_kernel(variant, delta,
     torch.cuda.synchronize()
     assert torch.equal(plain["mask"], res["mask"]) and torch.equal(plain["divergence"], res["divergence"])
     assert torch.equal(plain["grad_logits"][:, :V], res["grad_logits"][:, :V])
+    fwd = B.run_batch(b, backward=False, diagnostics=True)   # forward only: the TV form keeps the trainer's row resident too
+    torch.cuda.synchronize()
+    assert B.last_path() == ("fullvocab_resident" if variant == W.FULL_TV else "fullvocab")
+    assert torch.equal(fwd["mask"], res["mask"]) and (fwd["divergence"] - res["divergence"]).abs().max().item() <= 2e-6
+    assert torch.allclose(fwd["loss"], res["loss"], rtol=1e-5, atol=1e-9)
+    assert torch.allclose(fwd["diagnostics"], res["diagnostics"], rtol=1e-5, atol=1e-6, equal_nan=True)
     keep = res["grad_logits"][:, :V].clone()
     inp = B.run_batch(b, in_place=True)
     torch.cuda.synchronize()
@@ -228,9 +234,16 @@ def test_resident_form_more_rows_than_workgroups_and_fallbacks():
     st = P.compare_rows(b, res, rows)
     P.check_loss_scalar(b, res)
     _say(f"       {st}")
-    B.run_batch(b, backward=False)
+    B.run_batch(b, backward=False)                           # forward-only KL reads each row once anyway
     torch.cuda.synchronize()
     assert B.last_path() == "fullvocab"
+    tvb = dict(b, variant=W.FULL_TV, delta=0.2)
+    tvf = B.run_batch(tvb, backward=False, diagnostics=True)  # forward-only TV, several rows per workgroup, ignored rows
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab_resident"
+    st = P.compare_rows(tvb, tvf, rows, check_grad=False)
+    P.check_loss_scalar(tvb, tvf)
+    _say(f"       forward-only TV {st}")
     T, V = b["T"], b["V"]
     store = torch.zeros(T * V + 8, dtype=torch.bfloat16, device=DEV)
     mu2 = store[1:1 + T * V].view(T, V)
