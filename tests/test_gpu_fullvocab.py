@@ -60,11 +60,13 @@ def test_rows_of_the_two_matrices_misaligned_against_each_other(variant, delta):
     _say(f"       {st}")
 
 
-def test_excluded_tokens_and_infinite_kl():
+@pytest.mark.parametrize("V", [8192, 98312])
+def test_excluded_tokens_and_infinite_kl(V):
     """-inf logits: a token both policies exclude adds nothing; one only mu excludes adds nothing to
-    KL(mu || pi); one only pi excludes while mu can sample it makes KL infinite (TV stays finite)."""
+    KL(mu || pi); one only pi excludes while mu can sample it makes KL infinite (TV stays finite).
+    In the general kernel (V = 8192) and in the register-resident form (V = 98312)."""
     for variant, delta in FULL:
-        w = W.Workload("inf_full", 2, 6, 8192, variant, delta, mu_full=True, logit_std=2.0, noise_std=0.3, adv="pm1", seed=61)
+        w = W.Workload("inf_full", 2, 6, V, variant, delta, mu_full=True, logit_std=2.0, noise_std=0.3, adv="pm1", seed=61)
         b = W.make_batch(w, DEV)
         a = b["sampled_ids"].long()
         cols = torch.arange(100, 2000, device=DEV)
@@ -77,6 +79,7 @@ def test_excluded_tokens_and_infinite_kl():
         ref = P.oracle_rows(b, rows)
         res = B.run_batch(b, diagnostics=True)
         torch.cuda.synchronize()
+        assert B.last_path() == ("fullvocab" if V == 8192 else "fullvocab_resident")
         st = P.compare_rows(b, res, rows, ref=ref)
         D = res["divergence"].cpu().numpy()
         if variant == W.FULL_KL:
