@@ -263,28 +263,6 @@ dppo_status_t dppo_gemm_nn(const void* A, int64_t lda, const void* B, int64_t ld
 dppo_status_t dppo_gemm_tn_f32(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
                                int64_t M, int64_t N, int64_t K, int accumulate, void* stream);
 
-/* ---- measurement utilities (not part of the loss) ------------------------------------------
- * Plain device-to-device copy of `bytes` bytes with 16-byte vector loads/stores (dst, src and
- * bytes multiples of 16; buffers must not overlap), a write-only fill of `bytes` bytes with a
- * 32-bit pattern, and a read-only pass over `bytes` bytes (`sink` is a 4-byte device location
- * that is practically never written).  bench.py and the
- * counter-calibration probe use them: a copy of known size scales the HBM byte counters, and
- * their bandwidth is the device's streaming ceiling the loss kernels are compared with. */
-dppo_status_t dppo_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
-/* The same copy with the loss kernels' address pattern: one workgroup per row of `row_bytes` bytes
- * (rows `pitch_bytes` apart; both multiples of 16), as many workgroups as compute units. */
-dppo_status_t dppo_probe_copy_rows(void* dst, const void* src, int64_t rows, size_t row_bytes, size_t pitch_bytes, void* stream);
-dppo_status_t dppo_probe_fill(void* dst, size_t bytes, uint32_t value, void* stream);
-dppo_status_t dppo_probe_read(const void* src, size_t bytes, void* sink, void* stream);
-/* Matrix-core ceiling under the board's power limit: one workgroup of 4 waves per compute unit,
- * each wave `iters` rounds of independent bf16 products on register operands with 256 fp32
- * accumulators: `shape` 16 = 64 x v_mfma_f32_16x16x32_bf16 per round, 32 = 16 x
- * v_mfma_f32_32x32x16_bf16.  `out` (device, at least 1024 bytes per compute unit, `out_bytes`
- * says how many) receives one float per lane; `*flop` (host, may be NULL) the floating-point
- * operations of the launch, for the caller to divide by the time it measures.
- * DPPO_ERR_SHAPE for another shape or negative iters, DPPO_ERR_WORKSPACE if `out` is too small. */
-dppo_status_t dppo_probe_mfma(int shape, int iters, void* out, size_t out_bytes, double* flop, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

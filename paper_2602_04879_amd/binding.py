@@ -1,4 +1,5 @@
-"""Thin ctypes binding of the C ABI in include/dppo.h.
+"""Thin ctypes binding of the C ABI in include/dppo.h (and the measurement utilities of
+include/dppo_probe.h).
 
 Argument marshalling only: every step of the loss runs in the HIP kernels of libdppo.so.
 PyTorch is used for device memory and the stream handle.  There is no CPU fallback: if the
@@ -80,6 +81,8 @@ def lib() -> C.CDLL:
         l.dppo_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.dppo_probe_copy_rows.restype = C.c_int
         l.dppo_probe_copy_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_size_t, C.c_size_t, C.c_void_p]
+        l.dppo_probe_copy_resident.restype = C.c_int
+        l.dppo_probe_copy_resident.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_size_t, C.c_size_t, C.c_void_p]
         l.dppo_probe_fill.restype = C.c_int
         l.dppo_probe_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         l.dppo_probe_read.restype = C.c_int
@@ -187,6 +190,17 @@ def probe_copy_rows(dst, src, stream=None) -> None:
     es = src.element_size()
     st = lib().dppo_probe_copy_rows(dst.data_ptr(), src.data_ptr(), src.shape[0], src.shape[1] * es, src.stride(0) * es,
                                     C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def probe_copy_resident(dst, src, stream=None) -> None:
+    """dppo_probe_copy_resident: copy a 2-D tensor row by row with the register-resident loss
+    kernel's memory pattern (row held in registers, one run of stores, one run of loads)."""
+    assert dst.shape == src.shape and dst.stride() == src.stride() and src.stride(1) == 1
+    es = src.element_size()
+    st = lib().dppo_probe_copy_resident(dst.data_ptr(), src.data_ptr(), src.shape[0], src.shape[1] * es, src.stride(0) * es,
+                                        C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
 

@@ -1,6 +1,7 @@
 // C ABI of the DPPO loss library: argument checks, kernel-path choice, launches.
 #include <hip/hip_runtime.h>
 #include <cmath>
+#include <atomic>
 #include <cstdint>
 #include <mutex>
 
@@ -25,6 +26,30 @@ const DeviceInfo& device_info(int dev) {
     info[dev].cus = n;
   });
   return info[dev];
+}
+
+// The device a stream belongs to (NULL: the current device).
+bool stream_device(hipStream_t s, int* dev) {
+  hipDevice_t d = 0;
+  if (s != nullptr && hipStreamGetDevice(s, &d) == hipSuccess) {
+    *dev = static_cast<int>(d);
+    return true;
+  }
+  return hipGetDevice(dev) == hipSuccess;
+}
+
+// Workgroups per compute unit of a register-resident shape: a constant of (device, shape, form),
+// asked of the runtime once and kept.
+int resident_blocks_per_cu_cached(int dev, bool grad, int threads, int chunks) {
+  static std::atomic<int> cache[64][2][2][41];
+  if (dev < 0 || dev >= 64 || chunks < 0 || chunks > 40) return dppo::resident_blocks_per_cu(grad, threads, chunks);
+  std::atomic<int>& slot = cache[dev][grad ? 1 : 0][threads == 512 ? 1 : 0][chunks];
+  int n = slot.load(std::memory_order_relaxed);
+  if (n == 0) {
+    n = dppo::resident_blocks_per_cu(grad, threads, chunks);
+    slot.store(n, std::memory_order_relaxed);
+  }
+  return n;
 }
 
 thread_local const char* g_last_path = "none";
@@ -63,7 +88,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
   int nparts = 0;
   if (a->T > 0) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return DPPO_ERR_LAUNCH;
+    if (!stream_device(s, &dev)) return DPPO_ERR_LAUNCH;
     const int cus = device_info(dev).cus;
 
     dppo::KParams p;
@@ -121,7 +146,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
       if (dppo::launch_fullvocab(p, a->variant == DPPO_FULL_TV, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab";
     } else if (resident) {
-      int64_t grid = static_cast<int64_t>(cus) * dppo::resident_blocks_per_cu(grad, r_threads, r_chunks);
+      int64_t grid = static_cast<int64_t>(cus) * resident_blocks_per_cu_cached(dev, grad, r_threads, r_chunks);
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);

@@ -95,10 +95,14 @@ __device__ __forceinline__ u32x4 row_load16(row_rsrc_t r, uint32_t voff, uint32_
 // pending the compiler falls back to waiting for everything (s_waitcnt vmcnt(0)), whereas loads
 // alone complete in order and it waits for exactly the one it needs (vmcnt = number of loads
 // issued after it, which stays correct however many stores are in flight).
-// A store of more than 8 bytes whose offset comes from a scalar register needs one wait state
-// before a vector-ALU instruction may overwrite its data registers (the compiler inserts that
-// for the stores it sees; it does not see this one), so the statement carries an s_nop.  A later
-// vector-memory load into the same registers queues behind the store and needs nothing.
+// What the compiler no longer does for a store it cannot see: before a vector-ALU instruction may
+// overwrite the data registers of a vector-memory store of more than 8 bytes, this target wants
+// wait states (the compiler's own rule: two, when the store's scalar offset is not a register).
+// The scalar offset here is always a scalar-register operand (the "s" constraint below); the
+// statement nevertheless carries `s_nop 1` (two wait states), which covers either form of the
+// operand: without any wait state, rows of few chunks came out wrong once the stores stood back
+// to back and the compiler reused the data registers at once.  A later vector-memory load into
+// the same registers queues behind the store and needs nothing.
 // The store is marked non-temporal (a gradient row is not read again by this kernel): measured
 // 2.5 % faster on the headline shape; the same mark on the row loads measured slower.
 typedef int row_desc_t __attribute__((ext_vector_type(4)));
@@ -112,7 +116,7 @@ __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t b
   return d;
 }
 __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t voff, uint32_t soff, u32x4 v) {
-  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 0" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
+  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 1" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
 // First row of a workgroup in a row-per-workgroup kernel whose rows advance by gridDim.x: a

@@ -4,7 +4,7 @@
 // matrix-core products on every compute unit: what the matrix cores sustain under the board's
 // power limit, the ceiling the matrix-product kernel is compared with.
 #include <hip/hip_runtime.h>
-#include "dppo.h"
+#include "dppo_probe.h"
 #include "dppo_common.hpp"
 
 namespace {
@@ -60,6 +60,38 @@ __global__ __launch_bounds__(512) void dppo_probe_copy_rows_kernel(const dppo::u
       for (int u = 0; u < 4; ++u) d[i + u * 512] = v[u];
     }
     for (; i < row_vecs; i += 512) d[i] = s[i];
+  }
+}
+
+// The copy with the memory pattern of the register-resident loss kernel and none of its arithmetic:
+// one persistent workgroup of 512 threads per compute unit holds a whole row in its registers
+// (38 chunks of 16 bytes per thread through range-checked buffer resources), writes it out in one
+// run of non-temporal stores and then requests its next row in one run of loads; rows advance by
+// the number of workgroups, the workgroups of one die on neighbouring rows.  What this reaches is
+// the ceiling of that pattern on the device.
+__global__ __launch_bounds__(512) void dppo_probe_copy_resident_kernel(const char* __restrict__ src, char* __restrict__ dst, int rows,
+                                                                       uint32_t row_bytes, int64_t pitch_bytes) {
+  constexpr int NCHUNK = 38;
+  constexpr uint32_t kStride = 512 * 16u;
+  const uint32_t voff = threadIdx.x * 16u;
+  dppo::u32x4 buf[NCHUNK];
+  int row = dppo::first_row_of_workgroup();
+  {
+    const dppo::row_rsrc_t zr = dppo::make_row_rsrc(src + row * pitch_bytes, row_bytes);
+#pragma unroll
+    for (int i = 0; i < NCHUNK; ++i) buf[i] = dppo::row_load16<false>(zr, voff, i * kStride);
+  }
+  for (; row < rows; row += gridDim.x) {
+    const int next = row + gridDim.x;
+    const bool more = next < rows;
+    const dppo::row_rsrc_t zn = dppo::make_row_rsrc(src + (more ? next : row) * pitch_bytes, more ? row_bytes : 0u);
+    const dppo::row_desc_t out = dppo::make_row_desc(dst + row * pitch_bytes, row_bytes);
+#pragma unroll
+    for (int i = 0; i < NCHUNK; ++i) dppo::row_store16_untracked(out, voff, i * kStride, buf[i]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NCHUNK; ++i) buf[i] = dppo::row_load16<false>(zn, voff, i * kStride);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -159,6 +191,19 @@ dppo_status_t dppo_probe_copy_rows(void* dst, const void* src, int64_t rows, siz
   hipLaunchKernelGGL(dppo_probe_copy_rows_kernel, dim3(grid), dim3(512), 0, static_cast<hipStream_t>(stream),
                      static_cast<const dppo::u32x4*>(src), static_cast<dppo::u32x4*>(dst), static_cast<int>(rows),
                      static_cast<int>(row_bytes / 16), pitch_bytes / 16);
+  return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
+}
+
+dppo_status_t dppo_probe_copy_resident(void* dst, const void* src, int64_t rows, size_t row_bytes, size_t pitch_bytes, void* stream) {
+  if (!dst || !src) return DPPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | row_bytes | pitch_bytes) & 15u) return DPPO_ERR_ALIGN;
+  // a row must fit the registers of one workgroup: 512 threads x 38 chunks of 16 bytes
+  if (rows < 0 || rows >= (int64_t(1) << 31) || pitch_bytes < row_bytes || row_bytes > 512u * 38u * 16u) return DPPO_ERR_SHAPE;
+  if (rows == 0 || row_bytes == 0) return DPPO_OK;
+  const int grid = static_cast<int>(rows < probe_cus() ? rows : probe_cus());
+  hipLaunchKernelGGL(dppo_probe_copy_resident_kernel, dim3(grid), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(src), static_cast<char*>(dst), static_cast<int>(rows),
+                     static_cast<uint32_t>(row_bytes), static_cast<int64_t>(pitch_bytes));
   return hipGetLastError() == hipSuccess ? DPPO_OK : DPPO_ERR_LAUNCH;
 }
 

@@ -81,9 +81,14 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
   constexpr int GC = 2;                          // chunks per group of the online row statistics
   constexpr int kSplit = ((NCHUNK / 2 + GC - 1) / GC) * GC;   // forward only: chunks refilled mid-row
-  __shared__ float sh_b[NW];
-  __shared__ double sh_s[NW], sh_t[NW];
+  // Per-wave statistics, two sets used by alternate rows: forward only there is no barrier behind
+  // wave 0's epilogue, so the other waves may already publish the next row's statistics while
+  // wave 0 still reads this row's.  (A third row cannot follow before wave 0 has passed the next
+  // row's barrier, i.e. has finished with this set.)
+  __shared__ float sh_b[2][NW];
+  __shared__ double sh_s[2][NW], sh_t[2][NW];
   __shared__ RowCoef sh_rc;
+  int par = 0;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
   const int nvec = p.V >> 3;
@@ -242,20 +247,20 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       const double st = static_cast<double>((s0 + s1) + (s2 + s3)), tt = static_cast<double>((t0 + t1) + (t2 + t3));
       const double sw = wave_sum(st * scw);
       const double tw = DIAG ? wave_sum(scw * (tt + dw * st)) : 0.0;
-      if (lane == 0) { sh_b[wid] = bw; sh_s[wid] = sw; sh_t[wid] = tw; }
+      if (lane == 0) { sh_b[par][wid] = bw; sh_s[par][wid] = sw; sh_t[par][wid] = tw; }
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------
       if (wid == 0) {
         // the offset must also cover z[a_t], whose own term the epilogue adds
         float bb = -ceilf(fmaxf(rs.za, kNegBig) * kLog2e);
 #pragma unroll
-        for (int w = 0; w < NW; ++w) bb = fminf(bb, sh_b[w]);
+        for (int w = 0; w < NW; ++w) bb = fminf(bb, sh_b[par][w]);
         double S_rest = 0.0, T_rest = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-          const double dd = static_cast<double>(bb - sh_b[w]), sc = static_cast<double>(fast_exp2(bb - sh_b[w]));   // exact power of two
-          S_rest += sh_s[w] * sc;
-          T_rest += sc * (sh_t[w] + dd * sh_s[w]);
+          const double dd = static_cast<double>(bb - sh_b[par][w]), sc = static_cast<double>(fast_exp2(bb - sh_b[par][w]));   // exact power of two
+          S_rest += sh_s[par][w] * sc;
+          T_rest += sc * (sh_t[par][w] + dd * sh_s[par][w]);
         }
         // Shapes whose row data alone leaves room for one workgroup per compute unit: nothing
         // hides a call there, so the epilogue is inlined.  The shorter shapes keep the call and
@@ -272,6 +277,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
       }
+      par ^= 1;
       if (GRAD) {
         __syncthreads();
         rc.coef = uniform_f(sh_rc.coef);

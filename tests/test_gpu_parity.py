@@ -473,6 +473,16 @@ def test_probe_kernels_copy_fill_read():
     B.probe_copy_rows(b[:, :cols], a[:, :cols])
     torch.cuda.synchronize()
     assert torch.equal(b[:, :cols], a[:, :cols]) and (b[:, cols:] == -7.0).all()
+    # the register-resident copy (the loss kernel's memory pattern): a ragged row length, the longest
+    # row it holds, more rows than workgroups and fewer
+    for rows, cols, ld in ((700, 4104, 4112), (300, 155648, 155648), (5, 151936, 151936)):
+        a = torch.randn((rows, ld), generator=g, device=DEV).bfloat16()
+        b = torch.full((rows, ld), -7.0, dtype=torch.bfloat16, device=DEV)
+        B.probe_copy_resident(b[:, :cols], a[:, :cols])
+        torch.cuda.synchronize()
+        assert torch.equal(b[:, :cols], a[:, :cols]) and (b[:, cols:] == -7.0).all()
+    with pytest.raises(B.DppoError):
+        B.probe_copy_resident(torch.empty((2, 155656), dtype=torch.bfloat16, device=DEV), torch.empty((2, 155656), dtype=torch.bfloat16, device=DEV))
 
 
 def test_probe_matrix_core_loop():

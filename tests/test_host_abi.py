@@ -114,7 +114,7 @@ def test_header_is_plain_c(tmp_path):
     import shutil
     import subprocess
     src = tmp_path / "use_dppo.c"
-    src.write_text('#include "dppo.h"\n'
+    src.write_text('#include "dppo.h"\n#include "dppo_probe.h"\n'
                    'int probe(void) { dppo_args_t a; dppo_lmhead_args_t l; (void)a; (void)l;\n'
                    '  return (int)sizeof(a) + (int)sizeof(l) + DPPO_KMAX + DPPO_NDIAG + (int)DPPO_FULL_KL + (int)DPPO_MASK_NONE; }\n')
     inc = os.path.join(ROOT, "include")
