@@ -63,29 +63,70 @@ def algorithmic_bytes_per_token(V: int, K: int, full: bool = False, backward: bo
     return 2 * V + (2 * V if full else 0) + (2 * V if backward else 0) + side_in + side_out
 
 
-def cpu_baseline(batch, budget_s: float, chunk_rows: int = 256, backward: bool = True) -> dict:
-    """Time the float64 oracle, as it stands, on leading rows of the same batch: chunks of
-    chunk_rows rows until about budget_s seconds of CPU work are spent (or the batch ends)."""
+def host_threads() -> int:
+    """Hardware threads this process may use: its CPU affinity, capped by the share the
+    environment grants (OMP_NUM_THREADS)."""
+    n = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    try:
+        n = min(n, max(1, int(os.environ.get("OMP_NUM_THREADS", n))))
+    except ValueError:
+        pass
+    return max(1, n)
+
+
+def _oracle_rows(batch, sl, backward):
+    """Run the oracle, as it stands, on one block of rows (host arrays made outside the timing)."""
     from oracle import dppo_oracle as O
-    V, T = batch["V"], batch["T"]
-    done, wall, cpu = 0, 0.0, 0.0
-    while done < T and wall < budget_s:
+    V = batch["V"]
+    z = batch["logits"][sl, :V].float().cpu().numpy()
+    ids = batch["sampled_ids"][sl].cpu().numpy()
+    lmu = batch["mu_logp"][sl].cpu().numpy()
+    adv = batch["advantages"][sl].cpu().numpy()
+    tk_i = batch["mu_topk_ids"][sl].cpu().numpy() if batch["mu_topk_ids"] is not None else None
+    tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
+    y = batch["mu_logits"][sl, :V].float().cpu().numpy() if batch.get("mu_logits") is not None else None
+    return lambda: O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l,
+                               want_grad=backward, mu_logits=y)
+
+
+def cpu_baseline(batch, budget_s: float, chunk_rows: int = 64, backward: bool = True) -> dict:
+    """Time the float64 oracle, as it stands, on leading rows of the same batch, twice: on one
+    thread, and on all hardware threads (blocks of rows handed to a thread pool; numpy releases
+    the interpreter lock inside its array operations).  Each leg spends about budget_s / 2 seconds
+    of wall time.  `value` / `cores` are the all-threads leg."""
+    from concurrent.futures import ThreadPoolExecutor
+    T = batch["T"]
+    nthreads = host_threads()
+    kind = "fwd+bwd" if backward else "fwd"
+    # leg 1: one thread
+    done, wall = 0, 0.0
+    while done < T and wall < budget_s / 2:
         sl = slice(done, min(T, done + chunk_rows))
-        z = batch["logits"][sl, :V].float().cpu().numpy()
-        ids = batch["sampled_ids"][sl].cpu().numpy()
-        lmu = batch["mu_logp"][sl].cpu().numpy()
-        adv = batch["advantages"][sl].cpu().numpy()
-        tk_i = batch["mu_topk_ids"][sl].cpu().numpy() if batch["mu_topk_ids"] is not None else None
-        tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
-        t0, c0 = time.perf_counter(), time.process_time()
-        y = batch["mu_logits"][sl, :V].float().cpu().numpy() if batch.get("mu_logits") is not None else None
-        O.dppo_loss(z, ids, lmu, adv, batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l, want_grad=backward,
-                    mu_logits=y)
+        fn = _oracle_rows(batch, sl, backward)
+        t0 = time.perf_counter()
+        fn()
         wall += time.perf_counter() - t0
-        cpu += time.process_time() - c0
-        done += len(ids)
-    return {"value": done / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)), "kind": "oracle",
-            "sample": f"first {done} of {T} rows of the same batch, {'fwd+bwd' if backward else 'fwd'}, float64 numpy, {wall:.1f} s"}
+        done += sl.stop - sl.start
+    one = {"value": done / wall, "rows": done, "seconds": wall}
+    # leg 2: all threads, rounds of one block per thread
+    done2, wall2, cpu2 = 0, 0.0, 0.0
+    start = done
+    with ThreadPoolExecutor(max_workers=nthreads) as ex:
+        while wall2 < budget_s / 2:
+            blocks = []
+            for _ in range(nthreads):
+                r0 = (start + done2 + len(blocks) * chunk_rows) % max(T - chunk_rows, 1)
+                blocks.append(_oracle_rows(batch, slice(r0, min(T, r0 + chunk_rows)), backward))
+            t0, c0 = time.perf_counter(), time.process_time()
+            list(ex.map(lambda f: f(), blocks))
+            wall2 += time.perf_counter() - t0
+            cpu2 += time.process_time() - c0
+            done2 += sum(min(T, chunk_rows) for _ in blocks)
+    return {"value": done2 / wall2, "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"{done2} rows of the same batch in blocks of {chunk_rows} over {nthreads} threads, {kind}, float64 numpy, "
+                      f"{wall2:.1f} s wall, {cpu2:.1f} s of CPU time; one thread: first {one['rows']} rows in {one['seconds']:.1f} s",
+            "one_thread": {"value": one["value"], "unit": "tokens/s", "cores": 1},
+            "host_threads": nthreads, "nproc": os.cpu_count()}
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core peak
@@ -250,32 +291,28 @@ def main() -> int:
         for a, _ in calls:
             run(a, stream)
 
-    if in_place:
-        # every step overwrites its input, so the logits are restored before each one (untimed)
-        # and each step is timed by an event pair of its own
-        def timed(n):
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-            for e0, e1 in evs:
+    # One HIP event pair per step, on the stream the kernels are launched on; the step time reported
+    # is the MEDIAN over the steps.  In place, every step overwrites its input, so the logits are
+    # restored (untimed) before each one.
+    def timed(n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in evs:
+            if in_place:
                 batch["logits"].copy_(pristine)
-                e0.record(stream)
-                step()
-                e1.record(stream)
-            torch.cuda.synchronize()
-            return sum(e0.elapsed_time(e1) for e0, e1 in evs) / max(n, 1)
-        timed(args.warmup)
-        ms_per_step = timed(args.steps)
+            e0.record(stream)
+            step()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    timed(args.warmup)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter()
+    times = timed(args.steps)
+    t_wall = time.perf_counter() - t_wall
+    ms_per_step = times[len(times) // 2] if len(times) % 2 else 0.5 * (times[len(times) // 2 - 1] + times[len(times) // 2])
+    ms_mean = sum(times) / len(times)
+    if in_place:
         batch["logits"].copy_(pristine)
-    else:
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ev0.record(stream)
-        for _ in range(args.steps):
-            step()
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        ms_per_step = ev0.elapsed_time(ev1) / args.steps
     path = B.last_path()
 
     # the device's streaming ceilings on THESE buffers (the rate depends on the footprint), measured
@@ -290,6 +327,9 @@ def main() -> int:
                   ("read", lambda: B.probe_read(src2d.view(-1).view(torch.uint8), sink, stream), nbytes)]
         if (V * 2) % 16 == 0 and (batch["ld"] * 2) % 16 == 0:
             probes.append(("copy_rows", lambda: B.probe_copy_rows(dst2d[:, :V], src2d[:, :V], stream), 2 * T * V * 2))
+            if V * 2 <= 512 * 38 * 16:
+                # the loss kernel's own memory pattern with none of its arithmetic
+                probes.append(("copy_resident", lambda: B.probe_copy_resident(dst2d[:, :V], src2d[:, :V], stream), 2 * T * V * 2))
         for name, fn, moved in probes:
             fn()
             torch.cuda.synchronize()
@@ -303,29 +343,40 @@ def main() -> int:
 
     launches = len(calls)
     alg_bytes_launch = algorithmic_bytes_per_token(V, K, batch.get("mu_logits") is not None, not args.forward_only) * (T // launches)
-    kernel_ms = ms_per_step / launches           # the step is the dominant kernel plus a ~3 us reduction
-    achieved = alg_bytes_launch / (kernel_ms * 1e-3) / 1e9
+    # a launch of the dominant kernel plus its share of the step's small change (the ~5 us loss
+    # reduction and the gaps between launches): a little MORE than the kernel's own duration
+    step_ms_per_launch = ms_per_step / launches
+    achieved = alg_bytes_launch / (step_ms_per_launch * 1e-3) / 1e9
     loss = sum(float(o["loss"].item()) for _, o in calls)
 
     rec = {
         "metric": "dppo_loss_fwd_tokens_per_s" if args.forward_only else "dppo_loss_fwd_bwd_tokens_per_s",
         "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_stat": "median of one HIP event pair per step", "ms_per_step_mean": ms_mean,
+        "ms_per_step_min": times[0], "ms_per_step_max": times[-1], "timed_region_wall_s": t_wall,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "K": K, "variant": int(batch["variant"]),
+                   "recipe": {"logit_std": w.logit_std, "zipf_s": w.zipf_s, "rollout_noise_std": w.noise_std,
+                              "drift_frac": w.drift_frac, "drift_std": w.drift_std, "advantages": w.adv, "group": w.group,
+                              "seed": w.seed,
+                              "note": "drift: this share of the tokens has the trainer's sampled-token logit moved by "
+                                      "N(0, drift_std^2) after the rollout, so that a few tokens are masked; not part of "
+                                      "the configuration string this workload stands for, byte-neutral"},
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
                    "kernel_path": path, "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
-                     "kernel_ms": kernel_ms, "device_ceilings": ceilings,
-                     "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None},
+                     "step_ms_per_launch": step_ms_per_launch, "device_ceilings": ceilings,
+                     "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None,
+                     "frac_of_resident_copy": (achieved / ceilings["copy_resident_GBs"]) if ceilings.get("copy_resident_GBs") else None},
         "loss": loss, "masked_tokens": int((out["mask"] == 0).sum().item()),
     }
     if rec["roofline"]["traffic"]:
         # what the counters say went over the HBM interface per second of this run's kernel time
-        rec["roofline"]["traffic_GBs"] = rec["roofline"]["traffic"] / (kernel_ms * 1e-3) / 1e9
+        rec["roofline"]["traffic_GBs"] = rec["roofline"]["traffic"] / (step_ms_per_launch * 1e-3) / 1e9
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(batch, args.cpu_seconds, backward=not args.forward_only)
     print(json.dumps(rec), flush=True)

@@ -140,7 +140,8 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
     a.grad_logits = _ptr(grad_logits)
     a.diagnostics = _ptr(out.get("diagnostics"))
-    a.workspace, a.workspace_bytes = _ptr(out["workspace"]), out["workspace"].numel()
+    ws = out.get("workspace")
+    a.workspace, a.workspace_bytes = _ptr(ws), (0 if ws is None else ws.numel())
     a.flags = flags
     return a
 

@@ -184,30 +184,41 @@ __device__ __forceinline__ double wave_sum(double v) {
 //   s = sum_j 2^(z_j*log2e + b)   with b an INTEGER-valued offset, b <= -max_j(z_j*log2e).
 // Because b is an integer, changing it rescales s by an exact power of two, and offsets of
 // different threads combine without any rounding.
+// The sum itself is kept in float64: the exponentials of eight entries are summed among themselves
+// in fp32 (pairwise) and that sum is added to the float64 accumulator, so that a thread that has
+// met a dominant entry does not drop the thousands of small ones that follow it (in an fp32
+// accumulator every term below half an ulp of the running sum vanishes: a bias of several 1e-7 on
+// rows with a heavy tail).
+__device__ __forceinline__ float sum8(const float (&e)[8]) {
+  return ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+}
 struct OnlineStat {
   float b = 3.0e38f;   // current offset (starts at "+infinity": nothing seen yet)
-  float s = 0.f;       // sum 2^x,      x = z*log2e + b
+  double s = 0.0;      // sum 2^x,      x = z*log2e + b
   float t = 0.f;       // sum 2^x * x   (feeds the entropy)
   __device__ __forceinline__ void cover(float zmax) {   // make the offset cover a logit value
     const float bn = fminf(b, -ceilf(fmaxf(zmax, kNegBig) * kLog2e));
     const float d = bn - b, sc = fast_exp2(d);
-    t = sc * fmaf(d, s, t);     // e -> e*2^d, x -> x + d
-    s *= sc;
+    t = sc * fmaf(d, static_cast<float>(s), t);     // e -> e*2^d, x -> x + d
+    s *= static_cast<double>(sc);
     b = bn;
   }
   __device__ __forceinline__ void add1(float z) {
     cover(z);
-    add1_covered(z);
-  }
-  __device__ __forceinline__ void add1_covered(float z) {
     const float x = fmaf(z, kLog2e, b), e = fast_exp2(x);
-    s += e;
+    s += static_cast<double>(e);
     t = fma_ex(e, x, t);
   }
   __device__ __forceinline__ void add8(const float (&z)[8]) {
     cover(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+    float e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) add1_covered(z[i]);
+    for (int i = 0; i < 8; ++i) {
+      const float x = fmaf(z[i], kLog2e, b);
+      e[i] = fast_exp2(x);
+      t = fma_ex(e[i], x, t);
+    }
+    s += static_cast<double>(sum8(e));
   }
 };
 
@@ -224,36 +235,41 @@ __device__ __forceinline__ void unpack8(const u32x4& v, float (&z)[8]) {
 // adds nothing even where z_j = -inf too; a token pi excludes (z_j = -inf) that mu can still
 // sample makes u infinite, as the divergence then is.
 struct CrossStat {
-  float b = 3.0e38f, s = 0.f, u = 0.f;
+  float b = 3.0e38f, u = 0.f;
+  double s = 0.0;
   __device__ __forceinline__ void cover(float ymax) {
     const float bn = fminf(b, -ceilf(fmaxf(ymax, kNegBig) * kLog2e));
     const float sc = fast_exp2(bn - b);
-    s *= sc;
+    s *= static_cast<double>(sc);
     u *= sc;
     b = bn;
   }
-  __device__ __forceinline__ void add1_covered(float y, float z) {
+  __device__ __forceinline__ float term(float y, float z) {
     const float e = fast_exp2(fmaf(y, kLog2e, b));
     const float d = fminf(fmaxf(y - z, -3.0e38f), 3.0e38f);     // NaN (-inf - -inf) -> -3e38, times e = 0
-    s += e;
     u = fmaf(e, d, u);
+    return e;
   }
   __device__ __forceinline__ void add1(float y, float z) {
     cover(y);
-    add1_covered(y, z);
+    s += static_cast<double>(term(y, z));
   }
   __device__ __forceinline__ void add8(const float (&y)[8], const float (&z)[8]) {
     cover(fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7]))));
+    float e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) add1_covered(y[i], z[i]);
+    for (int i = 0; i < 8; ++i) e[i] = term(y[i], z[i]);
+    s += static_cast<double>(sum8(e));
   }
 };
 
 // ---- scalar math for the per-row epilogue ----------------------------------------------------
-// The epilogue runs once per row on one wave while the rest of the workgroup waits, so it is
-// built from the hardware's single-instruction exp2/log2 (about 1 ulp in fp32) with the range
-// reduction and every sum or difference that could cancel carried in float64.  Each probability
-// comes out with a relative error of about 2e-7, which is also what the fp32 row sum carries.
+// The epilogue runs once per row on one wave while the rest of the workgroup waits.  Everything a
+// per-token output is formed from (the K + 2 probabilities, the two or three logarithms, every sum
+// or difference that could cancel) is evaluated in float64: exp2_d / log2_d below are good to about
+// 1e-15, so what is left on a probability is the relative error of the fp32 row sum (about 1e-8).
+// The single-instruction fp32 forms (exp2_split, log2_fast; about 1 ulp of fp32) remain for
+// quantities that are rounded to bf16 afterwards (the gradient's exponent).
 
 constexpr double kLn2 = 0.6931471805599453;
 constexpr double kLog2eD = 1.4426950408889634;
@@ -274,18 +290,46 @@ __device__ __forceinline__ double log2_fast(double x) {
   return static_cast<double>(e) + static_cast<double>(__builtin_amdgcn_logf(m));
 }
 
+// 2^x in float64 (0 below the float64 range, +inf above it): x = n + f with |f| <= 1/2, and
+// 2^f = exp(f ln 2) by the Taylor polynomial of degree 12 (|f ln 2| <= 0.347: truncation below
+// 1e-16 relative), evaluated pairwise (Estrin) so that the dependent chain is five operations deep
+// instead of twelve, then scaled by 2^n.
+__device__ __forceinline__ double exp2_d(double x) {
+  if (!(x > -1080.0)) return 0.0;
+  if (x > 1024.0) return __builtin_inf();
+  const double n = __builtin_rint(x);
+  const double t = (x - n) * kLn2;
+  const double t2 = t * t, t4 = t2 * t2, t8 = t4 * t4;
+  const double a0 = 1.0 + t, a1 = fma(t, 1.0 / 6, 0.5), a2 = fma(t, 1.0 / 120, 1.0 / 24), a3 = fma(t, 1.0 / 5040, 1.0 / 720),
+               a4 = fma(t, 1.0 / 362880, 1.0 / 40320), a5 = fma(t, 1.0 / 39916800, 1.0 / 3628800);
+  const double b0 = fma(t2, a1, a0), b1 = fma(t2, a3, a2), b2 = fma(t2, a5, a4);
+  const double c0 = fma(t4, b1, b0), c1 = fma(t4, 1.0 / 479001600, b2);
+  return ldexp(fma(t8, c1, c0), static_cast<int>(n));
+}
+
+// log2(x) in float64 for a positive finite x: the hardware's fp32 logarithm of the mantissa as a
+// first guess y0 (about 1e-7), then one Newton step on 2^y = m: m 2^-y0 = 1 + d with |d| ~ 1e-7,
+// and log2(1 + d) = (d - d^2/2) log2(e) up to d^3.
+__device__ __forceinline__ double log2_d(double x) {
+  const int e = __builtin_amdgcn_frexp_exp(x);
+  const double m = __builtin_amdgcn_frexp_mant(x);                      // [0.5, 1)
+  const double y0 = static_cast<double>(__builtin_amdgcn_logf(static_cast<float>(m)));
+  const double d = fma(m, exp2_d(-y0), -1.0);
+  return static_cast<double>(e) + fma(d * fma(-0.5, d, 1.0), kLog2eD, y0);
+}
+
 // x * (ln x - max(ln y, ln 1e-30)) with 0 ln 0 = 0; the logarithms are passed in.
 __device__ __forceinline__ double xlogx_over_y(double x, double ln_x, double ln_y) {
   return (x > 0.0) ? x * (ln_x - fmax(ln_y, kLnTiny)) : 0.0;
 }
 
 // 1 - exp(t) for t <= 0 in float64, accurate when t -> 0.
-__device__ __forceinline__ double one_minus_exp(double t, float exp_t) {
+__device__ __forceinline__ double one_minus_exp(double t, double exp_t) {
   if (t > -0.0625) {
     const double u = t * (1.0 + t * (0.5 + t * (1.0 / 6 + t * (1.0 / 24 + t * (1.0 / 120 + t * (1.0 / 720))))));
     return -u;
   }
-  return 1.0 - static_cast<double>(exp_t);
+  return 1.0 - exp_t;
 }
 
 // Per-row inputs the epilogue needs besides the row statistics.  The kernels fetch them early
@@ -317,8 +361,9 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
   return t;
 }
 
-// Per-row epilogue, executed by ONE full wave (all 64 lanes call it with the same scalars).
-// The row statistics arrive in the base-2 domain the streaming passes work in:
+// ---- the per-row epilogue, in two parts -------------------------------------------------------
+// Executed by ONE full wave (all 64 lanes call both parts with the same scalars; lane k carries
+// top-K entry k).  The row statistics arrive in the base-2 domain the streaming passes work in:
 //   b      : offset (an integer-valued float) with z_j*log2e + b <= 0 for every j
 //   S_rest : sum over j != a_t of 2^(z_j*log2e + b).  The sampled token's own term is left out
 //            so that 1 - pi(a_t) = S_rest / S keeps full relative accuracy when pi(a_t) -> 1.
@@ -326,27 +371,103 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
 //            sum_j pi_j log2 pi_j = T/S - log2 S).
 // log2e is the fp32 constant kLog2e everywhere (passes and epilogue), so the probabilities
 // are mutually consistent; its rounding (1.3e-8 relative) acts as a temperature of 1+1.3e-8.
+//
+// row_pre  needs only the row's INPUTS (z[a_t], log mu(a_t), the lane's top-K entry), not its
+//          statistics: every exponential of the epilogue is taken here, as mantissa and integer
+//          exponent where the offset b is still to come (b is an integer: 2^(x + b) is an ldexp).
+//          A kernel that has those inputs early runs it in the shadow of the row's memory latency.
+// row_post needs the statistics: one logarithm and one reciprocal (two more logarithms for the KL
+//          forms), then ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv /
+//          topk_kl), mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad).
+//          It is the part the rest of the workgroup waits for.
+// row_store writes the per-token outputs (lane 0).
 // D_full : the exact full-vocabulary divergence, for the variants that gate on it (App. B).
-// Steps: ratio (Eq. ppo-clip), divergence (Eq. binary_tv / binary_kl / topk_tv / topk_kl),
-// mask and loss term (Eq. dppo_obj), gradient coefficient (Eq. unified_grad, C = infinity).
-// Lane 0 stores the per-token outputs; every lane returns the same RowResult.
-// Inlined into its caller; row_epilogue_call below is the same as a real call.
-__device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
-                                                  const uint16_t* zrow, float b, double S_rest, double T_rest, int lane,
-                                                  double D_full = 0.0) {
+
+// 2^x = m * 2^n with n = rint(x) and m = 2^(x - n) in [2^-1/2, 2^1/2]; x <= about -1e6 (or NaN)
+// gives m = 0, n = 0.
+struct Exp2Parts {
+  double m;
+  int n;
+};
+__device__ __forceinline__ Exp2Parts exp2_parts(double x) {
+  Exp2Parts r;
+  if (!(x > -1.0e6)) { r.m = 0.0; r.n = 0; return r; }
+  const double xc = fmin(x, 1.0e6);
+  const double n = __builtin_rint(xc);
+  r.m = exp2_d(xc - n);
+  r.n = static_cast<int>(n);
+  return r;
+}
+// m * 2^(n + b) for an integer-valued float b of any magnitude.
+__device__ __forceinline__ double scale_parts(Exp2Parts p, float b) {
+  const double e = fmin(fmax(static_cast<double>(p.n) + static_cast<double>(b), -4000.0), 4000.0);
+  return ldexp(p.m, static_cast<int>(e));
+}
+
+struct RowPre {
+  // uniform over the wave
+  Exp2Parts ea;        // 2^(z[a_t]*log2e)
+  double xa0;          // z[a_t]*log2e
+  double pa;           // mu(a_t) = exp(min(log mu(a_t), 0))
+  double inv_pa_raw;   // exp(-log mu(a_t)), for r = pi(a_t) / mu(a_t)
+  double lmu, lmu_raw; // min(log mu(a_t), 0) and the value as given
+  double A;            // advantage
+  // of this lane's top-K entry (valid: the entry exists and is not a_t)
+  bool valid;
+  Exp2Parts ek;        // 2^(z[id]*log2e)
+  double xk0;          // z[id]*log2e
+  double pk, lpk;      // mu(id) and min(log mu(id), 0)
+};
+
+__device__ __forceinline__ RowPre row_pre(RowScalars rs, TopkLane tk, bool topk) {
+  constexpr double kL = static_cast<double>(kLog2e);
+  RowPre q;
+  q.xa0 = static_cast<double>(rs.za) * kL;
+  q.ea = exp2_parts(q.xa0);
+  q.lmu_raw = static_cast<double>(rs.lmu);
+  q.lmu = fmin(q.lmu_raw, 0.0);
+  q.pa = exp2_d(q.lmu * kLog2eD);
+  q.inv_pa_raw = exp2_d(-q.lmu_raw * kLog2eD);
+  q.A = static_cast<double>(rs.adv);
+  q.valid = topk && tk.id >= 0;
+  q.xk0 = 0.0; q.pk = 0.0; q.lpk = 0.0;
+  q.ek.m = 0.0; q.ek.n = 0;
+  if (q.valid) {
+    q.lpk = fmin(static_cast<double>(tk.lp), 0.0);
+    q.pk = exp2_d(q.lpk * kLog2eD);
+    q.xk0 = static_cast<double>(tk.z) * kL;
+    q.ek = exp2_parts(q.xk0);
+  }
+  return q;
+}
+
+// What row_post leaves for row_store.
+struct RowOut {
+  float D, lt, r, lpi, abs_diff, H, mass_mu, mass_pi;
+  bool blocked;
+};
+
+// log2 of two positive values at once: lane 0 evaluates the first, every other lane the second.
+__device__ __forceinline__ void log2_pair(double x0, double x1, int lane, double& l0, double& l1) {
+  const double l = log2_d(lane == 0 ? x0 : x1);
+  const int hi = __double2hiint(l), lo = __double2loint(l);
+  l0 = __hiloint2double(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(lo, 0));
+  l1 = __hiloint2double(__builtin_amdgcn_readlane(hi, 1), __builtin_amdgcn_readlane(lo, 1));
+}
+
+template <typename P>
+__device__ __forceinline__ RowResult row_post(const P& p, int row, const RowPre& q, int a, const uint16_t* zrow, float b, double S_rest,
+                                              double T_rest, int lane, double D_full, RowOut& o) {
   constexpr double kL = static_cast<double>(kLog2e);
   const double bd = static_cast<double>(b);
-  const double xa = static_cast<double>(rs.za) * kL + bd;   // log2 of a_t's own term
-  const float ea = exp2_split(xa);
-  const double S = S_rest + static_cast<double>(ea);
-  const double log2S = log2_fast(S);
-  const float inv_S = 1.0f / static_cast<float>(S);
+  const double ea = scale_parts(q.ea, b);
+  const double S = S_rest + ea;
+  const double inv_S = 1.0 / S;
+  const double log2S = log2_d(S);
+  const double xa = q.xa0 + bd;
   const double lpi = (xa - log2S) * kLn2;
-  const double lmu_raw = static_cast<double>(rs.lmu);
-  const double lmu = fmin(lmu_raw, 0.0);
-  const float pa = exp2_split(lmu * kLog2eD);
-  const float qa = ea * inv_S;
-  const double one_minus_qa = static_cast<double>(static_cast<float>(S_rest) * inv_S);
+  const double pa = q.pa, qa = ea * inv_S;
+  const double one_minus_qa = S_rest * inv_S;
   const int variant = p.variant;
   double mass_mu = pa, mass_pi = qa;      // mass on A' (= {a_t} for the Binary variants)
   double D;
@@ -355,69 +476,77 @@ __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, R
     mass_mu = 1.0;
     mass_pi = 1.0;
   } else if (variant == kBinaryTV || (variant == kTopkTV && p.K == 0)) {
-    D = fabs(static_cast<double>(pa) - static_cast<double>(qa));
+    D = fabs(pa - qa);
   } else if (variant == kBinaryKL || (variant == kTopkKL && p.K == 0)) {
-    const double omp = one_minus_exp(lmu, pa);
-    D = xlogx_over_y(pa, lmu, lpi) +
-        xlogx_over_y(omp, log2_fast(fmax(omp, 1e-300)) * kLn2, log2_fast(fmax(one_minus_qa, 1e-300)) * kLn2);
+    const double omp = one_minus_exp(q.lmu, pa);
+    double l_omp, l_omq;
+    log2_pair(fmax(omp, 1e-300), fmax(one_minus_qa, 1e-300), lane, l_omp, l_omq);
+    D = xlogx_over_y(pa, q.lmu, lpi) + xlogx_over_y(omp, l_omp * kLn2, l_omq * kLn2);
   } else {
     // reduced distributions over TopK(mu, K) U {a_t} U {other}  (Sec. 4.4)
     const bool tv = (variant == kTopkTV);
     double sp = 0.0, sq = 0.0, acc = 0.0;
-    TopkLane t = tk;
-    for (int k = lane;;) {
+    if (q.valid) {
+      const double qk = scale_parts(q.ek, b) * inv_S;
+      sp = q.pk;
+      sq = qk;
+      acc = tv ? fabs(q.pk - qk) : xlogx_over_y(q.pk, q.lpk, (q.xk0 + bd - log2S) * kLn2);
+    }
+    for (int k = lane + kWave; k < p.K; k += kWave) {      // K > 64: further entries, fetched and evaluated here
+      const TopkLane t = load_topk_lane(p, row, a, zrow, k);
       if (t.id >= 0) {
         const double lpk = fmin(static_cast<double>(t.lp), 0.0);
         const double xk = static_cast<double>(t.z) * kL + bd - log2S;     // log2 pi(id)
-        const float pk = exp2_split(lpk * kLog2eD), qk = exp2_split(xk);
+        const double pk = exp2_d(lpk * kLog2eD), qk = exp2_d(xk);
         sp += pk;
         sq += qk;
-        acc += tv ? fabs(static_cast<double>(pk) - static_cast<double>(qk)) : xlogx_over_y(pk, lpk, xk * kLn2);
+        acc += tv ? fabs(pk - qk) : xlogx_over_y(pk, lpk, xk * kLn2);
       }
-      k += kWave;
-      if (k >= p.K) break;
-      t = load_topk_lane(p, row, rs.a, zrow, k);    // K > 64: further entries, fetched here
     }
     sp = wave_sum(sp) + pa;
     sq = wave_sum(sq) + qa;
     mass_mu = sp;
     mass_pi = sq;
-    acc = wave_sum(acc) + (tv ? fabs(static_cast<double>(pa) - static_cast<double>(qa)) : xlogx_over_y(pa, lmu, lpi));
+    acc = wave_sum(acc) + (tv ? fabs(pa - qa) : xlogx_over_y(pa, q.lmu, lpi));
     const double po = fmax(1.0 - sp, 0.0), qo = fmax(1.0 - sq, 0.0);
-    D = tv ? 0.5 * (acc + fabs(po - qo))
-           : acc + xlogx_over_y(po, log2_fast(fmax(po, 1e-300)) * kLn2, log2_fast(fmax(qo, 1e-300)) * kLn2);
+    if (tv) {
+      D = 0.5 * (acc + fabs(po - qo));
+    } else {
+      double l_po, l_qo;
+      log2_pair(fmax(po, 1e-300), fmax(qo, 1e-300), lane, l_po, l_qo);
+      D = acc + xlogx_over_y(po, l_po * kLn2, l_qo * kLn2);
+    }
   }
-  const double A = static_cast<double>(rs.adv);
+  const double A = q.A;
   // mask M_t: DPPO's divergence mask (Eq. dppo_obj), or one of the baselines' (App. C.1)
   bool blocked;
   if (p.mask_rule == 0) {
-    blocked = (D > static_cast<double>(p.delta)) && ((A > 0.0 && lpi > lmu_raw) || (A < 0.0 && lpi < lmu_raw));
+    blocked = (D > static_cast<double>(p.delta)) && ((A > 0.0 && lpi > q.lmu_raw) || (A < 0.0 && lpi < q.lmu_raw));
   } else if (p.mask_rule == 1) {
-    const double dl = lpi - lmu_raw;     // log r, compared with log(1 + eps_high) and log(1 - eps_low)
+    const double dl = lpi - q.lmu_raw;     // log r, compared with log(1 + eps_high) and log(1 - eps_low)
     blocked = (A > 0.0 && dl > log1p(static_cast<double>(p.eps_high))) || (A < 0.0 && dl < log1p(-static_cast<double>(p.eps_low)));
   } else {
     blocked = false;
   }
   const double M = blocked ? 0.0 : 1.0;
-  const double r = static_cast<double>(exp2_split((lpi - lmu_raw) * kLog2eD));
+  const double r = qa * q.inv_pa_raw;
   // weight min(r, C) of the unified gradient form (Eq. unified_grad); no cap for DPPO
   const double w = (p.ratio_cap > 0.f && r > static_cast<double>(p.ratio_cap)) ? static_cast<double>(p.ratio_cap) : r;
   const double lt = -M * w * A;
   const double c = static_cast<double>(p.loss_scale) * M * A * w;
-  if (lane == 0) {
-    p.divergence[row] = static_cast<float>(D);
-    p.mask[row] = blocked ? 0 : 1;
-    if (p.loss_tok) p.loss_tok[row] = static_cast<float>(lt);
-    if (p.diag) {
-      // token entropy: -sum pi ln pi = ln2 * (log2 S - T/S), T including a_t's own term
-      const double T = T_rest + ((ea > 0.f) ? static_cast<double>(ea) * xa : 0.0);
-      const double H = kLn2 * (log2S - T / S);
-      typedef float f32x4 __attribute__((ext_vector_type(4)));
-      f32x4* d = reinterpret_cast<f32x4*>(p.diag + static_cast<int64_t>(row) * 8);
-      d[0] = f32x4{static_cast<float>(r), static_cast<float>(lpi),
-                   static_cast<float>(fabs(static_cast<double>(pa) - static_cast<double>(qa))), static_cast<float>(fmax(H, 0.0))};
-      d[1] = f32x4{static_cast<float>(mass_mu), static_cast<float>(mass_pi), 0.f, 0.f};
-    }
+  o.D = static_cast<float>(D);
+  o.blocked = blocked;
+  o.lt = static_cast<float>(lt);
+  o.r = static_cast<float>(r);
+  o.lpi = static_cast<float>(lpi);
+  o.abs_diff = static_cast<float>(fabs(pa - qa));
+  o.mass_mu = static_cast<float>(mass_mu);
+  o.mass_pi = static_cast<float>(mass_pi);
+  o.H = 0.f;
+  if (p.diag) {
+    // token entropy: -sum pi ln pi = ln2 * (log2 S - T/S), T including a_t's own term
+    const double T = T_rest + ((ea > 0.0) ? ea * xa : 0.0);
+    o.H = static_cast<float>(fmax(kLn2 * (log2S - T * inv_S), 0.0));
   }
   RowResult res;
   res.loss_term = lt;
@@ -428,7 +557,35 @@ __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, R
   return res;
 }
 
-// The same epilogue as a real call.  Its float64 arithmetic needs some 50 registers; where
+template <typename P>
+__device__ __forceinline__ void row_store(const P& p, int row, const RowOut& o, int lane) {
+  if (lane == 0) {
+    p.divergence[row] = o.D;
+    p.mask[row] = o.blocked ? 0 : 1;
+    if (p.loss_tok) p.loss_tok[row] = o.lt;
+    if (p.diag) {
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      f32x4* d = reinterpret_cast<f32x4*>(p.diag + static_cast<int64_t>(row) * 8);
+      d[0] = f32x4{o.r, o.lpi, o.abs_diff, o.H};
+      d[1] = f32x4{o.mass_mu, o.mass_pi, 0.f, 0.f};
+    }
+  }
+}
+
+// Both parts and the stores back to back, for the kernels that have nothing to hide the first
+// part behind.  Every lane returns the same RowResult.
+__device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, RowScalars rs, TopkLane tk,
+                                                  const uint16_t* zrow, float b, double S_rest, double T_rest, int lane,
+                                                  double D_full = 0.0) {
+  const bool topk = (p.variant == kTopkTV || p.variant == kTopkKL) && p.K > 0;
+  const RowPre q = row_pre(rs, tk, topk);
+  RowOut o;
+  const RowResult res = row_post(p, row, q, rs.a, zrow, b, S_rest, T_rest, lane, D_full, o);
+  row_store(p, row, o, lane);
+  return res;
+}
+
+// The same epilogue as a real call.  Its float64 arithmetic needs many registers; where
 // several workgroups share a compute unit, keeping those out of the kernel's register budget
 // (the call saves and restores what it needs, in the one wave that makes it) buys occupancy,
 // and the other workgroups hide the call's latency.

@@ -132,9 +132,9 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
       {
         const double dd = static_cast<double>(bz - st.b), sc = static_cast<double>(fast_exp2(bz - st.b));
         const double scy = static_cast<double>(fast_exp2(by - cs.b));
-        const double sd = wave_sum(static_cast<double>(st.s) * sc);
-        const double td = wave_sum(sc * (static_cast<double>(st.t) + dd * static_cast<double>(st.s)));
-        const double sy = wave_sum(static_cast<double>(cs.s) * scy);
+        const double sd = wave_sum(st.s * sc);
+        const double td = wave_sum(sc * (static_cast<double>(st.t) + dd * st.s));
+        const double sy = wave_sum(cs.s * scy);
         const double uy = wave_sum(static_cast<double>(cs.u) * scy);
         if (lane == 0) { sh_sz[wid] = sd; sh_tz[wid] = td; sh_sy[wid] = sy; sh_uy[wid] = uy; }
       }
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
 #pragma unroll
       for (int w = 0; w < NW; ++w) { S_rest += sh_sz[w]; T_rest += sh_tz[w]; Sy += sh_sy[w]; Uy += sh_uy[w]; }
       const double xa = static_cast<double>(z_a) * static_cast<double>(kLog2e) + static_cast<double>(bz);
-      const double S = S_rest + static_cast<double>(exp2_split(xa));
+      const double S = S_rest + exp2_d(xa);
       double D;
       if (TV) {
         // ---- pass 2: TV = 1/2 sum |pi_j - mu_j| = 1 - sum_j min(pi_j, mu_j) -------------------
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         // z_j*log2e + b - log2 S.  The integer part of log2 S goes into the (integer) offset, which
         // stays exact, and only the fraction in [0, 1) is subtracted in fp32, so a probability
         // keeps a relative error of about 1e-7 however large the offset is.
-        const double l2z = log2_fast(S), l2y = log2_fast(Sy);
+        const double l2z = log2_d(S), l2y = log2_d(Sy);
         const double nz = floor(l2z), ny = floor(l2y);
         const float bz2 = bz - static_cast<float>(nz), by2 = by - static_cast<float>(ny);
         const float fz = static_cast<float>(l2z - nz), fy = static_cast<float>(l2y - ny);
@@ -172,13 +172,14 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
           __syncthreads();
           rc1 = sh_rc;
         }
-        float acc0 = 0.f, acc1 = 0.f;
-        auto min8 = [&](const u32x4& zq, const u32x4& yq, float& acc) {
-          float z[8], y[8];
+        double acc0 = 0.0, acc1 = 0.0;
+        auto min8 = [&](const u32x4& zq, const u32x4& yq, double& acc) {
+          float z[8], y[8], m[8];
           unpack8(zq, z);
           unpack8(yq, y);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc += fast_exp2(fminf(fmaf(z[i], kLog2e, bz2) - fz, fmaf(y[i], kLog2e, by2) - fy));
+          for (int i = 0; i < 8; ++i) m[i] = fast_exp2(fminf(fmaf(z[i], kLog2e, bz2) - fz, fmaf(y[i], kLog2e, by2) - fy));
+          acc += static_cast<double>(sum8(m));      // eight entries among themselves, then into float64
         };
         const bool write_grad = GRAD && rc1.coef != 0.f;
         int v2 = tid;
@@ -200,14 +201,14 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         }
         for (int e = tid; e < nscalar; e += THREADS) {
           const int j = (e < head) ? e : tail0 + (e - head);
-          acc1 += fast_exp2(fminf(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, bz2) - fz, fmaf(bf16_bits_to_float(yrow[j]), kLog2e, by2) - fy));
+          acc1 += static_cast<double>(fast_exp2(fminf(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, bz2) - fz, fmaf(bf16_bits_to_float(yrow[j]), kLog2e, by2) - fy)));
           if (write_grad) grad_scalar(j, rc1);
         }
         if (GRAD) {
           if (!write_grad) zero_row();
           grad_written = true;
         }
-        const double wa = wave_sum(static_cast<double>(acc0) + static_cast<double>(acc1));
+        const double wa = wave_sum(acc0 + acc1);
         if (lane == 0) sh_acc[wid] = wa;
         __syncthreads();
         double tot = 0.0;
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         if (tot != tot) D = tot;                  // NaN logits propagate
       } else {
         // KL = E_mu[y - z] - lse(y) + lse(z), the log-sum-exps in base 2 against their offsets
-        const double lse2_z = log2_fast(S) - static_cast<double>(bz), lse2_y = log2_fast(Sy) - static_cast<double>(by);
+        const double lse2_z = log2_d(S) - static_cast<double>(bz), lse2_y = log2_d(Sy) - static_cast<double>(by);
         D = Uy / Sy + kLn2 * (lse2_z - lse2_y);
         D = (D > 0.0 || D != D) ? D : 0.0;       // rounding can leave -1e-8 for identical rows
       }

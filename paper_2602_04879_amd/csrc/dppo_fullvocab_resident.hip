@@ -36,24 +36,27 @@ constexpr int kKeep = 18;         // TV form: chunks of y kept in LDS between th
 // cross term of the KL form (a vanished term adds nothing even where the other row is -inf too).
 template <bool T, bool U>
 struct RowStat {
-  float b = 3.0e38f, s = 0.f, t = 0.f, u = 0.f;
+  float b = 3.0e38f, t = 0.f, u = 0.f;
+  double s = 0.0;      // float64, fed with fp32 sums of eight entries (see sum8)
   __device__ __forceinline__ void cover(float vmax) {
     const float bn = fminf(b, -ceilf(fmaxf(vmax, kNegBig) * kLog2e));
     const float d = bn - b, sc = fast_exp2(d);
-    if (T) t = sc * fmaf(d, s, t);
+    if (T) t = sc * fmaf(d, static_cast<float>(s), t);
     if (U) u *= sc;
-    s *= sc;
+    s *= static_cast<double>(sc);
     b = bn;
   }
   __device__ __forceinline__ void add8(const float (&v)[8], const float (&other)[8]) {
     cover(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))));
+    float e[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float x = fmaf(v[i], kLog2e, b), e = fast_exp2(x);
-      s += e;
-      if (T) t = fma_ex(e, x, t);
-      if (U) u = fmaf(e, fminf(fmaxf(v[i] - other[i], -3.0e38f), 3.0e38f), u);     // NaN (-inf - -inf) -> -3e38, times e = 0
+      const float x = fmaf(v[i], kLog2e, b);
+      e[i] = fast_exp2(x);
+      if (T) t = fma_ex(e[i], x, t);
+      if (U) u = fmaf(e[i], fminf(fmaxf(v[i] - other[i], -3.0e38f), 3.0e38f), u);     // NaN (-inf - -inf) -> -3e38, times e = 0
     }
+    s += static_cast<double>(sum8(e));
   }
 };
 
@@ -167,9 +170,9 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
       {
         const double dd = static_cast<double>(bz - st.b), sc = static_cast<double>(fast_exp2(bz - st.b));
         const double scy = static_cast<double>(fast_exp2(by - cs.b));
-        const double sd = wave_sum(static_cast<double>(st.s) * sc);
-        const double td = DIAG ? wave_sum(sc * (static_cast<double>(st.t) + dd * static_cast<double>(st.s))) : 0.0;
-        const double sy = wave_sum(static_cast<double>(cs.s) * scy);
+        const double sd = wave_sum(st.s * sc);
+        const double td = DIAG ? wave_sum(sc * (static_cast<double>(st.t) + dd * st.s)) : 0.0;
+        const double sy = wave_sum(cs.s * scy);
         const double uy = TV ? 0.0 : wave_sum(static_cast<double>(cs.u) * scy);
         if (lane == 0) { sh_sz[wid] = sd; sh_tz[wid] = td; sh_sy[wid] = sy; sh_uy[wid] = uy; }
       }
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
 #pragma unroll
       for (int w = 0; w < NW; ++w) { S_rest += sh_sz[w]; T_rest += sh_tz[w]; Sy += sh_sy[w]; Uy += sh_uy[w]; }
       const double xa = static_cast<double>(z_a) * static_cast<double>(kLog2e) + static_cast<double>(bz);
-      const double S = S_rest + static_cast<double>(exp2_split(xa));
+      const double S = S_rest + exp2_d(xa);
       double D;
       if (TV) {
         // ---- pass 2: TV = 1/2 sum |pi_j - mu_j| = 1 - sum_j min(pi_j, mu_j) -----------------------
@@ -187,11 +190,11 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         // z_j*log2e + b - log2 S.  The integer part of log2 S goes into the (integer) offset, which
         // stays exact, and only the fraction in [0, 1) is subtracted in fp32, so a probability
         // keeps a relative error of about 1e-7 however large the offset is.
-        const double l2z = log2_fast(S), l2y = log2_fast(Sy);
+        const double l2z = log2_d(S), l2y = log2_d(Sy);
         const double nz = floor(l2z), ny = floor(l2y);
         const float bz2 = bz - static_cast<float>(nz), by2 = by - static_cast<float>(ny);
         const float fz = static_cast<float>(l2z - nz), fy = static_cast<float>(l2y - ny);
-        float acc0 = 0.f, acc1 = 0.f;
+        double acc0 = 0.0, acc1 = 0.0;
 #pragma unroll
         for (int i = 0; i < NCHUNK; ++i) {
           asm volatile("" : "+v"(buf[i]));     // unpack again here: nothing unpacked in pass 1 is kept alive
@@ -207,9 +210,11 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
           float z[8], y[8];
           unpack8(zq, z);
           unpack8(yq, y);
-          float& acc = (i & 1) ? acc1 : acc0;
+          double& acc = (i & 1) ? acc1 : acc0;
+          float m[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc += fast_exp2(fminf(fmaf(z[e], kLog2e, bz2) - fz, fmaf(y[e], kLog2e, by2) - fy));
+          for (int e = 0; e < 8; ++e) m[e] = fast_exp2(fminf(fmaf(z[e], kLog2e, bz2) - fz, fmaf(y[e], kLog2e, by2) - fy));
+          acc += static_cast<double>(sum8(m));      // eight entries among themselves, then into float64
           asm volatile("" : "+v"(acc0), "+v"(acc1));
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
           for (int i = 0; i < kWindow; ++i) yb[i] = row_load16<kY1Nt>(yn, voff, i * kStride);
           __builtin_amdgcn_sched_barrier(0);
         }
-        const double wa = wave_sum(static_cast<double>(acc0) + static_cast<double>(acc1));
+        const double wa = wave_sum(acc0 + acc1);
         if (lane == 0) sh_acc[wid] = wa;
         __syncthreads();
         double tot = 0.0;
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         if (tot != tot) D = tot;                  // NaN logits propagate
       } else {
         // KL = E_mu[y - z] - lse(y) + lse(z), the log-sum-exps in base 2 against their offsets
-        const double lse2_z = log2_fast(S) - static_cast<double>(bz), lse2_y = log2_fast(Sy) - static_cast<double>(by);
+        const double lse2_z = log2_d(S) - static_cast<double>(bz), lse2_y = log2_d(Sy) - static_cast<double>(by);
         D = Uy / Sy + kLn2 * (lse2_z - lse2_y);
         D = (D > 0.0 || D != D) ? D : 0.0;       // rounding can leave -1e-8 for identical rows
       }

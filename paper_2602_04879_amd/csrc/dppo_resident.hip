@@ -39,13 +39,13 @@ __device__ __forceinline__ u32x4 patch16(u32x4 v, int sub, uint32_t bits) {
   return r;
 }
 
-// One packed word (two bf16) into the running sums: s += e, t += e*x with x = z*log2e + b and
+// One packed word (two bf16): returns e0 + e1 and adds e*x to t, with x = z*log2e + b and
 // e = 2^x (t feeds the entropy; a vanished term, e = 0 with x = -inf, adds nothing).
-__device__ __forceinline__ void accum2(uint32_t w, float b, float& s, float& t) {
+__device__ __forceinline__ float accum2(uint32_t w, float b, float& t) {
   const float x0 = fmaf(__uint_as_float(w << 16), kLog2e, b), x1 = fmaf(__uint_as_float(w & 0xffff0000u), kLog2e, b);
   const float e0 = fast_exp2(x0), e1 = fast_exp2(x1);
-  s += e0 + e1;
   t = fma_ex(e0, x0, fma_ex(e1, x1, t));
+  return e0 + e1;
 }
 
 // 2^(z*log2e + k) for the two bf16 halves of a packed word.
@@ -174,8 +174,11 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // were loaded first, so their arithmetic hides the latency of the chunks requested last.
       s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
       float b = 3.0e38f;                       // "+infinity": nothing seen yet
-      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;      // sum e*x, same offset as s
+      // The sum is kept in float64 and fed with the fp32 sum of each group's exponentials (summed
+      // pairwise among themselves): a thread that has met a dominant entry then does not drop the
+      // small ones that follow it, as an fp32 accumulator would.
+      double sd = 0.0;
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;      // sum e*x, same offset as the sum
 #pragma unroll
       for (int g0 = 0; g0 < NCHUNK; g0 += GC) {
         // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
@@ -213,23 +216,27 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         // moving the offset by d: e -> e*2^d, x -> x + d, so s -> 2^d s and t -> 2^d (t + d s)
         const float d = bn - b;
         const float sc = fast_exp2(d);            // 1 when the maximum did not move
-        if (DIAG) { t0 = sc * fmaf(d, s0, t0); t1 = sc * fmaf(d, s1, t1); t2 = sc * fmaf(d, s2, t2); t3 = sc * fmaf(d, s3, t3); }
-        s0 *= sc; s1 *= sc; s2 *= sc; s3 *= sc;
+        if (DIAG) { t0 = sc * fmaf(d, static_cast<float>(sd), t0); t1 *= sc; t2 *= sc; t3 *= sc; }
         b = bn;
+        float gs = 0.f;
 #pragma unroll
         for (int i = 0; i < GC; ++i) {
+          float px, py, pz, pw;
           if (DIAG) {
-            accum2(v[i].x, b, s0, t0);
-            accum2(v[i].y, b, s1, t1);
-            accum2(v[i].z, b, s2, t2);
-            accum2(v[i].w, b, s3, t3);
+            px = accum2(v[i].x, b, t0);
+            py = accum2(v[i].y, b, t1);
+            pz = accum2(v[i].z, b, t2);
+            pw = accum2(v[i].w, b, t3);
           } else {
-            s0 += exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
-            s1 += exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
-            s2 += exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
-            s3 += exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
+            px = exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
+            py = exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
+            pz = exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
+            pw = exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
           }
+          const float c = (px + py) + (pz + pw);
+          gs = (i == 0) ? c : gs + c;
         }
+        sd = fma(sd, static_cast<double>(sc), static_cast<double>(gs));
         __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
         // Forward only: nothing needs the row after its statistics, so the first part of the
         // registers is refilled from the next row as soon as it has been consumed.  Those loads
@@ -244,12 +251,21 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // wave-level combine: common offset = the smallest one, rescaling is exact
       const float bw = -wave_max(-b);
       const double dw = static_cast<double>(bw - b), scw = static_cast<double>(fast_exp2(bw - b));
-      const double st = static_cast<double>((s0 + s1) + (s2 + s3)), tt = static_cast<double>((t0 + t1) + (t2 + t3));
+      const double st = sd, tt = static_cast<double>((t0 + t1) + (t2 + t3));
       const double sw = wave_sum(st * scw);
       const double tw = DIAG ? wave_sum(scw * (tt + dw * st)) : 0.0;
       if (lane == 0) { sh_b[par][wid] = bw; sh_s[par][wid] = sw; sh_t[par][wid] = tw; }
+      // Wave 0: the part of the epilogue that needs the row's inputs only (every exponential),
+      // before the barrier: the other waves are still on their way to it.
+      // Shapes whose row data alone leaves room for one workgroup per compute unit: nothing
+      // hides a call there, so the epilogue is inlined, in its two parts.  The shorter shapes keep
+      // the call and with it the second or third workgroup per compute unit.
+      constexpr bool kInlineEpilogue = (THREADS == 512 && NCHUNK >= (GRAD ? 16 : 28));
+      RowPre pre;
+      if (kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------
+      RowOut ro;
       if (wid == 0) {
         // the offset must also cover z[a_t], whose own term the epilogue adds
         float bb = -ceilf(fmaxf(rs.za, kNegBig) * kLog2e);
@@ -260,19 +276,16 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         for (int w = 0; w < NW; ++w) {
           const double dd = static_cast<double>(bb - sh_b[par][w]), sc = static_cast<double>(fast_exp2(bb - sh_b[par][w]));   // exact power of two
           S_rest += sh_s[par][w] * sc;
-          T_rest += sc * (sh_t[par][w] + dd * sh_s[par][w]);
+          if (DIAG) T_rest += sc * (sh_t[par][w] + dd * sh_s[par][w]);
         }
-        // Shapes whose row data alone leaves room for one workgroup per compute unit: nothing
-        // hides a call there, so the epilogue is inlined.  The shorter shapes keep the call and
-        // with it the second or third workgroup per compute unit.
-        // The row index goes through an empty asm statement first, so that the addresses of the
-        // per-token outputs are formed here and not hoisted to the top of the row, where they
-        // would sit in registers (or be spilled) across the streaming phases.
-        constexpr bool kInlineEpilogue = (THREADS == 512 && NCHUNK >= (GRAD ? 16 : 28));
-        int row_e = row;
-        asm volatile("" : "+s"(row_e));
-        const RowResult rr = kInlineEpilogue ? row_epilogue(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane)
-                                             : row_epilogue_call(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane);
+        RowResult rr;
+        if (kInlineEpilogue) {
+          rr = row_post(ep, row, pre, a, zrow, bb, S_rest, T_rest, lane, 0.0, ro);
+        } else {
+          int row_e = row;
+          asm volatile("" : "+s"(row_e));
+          rr = row_epilogue_call(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane);
+        }
         rc = rr.rc;
         loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
@@ -283,6 +296,14 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         rc.coef = uniform_f(sh_rc.coef);
         rc.kexp = uniform_f(sh_rc.kexp);
         rc.g_a = uniform_f(sh_rc.g_a);
+      }
+      // The per-token outputs leave after the other waves have been released.  The row index goes
+      // through an empty asm statement first, so that the output addresses are formed here and not
+      // hoisted to the top of the row, where they would sit in registers across the streaming phases.
+      if (kInlineEpilogue && wid == 0) {
+        int row_e = row;
+        asm volatile("" : "+s"(row_e));
+        row_store(ep, row_e, ro, lane);
       }
     } else if (tid == 0) {
       p.divergence[row] = 0.f;

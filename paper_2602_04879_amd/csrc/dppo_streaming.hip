@@ -75,8 +75,8 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
 #pragma unroll
       for (int w = 1; w < NW; ++w) b = fminf(b, sh_max[w]);
       const double dd = static_cast<double>(b - st.b), sc = static_cast<double>(fast_exp2(b - st.b));
-      const double sd = wave_sum(static_cast<double>(st.s) * sc);
-      const double td = wave_sum(sc * (static_cast<double>(st.t) + dd * static_cast<double>(st.s)));
+      const double sd = wave_sum(st.s * sc);
+      const double td = wave_sum(sc * (static_cast<double>(st.t) + dd * st.s));
       if (lane == 0) { sh_sum[wid] = sd; sh_tsum[wid] = td; }
       __syncthreads();
       // ---- epilogue on wave 0 -----------------------------------------------------------

@@ -1,16 +1,18 @@
 """Element-by-element comparison of the HIP path with the float64 oracle.
 
-Tolerances (the absolute terms are what fp32 accumulation of V terms leaves on a probability):
-  divergence : |gpu - ref| <= 1e-4 |ref| + 1e-6
-  loss_tok   : |gpu - ref| <= 1e-4 |ref| + 1e-6 |A|   (compared under the GPU's own mask for
+Tolerances (relative 1e-4; the absolute term 1e-7 is on the probability scale and only matters
+where pi ~ mu makes the divergence itself that small):
+  divergence : |gpu - ref| <= 1e-4 |ref| + 1e-7     (the exact full-vocabulary variants, whose
+               divergence is a sum over all V entries in fp32: 3e-7, see ATOL_D_FULL)
+  loss_tok   : |gpu - ref| <= 1e-4 |ref| + 1e-7 |A|   (compared under the GPU's own mask for
                tokens inside the exemption band)
-  loss       : |gpu - ref| <= 1e-4 |ref| + 1e-6 * loss_scale * sum|A|
+  loss       : |gpu - ref| <= 1e-4 |ref| + 1e-7 * loss_scale * sum|A|
   mask       : bit-exact, except tokens with |D_ref - delta| < 1e-6 or, where the divergence can
                exceed delta while r is at 1 (Top-K and full-vocabulary variants),
                |log pi(a) - log mu(a)| < 1e-6;
                under the ratio-clip rule, except tokens with log r within 1e-6 of a clip boundary
-  diagnostics: ratio 1e-4 rel; log pi(a) 1e-6 rel + 5e-6; |pi - mu| and covered masses 1e-6;
-               entropy 1e-4 rel + 1e-5
+  diagnostics: ratio 1e-4 rel; log pi(a) 1e-6 rel + 1e-6; |pi - mu| 1e-7; covered masses 2e-7 (fp32
+               outputs near 1 carry 6e-8 of rounding by themselves); entropy 1e-4 rel + 1e-5
   grad_logits: |gpu - ref| <= 1e-2 |ref| + 1e-30   (bf16 output, round to nearest even); the
                sampled token's entry also gets the oracle's own float64 cancellation error
 """
@@ -21,7 +23,12 @@ import torch
 
 from oracle import dppo_oracle as O
 
-RTOL_D, ATOL_D = 1e-4, 1e-6
+RTOL_D, ATOL_D = 1e-4, 1e-7
+# Exact full-vocabulary TV / KL: the divergence itself is accumulated over all V entries in fp32
+# with one hardware exponential per entry (relative error about 1e-7 each, common-mode part from
+# the fp32 fraction of log2 S about 3e-8), so its absolute error is bounded by about 2e-7 of the
+# total mass 1; 3e-7 leaves a margin of 1.5.
+ATOL_D_FULL = 3e-7
 RTOL_G, ATOL_G = 1e-2, 1e-30
 BAND = 1e-6
 
@@ -58,7 +65,8 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
     with np.errstate(invalid="ignore"):
         errD = np.where(D == ref["divergence"], 0.0, np.abs(D - ref["divergence"]))      # equal infinities agree
     finite_ref = np.where(np.isfinite(ref["divergence"]), np.abs(ref["divergence"]), 0.0)
-    assert np.all(errD <= RTOL_D * finite_ref + ATOL_D), \
+    atol_d = ATOL_D_FULL if batch["variant"] in (O.FULL_TV, O.FULL_KL) else ATOL_D
+    assert np.all(errD <= RTOL_D * finite_ref + atol_d), \
         f"divergence: max err {errD.max():.3e} at row {rows[errD.argmax()]}"
     rule = batch.get("rule", {})
     mask_rule = rule.get("mask_rule", O.MASK_DIVERGENCE)
@@ -79,7 +87,7 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
         lt = res["loss_tok"][loc].double().cpu().numpy()
         lt_ref = np.where(M == ref["mask"], ref["loss_tok"], -M * ref["weight"] * A)
         errL = np.abs(lt - lt_ref)
-        assert np.all(errL <= RTOL_D * np.abs(lt_ref) + 1e-6 * np.abs(A)), f"loss_tok: max err {errL.max():.3e}"
+        assert np.all(errL <= RTOL_D * np.abs(lt_ref) + ATOL_D * np.abs(A)), f"loss_tok: max err {errL.max():.3e}"
     stats = {"max_abs_err_D": float(errD.max()) if len(rows) else 0.0, "masked": int((M == 0).sum()),
              "exempt": int(exempt.sum()), "rows": int(len(rows))}
 
@@ -87,8 +95,8 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
         dg = res["diagnostics"][loc].double().cpu().numpy()
         live = (np.asarray(ref["logp"]) != 0) | (np.asarray(ref["ratio"]) != 0)      # ignored rows: all zeros
         assert np.all(dg[~live] == 0)
-        checks = (("ratio", 0, 1e-4, 1e-7), ("logp", 1, 1e-6, 5e-6), ("abs_diff", 2, 0.0, 1e-6),
-                  ("entropy", 3, 1e-4, 1e-5), ("mass_mu", 4, 0.0, 1e-6), ("mass_pi", 5, 0.0, 1e-6))
+        checks = (("ratio", 0, 1e-4, 1e-7), ("logp", 1, 1e-6, 1e-6), ("abs_diff", 2, 0.0, 1e-7),
+                  ("entropy", 3, 1e-4, 1e-5), ("mass_mu", 4, 0.0, 2e-7), ("mass_pi", 5, 0.0, 2e-7))
         for name, col, rtol, atol in checks:
             got, want = dg[live, col], np.asarray(ref[name], dtype=np.float64)[live]
             with np.errstate(invalid="ignore"):
@@ -143,4 +151,4 @@ def check_loss_scalar(batch: dict, res: dict, ref_loss_tok_sum: float | None = N
     assert abs(got - want) <= 2e-6 * abs(want) + 1e-7 * batch["loss_scale"] * (A_abs or 1.0) + 1e-12, (got, want)
     if ref_loss_tok_sum is not None:
         ref = batch["loss_scale"] * ref_loss_tok_sum
-        assert abs(got - ref) <= 1e-4 * abs(ref) + 1e-6 * batch["loss_scale"] * (A_abs or 1.0), (got, ref)
+        assert abs(got - ref) <= 1e-4 * abs(ref) + ATOL_D * batch["loss_scale"] * (A_abs or 1.0), (got, ref)
