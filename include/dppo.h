@@ -28,7 +28,7 @@
  * outputs and the workspace, must stay valid until the work enqueued on `stream` has finished.
  * The library allocates nothing, never synchronises and never touches another stream; every
  * kernel is enqueued on `stream` (a hipStream_t passed as void*; NULL = the legacy default
- * stream) and the call returns at once.  The return value reports host-side argument checks
+ * stream; it must belong to the current device) and the call returns at once.  The return value reports host-side argument checks
  * and launch errors only.  Results are bitwise reproducible for identical arguments on the
  * same device.
  */
@@ -164,6 +164,25 @@ dppo_status_t dppo_loss_fwd(const dppo_args_t* args, void* stream);
  * grad_logits.  (Eq. dppo_obj for the loss, Eq. unified_grad with C = infinity for the
  * gradient.) */
 dppo_status_t dppo_loss_fwd_bwd(const dppo_args_t* args, void* stream);
+
+/* For callers that cannot allocate or pass device scratch (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): dppo_loss_fwd_bwd with the partial sums of the
+ * loss kept in a static device array of DPPO_STATIC_SCRATCH_BYTES that the library itself holds on
+ * every GPU it runs on, from load until the process ends.  `workspace` / `workspace_bytes` are
+ * ignored (may be NULL / 0); inputs and outputs are passed as usual; the call allocates nothing
+ * and clears nothing (every partial sum it reads it has written).  Limits and errors beyond
+ * those of dppo_loss_fwd_bwd: T <= DPPO_STATIC_MAX_T, else DPPO_ERR_SHAPE; `stream` must belong
+ * to the CURRENT device, else DPPO_ERR_LAUNCH; DPPO_ERR_WORKSPACE if the runtime yields no
+ * address for the array.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU (different streams, or a replaying graph beside eager calls) race on it and
+ * return wrong losses; serialise them or use dppo_loss_fwd_bwd with distinct workspaces.  The
+ * array's address is looked up on the first call on a device, or by dppo_static_init() -- call
+ * that once per device, with the device current and outside any stream capture, if the first
+ * call would otherwise fall inside a capture. */
+#define DPPO_STATIC_SCRATCH_BYTES 65536
+#define DPPO_STATIC_MAX_T (1 << 22)
+dppo_status_t dppo_loss_fwd_bwd_static(const dppo_args_t* args, void* stream);
+dppo_status_t dppo_static_init(void);
 
 /* Static, NUL-terminated description of a status code. */
 const char* dppo_status_str(dppo_status_t status);

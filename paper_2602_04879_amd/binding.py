@@ -69,7 +69,9 @@ def lib() -> C.CDLL:
         l = C.CDLL(_LIB_PATH)
         l.dppo_workspace_bytes.restype = C.c_size_t
         l.dppo_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32]
-        for f in (l.dppo_loss_fwd, l.dppo_loss_fwd_bwd):
+        l.dppo_static_init.restype = C.c_int
+        l.dppo_static_init.argtypes = []
+        for f in (l.dppo_loss_fwd, l.dppo_loss_fwd_bwd, l.dppo_loss_fwd_bwd_static):
             f.restype = C.c_int
             f.argtypes = [C.POINTER(DppoArgs), C.c_void_p]
         l.dppo_status_str.restype = C.c_char_p
@@ -172,6 +174,13 @@ def dppo_loss_fwd(args: DppoArgs, stream=None) -> None:
 def dppo_loss_fwd_bwd(args: DppoArgs, stream=None) -> None:
     """dppo_loss_fwd_bwd of include/dppo.h on `stream` (default: torch's current stream)."""
     st = lib().dppo_loss_fwd_bwd(C.byref(args), C.c_void_p(_stream_handle(stream)))
+    if st != 0:
+        raise DppoError(st)
+
+
+def dppo_loss_fwd_bwd_static(args: DppoArgs, stream=None) -> None:
+    """dppo_loss_fwd_bwd_static of include/dppo.h: no workspace, nothing allocated."""
+    st = lib().dppo_loss_fwd_bwd_static(C.byref(args), C.c_void_p(_stream_handle(stream)))
     if st != 0:
         raise DppoError(st)
 

@@ -9,7 +9,27 @@
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 
+// Scratch of dppo_loss_fwd_bwd_static: the per-workgroup partial sums of the loss, in device memory
+// that every GPU the library runs on holds from the moment the library is loaded there.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address it yields (one per
+// GPU) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[DPPO_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on device `dev`, which must be the current device; asked of the
+// runtime once per device.  nullptr if the runtime refuses.
+void* static_scratch(int dev) {
+  static void* ptr[64];
+  static std::once_flag once[64];
+  if (dev < 0 || dev >= 64) return nullptr;
+  std::call_once(once[dev], [dev]() {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess) q = nullptr;
+    ptr[dev] = q;
+  });
+  return ptr[dev];
+}
 
 struct DeviceInfo {
   int cus = 0;
@@ -54,7 +74,7 @@ int resident_blocks_per_cu_cached(int dev, bool grad, int threads, int chunks) {
 
 thread_local const char* g_last_path = "none";
 
-dppo_status_t check_args(const dppo_args_t* a, bool grad) {
+dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = false) {
   if (!a) return DPPO_ERR_NULL;
   if (a->T < 0 || a->V < 1 || a->ld < a->V || a->V >= (int64_t(1) << 31) || a->T >= (int64_t(1) << 31)) return DPPO_ERR_SHAPE;
   if (a->variant < DPPO_BINARY_TV || a->variant > DPPO_FULL_KL) return DPPO_ERR_VARIANT;
@@ -65,8 +85,10 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad) {
   if (std::isnan(a->delta) || std::isnan(a->loss_scale) || std::isnan(a->ratio_cap)) return DPPO_ERR_VALUE;
   if (a->mask_rule < DPPO_MASK_DIVERGENCE || a->mask_rule > DPPO_MASK_NONE) return DPPO_ERR_VALUE;
   if (a->mask_rule == DPPO_MASK_RATIO_CLIP && !(a->eps_low >= 0.f && a->eps_low < 1.f && a->eps_high >= 0.f)) return DPPO_ERR_VALUE;
-  if (!a->workspace || a->workspace_bytes < dppo_workspace_bytes(a->T, a->V, a->K)) return DPPO_ERR_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
+  if (!own_scratch) {
+    if (!a->workspace || a->workspace_bytes < dppo_workspace_bytes(a->T, a->V, a->K)) return DPPO_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
+  }
   if (a->T > 0) {
     if (!a->logits || !a->sampled_ids || !a->mu_logp || !a->advantages || !a->divergence || !a->mask) return DPPO_ERR_NULL;
     if (grad && !a->grad_logits) return DPPO_ERR_NULL;
@@ -178,6 +200,25 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
   double* partial = static_cast<double*>(a->workspace);
   int nparts = 0;
   st = launch_loss(a, grad, partial, static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double)), &nparts, s);
+  if (st != DPPO_OK) return st;
+  if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  return DPPO_OK;
+}
+
+// The same call with the partial sums in the library's own static device array instead of the
+// caller's workspace: nothing is allocated, here or by the caller.
+dppo_status_t run_static(const dppo_args_t* a, void* stream) {
+  dppo_status_t st = check_args(a, true, true);
+  if (st != DPPO_OK) return st;
+  if (a->T > DPPO_STATIC_MAX_T) return DPPO_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int cur = 0, dev = 0;
+  if (hipGetDevice(&cur) != hipSuccess || !stream_device(s, &dev)) return DPPO_ERR_LAUNCH;
+  if (dev != cur) return DPPO_ERR_LAUNCH;          // each GPU has its own copy of the array: the current one's is used
+  double* partial = static_cast<double*>(static_scratch(cur));
+  if (!partial) return DPPO_ERR_WORKSPACE;
+  int nparts = 0;
+  st = launch_loss(a, true, partial, static_cast<int>(DPPO_STATIC_SCRATCH_BYTES / sizeof(double)), &nparts, s);
   if (st != DPPO_OK) return st;
   if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
   return DPPO_OK;
@@ -296,16 +337,24 @@ dppo_status_t dppo_loss_fwd(const dppo_args_t* args, void* stream) { return run(
 
 dppo_status_t dppo_loss_fwd_bwd(const dppo_args_t* args, void* stream) { return run(args, stream, true); }
 
+dppo_status_t dppo_loss_fwd_bwd_static(const dppo_args_t* args, void* stream) { return run_static(args, stream); }
+
+dppo_status_t dppo_static_init(void) {
+  int cur = 0;
+  if (hipGetDevice(&cur) != hipSuccess) return DPPO_ERR_LAUNCH;
+  return static_scratch(cur) ? DPPO_OK : DPPO_ERR_WORKSPACE;
+}
+
 const char* dppo_status_str(dppo_status_t status) {
   switch (status) {
     case DPPO_OK: return "ok";
     case DPPO_ERR_NULL: return "a required pointer is NULL";
-    case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld (and <= mu_ld for DPPO_FULL_*), T and V below 2^31";
+    case DPPO_ERR_SHAPE: return "bad shape: need T >= 0, 1 <= V <= ld (and <= mu_ld for DPPO_FULL_*), T and V below 2^31 (T <= DPPO_STATIC_MAX_T for dppo_loss_fwd_bwd_static)";
     case DPPO_ERR_ALIGN: return "misaligned pointer: bf16 buffers need 2-byte, workspace 8-byte, diagnostics 16-byte alignment";
     case DPPO_ERR_VARIANT: return "variant is not one of DPPO_BINARY_TV/KL, DPPO_TOPK_TV/KL, DPPO_FULL_TV/KL";
     case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
-    case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes()";
-    case DPPO_ERR_LAUNCH: return "HIP kernel launch failed";
+    case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes() (dppo_loss_fwd_bwd_static: the static scratch array has no device address)";
+    case DPPO_ERR_LAUNCH: return "HIP kernel launch failed (or the stream does not belong to the current device)";
     case DPPO_ERR_VALUE: return "bad value: NaN delta / loss_scale / ratio_cap, unknown mask_rule, or clip range outside 0 <= eps_low < 1, eps_high >= 0";
   }
   return "unknown status";
