@@ -233,6 +233,7 @@ def main() -> int:
     ap.add_argument("--ratio-cap", type=float, default=0.0, help="C of the unified gradient form (0: no cap)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits (the boundary allows it); the logits are restored, untimed, before every step")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
+    ap.add_argument("--static-rows", action="store_true", help="rows fixed by the workgroup index instead of handed out at run time")
     ap.add_argument("--ld", type=int, default=0, help="row pitch of logits / gradient in elements (0: V)")
     ap.add_argument("--forward-only", action="store_true", help="time dppo_loss_fwd (no gradient) instead of forward+backward")
     ap.add_argument("--chunk-rows", type=int, default=0, help="tokens per chunk of the hidden-state workloads (0: library default)")
@@ -257,7 +258,7 @@ def main() -> int:
     batch = W.make_batch(w, dev, rows_per_step=2048, ld=(args.ld or None))
     T, V, K = batch["T"], batch["V"], batch["K"]
     chunk = w.chunk_rows or T
-    flags = B.FLAG_FORCE_STREAMING if args.force_streaming else 0
+    flags = (B.FLAG_FORCE_STREAMING if args.force_streaming else 0) | (B.FLAG_STATIC_ROWS if args.static_rows else 0)
 
     # caller-side buffers, allocated once: gradient (separate from the logits so that every
     # step sees the same input), per-token outputs, one loss scalar per T-chunk
@@ -365,7 +366,7 @@ def main() -> int:
                                       "N(0, drift_std^2) after the rollout, so that a few tokens are masked; not part of "
                                       "the configuration string this workload stands for, byte-neutral"},
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
-                   "kernel_path": path, "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
+                   "kernel_path": path, "rows": "fixed by workgroup index" if args.static_rows else "library default", "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,

@@ -44,7 +44,7 @@ extern "C" {
 
 #define DPPO_VERSION 301          /* major*10000 + minor*100 + patch                          */
 #define DPPO_KMAX 1024            /* largest accepted K                                        */
-#define DPPO_WORKSPACE_BYTES 65536
+#define DPPO_WORKSPACE_BYTES 65536  /* smallest workspace any call accepts                      */
 
 /* Columns of the optional per-token diagnostics output [T, DPPO_NDIAG] (fp32): the health
  * metrics the paper monitors during training (App. F.1: mean |pi - mu| of the sampled token,
@@ -99,6 +99,8 @@ typedef enum {
 /* flags */
 #define DPPO_FLAG_FORCE_STREAMING 1u /* use the general kernels even where a register-resident
                                         one applies (testing / comparison)                     */
+#define DPPO_FLAG_STATIC_ROWS 2u     /* never hand rows out at run time: every workgroup takes the
+                                        rows its index fixes (testing / comparison)            */
 
 typedef struct {
   /* ---- inputs ---- */
@@ -146,14 +148,20 @@ typedef struct {
   float*         diagnostics;  /* [T, DPPO_NDIAG] per-token diagnostics (DPPO_DIAG_*), 16-byte  */
                                /* aligned; may be NULL.  Ignored rows get zeros               */
   /* ---- scratch ---- */
-  void*          workspace;    /* >= dppo_workspace_bytes(T, V, K) bytes, 8-byte aligned;      */
-                               /* contents on entry are irrelevant, calls that overlap in time */
-                               /* need distinct workspaces                                     */
+  void*          workspace;    /* dppo_workspace_bytes(T, V, K) bytes, 8-byte aligned; at      */
+                               /* least DPPO_WORKSPACE_BYTES are required (DPPO_ERR_WORKSPACE  */
+                               /* below that), and with less than dppo_workspace_bytes() the   */
+                               /* long-row forward+backward kernel cannot hand its rows out at */
+                               /* run time (about 2 % slower on 150k-entry rows).  Contents on */
+                               /* entry are irrelevant; calls that overlap in time need        */
+                               /* distinct workspaces                                          */
   size_t         workspace_bytes;
   uint32_t       flags;        /* DPPO_FLAG_*                                                  */
 } dppo_args_t;
 
-/* Bytes of device scratch one call needs (currently a constant, DPPO_WORKSPACE_BYTES). */
+/* Bytes of device scratch for one call: DPPO_WORKSPACE_BYTES (per-workgroup partial sums of the
+ * loss, row counters) + 8 T (one loss term per row, summed in a fixed order: the scalar loss is
+ * the same whichever workgroup took which row). */
 size_t dppo_workspace_bytes(int64_t T, int64_t V, int32_t K);
 
 /* Forward only: loss, loss_tok, divergence, mask.  grad_logits is ignored.

@@ -17,7 +17,8 @@ MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
 NDIAG = 8
 DIAG_RATIO, DIAG_LOGP, DIAG_ABS_DIFF, DIAG_ENTROPY, DIAG_MASS_MU, DIAG_MASS_PI = 0, 1, 2, 3, 4, 5
 FLAG_FORCE_STREAMING = 1
-WORKSPACE_BYTES = 65536
+FLAG_STATIC_ROWS = 2
+WORKSPACE_BYTES = 65536       # the smallest workspace any call accepts; workspace_bytes(T, V, K) is what a call wants
 
 # DPPO_LIB overrides the library path (e.g. a build with other compile-time settings).
 _LIB_PATH = os.environ.get("DPPO_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo.so")
@@ -155,7 +156,7 @@ def alloc_outputs(T: int, device, want_loss_tok: bool = True, want_diagnostics: 
         "loss_tok": torch.empty(T, dtype=torch.float32, device=device) if want_loss_tok else None,
         "divergence": torch.empty(T, dtype=torch.float32, device=device),
         "mask": torch.empty(T, dtype=torch.uint8, device=device),
-        "workspace": torch.empty(WORKSPACE_BYTES, dtype=torch.uint8, device=device),
+        "workspace": torch.empty(WORKSPACE_BYTES + 8 * T, dtype=torch.uint8, device=device),
     }
 
 

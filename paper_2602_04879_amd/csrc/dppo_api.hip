@@ -86,7 +86,7 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = fal
   if (a->mask_rule < DPPO_MASK_DIVERGENCE || a->mask_rule > DPPO_MASK_NONE) return DPPO_ERR_VALUE;
   if (a->mask_rule == DPPO_MASK_RATIO_CLIP && !(a->eps_low >= 0.f && a->eps_low < 1.f && a->eps_high >= 0.f)) return DPPO_ERR_VALUE;
   if (!own_scratch) {
-    if (!a->workspace || a->workspace_bytes < dppo_workspace_bytes(a->T, a->V, a->K)) return DPPO_ERR_WORKSPACE;
+    if (!a->workspace || a->workspace_bytes < DPPO_WORKSPACE_BYTES) return DPPO_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
   }
   if (a->T > 0) {
@@ -104,9 +104,35 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = fal
   return DPPO_OK;
 }
 
-// Launch the loss kernel of one (already validated) call; its per-workgroup partial loss sums
-// go to partial[0 .. *nparts), *nparts <= max_parts.
-dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int max_parts, int* nparts_out, hipStream_t s) {
+// Device scratch of one loss launch.  partial: one loss partial sum per workgroup (max_parts of
+// them).  counters / row_loss (both or neither): eight row counters and one loss term per row,
+// for the kernel form that hands its rows out at run time.
+struct LossScratch {
+  double* partial = nullptr;
+  int max_parts = 0;
+  int32_t* counters = nullptr;
+  double* row_loss = nullptr;
+};
+// The layout of a caller's workspace: [partial sums, 32 KiB | counters | unused up to 64 KiB | row loss terms, 8 T bytes]
+constexpr size_t kPartialBytes = 32768;
+LossScratch scratch_of(void* base, size_t bytes, int64_t T) {
+  LossScratch sc;
+  char* b = static_cast<char*>(base);
+  sc.partial = reinterpret_cast<double*>(b);
+  sc.max_parts = static_cast<int>(kPartialBytes / sizeof(double));
+  if (bytes >= DPPO_WORKSPACE_BYTES + static_cast<size_t>(T) * sizeof(double)) {
+    sc.counters = reinterpret_cast<int32_t*>(b + kPartialBytes);
+    sc.row_loss = reinterpret_cast<double*>(b + DPPO_WORKSPACE_BYTES);
+  }
+  return sc;
+}
+
+// Launch the loss kernel of one (already validated) call.  Afterwards the scalar loss is
+// loss_scale times the sum of fin[0 .. *fin_n) (per-workgroup partial sums, or per-row terms).
+dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc, const double** fin, int* fin_n, hipStream_t s) {
+  double* partial = sc.partial;
+  const int max_parts = sc.max_parts;
+  *fin = partial;
   int nparts = 0;
   if (a->T > 0) {
     int dev = 0;
@@ -128,6 +154,8 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
     p.mask = a->mask;
     p.diag = a->diagnostics;
     p.partial = partial;
+    p.row_counters = nullptr;
+    p.row_loss = nullptr;
     p.ld = a->ld;
     p.T = static_cast<int32_t>(a->T);
     p.V = static_cast<int32_t>(a->V);
@@ -168,12 +196,24 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
       if (dppo::launch_fullvocab(p, a->variant == DPPO_FULL_TV, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab";
     } else if (resident) {
-      int64_t grid = static_cast<int64_t>(cus) * resident_blocks_per_cu_cached(dev, grad, r_threads, r_chunks);
+      const int per_cu = resident_blocks_per_cu_cached(dev, grad, r_threads, r_chunks);
+      int64_t grid = static_cast<int64_t>(cus) * per_cu;
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
+      // One workgroup per compute unit, the gradient, several rows per workgroup, and scratch for it:
+      // rows are handed out at run time (the dies do not run at one speed).
+      if (grad && r_threads == 512 && per_cu == 1 && sc.counters && grid % 8 == 0 && a->T >= 4 * grid &&
+          !(a->flags & DPPO_FLAG_STATIC_ROWS)) {
+        p.row_counters = sc.counters;
+        p.row_loss = sc.row_loss;
+        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+        *fin = sc.row_loss;
+        *fin_n = static_cast<int>(a->T);
+      }
       if (dppo::launch_resident(p, grad, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident";
+      if (p.row_counters) return DPPO_OK;
     } else {
       // 16-byte vectors need logits and grad rows to share their misalignment.
       const bool vec = !grad || (((lz - lg) & 15u) == 0);
@@ -189,7 +229,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, double* partial, int 
       g_last_path = "streaming";
     }
   }
-  *nparts_out = nparts;
+  *fin_n = nparts;
   return DPPO_OK;
 }
 
@@ -197,11 +237,12 @@ dppo_status_t run(const dppo_args_t* a, void* stream, bool grad) {
   dppo_status_t st = check_args(a, grad);
   if (st != DPPO_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  double* partial = static_cast<double*>(a->workspace);
-  int nparts = 0;
-  st = launch_loss(a, grad, partial, static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double)), &nparts, s);
+  const LossScratch sc = scratch_of(a->workspace, a->workspace_bytes, a->T);
+  const double* fin = nullptr;
+  int fin_n = 0;
+  st = launch_loss(a, grad, sc, &fin, &fin_n, s);
   if (st != DPPO_OK) return st;
-  if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  if (dppo::launch_finalize(fin, fin_n, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
   return DPPO_OK;
 }
 
@@ -215,12 +256,15 @@ dppo_status_t run_static(const dppo_args_t* a, void* stream) {
   int cur = 0, dev = 0;
   if (hipGetDevice(&cur) != hipSuccess || !stream_device(s, &dev)) return DPPO_ERR_LAUNCH;
   if (dev != cur) return DPPO_ERR_LAUNCH;          // each GPU has its own copy of the array: the current one's is used
-  double* partial = static_cast<double*>(static_scratch(cur));
-  if (!partial) return DPPO_ERR_WORKSPACE;
-  int nparts = 0;
-  st = launch_loss(a, true, partial, static_cast<int>(DPPO_STATIC_SCRATCH_BYTES / sizeof(double)), &nparts, s);
+  void* base = static_scratch(cur);
+  if (!base) return DPPO_ERR_WORKSPACE;
+  // (with 64 KiB there is no room for per-row loss terms: every workgroup takes the rows its index fixes)
+  const LossScratch sc = scratch_of(base, DPPO_STATIC_SCRATCH_BYTES, a->T);
+  const double* fin = nullptr;
+  int fin_n = 0;
+  st = launch_loss(a, true, sc, &fin, &fin_n, s);
   if (st != DPPO_OK) return st;
-  if (dppo::launch_finalize(partial, nparts, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  if (dppo::launch_finalize(fin, fin_n, a->loss_scale, a->loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
   return DPPO_OK;
 }
 
@@ -279,7 +323,7 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
   const dppo_status_t st0 = check_args(&c, grad);
   if (st0 != DPPO_OK) return st0;
 
-  const int max_parts = static_cast<int>(DPPO_WORKSPACE_BYTES / sizeof(double));
+  const int max_parts = static_cast<int>(kPartialBytes / sizeof(double));
   const int64_t nchunks = T > 0 ? (T + chunk - 1) / chunk : 0;
   const int parts_per_chunk = nchunks > 0 ? static_cast<int>(max_parts / nchunks) : max_parts;
   if (nchunks > 0 && parts_per_chunk < 1) return DPPO_ERR_SHAPE;
@@ -302,7 +346,11 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
     c.mask = a->loss.mask + r0;
     c.diagnostics = a->loss.diagnostics ? a->loss.diagnostics + r0 * DPPO_NDIAG : nullptr;
     int np = 0;
-    const dppo_status_t st = launch_loss(&c, grad, partial + used, parts_per_chunk, &np, s);   // gradient in place
+    LossScratch sc;                   // per-workgroup partial sums only: the chunks of one call share the scratch
+    sc.partial = partial + used;
+    sc.max_parts = parts_per_chunk;
+    const double* fin = nullptr;
+    const dppo_status_t st = launch_loss(&c, grad, sc, &fin, &np, s);   // gradient in place
     if (st != DPPO_OK) return st;
     used += np;
     if (grad) {
@@ -331,7 +379,9 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
 
 extern "C" {
 
-size_t dppo_workspace_bytes(int64_t, int64_t, int32_t) { return DPPO_WORKSPACE_BYTES; }
+size_t dppo_workspace_bytes(int64_t T, int64_t, int32_t) {
+  return DPPO_WORKSPACE_BYTES + (T > 0 ? static_cast<size_t>(T) * sizeof(double) : 0);
+}
 
 dppo_status_t dppo_loss_fwd(const dppo_args_t* args, void* stream) { return run(args, stream, false); }
 

@@ -39,6 +39,9 @@ hipError_t launch_gemm_nn(const uint16_t* A, int64_t lda, const uint16_t* B, int
 hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, void* C, int64_t ldc,
                           int M, int N, int K, int out, hipStream_t s);
 
+// Clears the eight row counters of the register-resident kernel's run-time row hand-out.
+hipError_t launch_clear_counters(int32_t* counters, hipStream_t s);
+
 // loss[0] = loss_scale * sum(partial[0..n)) in a fixed order.
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s);
 

@@ -71,7 +71,16 @@ constexpr int kChunkStep = 4;
 // GRAD = false is the forward-only form: no gradient, no stores, refills in two halves.
 // DIAG = true also accumulates sum e*x for the entropy diagnostic (two more instructions per
 // element in the statistics loop), selected when the caller passes a diagnostics buffer.
-template <int THREADS, int NCHUNK, bool GRAD, bool DIAG>
+// DYN = true: rows are handed out at run time.  With one workgroup per compute unit and rows fixed
+// by the workgroup index, the kernel ends when its slowest compute unit does, and the dies do not
+// run at one speed (measured on the headline shape: four of the eight dies finish 2.5 % after the
+// other four, the last workgroup 2.5 % after the mean).  So each die owns a contiguous eighth of the
+// rows and a counter; a workgroup takes its next row from its own die's counter (its die's
+// workgroups so stay on neighbouring rows) and, once that range is used up, from the next die's.
+// The row after next is requested one row ahead (one thread, an atomic that returns while the row
+// streams) and published through shared memory at the row's barrier.  The loss terms go to one
+// slot per ROW, so the scalar loss does not depend on which workgroup took which row.
+template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
@@ -88,6 +97,7 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   __shared__ float sh_b[2][NW];
   __shared__ double sh_s[2][NW], sh_t[2][NW];
   __shared__ RowCoef sh_rc;
+  __shared__ int sh_row[2];
   int par = 0;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
@@ -109,6 +119,29 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   // id.  The shapes with several workgroups per compute unit and the forward-only form measure
   // 1-3 % slower that way and keep row = workgroup id.
   int row = (GRAD && THREADS == 512) ? first_row_of_workgroup() : static_cast<int>(blockIdx.x);
+  // DYN: the die whose counter this workgroup draws from next (thread 0 only), and its draws.
+  constexpr int kNoRow = 0x7fffffff;
+  int victim = static_cast<int>(blockIdx.x & 7u);
+  auto die_base = [&](int d) { return static_cast<int>(static_cast<int64_t>(p.T) * d / 8); };
+  auto take_row = [&]() -> int {          // synchronous: own die first, then the others in turn
+    for (int tries = 0; tries < 8; ++tries) {
+      const int t = atomicAdd(p.row_counters + victim, 1);
+      if (die_base(victim) + t < die_base(victim + 1)) return die_base(victim) + t;
+      victim = (victim + 1) & 7;
+    }
+    return kNoRow;
+  };
+  int next = row + static_cast<int>(gridDim.x);
+  if (DYN) {
+    if (tid == 0) {
+      sh_row[0] = take_row();
+      sh_row[1] = take_row();
+    }
+    __syncthreads();
+    row = uniform_i(sh_row[0]);
+    next = uniform_i(sh_row[1]);
+    __syncthreads();
+  }
   {
     const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
 #pragma unroll
@@ -125,11 +158,25 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
   }
 
-  for (; row < p.T; row += gridDim.x) {
+  for (; row < p.T;) {
     const int a = uniform_i(a_next);
-    const int next = row + gridDim.x;
     const bool more = next < p.T;
     if (more) a_next = p.sampled[next];
+    // DYN: request the row after next now; the answer is looked at before this row's barrier.
+    int drawn = 0;
+    if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters + victim, 1);
+    int next2 = kNoRow;
+    auto publish_row_after_next = [&]() {      // thread 0, before the barrier the others read it behind
+      int n2 = kNoRow;
+      if (more) {
+        n2 = die_base(victim) + drawn;
+        if (n2 >= die_base(victim + 1)) {      // that die's rows are used up: on to the next one's
+          victim = (victim + 1) & 7;
+          n2 = take_row();
+        }
+      }
+      sh_row[par] = n2;
+    };
     const int tkid = tkid_next;
     const float tklp = tklp_next;
     if (more && wid == 0 && lane < p.K) {
@@ -263,7 +310,9 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       constexpr bool kInlineEpilogue = (THREADS == 512 && NCHUNK >= (GRAD ? 16 : 28));
       RowPre pre;
       if (kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
+      if (DYN && tid == 0) publish_row_after_next();
       __syncthreads();
+      if (DYN) next2 = uniform_i(sh_row[par]);
       // ---- epilogue on wave 0 -----------------------------------------------------------
       RowOut ro;
       if (wid == 0) {
@@ -287,7 +336,8 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
           rr = row_epilogue_call(ep, row_e, rs, tk, zrow, bb, S_rest, T_rest, lane);
         }
         rc = rr.rc;
-        loss_acc += rr.loss_term;
+        if (DYN) { if (lane == 0) p.row_loss[row] = rr.loss_term; }
+        else loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
       }
       par ^= 1;
@@ -305,12 +355,21 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         asm volatile("" : "+s"(row_e));
         row_store(ep, row_e, ro, lane);
       }
-    } else if (tid == 0) {
-      p.divergence[row] = 0.f;
-      p.mask[row] = 0;
-      if (p.loss_tok) p.loss_tok[row] = 0.f;
-      if (p.diag) {
-        for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+    } else {
+      if (tid == 0) {
+        p.divergence[row] = 0.f;
+        p.mask[row] = 0;
+        if (p.loss_tok) p.loss_tok[row] = 0.f;
+        if (p.diag) {
+          for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+        }
+        if (DYN) p.row_loss[row] = 0.0;
+      }
+      if (DYN) {
+        if (tid == 0) publish_row_after_next();
+        __syncthreads();
+        next2 = uniform_i(sh_row[par]);
+        par ^= 1;
       }
     }
 
@@ -348,27 +407,35 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       for (int i = 0; i < NCHUNK; ++i)
         if (i >= kSplit || !live) buf[i] = row_load16<kNtLoads>(zn, voff, i * kStride);
     }
+    row = next;
+    next = DYN ? next2 : next + static_cast<int>(gridDim.x);
   }
-  if (tid == 0) p.partial[blockIdx.x] = loss_acc;
+  if (!DYN && tid == 0) p.partial[blockIdx.x] = loss_acc;
 }
 
 // One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
+// Rows are handed out at run time (p.row_counters set by the host) only in the form that has one
+// workgroup per compute unit and the gradient.
 template <int THREADS, int NCHUNK>
 hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
   const bool diag = p.diag != nullptr;
   const dim3 g(grid), b(THREADS);
-  if (grad && diag)       hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true>), g, b, 0, s, p);
-  else if (grad)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false>), g, b, 0, s, p);
-  else if (diag)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, true>), g, b, 0, s, p);
-  else                    hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, false>), g, b, 0, s, p);
+  if (THREADS == 512 && grad && p.row_counters != nullptr) {
+    if (diag)             hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true, THREADS == 512>), g, b, 0, s, p);
+    else                  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false, THREADS == 512>), g, b, 0, s, p);
+  }
+  else if (grad && diag)  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true, false>), g, b, 0, s, p);
+  else if (grad)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false, false>), g, b, 0, s, p);
+  else if (diag)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, true, false>), g, b, 0, s, p);
+  else                    hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, false, false>), g, b, 0, s, p);
   return hipGetLastError();
 }
 // The diagnostics form needs a few more registers; its occupancy bounds both.
 template <int THREADS, int NCHUNK>
 int occupancy_shape(bool grad) {
   int n = 0;
-  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true>, THREADS, 0)
-                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true>, THREADS, 0);
+  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, false>, THREADS, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true, false>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 

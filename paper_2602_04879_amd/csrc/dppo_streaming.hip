@@ -199,6 +199,15 @@ __global__ __launch_bounds__(256) void dppo_finalize_kernel(const double* partia
   if (threadIdx.x == 0) *loss = static_cast<float>(static_cast<double>(loss_scale) * sh[0]);
 }
 
+__global__ __launch_bounds__(64) void dppo_clear_counters_kernel(int32_t* counters) {
+  if (threadIdx.x < 8) counters[threadIdx.x] = 0;
+}
+
+hipError_t launch_clear_counters(int32_t* counters, hipStream_t s) {
+  hipLaunchKernelGGL(dppo_clear_counters_kernel, dim3(1), dim3(64), 0, s, counters);
+  return hipGetLastError();
+}
+
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s) {
   hipLaunchKernelGGL(dppo_finalize_kernel, dim3(1), dim3(256), 0, s, partial, n, loss_scale, loss);
   return hipGetLastError();

@@ -108,6 +108,42 @@ def test_resident_more_rows_than_workgroups_in_place_with_special_rows():
     _say(f"       {st}")
 
 
+def test_rows_handed_out_at_run_time_match_rows_fixed_by_index():
+    """Long rows with the gradient and many rows per workgroup: the kernel hands its rows out at run
+    time (per-die counters, one loss term per row).  Every per-row output must be bit for bit what
+    the form with rows fixed by the workgroup index writes, run after run, ignored / zero-advantage
+    / masked rows included; the scalar loss is summed per row in a fixed order, so it too repeats
+    bit for bit; and a workspace of the minimum size falls back to the fixed rows."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = 4 * cus + 37
+    w = W.Workload("dynrows", 1, T, 100000, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=61)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    b["advantages"] = torch.randn(T, device=DEV)             # per token, so that both signs and sizes occur
+    b["sampled_ids"][::17] = -1
+    b["advantages"][5::19] = 0.0
+    fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
+    runs = [B.run_batch(b, diagnostics=True) for _ in range(3)]
+    small = B.alloc_outputs(T, DEV, want_diagnostics=True)
+    small["workspace"] = torch.empty(B.WORKSPACE_BYTES, dtype=torch.uint8, device=DEV)
+    rmin = B.run_batch(b, out=small)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    for r in runs + [rmin]:
+        for k in ("loss_tok", "divergence", "mask", "diagnostics", "grad_logits"):
+            assert torch.equal(fixed[k], r[k]), k
+    for r in runs[1:]:
+        assert torch.equal(runs[0]["loss"], r["loss"])
+    assert torch.equal(fixed["loss"], rmin["loss"])
+    assert abs(runs[0]["loss"].item() - fixed["loss"].item()) <= 1e-6 * abs(fixed["loss"].item())
+    rows = np.arange(T)
+    ref = P.oracle_rows(b, rows, want_grad=False)
+    st = P.compare_rows(b, runs[0], rows, check_grad=False, ref=ref)
+    P.check_loss_scalar(b, runs[0], float(ref["loss_tok"].sum()))
+    P.compare_rows(b, runs[0], rows[::16])
+    assert st["masked"] > 50
+    _say(f"       {st}")
+
+
 def test_resident_saturated_rows():
     """pi(a_t) -> 1 on the register-resident path: 1 - pi(a_t) must keep its relative accuracy."""
     w = W.Workload("sat_res", 2, 8, 16384, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=41)

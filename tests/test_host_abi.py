@@ -34,7 +34,8 @@ def test_struct_mirror_and_constants():
     lib = B.lib()
     assert lib.dppo_args_size() == C.sizeof(B.DppoArgs)
     assert lib.dppo_version() >= 100
-    assert B.workspace_bytes(32768, 151936, 20) == B.WORKSPACE_BYTES
+    assert B.workspace_bytes(32768, 151936, 20) == B.WORKSPACE_BYTES + 8 * 32768
+    assert B.workspace_bytes(0, 151936, 0) == B.WORKSPACE_BYTES
     for code in range(0, 9):
         assert len(lib.dppo_status_str(code)) > 0
 
