@@ -60,13 +60,13 @@ bool stream_device(hipStream_t s, int* dev) {
 
 // Workgroups per compute unit of a register-resident shape: a constant of (device, shape, form),
 // asked of the runtime once and kept.
-int resident_blocks_per_cu_cached(int dev, bool grad, int threads, int chunks) {
-  static std::atomic<int> cache[64][2][2][41];
-  if (dev < 0 || dev >= 64 || chunks < 0 || chunks > 40) return dppo::resident_blocks_per_cu(grad, threads, chunks);
-  std::atomic<int>& slot = cache[dev][grad ? 1 : 0][threads == 512 ? 1 : 0][chunks];
+int resident_blocks_per_cu_cached(int dev, bool grad, bool dyn, int threads, int chunks) {
+  static std::atomic<int> cache[64][4][2][41];
+  if (dev < 0 || dev >= 64 || chunks < 0 || chunks > 40) return dppo::resident_blocks_per_cu(grad, dyn, threads, chunks);
+  std::atomic<int>& slot = cache[dev][(grad ? 1 : 0) + (dyn ? 2 : 0)][threads == 512 ? 1 : 0][chunks];
   int n = slot.load(std::memory_order_relaxed);
   if (n == 0) {
-    n = dppo::resident_blocks_per_cu(grad, threads, chunks);
+    n = dppo::resident_blocks_per_cu(grad, dyn, threads, chunks);
     slot.store(n, std::memory_order_relaxed);
   }
   return n;
@@ -105,7 +105,7 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = fal
 }
 
 // Device scratch of one loss launch.  partial: one loss partial sum per workgroup (max_parts of
-// them).  counters / row_loss (both or neither): eight row counters and one loss term per row,
+// them).  counters / row_loss (both or neither): the row counter and one loss term per row,
 // for the kernel form that hands its rows out at run time.
 struct LossScratch {
   double* partial = nullptr;
@@ -196,15 +196,29 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       if (dppo::launch_fullvocab(p, a->variant == DPPO_FULL_TV, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab";
     } else if (resident) {
-      const int per_cu = resident_blocks_per_cu_cached(dev, grad, r_threads, r_chunks);
+      int per_cu = resident_blocks_per_cu_cached(dev, grad, false, r_threads, r_chunks);
       int64_t grid = static_cast<int64_t>(cus) * per_cu;
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
+      // With the gradient and one workgroup per compute unit (the long rows), rows are handed out at
+      // run time: the dies do not run at one speed, and the slowest one would end the kernel.  (The
+      // forward-only form and the shapes with several workgroups per compute unit measure slower
+      // that way: their waves run ahead of wave 0, which would have to wait for the counter.)
+      const bool want_dyn = grad && r_threads == 512 && per_cu == 1 && sc.counters && !(a->flags & DPPO_FLAG_STATIC_ROWS);
+      bool dyn = false;
+      if (want_dyn) {
+        const int per_cu_dyn = resident_blocks_per_cu_cached(dev, grad, true, r_threads, r_chunks);
+        const int64_t grid_dyn = static_cast<int64_t>(cus) * per_cu_dyn;
+        if (grid_dyn % 8 == 0 && a->T >= 4 * grid_dyn && grid_dyn <= max_parts) {
+          grid = grid_dyn;
+          per_cu = per_cu_dyn;
+          dyn = true;
+        }
+      }
       nparts = static_cast<int>(grid);
       // One workgroup per compute unit, the gradient, several rows per workgroup, and scratch for it:
       // rows are handed out at run time (the dies do not run at one speed).
-      if (grad && r_threads == 512 && per_cu == 1 && sc.counters && grid % 8 == 0 && a->T >= 4 * grid &&
-          !(a->flags & DPPO_FLAG_STATIC_ROWS)) {
+      if (dyn) {
         p.row_counters = sc.counters;
         p.row_loss = sc.row_loss;
         if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;

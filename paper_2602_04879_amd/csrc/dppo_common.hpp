@@ -25,11 +25,11 @@ struct KParams {
   uint8_t* mask;            // [T]
   float* diag;              // [T, 8] or nullptr
   double* partial;          // [gridDim.x] per-workgroup loss partial sums (workspace)
-  // Rows handed out at run time (register-resident kernel with the gradient, see there): eight
-  // counters (one per die, cleared before the launch) and one loss term per ROW instead of one
-  // partial sum per workgroup, so that the scalar loss does not depend on which workgroup took
-  // which row.  Both nullptr: every workgroup takes the rows its index fixes.
-  int32_t* row_counters;    // [8]
+  // Rows handed out at run time (register-resident kernel with the gradient, see there): a
+  // counter (cleared before the launch) and one loss term per ROW instead of one partial sum per
+  // workgroup, so that the scalar loss does not depend on which workgroup took which row.  Both
+  // nullptr: every workgroup takes the rows its index fixes.
+  int32_t* row_counters;    // [1] (eight are cleared)
   double* row_loss;         // [T]
   int64_t ld;
   int32_t T, V, K, variant;

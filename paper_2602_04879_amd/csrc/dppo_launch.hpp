@@ -12,10 +12,11 @@ hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, 
 // Register-resident kernel (fused forward+backward, or forward only).  A shape is (threads per workgroup, 16-byte
 // chunks per thread); resident_shape() picks the smallest instantiated one that covers a row of
 // V entries (false: none does, or V is not a multiple of 8).  Needs 16-byte aligned rows of
-// logits and grad.  resident_blocks_per_cu() is the occupancy the runtime reports for a shape.
+// logits and grad.  resident_blocks_per_cu() is the occupancy the runtime reports for a shape (dyn: of the form
+// that hands its rows out at run time).
 bool resident_shape(int64_t V, int* threads, int* chunks);
 hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s);
-int resident_blocks_per_cu(bool grad, int threads, int chunks);
+int resident_blocks_per_cu(bool grad, bool dyn, int threads, int chunks);
 
 // Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
 hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);

@@ -74,12 +74,12 @@ constexpr int kChunkStep = 4;
 // DYN = true: rows are handed out at run time.  With one workgroup per compute unit and rows fixed
 // by the workgroup index, the kernel ends when its slowest compute unit does, and the dies do not
 // run at one speed (measured on the headline shape: four of the eight dies finish 2.5 % after the
-// other four, the last workgroup 2.5 % after the mean).  So each die owns a contiguous eighth of the
-// rows and a counter; a workgroup takes its next row from its own die's counter (its die's
-// workgroups so stay on neighbouring rows) and, once that range is used up, from the next die's.
-// The row after next is requested one row ahead (one thread, an atomic that returns while the row
-// streams) and published through shared memory at the row's barrier.  The loss terms go to one
-// slot per ROW, so the scalar loss does not depend on which workgroup took which row.
+// other four, the last workgroup 2.5 % after the mean).  So a workgroup takes its next row from a
+// counter (rows in the order they are asked for: one counter per die over a contiguous eighth of
+// the rows, with stealing at the end, measured 1.5 % slower than this).  The row after next is
+// requested one row ahead (one thread, an atomic that returns while the row streams) and
+// published through shared memory at the row's barrier.  The loss terms go to one slot per ROW,
+// so the scalar loss does not depend on which workgroup took which row.
 template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN>
 __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
@@ -119,28 +119,20 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
   // id.  The shapes with several workgroups per compute unit and the forward-only form measure
   // 1-3 % slower that way and keep row = workgroup id.
   int row = (GRAD && THREADS == 512) ? first_row_of_workgroup() : static_cast<int>(blockIdx.x);
-  // DYN: the die whose counter this workgroup draws from next (thread 0 only), and its draws.
   constexpr int kNoRow = 0x7fffffff;
-  int victim = static_cast<int>(blockIdx.x & 7u);
-  auto die_base = [&](int d) { return static_cast<int>(static_cast<int64_t>(p.T) * d / 8); };
-  auto take_row = [&]() -> int {          // synchronous: own die first, then the others in turn
-    for (int tries = 0; tries < 8; ++tries) {
-      const int t = atomicAdd(p.row_counters + victim, 1);
-      if (die_base(victim) + t < die_base(victim + 1)) return die_base(victim) + t;
-      victim = (victim + 1) & 7;
-    }
-    return kNoRow;
-  };
   int next = row + static_cast<int>(gridDim.x);
   if (DYN) {
     if (tid == 0) {
-      sh_row[0] = take_row();
-      sh_row[1] = take_row();
+      sh_row[0] = atomicAdd(p.row_counters, 1);
+      sh_row[1] = atomicAdd(p.row_counters, 1);
     }
     __syncthreads();
     row = uniform_i(sh_row[0]);
     next = uniform_i(sh_row[1]);
     __syncthreads();
+    // A workgroup that starts when every row has been handed out (the launch need not be resident
+    // all at once) has nothing to do, and must not form an address from "no row".
+    if (row >= p.T) return;
   }
   {
     const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
@@ -164,19 +156,10 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
     if (more) a_next = p.sampled[next];
     // DYN: request the row after next now; the answer is looked at before this row's barrier.
     int drawn = 0;
-    if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters + victim, 1);
+    if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters, 1);
     int next2 = kNoRow;
-    auto publish_row_after_next = [&]() {      // thread 0, before the barrier the others read it behind
-      int n2 = kNoRow;
-      if (more) {
-        n2 = die_base(victim) + drawn;
-        if (n2 >= die_base(victim + 1)) {      // that die's rows are used up: on to the next one's
-          victim = (victim + 1) & 7;
-          n2 = take_row();
-        }
-      }
-      sh_row[par] = n2;
-    };
+    // thread 0, before the barrier the others read it behind (a number >= T means: no row)
+    auto publish_row_after_next = [&]() { sh_row[par] = more ? drawn : kNoRow; };
     const int tkid = tkid_next;
     const float tklp = tklp_next;
     if (more && wid == 0 && lane < p.K) {
@@ -309,9 +292,22 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
       // the call and with it the second or third workgroup per compute unit.
       constexpr bool kInlineEpilogue = (THREADS == 512 && NCHUNK >= (GRAD ? 16 : 28));
       RowPre pre;
-      if (kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
+      // With the gradient the whole row is still needed after the epilogue, whose float64 arithmetic
+      // finds no registers beside it: wave 0 parks its last chunks in shared memory around the
+      // epilogue (its own 16 bytes per lane and chunk, no synchronisation) instead of letting the
+      // compiler spill to scratch memory, whose round trips would sit on the path the other seven
+      // waves wait for (measured on the headline shapes: 1.8 % faster Binary, 3.6 % faster Top-K;
+      // 8, 16 and 24 chunks measure the same).
+      constexpr int kPark = (GRAD && kInlineEpilogue) ? 16 : 0;
+      __shared__ u32x4 sh_park[kPark > 0 ? kPark * kWave : 1];
+      if (kPark > 0 && wid == 0) {
+#pragma unroll
+        for (int i = 0; i < kPark; ++i) sh_park[i * kWave + lane] = buf[NCHUNK - 1 - i];
+      }
+      if (GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
       if (DYN && tid == 0) publish_row_after_next();
       __syncthreads();
+      if (!GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
       if (DYN) next2 = uniform_i(sh_row[par]);
       // ---- epilogue on wave 0 -----------------------------------------------------------
       RowOut ro;
@@ -339,6 +335,10 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
         if (DYN) { if (lane == 0) p.row_loss[row] = rr.loss_term; }
         else loss_acc += rr.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
+        if (kPark > 0) {
+#pragma unroll
+          for (int i = 0; i < kPark; ++i) buf[NCHUNK - 1 - i] = sh_park[i * kWave + lane];
+        }
       }
       par ^= 1;
       if (GRAD) {
@@ -414,28 +414,33 @@ __global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p)
 }
 
 // One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
-// Rows are handed out at run time (p.row_counters set by the host) only in the form that has one
-// workgroup per compute unit and the gradient.
+// Rows are handed out at run time when the host sets p.row_counters.
 template <int THREADS, int NCHUNK>
 hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
   const bool diag = p.diag != nullptr;
+  constexpr bool kDyn = (THREADS == 512);     // the forms with run-time rows exist for the 512-thread shapes, with the gradient
+  const bool dyn = kDyn && grad && p.row_counters != nullptr;
+  if (p.row_counters != nullptr && !dyn) return hipErrorInvalidValue;
   const dim3 g(grid), b(THREADS);
-  if (THREADS == 512 && grad && p.row_counters != nullptr) {
-    if (diag)             hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true, THREADS == 512>), g, b, 0, s, p);
-    else                  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false, THREADS == 512>), g, b, 0, s, p);
+#define DPPO_FORM(G, D, Y) hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, G, D, Y>), g, b, 0, s, p)
+  if (grad) {
+    if (diag) { if (dyn) DPPO_FORM(true, true, kDyn); else DPPO_FORM(true, true, false); }
+    else      { if (dyn) DPPO_FORM(true, false, kDyn); else DPPO_FORM(true, false, false); }
+  } else {
+    if (diag) DPPO_FORM(false, true, false); else DPPO_FORM(false, false, false);
   }
-  else if (grad && diag)  hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, true, false>), g, b, 0, s, p);
-  else if (grad)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, true, false, false>), g, b, 0, s, p);
-  else if (diag)          hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, true, false>), g, b, 0, s, p);
-  else                    hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, false, false, false>), g, b, 0, s, p);
+#undef DPPO_FORM
   return hipGetLastError();
 }
 // The diagnostics form needs a few more registers; its occupancy bounds both.
 template <int THREADS, int NCHUNK>
-int occupancy_shape(bool grad) {
+int occupancy_shape(bool grad, bool dyn) {
   int n = 0;
-  const hipError_t e = grad ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, false>, THREADS, 0)
-                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true, false>, THREADS, 0);
+  constexpr bool kDyn = (THREADS == 512);
+  hipError_t e;
+  if (grad && dyn && kDyn) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, kDyn>, THREADS, 0);
+  else if (grad)           e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, false>, THREADS, 0);
+  else                     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true, false>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 
@@ -461,8 +466,8 @@ hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks,
   return hipErrorInvalidValue;
 }
 
-int resident_blocks_per_cu(bool grad, int threads, int chunks) {
-#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>(grad);
+int resident_blocks_per_cu(bool grad, bool dyn, int threads, int chunks) {
+#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>(grad, dyn);
   DPPO_SHAPES(DPPO_OCC)
 #undef DPPO_OCC
   return 1;
