@@ -123,7 +123,7 @@ def cpu_baseline(batch, budget_s: float, chunk_rows: int = 64, backward: bool = 
             cpu2 += time.process_time() - c0
             done2 += sum(min(T, chunk_rows) for _ in blocks)
     return {"value": done2 / wall2, "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
-            "sample": f"{done2} rows of the same batch in blocks of {chunk_rows} over {nthreads} threads, {kind}, float64 numpy, "
+            "sample": f"{done2} rows of the same batch (blocks of {chunk_rows} rows, wrapping around) over {nthreads} threads, {kind}, float64 numpy, "
                       f"{wall2:.1f} s wall, {cpu2:.1f} s of CPU time; one thread: first {one['rows']} rows in {one['seconds']:.1f} s",
             "one_thread": {"value": one["value"], "unit": "tokens/s", "cores": 1},
             "host_threads": nthreads, "nproc": os.cpu_count()}
@@ -142,14 +142,18 @@ def bench_lmhead(args, w, dev) -> int:
     batch = W.make_lmhead_batch(w, w.d_model, dev, rows_per_step=2048)
     T, V, d = batch["T"], batch["V"], batch["d"]
     out = B.alloc_outputs(T, dev)
-    grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
-    grad_weight = torch.empty((V, d), dtype=torch.float32, device=dev)
-    ws = torch.empty(B.lmhead_workspace_bytes(T, V, args.chunk_rows), dtype=torch.uint8, device=dev)
+    fwd = args.forward_only
+    flags = B.FLAG_FORCE_STREAMING if args.force_streaming else 0
+    grad_hidden = None if fwd else torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    grad_weight = None if fwd else torch.empty((V, d), dtype=torch.float32, device=dev)
+    fused = fwd and not args.force_streaming
+    ws_bytes = B.lmhead_fwd_workspace_bytes(T, V, batch["K"], args.chunk_rows) if fused else B.lmhead_workspace_bytes(T, V, args.chunk_rows)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step():
-        return B.run_lmhead(batch, chunk_rows=args.chunk_rows, out=out, grad_hidden=grad_hidden, grad_weight=grad_weight,
-                            workspace=ws, stream=stream)
+        return B.run_lmhead(batch, backward=not fwd, chunk_rows=args.chunk_rows, out=out, grad_hidden=grad_hidden, grad_weight=grad_weight,
+                            workspace=ws, stream=stream, flags=flags)
 
     for _ in range(args.warmup):
         step()
@@ -172,18 +176,20 @@ def bench_lmhead(args, w, dev) -> int:
             ev1.record(stream)
             torch.cuda.synchronize()
         ceilings[key] = fl / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
-    # the three products (logits, gradient of the hidden states, gradient of the weight): 2 T V d flops each
-    flops = 6.0 * T * V * d
+    # the three products (logits, gradient of the hidden states, gradient of the weight): 2 T V d flops each;
+    # forward only: the first one
+    flops = (2.0 if fwd else 6.0) * T * V * d
     achieved = flops / (ms * 1e-3) / 1e12
     chunk = args.chunk_rows if args.chunk_rows > 0 else 8192
     rec = {
-        "metric": "dppo_lmhead_loss_fwd_bwd_tokens_per_s", "value": T / (ms * 1e-3), "unit": "tokens/s",
+        "metric": "dppo_lmhead_loss_fwd_tokens_per_s" if fwd else "dppo_lmhead_loss_fwd_bwd_tokens_per_s", "value": T / (ms * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "V": V, "d": d, "K": batch["K"], "variant": int(batch["variant"]),
                    "delta": batch["delta"], "chunk_rows": chunk, "kernel_path": B.last_path(),
-                   "outputs": "loss, per-token, grad_hidden bf16, grad_weight fp32",
-                   "logits_bytes_resident": min(chunk, T) * V * 2, "logits_bytes_if_materialised": T * V * 2},
+                   "outputs": "loss, per-token" if fwd else "loss, per-token, grad_hidden bf16, grad_weight fp32",
+                   "workspace_bytes": ws_bytes, "logits_bytes_resident": 0 if fused else min(chunk, T) * V * 2,
+                   "logits_bytes_if_materialised": T * V * 2},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "dppo_gemm_nt_kernel",
                      "algorithmic_flops_per_step": flops, "ceilings": ceilings,
@@ -191,12 +197,12 @@ def bench_lmhead(args, w, dev) -> int:
         "loss": float(out["loss"].item()), "masked_tokens": int((out["mask"] == 0).sum().item()),
     }
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline_lmhead(batch, args.cpu_seconds)
+        rec["cpu_baseline"] = cpu_baseline_lmhead(batch, args.cpu_seconds, backward=not fwd)
     print(json.dumps(rec), flush=True)
     return 0
 
 
-def cpu_baseline_lmhead(batch, budget_s: float, chunk_rows: int = 16) -> dict:
+def cpu_baseline_lmhead(batch, budget_s: float, chunk_rows: int = 16, backward: bool = True) -> dict:
     """Time the float64 oracle of the hidden-state path on leading rows of the same batch."""
     from oracle import dppo_oracle as O
     T = batch["T"]
@@ -209,12 +215,13 @@ def cpu_baseline_lmhead(batch, budget_s: float, chunk_rows: int = 16) -> dict:
         tk_l = batch["mu_topk_logp"][sl].cpu().numpy() if batch["mu_topk_logp"] is not None else None
         t0, c0 = time.perf_counter(), time.process_time()
         O.lmhead_dppo_loss(h, Wd, batch["sampled_ids"][sl].cpu().numpy(), batch["mu_logp"][sl].cpu().numpy(),
-                           batch["advantages"][sl].cpu().numpy(), batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l)
+                           batch["advantages"][sl].cpu().numpy(), batch["delta"], batch["variant"], batch["loss_scale"], tk_i, tk_l,
+                           want_grad=backward)
         wall += time.perf_counter() - t0
         cpu += time.process_time() - c0
         done += sl.stop - sl.start
     return {"value": done / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)), "kind": "oracle",
-            "sample": f"first {done} of {T} rows of the same batch, logits + fwd+bwd + hidden-state gradient, float64 numpy, {wall:.1f} s"}
+            "sample": f"first {done} of {T} rows of the same batch, logits + {'fwd+bwd + hidden-state and weight gradients' if backward else 'fwd'}, float64 numpy, {wall:.1f} s"}
 
 
 def main() -> int:

@@ -206,7 +206,8 @@ size_t dppo_args_size(void);
  * "resident" (row held in registers between the two passes), "streaming" (row re-read),
  * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
  * backward, and the forward-only TV form, on long aligned rows: the trainer's row held in
- * registers, the rollout row streamed past it); "lmhead" after a dppo_lmhead_* call. */
+ * registers, the rollout row streamed past it); "lmhead" after a dppo_lmhead_* call that went
+ * through chunks of logits, "lmhead_fused" after a forward-only one that did not. */
 const char* dppo_last_path(void);
 
 /* ---- the same loss from the hidden states: the [T, V] logits never exist in full -------------
@@ -244,10 +245,19 @@ typedef struct {
   size_t         workspace_bytes;
 } dppo_lmhead_args_t;
 
-/* 64 KiB + min(chunk_rows, T) * V * 2 bytes (chunk_rows <= 0: the default). */
+/* 64 KiB + min(chunk_rows, T) * V * 2 bytes (chunk_rows <= 0: the default); enough for either call. */
 size_t dppo_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t chunk_rows);
 
-/* Forward only (loss, loss_tok, divergence, mask, diagnostics). */
+/* What dppo_lmhead_loss_fwd alone needs: 64 KiB + 8 T + min(chunk_rows, T) * (16 ceil(V / 256) +
+ * 4 (K + 1)) bytes (each part rounded up to 256), K as the Top-K variants use it (0 for Binary). */
+size_t dppo_lmhead_fwd_workspace_bytes(int64_t T, int64_t V, int32_t K, int64_t chunk_rows);
+
+/* Forward only (loss, loss_tok, divergence, mask, diagnostics).  No logit is written to memory:
+ * the product kernel itself reduces every 256 x 256 tile of bf16-rounded logits to per-row softmax
+ * statistics (and picks the logits at the sampled and top-K ids out of the tile); a second small
+ * kernel combines the tiles of a row and evaluates the loss.  The results are those of
+ * dppo_loss_fwd on the bf16 logits.  (DPPO_FLAG_FORCE_STREAMING in loss.flags selects the general
+ * route through a chunk of logits instead, for comparison; it needs the larger workspace.) */
 dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream);
 
 /* Forward and backward: also grad_hidden = d loss / d hidden and, if asked for, grad_weight. */

@@ -105,6 +105,8 @@ def lib() -> C.CDLL:
         for f in (l.dppo_lmhead_loss_fwd, l.dppo_lmhead_loss_fwd_bwd):
             f.restype = C.c_int
             f.argtypes = [C.POINTER(DppoLmheadArgs), C.c_void_p]
+        l.dppo_lmhead_fwd_workspace_bytes.restype = C.c_size_t
+        l.dppo_lmhead_fwd_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int64]
         l.dppo_lmhead_args_size.restype = C.c_size_t
         if l.dppo_lmhead_args_size() != C.sizeof(DppoLmheadArgs):
             raise ImportError("dppo_lmhead_args_t layout differs between libdppo.so and this binding")
@@ -328,9 +330,13 @@ def lmhead_workspace_bytes(T: int, V: int, chunk_rows: int = 0) -> int:
     return lib().dppo_lmhead_workspace_bytes(T, V, chunk_rows)
 
 
+def lmhead_fwd_workspace_bytes(T: int, V: int, K: int, chunk_rows: int = 0) -> int:
+    return lib().dppo_lmhead_fwd_workspace_bytes(T, V, K, chunk_rows)
+
+
 def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, out=None, grad_hidden=None,
                workspace=None, stream=None, diagnostics: bool = False, grad_weight=None, accumulate: bool = False,
-               **rule) -> dict:
+               flags: int = 0, **rule) -> dict:
     """Run one hidden-state batch (workloads.make_lmhead_batch) through dppo_lmhead_loss_fwd[_bwd].
     Returns the output tensors (device), grad_hidden among them."""
     h, w = batch["hidden"], batch["weight"]
@@ -341,12 +347,14 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, out=None
     if backward and grad_hidden is None:
         grad_hidden = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
     if workspace is None:
-        workspace = torch.empty(lmhead_workspace_bytes(T, V, chunk_rows),
+        fused = not backward and not (flags & FLAG_FORCE_STREAMING)
+        K = batch["mu_topk_ids"].shape[1] if batch["mu_topk_ids"] is not None else 0
+        workspace = torch.empty(lmhead_fwd_workspace_bytes(T, V, K, chunk_rows) if fused else lmhead_workspace_bytes(T, V, chunk_rows),
                                 dtype=torch.uint8, device=dev)
     a = DppoLmheadArgs()
     a.loss = make_args(torch.empty((0, V), dtype=torch.bfloat16, device=dev), batch["sampled_ids"], batch["mu_logp"],
                        batch["advantages"], batch["delta"], batch["variant"], batch["loss_scale"], out,
-                       batch["mu_topk_ids"], batch["mu_topk_logp"], V=V, **rule)
+                       batch["mu_topk_ids"], batch["mu_topk_logp"], V=V, flags=flags, **rule)
     a.loss.T, a.loss.logits = T, None
     a.hidden, a.ld_hidden, a.d = h.data_ptr(), h.stride(0), d
     a.weight, a.ld_weight = w.data_ptr(), w.stride(0)

@@ -104,6 +104,42 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = fal
   return DPPO_OK;
 }
 
+// The kernel arguments of one (validated) call, scratch pointers left empty.
+dppo::KParams make_kparams(const dppo_args_t* a, bool grad) {
+  dppo::KParams p;
+  p.logits = static_cast<const uint16_t*>(a->logits);
+  p.grad = grad ? static_cast<uint16_t*>(a->grad_logits) : nullptr;
+  p.sampled = a->sampled_ids;
+  p.mu_logp = a->mu_logp;
+  const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
+  p.tk_ids = topk ? a->mu_topk_ids : nullptr;
+  p.tk_lp = topk ? a->mu_topk_logp : nullptr;
+  p.K = topk ? a->K : 0;
+  p.adv = a->advantages;
+  p.loss_tok = a->loss_tok;
+  p.divergence = a->divergence;
+  p.mask = a->mask;
+  p.diag = a->diagnostics;
+  p.partial = nullptr;
+  p.row_counters = nullptr;
+  p.row_loss = nullptr;
+  p.gath = nullptr;
+  p.ld = a->ld;
+  p.T = static_cast<int32_t>(a->T);
+  p.V = static_cast<int32_t>(a->V);
+  p.variant = a->variant;
+  p.delta = a->delta;
+  p.loss_scale = a->loss_scale;
+  p.mask_rule = a->mask_rule;
+  p.eps_low = a->eps_low;
+  p.eps_high = a->eps_high;
+  p.ratio_cap = (a->ratio_cap > 0.f && std::isfinite(a->ratio_cap)) ? a->ratio_cap : 0.f;   // 0: no cap
+  const bool full = (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL);
+  p.mu_logits = full ? static_cast<const uint16_t*>(a->mu_logits) : nullptr;
+  p.mu_ld = full ? a->mu_ld : 0;
+  return p;
+}
+
 // Device scratch of one loss launch.  partial: one loss partial sum per workgroup (max_parts of
 // them).  counters / row_loss (both or neither): the row counter and one loss term per row,
 // for the kernel form that hands its rows out at run time.
@@ -139,36 +175,9 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     if (!stream_device(s, &dev)) return DPPO_ERR_LAUNCH;
     const int cus = device_info(dev).cus;
 
-    dppo::KParams p;
-    p.logits = static_cast<const uint16_t*>(a->logits);
-    p.grad = grad ? static_cast<uint16_t*>(a->grad_logits) : nullptr;
-    p.sampled = a->sampled_ids;
-    p.mu_logp = a->mu_logp;
-    const bool topk = (a->variant == DPPO_TOPK_TV || a->variant == DPPO_TOPK_KL);
-    p.tk_ids = topk ? a->mu_topk_ids : nullptr;
-    p.tk_lp = topk ? a->mu_topk_logp : nullptr;
-    p.K = topk ? a->K : 0;
-    p.adv = a->advantages;
-    p.loss_tok = a->loss_tok;
-    p.divergence = a->divergence;
-    p.mask = a->mask;
-    p.diag = a->diagnostics;
+    dppo::KParams p = make_kparams(a, grad);
     p.partial = partial;
-    p.row_counters = nullptr;
-    p.row_loss = nullptr;
-    p.ld = a->ld;
-    p.T = static_cast<int32_t>(a->T);
-    p.V = static_cast<int32_t>(a->V);
-    p.variant = a->variant;
-    p.delta = a->delta;
-    p.loss_scale = a->loss_scale;
-    p.mask_rule = a->mask_rule;
-    p.eps_low = a->eps_low;
-    p.eps_high = a->eps_high;
-    p.ratio_cap = (a->ratio_cap > 0.f && std::isfinite(a->ratio_cap)) ? a->ratio_cap : 0.f;   // 0: no cap
     const bool full = (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL);
-    p.mu_logits = full ? static_cast<const uint16_t*>(a->mu_logits) : nullptr;
-    p.mu_ld = full ? a->mu_ld : 0;
 
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
     // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
@@ -292,14 +301,29 @@ int64_t lmhead_chunk_rows(const dppo_lmhead_args_t* a) {
   return c < 1 ? 1 : c;
 }
 
-// [partial sums | one chunk of logits, which becomes the chunk's logit gradient in place]
+size_t align256(size_t n) { return (n + 255u) & ~static_cast<size_t>(255u); }
+
+// Forward only: [64 KiB | one loss term per row | per chunk: tile statistics, 16 bytes per row and
+// 256-column tile | per chunk: the logits at the sampled and top-K ids, 4 (K + 1) bytes per row]
+size_t lmhead_fwd_workspace(int64_t T, int64_t V, int32_t K, int64_t chunk_rows) {
+  int64_t c = chunk_rows > 0 ? chunk_rows : kLmheadDefaultChunk;
+  if (c > T) c = T;
+  if (c < 1) c = 1;
+  const size_t tiles_n = static_cast<size_t>((V + dppo::kGemmTileN - 1) / dppo::kGemmTileN);
+  return DPPO_WORKSPACE_BYTES + align256(static_cast<size_t>(T > 0 ? T : 0) * sizeof(double)) +
+         align256(static_cast<size_t>(c) * tiles_n * 16) + align256(static_cast<size_t>(c) * static_cast<size_t>(K + 1) * 4);
+}
+
+// Forward + backward: [partial sums | one chunk of logits, which becomes the chunk's logit gradient
+// in place]; never less than the forward-only call needs with the largest K.
 size_t lmhead_workspace(int64_t T, int64_t V, int64_t chunk_rows) {
   int64_t c = chunk_rows > 0 ? chunk_rows : kLmheadDefaultChunk;
   if (c > T) c = T;
   if (c < 1) c = 1;
   size_t b = DPPO_WORKSPACE_BYTES;
   b += static_cast<size_t>(c) * static_cast<size_t>(V) * 2;
-  return b;
+  const size_t f = lmhead_fwd_workspace(T, V, DPPO_KMAX, chunk_rows);
+  return b > f ? b : f;
 }
 
 dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
@@ -314,7 +338,14 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
   const bool want_gw = grad && a->grad_weight != nullptr;
   if (want_gw && (a->ld_grad_weight < d || a->ld_grad_weight % 4 != 0)) return DPPO_ERR_SHAPE;
   if (want_gw && (reinterpret_cast<uintptr_t>(a->grad_weight) & 15u)) return DPPO_ERR_ALIGN;
-  if (!a->workspace || a->workspace_bytes < lmhead_workspace(T, V, a->chunk_rows)) return DPPO_ERR_WORKSPACE;
+  // Forward only, nothing of size [chunk, V] is needed: the first product leaves softmax statistics
+  // instead of logits (unless the caller asks for the general kernels, for comparison).
+  const bool fused_fwd = !grad && !(a->loss.flags & DPPO_FLAG_FORCE_STREAMING);
+  if (a->loss.K < 0 || a->loss.K > DPPO_KMAX) return DPPO_ERR_K;
+  const bool topk_variant = (a->loss.variant == DPPO_TOPK_TV || a->loss.variant == DPPO_TOPK_KL);
+  const int32_t Ktop = topk_variant ? a->loss.K : 0;
+  if (!a->workspace || a->workspace_bytes < (fused_fwd ? lmhead_fwd_workspace(T, V, Ktop, a->chunk_rows) : lmhead_workspace(T, V, a->chunk_rows)))
+    return DPPO_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DPPO_ERR_ALIGN;
   if (T > 0) {
     if (!a->hidden || !a->weight || (grad && !a->grad_hidden)) return DPPO_ERR_NULL;
@@ -337,6 +368,43 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
   const dppo_status_t st0 = check_args(&c, grad);
   if (st0 != DPPO_OK) return st0;
 
+  if (fused_fwd) {
+    const int tiles_n = static_cast<int>((V + dppo::kGemmTileN - 1) / dppo::kGemmTileN);
+    double* row_loss = reinterpret_cast<double*>(ws + DPPO_WORKSPACE_BYTES);
+    char* part = ws + DPPO_WORKSPACE_BYTES + align256(static_cast<size_t>(T) * sizeof(double));
+    char* gath = part + align256(static_cast<size_t>(chunk) * static_cast<size_t>(tiles_n) * 16);
+    for (int64_t r0 = 0; r0 < T; r0 += chunk) {
+      const int64_t rows = (T - r0 < chunk) ? (T - r0) : chunk;
+      c.T = rows;
+      c.sampled_ids = a->loss.sampled_ids + r0;
+      c.mu_logp = a->loss.mu_logp + r0;
+      c.advantages = a->loss.advantages + r0;
+      c.mu_topk_ids = a->loss.mu_topk_ids ? a->loss.mu_topk_ids + r0 * a->loss.K : nullptr;
+      c.mu_topk_logp = a->loss.mu_topk_logp ? a->loss.mu_topk_logp + r0 * a->loss.K : nullptr;
+      c.loss_tok = a->loss.loss_tok ? a->loss.loss_tok + r0 : nullptr;
+      c.divergence = a->loss.divergence + r0;
+      c.mask = a->loss.mask + r0;
+      c.diagnostics = a->loss.diagnostics ? a->loss.diagnostics + r0 * DPPO_NDIAG : nullptr;
+      dppo::KParams p = make_kparams(&c, false);
+      p.logits = nullptr;
+      dppo::GemmStats gs;
+      gs.part = reinterpret_cast<dppo::gemm_f32x4*>(part);
+      gs.gath = reinterpret_cast<float*>(gath);
+      gs.sampled = p.sampled;
+      gs.tk_ids = p.tk_ids;
+      gs.Ktop = p.K;
+      gs.tiles_n = tiles_n;
+      p.gath = gs.gath;
+      const uint16_t* h = static_cast<const uint16_t*>(a->hidden) + r0 * a->ld_hidden;
+      if (dppo::launch_gemm_stats(h, a->ld_hidden, static_cast<const uint16_t*>(a->weight), a->ld_weight, static_cast<int>(rows),
+                                  static_cast<int>(V), static_cast<int>(d), gs, s) != hipSuccess)
+        return DPPO_ERR_LAUNCH;
+      if (dppo::launch_lmhead_rows(p, gs, row_loss + r0, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+    }
+    if (dppo::launch_finalize(row_loss, static_cast<int>(T), a->loss.loss_scale, a->loss.loss, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+    if (T > 0) g_last_path = "lmhead_fused";
+    return DPPO_OK;
+  }
   const int max_parts = static_cast<int>(kPartialBytes / sizeof(double));
   const int64_t nchunks = T > 0 ? (T + chunk - 1) / chunk : 0;
   const int parts_per_chunk = nchunks > 0 ? static_cast<int>(max_parts / nchunks) : max_parts;
@@ -439,6 +507,10 @@ dppo_status_t dppo_lmhead_loss_fwd(const dppo_lmhead_args_t* args, void* stream)
 dppo_status_t dppo_lmhead_loss_fwd_bwd(const dppo_lmhead_args_t* args, void* stream) { return run_lmhead(args, stream, true); }
 
 size_t dppo_lmhead_args_size(void) { return sizeof(dppo_lmhead_args_t); }
+
+size_t dppo_lmhead_fwd_workspace_bytes(int64_t T, int64_t V, int32_t K, int64_t chunk_rows) {
+  return lmhead_fwd_workspace(T, V, K < 0 ? 0 : K, chunk_rows);
+}
 
 dppo_status_t dppo_gemm_nt(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
                            int64_t M, int64_t N, int64_t K, void* stream) {

@@ -39,6 +39,9 @@ struct KParams {
   float ratio_cap;          // C of the unified gradient form; 0 = no cap
   const uint16_t* mu_logits;  // bf16 bits [T, mu_ld]: the rollout policy's logits (full-vocabulary variants) or nullptr
   int64_t mu_ld;
+  // Hidden-state path, forward only: there is no logits matrix; the logit of the row's sampled id is
+  // gath[row * (K + 1)], that of its top-K entry k is gath[row * (K + 1) + 1 + k].  Else nullptr.
+  const float* gath;
 };
 
 // The subset of the kernel arguments the per-row epilogue needs.
@@ -53,12 +56,14 @@ struct EpiParams {
   float delta, loss_scale;
   int32_t mask_rule;
   float eps_low, eps_high, ratio_cap;
+  const float* gath;
 };
 __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   EpiParams e;
   e.tk_ids = p.tk_ids; e.tk_lp = p.tk_lp; e.loss_tok = p.loss_tok; e.divergence = p.divergence; e.mask = p.mask; e.diag = p.diag;
   e.V = p.V; e.K = p.K; e.variant = p.variant; e.delta = p.delta; e.loss_scale = p.loss_scale;
   e.mask_rule = p.mask_rule; e.eps_low = p.eps_low; e.eps_high = p.eps_high; e.ratio_cap = p.ratio_cap;
+  e.gath = p.gath;
   return e;
 }
 
@@ -101,14 +106,19 @@ __device__ __forceinline__ u32x4 row_load16(row_rsrc_t r, uint32_t voff, uint32_
 // pending the compiler falls back to waiting for everything (s_waitcnt vmcnt(0)), whereas loads
 // alone complete in order and it waits for exactly the one it needs (vmcnt = number of loads
 // issued after it, which stays correct however many stores are in flight).
-// What the compiler no longer does for a store it cannot see: before a vector-ALU instruction may
-// overwrite the data registers of a vector-memory store of more than 8 bytes, this target wants
-// wait states (the compiler's own rule: two, when the store's scalar offset is not a register).
-// The scalar offset here is always a scalar-register operand (the "s" constraint below); the
-// statement nevertheless carries `s_nop 1` (two wait states), which covers either form of the
-// operand: without any wait state, rows of few chunks came out wrong once the stores stood back
-// to back and the compiler reused the data registers at once.  A later vector-memory load into
-// the same registers queues behind the store and needs nothing.
+// What the compiler no longer does for a store it cannot see, and the statement therefore does
+// itself:
+//  * BEFORE the store, five wait states (`s_nop 4`).  On this target a vector-memory instruction
+//    must not read a scalar register within five wait states of a vector-ALU instruction writing
+//    it, and the compiler restores spilled scalar registers with exactly such an instruction
+//    (v_readlane_b32) wherever it likes, also directly in front of this statement, whose scalar
+//    operands (descriptor, offset) it then believes to be ready.  Seen in the generated code of the
+//    full-vocabulary kernel: the offset register reloaded one instruction ahead of the first store
+//    of a row, and that store going to the address of a stale offset.
+//  * AFTER it, two wait states (`s_nop 1`) before a vector-ALU instruction may overwrite the data
+//    registers of a store of more than 8 bytes (the compiler's own rule for this target, in the
+//    form with an immediate scalar offset; it covers the register form used here too).  A later
+//    vector-memory load into the same registers queues behind the store and needs nothing.
 // The store is marked non-temporal (a gradient row is not read again by this kernel): measured
 // 2.5 % faster on the headline shape; the same mark on the row loads measured slower.
 typedef int row_desc_t __attribute__((ext_vector_type(4)));
@@ -122,7 +132,7 @@ __device__ __forceinline__ row_desc_t make_row_desc(const void* base, uint32_t b
   return d;
 }
 __device__ __forceinline__ void row_store16_untracked(row_desc_t d, uint32_t voff, uint32_t soff, u32x4 v) {
-  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 1" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
+  asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 1" ::"v"(v), "v"(voff), "s"(d), "s"(soff) : "memory");
 }
 
 // First row of a workgroup in a row-per-workgroup kernel whose rows advance by gridDim.x: a
@@ -361,7 +371,7 @@ __device__ __forceinline__ TopkLane load_topk_lane(const P& p, int row, int a, c
     if (id >= 0 && id < p.V && id != a) {
       t.id = id;
       t.lp = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
-      t.z = bf16_bits_to_float(zrow[id]);
+      t.z = p.gath ? p.gath[static_cast<int64_t>(row) * (p.K + 1) + 1 + lane] : bf16_bits_to_float(zrow[id]);
     }
   }
   return t;

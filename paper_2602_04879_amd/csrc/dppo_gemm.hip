@@ -51,7 +51,10 @@ __device__ __forceinline__ uint32_t lds_off(int row, int kvec) {
 // One 256 x 256 tile.  FULL: all 256 rows and columns of the tile exist, so the stores need no
 // range checks.  A panel row past the matrix re-reads the last valid row: its products are never stored.
 // OUT selects what leaves the tile: bf16 (rounded to nearest even), fp32, or fp32 added to what C holds.
-enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
+// kOutStats: nothing of C is stored.  The tile's logits, rounded to bf16 as a stored tile would be,
+// leave as softmax statistics per row (GemmStats below): the forward of the hidden-state path then
+// never writes a logit to memory.
+enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2, kOutStats = 3 };
 
 // TA: A is [K, M]; TB: B is [K, N] (the contraction index is the ROW index of that operand; with
 // both, C = A^T B; with TB alone, C = A B).  The panel of such an operand
@@ -62,7 +65,7 @@ enum : int { kOutBf16 = 0, kOutF32 = 1, kOutF32Add = 2 };
 template <bool FULL, int OUT, bool TA, bool TB>
 __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* lds1, const uint16_t* __restrict__ A, int64_t lda,
                                           const uint16_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv, int64_t ldc,
-                                          int M, int N, int K, int m0, int n0) {
+                                          int M, int N, int K, int m0, int n0, const GemmStats& gs) {
   const int tid = threadIdx.x, lane = tid & 63, wid = uniform_i(tid >> 6);
   const int wm = wid >> 1, wn = wid & 1;
   const int rows_a = min(kBM, M - m0), rows_b = min(kBN, N - n0);     // (TA / TB: columns of A / of B)
@@ -218,9 +221,86 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   DPPO_PIN;
 
-  // Store.  The products were formed with the operands swapped (B fragment first), so a lane's
-  // four accumulators of a 16 x 16 block are four consecutive COLUMNS (lane/16)*4 + 0..3 of row
-  // lane%16.  bf16: two neighbouring blocks exchange halves between lane rows (one
+  // The products were formed with the operands swapped (B fragment first), so a lane's four
+  // accumulators of a 16 x 16 block are four consecutive COLUMNS (lane/16)*4 + 0..3 of row lane%16.
+  if (OUT == kOutStats) {
+    // ---- softmax statistics of the tile instead of the tile ------------------------------------
+    // Per row of the tile, over its 256 columns (those below N), of the logits ROUNDED to bf16:
+    // the integer offset b = -ceil(max * log2e), s = sum 2^(z*log2e + b) and t = sum 2^x * x (for
+    // the entropy), the row's sampled token left out as in the loss kernels.  A lane holds 32
+    // columns of each of its 8 rows; the four lanes of a row (lane, lane+16, +32, +48) combine by
+    // shuffles, the two waves of a row through shared memory.  The rounded tile itself goes to
+    // shared memory (the two stages are free now: 128 rows of 512 bytes each, 32-byte blocks
+    // XOR-ed with the row so that a 16-lane write spreads over the banks), from where the logits at
+    // the sampled and the top-K ids that fall into this tile are picked.
+    __shared__ float sh_part[2][kBM][3];
+    __syncthreads();                       // every wave has read its last fragments: the stages can be overwritten
+    unsigned char* half = wm ? lds1 : lds0;
+    const int col0 = n0 + wn * 128;        // first column of this wave's quadrant
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rl = i * 16 + frow;                       // row inside the wave's 128
+      const int row = m0 + wm * 128 + rl;
+      const int a_loc = (row < M) ? gs.sampled[row] - col0 : -1;
+      float z[8][4];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t lo = pack_bf16x2(acc[i][j][0], acc[i][j][1]), hi = pack_bf16x2(acc[i][j][2], acc[i][j][3]);
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        *reinterpret_cast<u32x2*>(half + rl * 512 + (((wn * 8 + j) ^ frow) << 5) + fk * 8) = u32x2{lo, hi};
+        z[j][0] = __uint_as_float(lo << 16); z[j][1] = __uint_as_float(lo & 0xffff0000u);
+        z[j][2] = __uint_as_float(hi << 16); z[j][3] = __uint_as_float(hi & 0xffff0000u);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int cl = j * 16 + fk * 4 + e;
+          if ((!FULL && col0 + cl >= N) || cl == a_loc) z[j][e] = -INFINITY;
+          mx = fmaxf(mx, z[j][e]);
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float b = -ceilf(fmaxf(mx, kNegBig) * kLog2e);
+      float s = 0.f, t = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float e4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x = fmaf(z[j][e], kLog2e, b);
+          e4[e] = fast_exp2(x);
+          t = fma_ex(e4[e], x, t);
+        }
+        s += (e4[0] + e4[1]) + (e4[2] + e4[3]);
+      }
+      s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
+      t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);
+      if (fk == 0) { sh_part[wn][wm * 128 + rl][0] = b; sh_part[wn][wm * 128 + rl][1] = s; sh_part[wn][wm * 128 + rl][2] = t; }
+    }
+    __syncthreads();
+    {
+      const int row = m0 + tid;
+      const float b0 = sh_part[0][tid][0], b1 = sh_part[1][tid][0], b = fminf(b0, b1);
+      const float d0 = b - b0, d1 = b - b1, c0 = fast_exp2(d0), c1 = fast_exp2(d1);       // exact powers of two
+      const float s = sh_part[0][tid][1] * c0 + sh_part[1][tid][1] * c1;
+      const float t = c0 * fmaf(d0, sh_part[0][tid][1], sh_part[0][tid][2]) + c1 * fmaf(d1, sh_part[1][tid][1], sh_part[1][tid][2]);
+      if (row < M) gs.part[static_cast<int64_t>(row) * gs.tiles_n + n0 / kBN] = f32x4{b, s, t, 0.f};
+    }
+    const int K1 = gs.Ktop + 1;
+    for (int idx = tid; idx < kBM * K1; idx += 256) {
+      const int rl = idx / K1, k = idx - rl * K1, row = m0 + rl;
+      if (row < M) {
+        const int id = (k == 0) ? gs.sampled[row] : gs.tk_ids[static_cast<int64_t>(row) * gs.Ktop + (k - 1)];
+        const int c = id - n0;
+        if (c >= 0 && c < kBN && id < N) {
+          const unsigned char* src = ((rl >> 7) ? lds1 : lds0) + (rl & 127) * 512 + (((c >> 4) ^ (rl & 15)) << 5) + (c & 15) * 2;
+          gs.gath[static_cast<int64_t>(row) * K1 + k] = bf16_bits_to_float(*reinterpret_cast<const uint16_t*>(src));
+        }
+      }
+    }
+    return;
+  }
+  // Store.  bf16: two neighbouring blocks exchange halves between lane rows (one
   // v_permlane16_swap per register pair), after which a lane owns 8 consecutive columns: one
   // 16-byte store, 64 contiguous bytes per row and instruction.  fp32: 16 bytes per lane as they are.
   const bool quad_aligned = ((reinterpret_cast<uintptr_t>(Cv) & 15u) == 0) && (ldc % 8 == 0);
@@ -282,7 +362,7 @@ template <int OUT, bool TA, bool TB>
 __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                            const uint16_t* __restrict__ B, int64_t ldb,
                                                            void* __restrict__ C, int64_t ldc, int M, int N, int K,
-                                                           int tiles_m, int tiles_n, int blocks_m, int blocks_per_die) {
+                                                           int tiles_m, int tiles_n, int blocks_m, int blocks_per_die, const GemmStats gs) {
   // two stages of (A panel | B panel): 2 x 64 KiB of the compute unit's 160 KiB
   __shared__ __attribute__((aligned(16))) unsigned char lds0[kStageBytes];
   __shared__ __attribute__((aligned(16))) unsigned char lds1[kStageBytes];
@@ -292,8 +372,8 @@ __global__ __launch_bounds__(256) void dppo_gemm_nt_kernel(const uint16_t* __res
   const int tm = bm * kGroupM + (within % kGroupM), tn = bn * kGroupN + (within / kGroupM);
   if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * kBM, n0 = tn * kBN;
-  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
-  else                                gemm_tile<false, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0);
+  if (M - m0 >= kBM && N - n0 >= kBN) gemm_tile<true, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0, gs);
+  else                                gemm_tile<false, OUT, TA, TB>(lds0, lds1, A, lda, B, ldb, C, ldc, M, N, K, m0, n0, gs);
 }
 
 }  // namespace
@@ -305,9 +385,24 @@ hipError_t launch_gemm_nt(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  if (out == 0)      hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else               hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  if (out == 0)      hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
+  else if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
+  else               hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, false, false>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
+  return hipGetLastError();
+}
+
+// The first product of the hidden-state path with nothing of C stored: per row and column tile the
+// softmax statistics of the bf16-rounded logits, and the logits at the sampled and top-K ids.
+hipError_t launch_gemm_stats(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, int K,
+                             const GemmStats& gs, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
+  if (gs.tiles_n != tiles_n) return hipErrorInvalidValue;
+  const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
+  const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
+  const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
+  hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutStats, false, false>), grid, wg, 0, s, A, lda, B, ldb, static_cast<void*>(nullptr), int64_t(0), M, N, K,
+                     tiles_m, tiles_n, blocks_m, blocks_per_die, gs);
   return hipGetLastError();
 }
 
@@ -319,8 +414,8 @@ hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
-  else          hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  if (out == 1) hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
+  else          hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutF32Add, true, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
   return hipGetLastError();
 }
 
@@ -332,7 +427,7 @@ hipError_t launch_gemm_nn(const uint16_t* A, int64_t lda, const uint16_t* B, int
   const int blocks_m = (tiles_m + kGroupM - 1) / kGroupM, blocks_n = (tiles_n + kGroupN - 1) / kGroupN;
   const int blocks_per_die = (blocks_m * blocks_n + 7) / 8;
   const dim3 grid(8 * blocks_per_die * kGroupM * kGroupN), wg(256);
-  hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die);
+  hipLaunchKernelGGL((dppo_gemm_nt_kernel<kOutBf16, false, true>), grid, wg, 0, s, A, lda, B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, blocks_m, blocks_per_die, GemmStats{});
   return hipGetLastError();
 }
 

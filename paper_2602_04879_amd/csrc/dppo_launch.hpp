@@ -43,6 +43,25 @@ hipError_t launch_gemm_tn(const uint16_t* A, int64_t lda, const uint16_t* B, int
 // Clears the eight row counters of the register-resident kernel's run-time row hand-out.
 hipError_t launch_clear_counters(int32_t* counters, hipStream_t s);
 
+// What the first product of the hidden-state path leaves instead of logits (forward only): per row
+// and 256-column tile the statistics (b, s, t, -) of the bf16-rounded logits of that tile, the
+// sampled token's own term left out (b: integer offset -ceil(max * log2e); s = sum 2^(z*log2e + b);
+// t = sum 2^x * x), and the rounded logits at the row's sampled id and top-K ids.
+typedef float gemm_f32x4 __attribute__((ext_vector_type(4)));
+struct GemmStats {
+  gemm_f32x4* part = nullptr;        // [M][tiles_n]
+  float* gath = nullptr;             // [M][Ktop + 1]: column 0 the sampled id, 1..Ktop the top-K ids; ids outside [0, N) leave their entry unwritten
+  const int32_t* sampled = nullptr;  // [M]
+  const int32_t* tk_ids = nullptr;   // [M][Ktop] (unused if Ktop = 0)
+  int32_t Ktop = 0, tiles_n = 0;
+};
+constexpr int kGemmTileN = 256;
+hipError_t launch_gemm_stats(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, int K,
+                             const GemmStats& gs, hipStream_t s);
+// Per row: combine the tiles' statistics and run the per-row epilogue (one wave per row).  p holds the
+// per-token arrays of the rows (logits unused), row_loss [p.T] receives the loss terms.
+hipError_t launch_lmhead_rows(const KParams& p, const GemmStats& gs, double* row_loss, hipStream_t s);
+
 // loss[0] = loss_scale * sum(partial[0..n)) in a fixed order.
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s);
 

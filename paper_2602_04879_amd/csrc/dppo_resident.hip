@@ -80,8 +80,14 @@ constexpr int kChunkStep = 4;
 // requested one row ahead (one thread, an atomic that returns while the row streams) and
 // published through shared memory at the row's barrier.  The loss terms go to one slot per ROW,
 // so the scalar loss does not depend on which workgroup took which row.
+// Waves per SIMD the register allocation must leave room for: the 512-thread shapes are one
+// workgroup of two waves per SIMD; the 256-thread shapes (one wave per SIMD and workgroup) keep three
+// workgroups per compute unit up to 16 chunks (a budget of 168 registers; left to itself the
+// compiler lands within a register or two of that limit, on either side).
+constexpr int resident_min_waves(int threads, int nchunk) { return threads == 512 ? 2 : (nchunk <= 16 ? 3 : 2); }
+
 template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN>
-__global__ __launch_bounds__(THREADS) void dppo_resident_kernel(const KParams p) {
+__global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
   // Forward only, the row loads are marked non-temporal (measured 3.5 % faster on the headline shape);

@@ -185,14 +185,27 @@ hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, 
   }
 }
 
-// Sum the per-workgroup partial sums in a fixed order and store loss = loss_scale * sum.
-__global__ __launch_bounds__(256) void dppo_finalize_kernel(const double* partial, int n, float loss_scale, float* loss) {
-  __shared__ double sh[256];
-  double acc = 0.0;
-  for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
-  sh[threadIdx.x] = acc;
+// Sum the n terms (per-workgroup partial sums, or one term per row) in a fixed order and store
+// loss = loss_scale * sum.  One workgroup of 1024 threads: thread i takes terms i, i + 1024, ...
+// into eight accumulators (so that eight loads are in flight; term k goes to accumulator
+// (k / 1024) % 8), which are then added in a fixed order, and a tree over the threads follows.
+__global__ __launch_bounds__(1024) void dppo_finalize_kernel(const double* partial, int n, float loss_scale, float* loss) {
+  __shared__ double sh[1024];
+  double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+  int i = threadIdx.x;
+  for (; i + 7 * 1024 < n; i += 8 * 1024) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[i + u * 1024];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] += v[u];
+  }
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    if (i + u * 1024 < n) acc[u] += partial[i + u * 1024];
+  sh[threadIdx.x] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = 512; o > 0; o >>= 1) {
     if (static_cast<int>(threadIdx.x) < o) sh[threadIdx.x] += sh[threadIdx.x + o];
     __syncthreads();
   }
@@ -209,7 +222,7 @@ hipError_t launch_clear_counters(int32_t* counters, hipStream_t s) {
 }
 
 hipError_t launch_finalize(const double* partial, int n, float loss_scale, float* loss, hipStream_t s) {
-  hipLaunchKernelGGL(dppo_finalize_kernel, dim3(1), dim3(256), 0, s, partial, n, loss_scale, loss);
+  hipLaunchKernelGGL(dppo_finalize_kernel, dim3(1), dim3(1024), 0, s, partial, n, loss_scale, loss);
   return hipGetLastError();
 }
 

@@ -81,7 +81,7 @@ def _run_and_compare(w, d, *, exact=True, backward=True, chunk_rows=0, shift=0.0
     gw = torch.full((b["V"], d + 4), 7.0, dtype=torch.float32, device=DEV)[:, :d] if (backward and all_rows) else None
     res = B.run_lmhead(b, backward=backward, chunk_rows=chunk_rows, diagnostics=True, grad_weight=gw, **rule)
     torch.cuda.synchronize()
-    ref = _oracle(b, rows, **rule)
+    ref = _oracle(b, rows, want_grad=backward, **rule)
     cmp_batch = dict(b, logits=None)
     st = P.compare_rows(cmp_batch, res, rows, check_grad=False, ref=ref)
     if len(rows) == b["T"]:
@@ -413,6 +413,77 @@ def test_headline_vocabulary_sampled_rows():
     _say(f"       masked={(mask == 0).sum()} {st}")
 
 
+# --------------------------------------------------------------------------- forward only: no logit is ever written
+@pytest.mark.parametrize("variant,K,delta", [(W.BINARY_TV, 0, 0.2), (W.BINARY_KL, 0, 0.05), (W.TOPK_TV, 20, 0.2), (W.TOPK_KL, 150, 0.05)])
+@pytest.mark.parametrize("shift", [0.0, 2.0])
+def test_forward_only_from_tile_statistics(variant, K, delta, shift):
+    """dppo_lmhead_loss_fwd: the product kernel leaves per-tile softmax statistics and the gathered
+    logits instead of logits.  T = 300 in chunks of 128, V = 4160 = 16 tiles + a quarter tile, every
+    row against the oracle at the bar of the logits path, and against the route through a chunk of
+    logits (same bf16 logits, another summation order)."""
+    w = W.Workload("lm_fused", 3, 100, 4160, variant, delta, K=K, logit_std=3.0, noise_std=1.0 if shift else 0.05, adv="normal", seed=107)
+    b, res, st, ref = _run_and_compare(w, 128, chunk_rows=128, shift=shift, backward=False)
+    assert B.last_path() == "lmhead_fused"
+    if shift:
+        assert 0 < st["masked"] < b["T"]
+    ws = res["workspace_buf"].numel()
+    assert ws == B.lmhead_fwd_workspace_bytes(b["T"], b["V"], K, 128) and ws < B.lmhead_workspace_bytes(b["T"], b["V"], 128)
+    chunked = B.run_lmhead(b, backward=False, chunk_rows=128, diagnostics=True, flags=B.FLAG_FORCE_STREAMING)
+    torch.cuda.synchronize()
+    assert B.last_path() == "lmhead"
+    assert torch.equal(res["mask"], chunked["mask"])
+    torch.testing.assert_close(res["divergence"], chunked["divergence"], rtol=1e-4, atol=2e-7)
+    torch.testing.assert_close(res["loss"], chunked["loss"], rtol=1e-5, atol=1e-9)
+    again = B.run_lmhead(b, backward=False, chunk_rows=128, diagnostics=True)      # bitwise reproducible
+    torch.cuda.synchronize()
+    for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics"):
+        assert torch.equal(res[k], again[k]), k
+
+
+def test_forward_only_ignored_rows_padding_ids_and_ids_in_the_ragged_last_tile():
+    w = W.Workload("lm_fused_edge", 2, 140, 4160, W.TOPK_TV, 0.1, K=12, logit_std=3.0, noise_std=1.0, adv="normal", seed=109)
+    b = W.make_lmhead_batch(w, 64, DEV, exact=True, shift_sampled=2.0)
+    b["sampled_ids"][::9] = -1
+    b["sampled_ids"][3::13] = b["V"] + 5
+    b["sampled_ids"][5::17] = b["V"] - 1                       # last column, in the quarter tile
+    b["mu_logp"][5::17] = -3.0
+    b["mu_topk_ids"][:, 4] = -1                                # padding entries
+    b["mu_topk_ids"][1::2, 7] = b["V"]
+    b["mu_topk_ids"][::3, 2] = b["V"] - 2
+    b["advantages"][2::6] = 0.0
+    rows = np.arange(b["T"])
+    ref = _oracle(b, rows, want_grad=False)
+    res = B.run_lmhead(b, backward=False, chunk_rows=100, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "lmhead_fused"
+    st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    ign = (b["sampled_ids"] < 0) | (b["sampled_ids"] >= b["V"])
+    assert torch.all(res["mask"][ign] == 0) and torch.all(res["divergence"][ign] == 0) and torch.all(res["loss_tok"][ign] == 0)
+    _say(f"       {st}")
+
+
+def test_forward_only_headline_vocabulary_sampled_rows():
+    """V = 151936 (593 tiles and a half), d = 4096, T = 2560 in chunks of 1024: sampled rows against
+    the oracle on inputs whose logits are exact in fp32, Top-K TV and Binary KL."""
+    for variant, K, delta in ((W.TOPK_TV, 20, 0.2), (W.BINARY_KL, 0, 0.05)):
+        w = W.Workload("lm_qwen3_fwd", 5, 512, 151936, variant, delta, K=K, logit_std=3.0, noise_std=0.3, adv="pm1", seed=113)
+        _say(f"[case] lmhead forward only {w.name} T={w.T} V={w.V} d=4096 variant={variant}")
+        b = W.make_lmhead_batch(w, 4096, DEV, exact=True, shift_sampled=1.0)
+        res = B.run_lmhead(b, backward=False, chunk_rows=1024, diagnostics=True)
+        torch.cuda.synchronize()
+        assert B.last_path() == "lmhead_fused"
+        mask = res["mask"].cpu().numpy()
+        rng = np.random.default_rng(13)
+        pick = {0, w.T - 1, 1023, 1024, 2047, 2048} | set(rng.integers(0, w.T, 6).tolist()) | set(np.nonzero(mask == 0)[0][:4].tolist())
+        rows = np.array(sorted(pick))
+        ref = _oracle(b, rows, want_grad=False)
+        st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
+        P.check_loss_scalar(b, res)
+        assert 0 < (mask == 0).sum() < w.T and st["masked"] > 0
+        _say(f"       masked={(mask == 0).sum()} {st}")
+
+
 def test_empty_batch_and_single_token():
     w = W.Workload("lm_one", 1, 1, 256, W.TOPK_KL, 0.05, K=4, logit_std=3.0, noise_std=0.5, adv="pm1", seed=103)
     _run_and_compare(w, 64, shift=1.0)
@@ -423,3 +494,7 @@ def test_empty_batch_and_single_token():
     res = B.run_lmhead(empty, grad_weight=gw)
     torch.cuda.synchronize()
     assert res["loss"].item() == 0.0 and (gw == 2.0).all()          # nothing to add, nothing touched
+    res = B.run_lmhead(empty, backward=False)
+    torch.cuda.synchronize()
+    assert res["loss"].item() == 0.0
+    _run_and_compare(w, 64, shift=1.0, backward=False)
