@@ -308,19 +308,35 @@ __device__ __forceinline__ double log2_fast(double x) {
 
 // 2^x in float64 (0 below the float64 range, +inf above it): x = n + f with |f| <= 1/2, and
 // 2^f = exp(f ln 2) by the Taylor polynomial of degree 12 (|f ln 2| <= 0.347: truncation below
-// 1e-16 relative), evaluated pairwise (Estrin) so that the dependent chain is five operations deep
-// instead of twelve, then scaled by 2^n.
+// 1e-16 relative), then scaled by 2^n.  Horner form on purpose: every step then has ONE constant
+// operand, which the instruction can take from scalar registers; a pairwise (Estrin) evaluation is
+// five steps deep instead of twelve but needs two constants per step, i.e. a dozen constants in
+// vector registers, which the compiler keeps for the whole kernel and, beside a resident row, spills.
+// kconst() pins a constant to scalar registers at its point of use (left to itself the compiler
+// builds float64 constants in vector registers once, at the top of the kernel, and spills them).
+__device__ __forceinline__ double kconst(double c) {
+  asm volatile("" : "+s"(c));
+  return c;
+}
 __device__ __forceinline__ double exp2_d(double x) {
   if (!(x > -1080.0)) return 0.0;
   if (x > 1024.0) return __builtin_inf();
   const double n = __builtin_rint(x);
-  const double t = (x - n) * kLn2;
-  const double t2 = t * t, t4 = t2 * t2, t8 = t4 * t4;
-  const double a0 = 1.0 + t, a1 = fma(t, 1.0 / 6, 0.5), a2 = fma(t, 1.0 / 120, 1.0 / 24), a3 = fma(t, 1.0 / 5040, 1.0 / 720),
-               a4 = fma(t, 1.0 / 362880, 1.0 / 40320), a5 = fma(t, 1.0 / 39916800, 1.0 / 3628800);
-  const double b0 = fma(t2, a1, a0), b1 = fma(t2, a3, a2), b2 = fma(t2, a5, a4);
-  const double c0 = fma(t4, b1, b0), c1 = fma(t4, 1.0 / 479001600, b2);
-  return ldexp(fma(t8, c1, c0), static_cast<int>(n));
+  const double t = (x - n) * kconst(kLn2);
+  double p = kconst(1.0 / 479001600);
+  p = fma(p, t, kconst(1.0 / 39916800));
+  p = fma(p, t, kconst(1.0 / 3628800));
+  p = fma(p, t, kconst(1.0 / 362880));
+  p = fma(p, t, kconst(1.0 / 40320));
+  p = fma(p, t, kconst(1.0 / 5040));
+  p = fma(p, t, kconst(1.0 / 720));
+  p = fma(p, t, kconst(1.0 / 120));
+  p = fma(p, t, kconst(1.0 / 24));
+  p = fma(p, t, kconst(1.0 / 6));
+  p = fma(p, t, 0.5);
+  p = fma(p, t, 1.0);
+  p = fma(p, t, 1.0);
+  return ldexp(p, static_cast<int>(n));
 }
 
 // log2(x) in float64 for a positive finite x: the hardware's fp32 logarithm of the mantissa as a

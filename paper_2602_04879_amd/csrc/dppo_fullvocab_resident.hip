@@ -46,17 +46,18 @@ struct RowStat {
     s *= static_cast<double>(sc);
     b = bn;
   }
+  __device__ __forceinline__ float term(float v, float other) {
+    const float x = fmaf(v, kLog2e, b), e = fast_exp2(x);
+    if (T) t = fma_ex(e, x, t);
+    if (U) u = fmaf(e, fminf(fmaxf(v - other, -3.0e38f), 3.0e38f), u);     // NaN (-inf - -inf) -> -3e38, times e = 0
+    return e;
+  }
   __device__ __forceinline__ void add8(const float (&v)[8], const float (&other)[8]) {
     cover(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))));
-    float e[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float x = fmaf(v[i], kLog2e, b);
-      e[i] = fast_exp2(x);
-      if (T) t = fma_ex(e[i], x, t);
-      if (U) u = fmaf(e[i], fminf(fmaxf(v[i] - other[i], -3.0e38f), 3.0e38f), u);     // NaN (-inf - -inf) -> -3e38, times e = 0
-    }
-    s += static_cast<double>(sum8(e));
+    // the eight exponentials summed pairwise as they are formed (few of them alive at a time)
+    const float q0 = (term(v[0], other[0]) + term(v[1], other[1])) + (term(v[2], other[2]) + term(v[3], other[3]));
+    const float q1 = (term(v[4], other[4]) + term(v[5], other[5])) + (term(v[6], other[6]) + term(v[7], other[7]));
+    s += static_cast<double>(q0 + q1);
   }
 };
 
@@ -73,6 +74,12 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
   __shared__ float sh_bz[NW], sh_by[NW];
   __shared__ double sh_sz[NW], sh_tz[NW], sh_sy[NW], sh_uy[NW], sh_acc[NW];
   __shared__ RowCoef sh_rc;
+  __shared__ float sh_norm[4];
+  // chunks wave 0 parks around its float64 arithmetic (the TV form's kept chunks of y leave room for
+  // 8), and chunks whose refill waits for the epilogue (forward only)
+  constexpr int kPark = TV ? 8 : 16;
+  constexpr int kLate = GRAD ? 0 : 8;
+  __shared__ u32x4 sh_park[kPark > 0 ? kPark * kWave : 1];
   // every thread parks its own 16 bytes per kept chunk and takes them back itself: no synchronisation
   __shared__ u32x4 sh_y[KEEP > 0 ? KEEP * THREADS : 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -177,23 +184,50 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         if (lane == 0) { sh_sz[wid] = sd; sh_tz[wid] = td; sh_sy[wid] = sy; sh_uy[wid] = uy; }
       }
       __syncthreads();
-      // Every thread forms the two normalisers (pass 2 needs them everywhere).
-      double S_rest = 0.0, T_rest = 0.0, Sy = 0.0, Uy = 0.0;
+      // Wave 0 forms the two normalisers and their logarithms (float64, with its last chunks parked
+      // in shared memory meanwhile: beside the resident row there are no registers for that) and,
+      // for the TV form, hands what pass 2 needs to the other waves through shared memory.
+      double S_rest = 0.0, T_rest = 0.0, Sy = 0.0, Uy = 0.0, l2z = 0.0, l2y = 0.0;
+      auto park = [&]() {
+        if (kPark > 0) {
 #pragma unroll
-      for (int w = 0; w < NW; ++w) { S_rest += sh_sz[w]; T_rest += sh_tz[w]; Sy += sh_sy[w]; Uy += sh_uy[w]; }
-      const double xa = static_cast<double>(z_a) * static_cast<double>(kLog2e) + static_cast<double>(bz);
-      const double S = S_rest + exp2_d(xa);
-      double D;
+          for (int i = 0; i < kPark; ++i) sh_park[i * kWave + lane] = buf[NCHUNK - 1 - i];
+        }
+      };
+      auto unpark = [&]() {
+        if (kPark > 0) {
+#pragma unroll
+          for (int i = 0; i < kPark; ++i) buf[NCHUNK - 1 - i] = sh_park[i * kWave + lane];
+        }
+      };
+      if (wid == 0) {
+        park();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { S_rest += sh_sz[w]; T_rest += sh_tz[w]; Sy += sh_sy[w]; Uy += sh_uy[w]; }
+        const double xa = static_cast<double>(z_a) * static_cast<double>(kLog2e) + static_cast<double>(bz);
+        const double S = S_rest + exp2_d(xa);
+        l2z = log2_d(S);
+        l2y = log2_d(Sy);
+        if (TV) {
+          // The integer part of log2 S goes into the (integer) offset, which stays exact, and only
+          // the fraction in [0, 1) is subtracted in fp32 (pass 2), so a probability keeps a relative
+          // error of about 1e-7 however large the offset is.
+          const double nz = floor(l2z), ny = floor(l2y);
+          if (lane == 0) {
+            sh_norm[0] = bz - static_cast<float>(nz); sh_norm[1] = by - static_cast<float>(ny);
+            sh_norm[2] = static_cast<float>(l2z - nz); sh_norm[3] = static_cast<float>(l2y - ny);
+          }
+          unpark();
+        }
+      }
+      double D = 0.0;               // meaningful in wave 0
       if (TV) {
         // ---- pass 2: TV = 1/2 sum |pi_j - mu_j| = 1 - sum_j min(pi_j, mu_j) -----------------------
         // One exponential per entry: the minimum is taken on the base-2 log-probabilities
-        // z_j*log2e + b - log2 S.  The integer part of log2 S goes into the (integer) offset, which
-        // stays exact, and only the fraction in [0, 1) is subtracted in fp32, so a probability
-        // keeps a relative error of about 1e-7 however large the offset is.
-        const double l2z = log2_d(S), l2y = log2_d(Sy);
-        const double nz = floor(l2z), ny = floor(l2y);
-        const float bz2 = bz - static_cast<float>(nz), by2 = by - static_cast<float>(ny);
-        const float fz = static_cast<float>(l2z - nz), fy = static_cast<float>(l2y - ny);
+        // z_j*log2e + b - log2 S
+        // (offsets and fractions from wave 0, see above).
+        __syncthreads();
+        const float bz2 = sh_norm[0], by2 = sh_norm[1], fz = sh_norm[2], fy = sh_norm[3];
         double acc0 = 0.0, acc1 = 0.0;
 #pragma unroll
         for (int i = 0; i < NCHUNK; ++i) {
@@ -211,17 +245,19 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
           unpack8(zq, z);
           unpack8(yq, y);
           double& acc = (i & 1) ? acc1 : acc0;
-          float m[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) m[e] = fast_exp2(fminf(fmaf(z[e], kLog2e, bz2) - fz, fmaf(y[e], kLog2e, by2) - fy));
-          acc += static_cast<double>(sum8(m));      // eight entries among themselves, then into float64
+          auto mn = [&](int e) { return fast_exp2(fminf(fmaf(z[e], kLog2e, bz2) - fz, fmaf(y[e], kLog2e, by2) - fy)); };
+          // eight entries among themselves (pairwise, as they are formed), then into float64
+          const float q0 = (mn(0) + mn(1)) + (mn(2) + mn(3)), q1 = (mn(4) + mn(5)) + (mn(6) + mn(7));
+          acc += static_cast<double>(q0 + q1);
           asm volatile("" : "+v"(acc0), "+v"(acc1));
           __builtin_amdgcn_sched_barrier(0);
         }
         if (!GRAD) {
-          // forward only: nothing needs the rows any more, the next ones start to travel now
+          // forward only: nothing needs the rows any more, the next ones start to travel now -- but
+          // for the last kLate chunks, whose registers the float64 epilogue of wave 0 works in; they
+          // are requested behind it (they are consumed last, and the delay is the epilogue's length)
 #pragma unroll
-          for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<false>(zn, voff, i * kStride);
+          for (int i = 0; i < NCHUNK - kLate; ++i) buf[i] = row_load16<false>(zn, voff, i * kStride);
 #pragma unroll
           for (int i = 0; i < kWindow; ++i) yb[i] = row_load16<kY1Nt>(yn, voff, i * kStride);
           __builtin_amdgcn_sched_barrier(0);
@@ -230,17 +266,24 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         if (lane == 0) sh_acc[wid] = wa;
         __syncthreads();
         double tot = 0.0;
+        if (wid == 0) {
 #pragma unroll
-        for (int w = 0; w < NW; ++w) tot += sh_acc[w];
+          for (int w = 0; w < NW; ++w) tot += sh_acc[w];
+        }
         D = fmax(1.0 - tot, 0.0);
         if (tot != tot) D = tot;                  // NaN logits propagate
-      } else {
+        if (GRAD && wid == 0) park();             // (forward only, the chunks refilled late are free anyway)
+      } else if (wid == 0) {
         // KL = E_mu[y - z] - lse(y) + lse(z), the log-sum-exps in base 2 against their offsets
-        const double lse2_z = log2_d(S) - static_cast<double>(bz), lse2_y = log2_d(Sy) - static_cast<double>(by);
+        const double lse2_z = l2z - static_cast<double>(bz), lse2_y = l2y - static_cast<double>(by);
         D = Uy / Sy + kLn2 * (lse2_z - lse2_y);
         D = (D > 0.0 || D != D) ? D : 0.0;       // rounding can leave -1e-8 for identical rows
       }
       // ---- epilogue on wave 0 (inlined: one workgroup per compute unit, nothing would hide a call)
+      // With the gradient the resident row is still needed afterwards, and the epilogue's float64
+      // arithmetic finds no registers beside it: wave 0 parks its last chunks in shared memory around
+      // it (its own 16 bytes per lane and chunk, no synchronisation) instead of spilling to scratch
+      // memory, whose round trips would sit on the path the other seven waves wait for.
       if (wid == 0) {
         RowScalars rs;
         rs.a = a;
@@ -257,10 +300,15 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         rc = res.rc;
         loss_acc += res.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
+        if (GRAD) unpark();
       }
       // (forward only, this barrier also keeps the next row's statistics from overwriting the
       // shared sums while a slower wave still reads them)
       __syncthreads();
+      if (!GRAD) {
+#pragma unroll
+        for (int i = NCHUNK - kLate; i < NCHUNK; ++i) buf[i] = row_load16<false>(zn, voff, i * kStride);
+      }
       if (GRAD) {
         rc.coef = uniform_f(sh_rc.coef);
         rc.kexp = uniform_f(sh_rc.kexp);
