@@ -192,8 +192,18 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
+      // with the gradient and several rows per workgroup: rows handed out at run time
+      const bool dyn = grad && sc.counters && grid % 8 == 0 && a->T >= 4 * grid && !(a->flags & DPPO_FLAG_STATIC_ROWS);
+      if (dyn) {
+        p.row_counters = sc.counters;
+        p.row_loss = sc.row_loss;
+        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+        *fin = sc.row_loss;
+        *fin_n = static_cast<int>(a->T);
+      }
       if (dppo::launch_fullvocab_resident(p, tv_full, grad, fr_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab_resident";
+      if (dyn) return DPPO_OK;
     } else if (full) {
       // Two rows per workgroup in flight: one workgroup of 1024 threads per compute unit keeps the
       // rows that pass 2 and 3 re-read within reach of the caches.

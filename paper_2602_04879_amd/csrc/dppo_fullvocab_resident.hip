@@ -61,9 +61,13 @@ struct RowStat {
   }
 };
 
-template <int NCHUNK, bool TV, bool DIAG, bool GRAD>
+// DYN: rows handed out at run time from a counter (as in the register-resident kernel of the Binary
+// / Top-K variants: the dies do not run at one speed, and with rows fixed by the workgroup index the
+// slowest compute unit ends the kernel), the loss terms to one slot per row.
+template <int NCHUNK, bool TV, bool DIAG, bool GRAD, bool DYN>
 __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const KParams p) {
   static_assert(GRAD || TV, "forward only, the KL form reads each row once anyway: the general kernel serves it");
+  static_assert(GRAD || !DYN, "rows at run time: the gradient forms only");
   static_assert(NCHUNK == 32 || NCHUNK == 38, "the forms the host selects: rows of more than 24 and up to 32, more than 32 and up to 38 chunks");
   constexpr int THREADS = kThreads, NW = THREADS / kWave;
   constexpr uint32_t kStride = THREADS * 16u;      // bytes between a thread's consecutive chunks
@@ -75,6 +79,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
   __shared__ double sh_sz[NW], sh_tz[NW], sh_sy[NW], sh_uy[NW], sh_acc[NW];
   __shared__ RowCoef sh_rc;
   __shared__ float sh_norm[4];
+  __shared__ int sh_row[2];
   // chunks wave 0 parks around its float64 arithmetic (the TV form's kept chunks of y leave room for
   // 8), and chunks whose refill waits for the epilogue (forward only)
   constexpr int kPark = TV ? 8 : 16;
@@ -101,6 +106,19 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
   // TV form the first read is plain, so that the second finds what it can in the caches.
   constexpr bool kY1Nt = !TV;
   int row = first_row_of_workgroup();      // the workgroups of one die take neighbouring rows
+  int next = row + static_cast<int>(gridDim.x);
+  constexpr int kNoRow = 0x7fffffff;
+  if (DYN) {
+    if (tid == 0) {
+      sh_row[0] = atomicAdd(p.row_counters, 1);
+      sh_row[1] = atomicAdd(p.row_counters, 1);
+    }
+    __syncthreads();
+    row = uniform_i(sh_row[0]);
+    next = uniform_i(sh_row[1]);
+    __syncthreads();
+    if (row >= p.T) return;            // every row already handed out: nothing to do, and no address to form
+  }
   {
     const row_rsrc_t zr = make_row_rsrc(zbase + row * pitch, row_bytes);
     const row_rsrc_t yr = make_row_rsrc(ybase + row * pitch_y, row_bytes);
@@ -111,11 +129,13 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
   }
   int a_next = p.sampled[row];
 
-  for (; row < p.T; row += gridDim.x) {
+  for (; row < p.T;) {
     const int a = uniform_i(a_next);
-    const int next = row + gridDim.x;
     const bool more = next < p.T;
     if (more) a_next = p.sampled[next];
+    // DYN: request the row after next now (thread 0); the answer is published at this row's first barrier
+    int drawn = 0, next2 = kNoRow;
+    if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters, 1);
     const bool live = (a >= 0 && a < p.V);
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
     const row_rsrc_t yr = make_row_rsrc(ybase + row * pitch_y, row_bytes);
@@ -170,7 +190,9 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
       // workgroup-wide offsets = the smallest ones; rescaling to them is exact
       const float wbz = -wave_max(-st.b), wby = -wave_max(-cs.b);
       if (lane == 0) { sh_bz[wid] = wbz; sh_by[wid] = wby; }
+      if (DYN && tid == 0) sh_row[0] = more ? drawn : kNoRow;
       __syncthreads();
+      if (DYN) next2 = uniform_i(sh_row[0]);
       float bz = sh_bz[0], by = sh_by[0];
 #pragma unroll
       for (int w = 1; w < NW; ++w) { bz = fminf(bz, sh_bz[w]); by = fminf(by, sh_by[w]); }
@@ -298,7 +320,8 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         asm volatile("" : "+s"(row_e));
         const RowResult res = row_epilogue(ep, row_e, rs, tk, zrow, bz, S_rest, T_rest, lane, D);
         rc = res.rc;
-        loss_acc += res.loss_term;
+        if (DYN) { if (lane == 0) p.row_loss[row] = res.loss_term; }
+        else loss_acc += res.loss_term;
         if (GRAD && lane == 0) sh_rc = rc;
         if (GRAD) unpark();
       }
@@ -314,12 +337,21 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         rc.kexp = uniform_f(sh_rc.kexp);
         rc.g_a = uniform_f(sh_rc.g_a);
       }
-    } else if (tid == 0) {
-      p.divergence[row] = 0.f;
-      p.mask[row] = 0;
-      if (p.loss_tok) p.loss_tok[row] = 0.f;
-      if (p.diag) {
-        for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+    } else {
+      if (tid == 0) {
+        p.divergence[row] = 0.f;
+        p.mask[row] = 0;
+        if (p.loss_tok) p.loss_tok[row] = 0.f;
+        if (p.diag) {
+          for (int k = 0; k < 8; ++k) p.diag[static_cast<int64_t>(row) * 8 + k] = 0.f;
+        }
+        if (DYN) p.row_loss[row] = 0.0;
+      }
+      if (DYN) {
+        if (tid == 0) sh_row[0] = more ? drawn : kNoRow;
+        __syncthreads();
+        next2 = uniform_i(sh_row[0]);
+        __syncthreads();
       }
     }
 
@@ -366,24 +398,28 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         reinterpret_cast<uint16_t*>(gr)[a] = float_to_bf16_bits(rc.g_a);
       }
     }
+    row = next;
+    next = DYN ? next2 : next + static_cast<int>(gridDim.x);
   }
-  if (tid == 0) p.partial[blockIdx.x] = loss_acc;
+  if (!DYN && tid == 0) p.partial[blockIdx.x] = loss_acc;
 }
 
 template <int NCHUNK>
 hipError_t launch_chunks(const KParams& p, bool tv, bool grad, int grid, hipStream_t s) {
-  const bool diag = p.diag != nullptr;
+  const bool diag = p.diag != nullptr, dyn = p.row_counters != nullptr;
+  if (dyn && !grad) return hipErrorInvalidValue;       // rows at run time: the gradient forms only
   const dim3 g(grid), b(kThreads);
+#define DPPO_FORM(TVF, D, G, Y) hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, TVF, D, G, Y>), g, b, 0, s, p)
   if (!grad) {
-    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, true, false>), g, b, 0, s, p);
-    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, false, false>), g, b, 0, s, p);
+    if (diag) DPPO_FORM(true, true, false, false); else DPPO_FORM(true, false, false, false);
   } else if (tv) {
-    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, true, true>), g, b, 0, s, p);
-    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, true, false, true>), g, b, 0, s, p);
+    if (diag) { if (dyn) DPPO_FORM(true, true, true, true); else DPPO_FORM(true, true, true, false); }
+    else      { if (dyn) DPPO_FORM(true, false, true, true); else DPPO_FORM(true, false, true, false); }
   } else {
-    if (diag)      hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, true, true>), g, b, 0, s, p);
-    else           hipLaunchKernelGGL((dppo_fullvocab_resident_kernel<NCHUNK, false, false, true>), g, b, 0, s, p);
+    if (diag) { if (dyn) DPPO_FORM(false, true, true, true); else DPPO_FORM(false, true, true, false); }
+    else      { if (dyn) DPPO_FORM(false, false, true, true); else DPPO_FORM(false, false, true, false); }
   }
+#undef DPPO_FORM
   return hipGetLastError();
 }
 

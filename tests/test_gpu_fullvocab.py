@@ -259,3 +259,37 @@ def test_resident_form_more_rows_than_workgroups_and_fallbacks():
     B.run_batch(W.make_batch(short, DEV))
     torch.cuda.synchronize()
     assert B.last_path() == "fullvocab"
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+def test_rows_handed_out_at_run_time_match_rows_fixed_by_index(variant, delta):
+    """The gradient forms of the register-resident kernel hand their rows out at run time when each
+    workgroup has several: every per-row output bit for bit what the form with rows fixed by the
+    workgroup index writes, the scalar loss repeatable bit for bit, a minimum-size workspace falling
+    back to fixed rows; ignored and zero-advantage rows included; a sample against the oracle."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = 4 * cus + 29
+    w = W.Workload("dynfull", 1, T, 100000, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.7, zipf_s=1.1, adv="normal", seed=127)
+    b = W.make_batch(w, DEV, shift_sampled=1.0)
+    b["advantages"] = torch.randn(T, device=DEV)
+    b["sampled_ids"][::17] = -1
+    b["advantages"][5::19] = 0.0
+    fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
+    assert B.last_path() == "fullvocab_resident"
+    runs = [B.run_batch(b, diagnostics=True) for _ in range(3)]
+    small = B.alloc_outputs(T, DEV, want_diagnostics=True)
+    small["workspace"] = torch.empty(B.WORKSPACE_BYTES, dtype=torch.uint8, device=DEV)
+    rmin = B.run_batch(b, out=small)
+    torch.cuda.synchronize()
+    assert B.last_path() == "fullvocab_resident"
+    for r in runs + [rmin]:
+        for k in ("loss_tok", "divergence", "mask", "diagnostics", "grad_logits"):
+            assert torch.equal(fixed[k], r[k]), k
+    for r in runs[1:]:
+        assert torch.equal(runs[0]["loss"], r["loss"])
+    assert torch.equal(fixed["loss"], rmin["loss"])
+    assert abs(runs[0]["loss"].item() - fixed["loss"].item()) <= 1e-6 * abs(fixed["loss"].item())
+    rows = np.arange(T)[::8]
+    st = P.compare_rows(b, runs[0], rows)
+    assert 0 < (runs[0]["mask"] == 0).sum().item() < T
+    _say(f"       {st}")
