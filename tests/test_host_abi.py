@@ -125,3 +125,35 @@ def test_header_is_plain_c(tmp_path):
         r = subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c" if cc == "gcc" else "c++",
                             "-I", inc, str(src)], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_static_scratch_entry_point_validates_on_the_host():
+    """dppo_loss_fwd_bwd_static: the usual argument checks (workspace excepted: it takes none), then
+    its own size limit, all before any device call."""
+    lib = B.lib()
+    assert lib.dppo_loss_fwd_bwd_static(None, None) == 1
+    a = _valid_args()
+    a.workspace, a.workspace_bytes = None, 0
+    a.grad_logits = None
+    assert lib.dppo_loss_fwd_bwd_static(C.byref(a), None) == 1          # a gradient buffer is required
+    a = _valid_args()
+    a.workspace, a.workspace_bytes = None, 0
+    a.V = 0
+    assert lib.dppo_loss_fwd_bwd_static(C.byref(a), None) == 2
+    a = _valid_args()
+    a.workspace, a.workspace_bytes = None, 0
+    a.T = (1 << 22) + 1                                                  # beyond DPPO_STATIC_MAX_T
+    assert lib.dppo_loss_fwd_bwd_static(C.byref(a), None) == 2
+
+
+def test_workspace_sizes():
+    """64 KiB + 8 bytes per row for the logits entry points; the hidden-state forward needs tile
+    statistics and gathered logits only, far less than a chunk of logits."""
+    assert B.workspace_bytes(1000, 4096, 0) == 65536 + 8000
+    T, V, K, chunk = 32768, 151936, 20, 8192
+    tiles = (V + 255) // 256
+    fwd = B.lmhead_fwd_workspace_bytes(T, V, K, chunk)
+    assert fwd == 65536 + 8 * T + chunk * tiles * 16 + chunk * (K + 1) * 4      # every part already a multiple of 256
+    both = B.lmhead_workspace_bytes(T, V, chunk)
+    assert both == 65536 + chunk * V * 2 and fwd < both // 20
+    assert B.lmhead_fwd_workspace_bytes(10, 64, 0, 0) <= B.lmhead_workspace_bytes(10, 64, 0)
