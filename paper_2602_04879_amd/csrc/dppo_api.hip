@@ -180,7 +180,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     const bool full = (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL);
 
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
-    // Register-resident kernel: rows of 8192 .. 155648 entries, a multiple of 8, 16-byte aligned.
+    // Register-resident kernel: rows of 1024 .. 155648 entries, a multiple of 8, 16-byte aligned.
     int r_threads = 0, r_chunks = 0;
     const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);

@@ -15,6 +15,10 @@
 //   forward only: no phase C; the first half of the registers is refilled mid-row, the second
 //               after the epilogue, so at least half a row is in flight at any time.
 //
+// Shorter rows use the same code in smaller shapes: several workgroups of 256 threads per compute
+// unit (V up to 40960), and for rows of up to 8192 entries ONE WAVE per row (64 threads), many of
+// them per compute unit, each running its own row's epilogue.
+//
 // Preconditions (checked by the host): V % 8 == 0, V/8 <= THREADS*NCHUNK, logits and
 // grad_logits 16-byte aligned with ld % 8 == 0.
 #include "dppo_common.hpp"
@@ -420,6 +424,11 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
 }
 
 // One instantiation per (threads, chunks) shape; chunks in steps of kChunkStep up to the maximum.
+// Rows of up to 8192 entries belong to ONE wave each (64 threads: a workgroup's barriers cost nothing,
+// no wave waits for another one's epilogue, and 12-20 independent rows are in flight per compute
+// unit); measured against the two-pass kernel at V = 4096: 4.5 against 2.0 TB/s, and at V = 8192
+// against 256 threads x 4 chunks: 4.9 against 4.1 TB/s.  From 16384 entries on, the 256-thread
+// shapes measure the same or better (V = 16384: 4.94 against 4.83 TB/s with 64 threads x 32 chunks).
 // Rows are handed out at run time when the host sets p.row_counters.
 template <int THREADS, int NCHUNK>
 hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
@@ -453,13 +462,15 @@ int occupancy_shape(bool grad, bool dyn) {
 }  // namespace
 
 #define DPPO_SHAPES(X) \
-  X(256, 4) X(256, 8) X(256, 12) X(256, 16) X(256, 20) \
+  X(64, 4) X(64, 8) X(64, 12) X(64, 16) X(256, 4) X(256, 8) X(256, 12) X(256, 16) X(256, 20) \
   X(512, 12) X(512, 16) X(512, 20) X(512, 24) X(512, 28) X(512, 32) X(512, 36) X(512, 38)
 
 bool resident_shape(int64_t V, int* threads, int* chunks) {
-  if (V < 8192 || V % 8 != 0) return false;
+  if (V < 1024 || V % 8 != 0) return false;
   const int64_t nvec = V / 8;
-#define DPPO_TRY(T, C) if (nvec <= static_cast<int64_t>(T) * C) { *threads = T; *chunks = C; return true; }
+  // (a shape is only taken with less than kChunkStep chunks of slack: the kernel turns lanes past
+  // the row into -inf in its last kChunkStep chunks only)
+#define DPPO_TRY(T, C) if (nvec <= static_cast<int64_t>(T) * C) { *threads = T; *chunks = C; return nvec > static_cast<int64_t>(T) * (C - kChunkStep); }
   DPPO_SHAPES(DPPO_TRY)
 #undef DPPO_TRY
   return false;

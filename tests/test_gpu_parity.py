@@ -38,17 +38,25 @@ def _run_and_compare(w, *, backward=True, in_place=False, flags=0, ld=None, shif
 
 
 # --------------------------------------------------------------------------- small: every row
+# V = 4096: one wave per row with the row in registers, or (forced) the general two-pass kernel
+PATHS_SMALL_V = [(0, "resident"), (B.FLAG_FORCE_STREAMING, "streaming")]
+
+
 @pytest.mark.parametrize("name", ["c1_tiny_binary_tv"])
-def test_c1_tiny_all_rows(name):
-    _run_and_compare(W.WORKLOADS[name])
+@pytest.mark.parametrize("flags,path", PATHS_SMALL_V)
+def test_c1_tiny_all_rows(name, flags, path):
+    _run_and_compare(W.WORKLOADS[name], flags=flags)
+    assert B.last_path() == path
 
 
 @pytest.mark.parametrize("variant,K", [(W.BINARY_TV, 0), (W.BINARY_KL, 0), (W.TOPK_TV, 20), (W.TOPK_KL, 64)])
 @pytest.mark.parametrize("shift", [0.0, 2.0])
-def test_c1_shape_all_variants_with_mask_stress(variant, K, shift):
+@pytest.mark.parametrize("flags,path", PATHS_SMALL_V)
+def test_c1_shape_all_variants_with_mask_stress(variant, K, shift, flags, path):
     w = W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], variant=variant, K=K,
                  noise_std=1.0 if shift else 0.05, delta=0.05 if variant in (W.BINARY_KL, W.TOPK_KL) else 0.2)
-    b, res, st = _run_and_compare(w, shift=shift)
+    b, res, st = _run_and_compare(w, shift=shift, flags=flags)
+    assert B.last_path() == path
     if shift:
         assert 0 < st["masked"] < b["T"]     # the stress recipe exercises both mask values
 
@@ -71,8 +79,13 @@ def test_qwen3_vocab_small_t(name):
 
 # --------------------------------------------------------------------------- resident-kernel shapes
 @pytest.mark.parametrize("V,ld,expect", [
-    (8192, 8192, "resident"),          # smallest resident row: 256 threads x 4 chunks, exactly full
-    (8200, 8200, "resident"),          # one vector into the next shape (256 x 8), 3 chunks of slack
+    (1016, 1016, "streaming"),         # below the smallest resident row
+    (1024, 1024, "resident"),          # smallest resident row: one wave x 4 chunks, two of them used
+    (2048, 2056, "resident"),          # one wave x 4 chunks exactly full, pitch > V
+    (4104, 4104, "resident"),          # one vector into one wave x 16 chunks
+    (8192, 8192, "resident"),          # longest row of one wave: 64 threads x 16 chunks, exactly full
+    (8200, 8200, "resident"),          # one vector more: 256 threads x 4 chunks
+    (16384, 16384, "resident"),        # 256 x 8 exactly full
     (12296, 12304, "resident"),        # pitch > V (still a multiple of 8)
     (40960, 40960, "resident"),        # 256 x 20 exactly full
     (40968, 40968, "resident"),        # first 512-thread shape (512 x 12)
@@ -97,6 +110,24 @@ def test_resident_more_rows_than_workgroups_in_place_with_special_rows():
     b = W.make_batch(w, DEV, shift_sampled=2.0)
     b["sampled_ids"][::11] = -1
     b["advantages"][5::13] = 0.0
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, in_place=True, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    st = P.compare_rows(b, res, rows, ref=ref)
+    assert st["masked"] > 50
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    _say(f"       {st}")
+
+
+def test_one_wave_per_row_many_rows_per_wave_in_place_with_special_rows():
+    """V = 4096: one wave per row, more rows than resident waves (several rows per wave), gradient in
+    place, ignored / zero-advantage / masked rows among them, Top-K with K beyond the wave's width."""
+    w = W.Workload("waves", 8, 1200, 4096, W.TOPK_KL, 0.05, K=70, logit_std=3.0, noise_std=1.0, adv="normal", seed=41)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    b["sampled_ids"][::17] = -1
+    b["advantages"][3::19] = 0.0
     rows = np.arange(b["T"])
     ref = P.oracle_rows(b, rows)
     res = B.run_batch(b, in_place=True, diagnostics=True)
@@ -491,7 +522,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     capturable.  Capture forward+backward of two shapes (both kernel paths) in one graph, replay it
     several times with eager work and synchronisations in between, and compare every replay bit for
     bit with the eager result."""
-    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV)]
+    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4090)]
     batches = [W.make_batch(w, DEV, shift_sampled=1.0) for w in shapes]
     eager = []
     for b in batches:
