@@ -203,7 +203,8 @@ int dppo_version(void);
 size_t dppo_args_size(void);
 
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
- * "resident" (row held in registers between the two passes), "streaming" (row re-read),
+ * "resident" (row held in registers between the two passes), "resident_long" (rows of 155657 ..
+ * 262144 entries with the gradient: registers, LDS and a short tail read twice), "streaming" (row re-read),
  * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
  * backward, and the forward-only TV form, on long aligned rows: the trainer's row held in
  * registers, the rollout row streamed past it); "lmhead" after a dppo_lmhead_* call that went

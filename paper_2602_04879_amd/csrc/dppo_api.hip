@@ -184,6 +184,9 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     int r_threads = 0, r_chunks = 0;
     const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
                           dppo::resident_shape(a->V, &r_threads, &r_chunks);
+    // Longer rows, forward + backward: the long-row form of the same kernel, up to 262144 entries.
+    const int long_chunks = (!full && grad && !resident && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0)
+                                ? dppo::resident_long_chunks(a->V) : 0;
     const bool tv_full = a->variant == DPPO_FULL_TV;
     const int fr_chunks = (full && !(a->flags & DPPO_FLAG_FORCE_STREAMING)) ? dppo::fullvocab_resident_chunks(p, tv_full, grad) : 0;
     if (fr_chunks) {
@@ -214,6 +217,23 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       nparts = static_cast<int>(grid);
       if (dppo::launch_fullvocab(p, a->variant == DPPO_FULL_TV, grad, threads, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab";
+    } else if (long_chunks) {
+      // rows beyond the register file: registers + LDS + a re-read tail, one workgroup per compute unit
+      int64_t grid = cus;
+      if (grid > a->T) grid = a->T;
+      if (grid > max_parts) grid = max_parts;
+      nparts = static_cast<int>(grid);
+      const bool dyn = sc.counters && grid % 8 == 0 && a->T >= 4 * grid && !(a->flags & DPPO_FLAG_STATIC_ROWS);
+      if (dyn) {
+        p.row_counters = sc.counters;
+        p.row_loss = sc.row_loss;
+        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+        *fin = sc.row_loss;
+        *fin_n = static_cast<int>(a->T);
+      }
+      if (dppo::launch_resident_long(p, long_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      g_last_path = "resident_long";
+      if (dyn) return DPPO_OK;
     } else if (resident) {
       int per_cu = resident_blocks_per_cu_cached(dev, grad, false, r_threads, r_chunks);
       int64_t grid = static_cast<int64_t>(cus) * per_cu;

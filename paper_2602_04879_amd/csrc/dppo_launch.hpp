@@ -18,6 +18,14 @@ bool resident_shape(int64_t V, int* threads, int* chunks);
 hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s);
 int resident_blocks_per_cu(bool grad, bool dyn, int threads, int chunks);
 
+// Register-resident kernel for rows too long for the register file alone (forward+backward only):
+// part of the row in registers, part in LDS, the rest passed through twice.  resident_long_chunks()
+// gives the number of 512 x 16-byte chunks of a row this form takes, 0 where it does not apply
+// (V not a multiple of 8, or outside 155 657 .. 262 144).  Needs 16-byte aligned rows of logits and
+// grad; one workgroup per compute unit.
+int resident_long_chunks(int64_t V);
+hipError_t launch_resident_long(const KParams& p, int chunks, int grid, hipStream_t s);
+
 // Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
 hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);
 

@@ -92,7 +92,14 @@ def test_qwen3_vocab_small_t(name):
     (100000, 100000, "resident"),      # 512 x 28, ragged last chunk
     (128256, 128256, "resident"),      # a Llama-3 sized vocabulary: 512 x 32
     (155648, 155648, "resident"),      # largest resident row: 512 x 38 exactly full
-    (155656, 155656, "streaming"),     # one vector more: falls back to the two-pass kernel
+    (155656, 155656, "resident_long"), # one vector more: 39 chunks, 30 in registers and 9 in LDS
+    (196608, 196608, "resident_long"), # 48 chunks exactly full: registers and LDS, nothing read twice
+    (196616, 196624, "resident_long"), # one vector into the first chunk that passes through twice; pitch > V
+    (229376, 229376, "resident_long"), # 56 chunks: one full window of them
+    (229384, 229384, "resident_long"), # one vector into the second window
+    (256000, 256000, "resident_long"), # a Gemma-2 sized vocabulary: 62.5 chunks
+    (262144, 262144, "resident_long"), # longest row of this form: 64 chunks exactly full
+    (262152, 262152, "streaming"),     # one vector more: the two-pass kernel
     (40004, 40004, "streaming"),       # V not a multiple of 8
     (16384, 16388, "streaming"),       # pitch not a multiple of 8: rows not 16-byte aligned
 ])
@@ -172,6 +179,50 @@ def test_rows_handed_out_at_run_time_match_rows_fixed_by_index():
     P.check_loss_scalar(b, runs[0], float(ref["loss_tok"].sum()))
     P.compare_rows(b, runs[0], rows[::16])
     assert st["masked"] > 50
+    _say(f"       {st}")
+
+
+@pytest.mark.parametrize("V", [256000, 180000])
+def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
+    """Rows beyond the register file (registers + LDS + a tail read twice; V = 180000: registers +
+    LDS only), several rows per workgroup, in place: rows handed out at run time must equal rows
+    fixed by the workgroup index bit for bit, run after run, ignored / zero-advantage / masked rows
+    and sampled tokens in every part of the row included; per-token outputs against the oracle on
+    every row, gradients on a sample."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = 4 * cus + 37
+    w = W.Workload("longrows", 1, T, V, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=67)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    b["advantages"] = torch.randn(T, device=DEV)
+    b["sampled_ids"][::17] = -1
+    b["advantages"][5::19] = 0.0
+    # sampled tokens in the register part, the LDS part, both windows of the tail, and the last entry
+    for t, a in zip(range(2, 62, 6), [0, 4095, 30 * 4096 - 1, 30 * 4096, 40 * 4096 + 77, 48 * 4096 - 1, 48 * 4096, 52 * 4096 + 5, 56 * 4096, V - 1]):
+        b["sampled_ids"][t] = min(a, V - 1)
+    fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
+    assert B.last_path() == "resident_long"
+    runs = [B.run_batch(b, diagnostics=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident_long"
+    for r in runs:
+        for k in ("loss_tok", "divergence", "mask", "diagnostics", "grad_logits"):
+            assert torch.equal(fixed[k], r[k]), k
+    assert torch.equal(runs[0]["loss"], runs[1]["loss"])
+    assert abs(runs[0]["loss"].item() - fixed["loss"].item()) <= 1e-6 * abs(fixed["loss"].item())
+    two_pass = B.run_batch(b, diagnostics=True, flags=B.FLAG_FORCE_STREAMING)
+    torch.cuda.synchronize()
+    assert B.last_path() == "streaming"
+    assert torch.equal(two_pass["mask"], fixed["mask"])
+    rows = np.arange(T)
+    ref = P.oracle_rows(b, rows, want_grad=False)
+    st = P.compare_rows(b, runs[0], rows, check_grad=False, ref=ref)
+    P.check_loss_scalar(b, runs[0], float(ref["loss_tok"].sum()))
+    P.compare_rows(b, runs[0], np.unique(np.concatenate([np.arange(0, 62), rows[::29], rows[-3:]])))
+    assert st["masked"] > 50
+    # in place: the gradient over the logits
+    inp = B.run_batch(b, in_place=True, diagnostics=True)
+    torch.cuda.synchronize()
+    assert torch.equal(inp["grad_logits"], fixed["grad_logits"]) and torch.equal(inp["loss_tok"], fixed["loss_tok"])
     _say(f"       {st}")
 
 
