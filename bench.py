@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c3_qwen3_binary_tv"
-DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "streaming": "dppo_streaming_kernel",
+DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "resident_long": "dppo_resident_long_kernel", "streaming": "dppo_streaming_kernel",
                    "fullvocab": "dppo_fullvocab_kernel", "fullvocab_resident": "dppo_fullvocab_resident_kernel"}
 
 
@@ -34,7 +34,8 @@ def kernel_source_hash(path: str) -> str:
     helpers): stored HBM-traffic counters hold only for it."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
-    for fn in ("dppo_common.hpp", f"dppo_{path}.hip"):
+    files = ["dppo_common.hpp", f"dppo_{path}.hip"] + (["dppo_resident_parts.hpp"] if path.startswith("resident") else [])
+    for fn in files:
         h.update(open(os.path.join(src, fn), "rb").read())
     return h.hexdigest()[:16]
 
@@ -329,7 +330,7 @@ def main() -> int:
     ceilings = {}
     src2d, dst2d = (pristine if in_place else batch["logits"]), grad
     nbytes = src2d.numel() * 2
-    if nbytes % 16 == 0 and nbytes >= (1 << 30):
+    if nbytes % 16 == 0 and nbytes >= (1 << 28):
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
         probes = [("copy", lambda: B.probe_copy(dst2d.view(-1).view(torch.uint8), src2d.view(-1).view(torch.uint8), stream), 2 * nbytes),
                   ("read", lambda: B.probe_read(src2d.view(-1).view(torch.uint8), sink, stream), nbytes)]
@@ -342,12 +343,13 @@ def main() -> int:
             fn()
             torch.cuda.synchronize()
             c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(5, int(2e10 // moved))      # about 20 GB moved per probe, whatever the buffers' size
             c0.record(stream)
-            for _ in range(5):
+            for _ in range(reps):
                 fn()
             c1.record(stream)
             torch.cuda.synchronize()
-            ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
+            ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / reps * 1e-3) / 1e9
 
     launches = len(calls)
     alg_bytes_launch = algorithmic_bytes_per_token(V, K, batch.get("mu_logits") is not None, not args.forward_only) * (T // launches)

@@ -26,7 +26,8 @@ def kernel_source_hash(path: str) -> str:
     helpers): stored HBM-traffic counters hold only for it."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2602_04879_amd", "csrc")
-    for fn in ("dppo_common.hpp", f"dppo_{path}.hip"):
+    files = ["dppo_common.hpp", f"dppo_{path}.hip"] + (["dppo_resident_parts.hpp"] if path.startswith("resident") else [])
+    for fn in files:
         h.update(open(os.path.join(src, fn), "rb").read())
     return h.hexdigest()[:16]
 
@@ -45,7 +46,7 @@ def counter_avg(directory: str, kernel_substr: str, counter: str) -> float:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--path", required=True, choices=["resident", "streaming", "fullvocab", "fullvocab_resident"])
+    ap.add_argument("--path", required=True, choices=["resident", "resident_long", "streaming", "fullvocab", "fullvocab_resident"])
     ap.add_argument("--probe-fetch", required=True)
     ap.add_argument("--probe-write", required=True)
     ap.add_argument("--fetch", required=True)

@@ -51,7 +51,7 @@ class Workload:
         return self.n_seq * self.seq_len
 
 
-# The five configurations this repository is measured and tested on.
+# The configurations this repository is measured and tested on.
 WORKLOADS = {
     "c1_tiny_binary_tv": Workload("c1_tiny_binary_tv", 4, 64, 4096, BINARY_TV, 0.2,
                                   logit_std=2.0, noise_std=0.05, adv="pm1", seed=1000),
@@ -76,6 +76,11 @@ WORKLOADS = {
     "c6_qwen3_full_kl": Workload("c6_qwen3_full_kl", 16, 2048, 151936, FULL_KL, 0.05, mu_full=True,
                                  logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
                                  adv="group_norm", group=8, seed=1002),
+    # The headline recipe at the vocabulary of the paper's other model family (Sec. 5, alignment
+    # runs on Gemma-2: 256000 entries, rows of 500 KiB), half the rows: the long-row kernel.
+    "c8_vocab256k_binary_tv": Workload("c8_vocab256k_binary_tv", 16, 1024, 256000, BINARY_TV, 0.2,
+                                       logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                       adv="group_norm", group=8, seed=1008),
     # The headline shape entered one step earlier: final hidden states of a d = 4096 model (the
     # Qwen3-8B size) and its lm_head weight; the logits exist one chunk of tokens at a time.
     "c7_qwen3_lmhead_binary_tv": Workload("c7_qwen3_lmhead_binary_tv", 16, 2048, 151936, BINARY_TV, 0.2, d_model=4096,

@@ -476,14 +476,15 @@ def _full_size_properties(b, res):
     assert torch.all(res["grad_logits"][zero] == 0)
 
 
-@pytest.mark.parametrize("name", ["c3_qwen3_binary_tv", "c4_qwen3_topk_tv"])
-def test_full_size_headline_configs(name):
+@pytest.mark.parametrize("name,path", [("c3_qwen3_binary_tv", "resident"), ("c4_qwen3_topk_tv", "resident"), ("c8_vocab256k_binary_tv", "resident_long")])
+def test_full_size_headline_configs(name, path):
     w = W.WORKLOADS[name]
     _say(f"[case] full size {name} T={w.T} V={w.V}")
     b = W.make_batch(w, DEV, rows_per_step=2048)
     res = B.run_batch(b, diagnostics=True)
     torch.cuda.synchronize()
     _say(f"       path={B.last_path()} loss={res['loss'].item():.6e} masked={(res['mask'] == 0).sum().item()}")
+    assert B.last_path() == path
     _full_size_properties(b, res)
     rows = _sample_rows(b, res)
     st = P.compare_rows(b, res, rows)
