@@ -63,7 +63,7 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
   // with the gradient stores in the mix the same mark measured 4 % slower, so there they are plain.
   constexpr bool kNtLoads = !GRAD;
   constexpr uint32_t kStride = THREADS * 16u;   // bytes between a thread's consecutive chunks
-  constexpr int GC = 2;                          // chunks per group of the online row statistics
+  constexpr int GC = 2;                          // chunks per group of the online row statistics (PackedRowStat::add2)
   constexpr int kSplit = ((NCHUNK / 2 + GC - 1) / GC) * GC;   // forward only: chunks refilled mid-row
   // Per-wave statistics, two sets used by alternate rows: forward only there is no barrier behind
   // wave 0's epilogue, so the other waves may already publish the next row's statistics while
@@ -169,21 +169,10 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
           tk.z = bf16_bits_to_float(zrow[tkid]);
         }
       }
-      // ---- phases A+B, online over groups of GC chunks ------------------------------------
-      // Per thread: s = sum 2^(z*log2e + b) with an integer offset b <= -max(z)*log2e that only
-      // ever decreases; lowering it rescales s by an exact power of two.  The maximum is taken
-      // on the PACKED bf16 patterns, as signed 16-bit integers: non-negative patterns order like
-      // the floats and every negative one stays below them, so the integer maximum is the float
-      // maximum whenever it is >= 0; if every entry so far is negative, the float maximum is
-      // the negative of smallest magnitude, which is the integer MINIMUM.  The first groups
-      // were loaded first, so their arithmetic hides the latency of the chunks requested last.
-      s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
-      float b = 3.0e38f;                       // "+infinity": nothing seen yet
-      // The sum is kept in float64 and fed with the fp32 sum of each group's exponentials (summed
-      // pairwise among themselves): a thread that has met a dominant entry then does not drop the
-      // small ones that follow it, as an fp32 accumulator would.
-      double sd = 0.0;
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;      // sum e*x, same offset as the sum
+      // ---- phases A+B, online over groups of GC chunks (PackedRowStat) -------------------------
+      // The first groups were loaded first, so their arithmetic hides the latency of the chunks
+      // requested last.
+      PackedRowStat<DIAG> ps;
 #pragma unroll
       for (int g0 = 0; g0 < NCHUNK; g0 += GC) {
         // The sampled token's own term is left out of the sum (see row_epilogue): overwrite it
@@ -203,46 +192,7 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
           // lanes past the row loaded 0: make them -inf (only the last chunks can have any)
           if (g0 + i < NCHUNK && g0 + i >= NCHUNK - kChunkStep && c * THREADS + tid >= nvec) v[i] = neg_inf;
         }
-#pragma unroll
-        for (int i = 0; i < GC; ++i) {
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].x));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].y));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].z));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].w));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].x));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].y));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].z));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].w));
-        }
-        const int hi16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
-        const int lo16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
-        const float zmax = __uint_as_float(static_cast<uint32_t>(hi16 >= 0 ? hi16 : lo16) << 16);
-        const float bn = -ceilf(fmaxf(zmax, kNegBig) * kLog2e);
-        // moving the offset by d: e -> e*2^d, x -> x + d, so s -> 2^d s and t -> 2^d (t + d s)
-        const float d = bn - b;
-        const float sc = fast_exp2(d);            // 1 when the maximum did not move
-        if (DIAG) { t0 = sc * fmaf(d, static_cast<float>(sd), t0); t1 *= sc; t2 *= sc; t3 *= sc; }
-        b = bn;
-        float gs = 0.f;
-#pragma unroll
-        for (int i = 0; i < GC; ++i) {
-          float px, py, pz, pw;
-          if (DIAG) {
-            px = accum2(v[i].x, b, t0);
-            py = accum2(v[i].y, b, t1);
-            pz = accum2(v[i].z, b, t2);
-            pw = accum2(v[i].w, b, t3);
-          } else {
-            px = exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
-            py = exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
-            pz = exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
-            pw = exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
-          }
-          const float c = (px + py) + (pz + pw);
-          gs = (i == 0) ? c : gs + c;
-        }
-        sd = fma(sd, static_cast<double>(sc), static_cast<double>(gs));
-        __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
+        ps.add2(v[0], v[1]);
         // Forward only: nothing needs the row after its statistics, so the first part of the
         // registers is refilled from the next row as soon as it has been consumed.  Those loads
         // are in flight during the rest of this row and its epilogue; the rest is refilled after
@@ -254,9 +204,9 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
         }
       }
       // wave-level combine: common offset = the smallest one, rescaling is exact
-      const float bw = -wave_max(-b);
-      const double dw = static_cast<double>(bw - b), scw = static_cast<double>(fast_exp2(bw - b));
-      const double st = sd, tt = static_cast<double>((t0 + t1) + (t2 + t3));
+      const float bw = -wave_max(-ps.b);
+      const double dw = static_cast<double>(bw - ps.b), scw = static_cast<double>(fast_exp2(bw - ps.b));
+      const double st = ps.sd, tt = static_cast<double>(ps.tsum());
       const double sw = wave_sum(st * scw);
       const double tw = DIAG ? wave_sum(scw * (tt + dw * st)) : 0.0;
       if (lane == 0) { sh_b[par][wid] = bw; sh_s[par][wid] = sw; sh_t[par][wid] = tw; }

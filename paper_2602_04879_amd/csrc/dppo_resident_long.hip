@@ -161,52 +161,8 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
         tk = load_topk_lane(p, row, a, zrow, lane);
       }
       // ---- statistics: online over groups of two chunks (see the shorter kernel) ---------------
-      s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
-      float b = 3.0e38f;
-      double sd = 0.0;
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
-      auto group = [&](const u32x4 v0, const u32x4 v1) {
-        const u32x4 v[2] = {v0, v1};
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].x));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].y));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].z));
-          mx = __builtin_elementwise_max(mx, as_s16x2(v[i].w));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].x));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].y));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].z));
-          mn = __builtin_elementwise_min(mn, as_s16x2(v[i].w));
-        }
-        const int hi16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
-        const int lo16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
-        const float zmax = __uint_as_float(static_cast<uint32_t>(hi16 >= 0 ? hi16 : lo16) << 16);
-        const float bn = -ceilf(fmaxf(zmax, kNegBig) * kLog2e);
-        const float d = bn - b;
-        const float sc = fast_exp2(d);
-        if (DIAG) { t0 = sc * fmaf(d, static_cast<float>(sd), t0); t1 *= sc; t2 *= sc; t3 *= sc; }
-        b = bn;
-        float gs = 0.f;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          float px, py, pz, pw;
-          if (DIAG) {
-            px = accum2(v[i].x, b, t0);
-            py = accum2(v[i].y, b, t1);
-            pz = accum2(v[i].z, b, t2);
-            pw = accum2(v[i].w, b, t3);
-          } else {
-            px = exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
-            py = exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
-            pz = exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
-            pw = exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
-          }
-          const float c = (px + py) + (pz + pw);
-          gs = (i == 0) ? c : gs + c;
-        }
-        sd = fma(sd, static_cast<double>(sc), static_cast<double>(gs));
-        __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds the live temporaries
-      };
+      PackedRowStat<DIAG> ps;
+      auto group = [&](const u32x4 v0, const u32x4 v1) { ps.add2(v0, v1); };
       // a chunk that is not kept in registers, as the statistics see it: lanes past the row and
       // the sampled token's own entry (left out of the sum, see row_epilogue) are -inf
       auto seen = [&](u32x4 v, int chunk) {
@@ -250,9 +206,9 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
       else           { stats_regs(); stats_a(); stats_lds(); stats_b(); }
 
       // wave-level combine: common offset = the smallest one, rescaling is exact
-      const float bw = -wave_max(-b);
-      const double dw = static_cast<double>(bw - b), scw = static_cast<double>(fast_exp2(bw - b));
-      const double st = sd, tt = static_cast<double>((t0 + t1) + (t2 + t3));
+      const float bw = -wave_max(-ps.b);
+      const double dw = static_cast<double>(bw - ps.b), scw = static_cast<double>(fast_exp2(bw - ps.b));
+      const double st = ps.sd, tt = static_cast<double>(ps.tsum());
       const double sw = wave_sum(st * scw);
       const double tw = DIAG ? wave_sum(scw * (tt + dw * st)) : 0.0;
       if (lane == 0) { sh_b[par][wid] = bw; sh_s[par][wid] = sw; sh_t[par][wid] = tw; }

@@ -42,5 +42,67 @@ __device__ __forceinline__ u32x4 grad8(u32x4 v, float kexp, uint32_t sgn) {
   return o;
 }
 
+// Per-thread online statistics of a row, fed two 16-byte chunks at a time:
+//   sd = sum 2^(z*log2e + b) with an integer offset b <= -max(z)*log2e that only ever decreases;
+//   lowering it rescales the sum by an exact power of two.  t0..t3 (DIAG): sum 2^x * x, x = z*log2e + b.
+// The maximum is taken on the PACKED bf16 patterns, as signed 16-bit integers: non-negative
+// patterns order like the floats and every negative one stays below them, so the integer maximum
+// is the float maximum whenever it is >= 0; if every entry so far is negative, the float maximum
+// is the negative of smallest magnitude, which is the integer MINIMUM.
+// The sum is kept in float64 and fed with the fp32 sum of each pair's exponentials (summed
+// pairwise among themselves): a thread that has met a dominant entry then does not drop the small
+// ones that follow it, as an fp32 accumulator would.
+template <bool DIAG>
+struct PackedRowStat {
+  s16x2 mx = as_s16x2(0x80008000u), mn = as_s16x2(0x7FFF7FFFu);
+  float b = 3.0e38f;                       // "+infinity": nothing seen yet
+  double sd = 0.0;
+  float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+  __device__ __forceinline__ void add2(const u32x4& v0, const u32x4& v1) {
+    const u32x4 v[2] = {v0, v1};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      mx = __builtin_elementwise_max(mx, as_s16x2(v[i].x));
+      mx = __builtin_elementwise_max(mx, as_s16x2(v[i].y));
+      mx = __builtin_elementwise_max(mx, as_s16x2(v[i].z));
+      mx = __builtin_elementwise_max(mx, as_s16x2(v[i].w));
+      mn = __builtin_elementwise_min(mn, as_s16x2(v[i].x));
+      mn = __builtin_elementwise_min(mn, as_s16x2(v[i].y));
+      mn = __builtin_elementwise_min(mn, as_s16x2(v[i].z));
+      mn = __builtin_elementwise_min(mn, as_s16x2(v[i].w));
+    }
+    const int hi16 = max(static_cast<int>(mx.x), static_cast<int>(mx.y));
+    const int lo16 = min(static_cast<int>(mn.x), static_cast<int>(mn.y));
+    const float zmax = __uint_as_float(static_cast<uint32_t>(hi16 >= 0 ? hi16 : lo16) << 16);
+    const float bn = -ceilf(fmaxf(zmax, kNegBig) * kLog2e);
+    // moving the offset by d: e -> e*2^d, x -> x + d, so s -> 2^d s and t -> 2^d (t + d s)
+    const float d = bn - b;
+    const float sc = fast_exp2(d);            // 1 when the maximum did not move
+    if (DIAG) { t0 = sc * fmaf(d, static_cast<float>(sd), t0); t1 *= sc; t2 *= sc; t3 *= sc; }
+    b = bn;
+    float gs = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float px, py, pz, pw;
+      if (DIAG) {
+        px = accum2(v[i].x, b, t0);
+        py = accum2(v[i].y, b, t1);
+        pz = accum2(v[i].z, b, t2);
+        pw = accum2(v[i].w, b, t3);
+      } else {
+        px = exp_lo(v[i].x, b) + exp_hi(v[i].x, b);
+        py = exp_lo(v[i].y, b) + exp_hi(v[i].y, b);
+        pz = exp_lo(v[i].z, b) + exp_hi(v[i].z, b);
+        pw = exp_lo(v[i].w, b) + exp_hi(v[i].w, b);
+      }
+      const float c = (px + py) + (pz + pw);
+      gs = (i == 0) ? c : gs + c;
+    }
+    sd = fma(sd, static_cast<double>(sc), static_cast<double>(gs));
+    __builtin_amdgcn_sched_barrier(0);   // one pair at a time: bounds the live temporaries
+  }
+  __device__ __forceinline__ float tsum() const { return (t0 + t1) + (t2 + t3); }
+};
+
 }  // namespace
 }  // namespace dppo
