@@ -276,29 +276,41 @@ def main() -> int:
     out = B.alloc_outputs(T, dev, want_diagnostics=args.diagnostics)
     rule = {"mask_rule": {"dppo": B.MASK_DIVERGENCE, "ratio_clip": B.MASK_RATIO_CLIP, "none": B.MASK_NONE}[args.mask_rule],
             "eps_low": args.eps_low, "eps_high": args.eps_high, "ratio_cap": args.ratio_cap}
-    calls = []
-    for c0 in range(0, T, chunk):
-        c1 = min(T, c0 + chunk)
-        o = dict(out)
-        o["loss"] = torch.empty(1, dtype=torch.float32, device=dev)
-        for k in ("loss_tok", "divergence", "mask") + (("diagnostics",) if args.diagnostics else ()):
-            o[k] = out[k][c0:c1]
-        sl = slice(c0, c1)
-        a = B.make_args(batch["logits"][sl], batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
-                        batch["delta"], batch["variant"], batch["loss_scale"], o,
-                        batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
-                        V=V, flags=flags, grad_logits=grad[sl],
-                        mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
-        a.ld = batch["ld"]
-        calls.append((a, o))
+    # A small working set would otherwise be served by the 256 MB Infinity Cache step after step:
+    # consecutive steps then rotate among enough copies of (logits, gradient) to make 4 GiB.
+    per_step_bytes = 2 * batch["logits"].numel() * 2
+    nrot = 1 if (in_place or batch.get("mu_logits") is not None) else max(1, min(128, -(-(4 << 30) // per_step_bytes)))
+    copies = [(batch["logits"], grad)] + [(batch["logits"].clone(), torch.empty_like(grad)) for _ in range(nrot - 1)]
+
+    def make_calls(logits_c, grad_c):
+        cs = []
+        for c0 in range(0, T, chunk):
+            c1 = min(T, c0 + chunk)
+            o = dict(out)
+            o["loss"] = torch.empty(1, dtype=torch.float32, device=dev)
+            for k in ("loss_tok", "divergence", "mask") + (("diagnostics",) if args.diagnostics else ()):
+                o[k] = out[k][c0:c1]
+            sl = slice(c0, c1)
+            a = B.make_args(logits_c[sl], batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
+                            batch["delta"], batch["variant"], batch["loss_scale"], o,
+                            batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
+                            V=V, flags=flags, grad_logits=grad_c[sl],
+                            mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
+            a.ld = batch["ld"]
+            cs.append((a, o))
+        return cs
+    call_sets = [make_calls(lc, gc) for lc, gc in copies]
+    calls = call_sets[0]
 
     stream = torch.cuda.current_stream()
 
     run = B.dppo_loss_fwd if args.forward_only else B.dppo_loss_fwd_bwd
+    step_no = [0]
 
     def step():
-        for a, _ in calls:
+        for a, _ in call_sets[step_no[0] % nrot]:
             run(a, stream)
+        step_no[0] += 1
 
     # One HIP event pair per step, on the stream the kernels are launched on; the step time reported
     # is the MEDIAN over the steps.  In place, every step overwrites its input, so the logits are
@@ -328,25 +340,27 @@ def main() -> int:
     # with the library's plain copy kernels (grid-stride, and one workgroup per row like the loss
     # kernels) and its read kernel
     ceilings = {}
-    src2d, dst2d = (pristine if in_place else batch["logits"]), grad
-    nbytes = src2d.numel() * 2
+    nbytes = batch["logits"].numel() * 2
     if nbytes % 16 == 0 and nbytes >= (1 << 28):
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
-        probes = [("copy", lambda: B.probe_copy(dst2d.view(-1).view(torch.uint8), src2d.view(-1).view(torch.uint8), stream), 2 * nbytes),
-                  ("read", lambda: B.probe_read(src2d.view(-1).view(torch.uint8), sink, stream), nbytes)]
+        flat = lambda t: t.view(-1).view(torch.uint8)
+        # (source, destination) pairs: the same rotating copies the timed steps used
+        pairs = [(pristine, grad)] if in_place else copies
+        probes = [("copy", lambda s_, d_: B.probe_copy(flat(d_), flat(s_), stream), 2 * nbytes),
+                  ("read", lambda s_, d_: B.probe_read(flat(s_), sink, stream), nbytes)]
         if (V * 2) % 16 == 0 and (batch["ld"] * 2) % 16 == 0:
-            probes.append(("copy_rows", lambda: B.probe_copy_rows(dst2d[:, :V], src2d[:, :V], stream), 2 * T * V * 2))
+            probes.append(("copy_rows", lambda s_, d_: B.probe_copy_rows(d_[:, :V], s_[:, :V], stream), 2 * T * V * 2))
             if V * 2 <= 512 * 38 * 16:
                 # the loss kernel's own memory pattern with none of its arithmetic
-                probes.append(("copy_resident", lambda: B.probe_copy_resident(dst2d[:, :V], src2d[:, :V], stream), 2 * T * V * 2))
+                probes.append(("copy_resident", lambda s_, d_: B.probe_copy_resident(d_[:, :V], s_[:, :V], stream), 2 * T * V * 2))
         for name, fn, moved in probes:
-            fn()
+            fn(*pairs[0])
             torch.cuda.synchronize()
             c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             reps = max(5, int(2e10 // moved))      # about 20 GB moved per probe, whatever the buffers' size
             c0.record(stream)
-            for _ in range(reps):
-                fn()
+            for i in range(reps):
+                fn(*pairs[i % len(pairs)])
             c1.record(stream)
             torch.cuda.synchronize()
             ceilings[name + "_GBs"] = moved / (c0.elapsed_time(c1) / reps * 1e-3) / 1e9
@@ -375,7 +389,7 @@ def main() -> int:
                                       "N(0, drift_std^2) after the rollout, so that a few tokens are masked; not part of "
                                       "the configuration string this workload stands for, byte-neutral"},
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
-                   "kernel_path": path, "rows": "fixed by workgroup index" if args.static_rows else "library default", "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
+                   "kernel_path": path, "buffer_sets": nrot, "rows": "fixed by workgroup index" if args.static_rows else "library default", "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
