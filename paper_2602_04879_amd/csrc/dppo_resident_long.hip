@@ -24,14 +24,14 @@
 // side, every younger store: waiting for a load in front of a run of younger stores means waiting
 // for those stores to drain.)  Hence, per row:
 //   statistics   register chunks (as they arrive), window batch A (tail chunks 0..W-1), request
-//                batch B (tail chunks W..2W-1), LDS chunks, batch B, then request the FIRST W tail
-//                chunks again: they travel during the epilogue and are the first thing the
+//                batch B (tail chunks W..2W-1), LDS chunks, batch B, then request batch B AGAIN
+//                (read a few microseconds ago: its lines may still be in the L2; with a tail of one
+//                batch, that one): it travels during the epilogue and is the first thing the
 //                gradient pass turns into stores;
-//   gradient     window (tail 0..W-1), registers, LDS chunks: one run of stores;
-//   next row     request the remaining tail chunks (W..2W-1) of THIS row again, then the next row's
-//                register and LDS chunks in one run of loads; the tail chunks come back first and
-//                leave as (a few) stores while the rest of the run is on its way; then batch A of
-//                the next row is requested.
+//   gradient     window, registers, LDS chunks: one run of stores;
+//   next row     request batch A of THIS row again, then the next row's register and LDS chunks in
+//                one run of loads; batch A comes back first and leaves as (a few) stores while the
+//                rest of the run is on its way; then batch A of the next row is requested.
 // (Without a window the LDS chunks are requested and consumed first.)
 // Preconditions (checked by the host): V % 8 == 0, 38 < ceil(V / 4096) <= 64, logits and
 // grad_logits 16-byte aligned with ld % 8 == 0.
@@ -100,10 +100,20 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
 #pragma unroll
     for (int k = 0; k < kLWin; ++k)
       if (first + k < nt) {
-        const uint32_t so = (kLReg + kLLds + first + k) * kLStride;
+        const uint32_t so = static_cast<uint32_t>(kLReg + kLLds + first + k) * kLStride;
         w[k] = nontemporal ? row_load16<true>(r, voff, so) : row_load16<false>(r, voff, so);
       }
   };
+  // gradient of the window's chunks, which hold tail chunks first .. first + W - 1
+  auto store_window = [&](row_desc_t gout, int first, float kexp, uint32_t sgn) {
+#pragma unroll
+    for (int k = 0; k < kLWin; ++k)
+      if (first + k < nt) row_store16_untracked(gout, voff, static_cast<uint32_t>(kLReg + kLLds + first + k) * kLStride, grad8(w[k], kexp, sgn));
+  };
+  // With a tail of two batches, the batch read LAST for the statistics (B) is the one requested
+  // again before the epilogue: its lines were fetched a few microseconds earlier and may still be
+  // in the L2; batch A, read at the row's start, comes again at the head of the next run of loads.
+  const int re1 = uniform_i(nt > kLWin ? kLWin : 0), re2 = uniform_i(nt > kLWin ? 0 : kLWin);
   // lanes past the row loaded 0: -inf instead (only chunks from 38 on can have any)
   auto in_row = [&](u32x4 v, int chunk) { return (chunk * kLThreads + tid >= nvec) ? neg_inf : v; };
 
@@ -199,7 +209,7 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
         for (int k = 0; k < kLWin; k += 2)
           if (kLWin + k < nt) group(seen(w[k], kLReg + kLLds + kLWin + k), (kLWin + k + 1 < nt) ? seen(w[k + 1], kLReg + kLLds + kLWin + k + 1) : neg_inf);
         __builtin_amdgcn_sched_barrier(0);
-        load_window(zr, 0, nt <= kLWin);
+        load_window(zr, re1, false);
         __builtin_amdgcn_sched_barrier(0);
       };
       if (kLdsFirst) { stats_lds(); stats_regs(); }
@@ -283,11 +293,9 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
       for (int c = 0; c < kLReg + kLLds + 2 * kLWin; ++c)
         if (c < nchunks) row_store16_untracked(gout, voff, c * kLStride, zero);
     } else {
-      // the window first (tail chunks 0..7, requested before the epilogue), so that nothing waits
+      // the window first (the tail chunks requested before the epilogue), so that nothing waits
       // for a load behind younger stores
-#pragma unroll
-      for (int k = 0; k < kLWin; ++k)
-        if (k < nt) row_store16_untracked(gout, voff, (kLReg + kLLds + k) * kLStride, grad8(w[k], rc.kexp, sgn));
+      store_window(gout, re1, rc.kexp, sgn);
 #pragma unroll
       for (int i = 0; i < kLReg; ++i) row_store16_untracked(gout, voff, i * kLStride, grad8(buf[i], rc.kexp, sgn));
 #pragma unroll
@@ -297,16 +305,12 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
     // Keep the instruction scheduler from hoisting the loads above the stores: a load can only
     // reuse its chunk's registers (or its LDS slot) once the store has been given them.
     __builtin_amdgcn_sched_barrier(0);
-    if (!zero_row) load_window(zr, kLWin, true);      // the rest of this row's tail, once more
+    if (!zero_row) load_window(zr, re2, true);        // the rest of this row's tail, once more (re2 = W: none)
     if (!kLdsFirst) load_regs(zn);
     load_lds(zn);
     if (kLdsFirst) load_regs(zn);
     __builtin_amdgcn_sched_barrier(0);
-    if (!zero_row) {
-#pragma unroll
-      for (int k = 0; k < kLWin; ++k)
-        if (kLWin + k < nt) row_store16_untracked(gout, voff, (kLReg + kLLds + kLWin + k) * kLStride, grad8(w[k], rc.kexp, sgn));
-    }
+    if (!zero_row && nt > kLWin) store_window(gout, re2, rc.kexp, sgn);
     __builtin_amdgcn_sched_barrier(0);
     load_window(zn, 0, false);                        // batch A of the next row
     __builtin_amdgcn_sched_barrier(0);
