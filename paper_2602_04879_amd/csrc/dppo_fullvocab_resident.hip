@@ -9,8 +9,9 @@
 // 16-byte chunks per thread at a time and is never kept in registers:
 //   pass 1   statistics of z (sampled token left out) and of y, and for the KL form the cross term
 //            sum_j 2^(y_j..) (y_j - z_j); KL = E_mu[y - z] - lse(y) + lse(z) needs nothing else.
-//   pass 2   (TV only) sum_j min(pi_j, mu_j) with z from the registers and y read again; the last
-//            chunks of y each thread consumed in pass 1 wait for it in LDS, the others are re-read.
+//   pass 2   (TV only) sum_j min(pi_j, mu_j) with z from the registers and y read again; the first
+//            chunks of y each thread consumed in pass 1 wait for it in LDS, the later ones (read a
+//            few microseconds earlier, partly still in the L2) are requested again.
 //   epilogue on one wave: mask, loss term, gradient coefficient.
 //   gradient every resident entry, the whole row in one run of 16-byte stores; then the next row of
 //            z and the first chunks of the next row of y are requested in one run of loads.
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         if (i + kWindow < NCHUNK) yb[i % kWindow] = row_load16<kY1Nt>(yr, voff, (i + kWindow) * kStride);
         // lanes past the row loaded 0: make them -inf in both rows (they then add nothing)
         if (i >= FULLCHUNKS && i * THREADS + tid >= nvec) { zq = neg_inf; yq = neg_inf; }
-        if (TV && i >= REREAD) sh_y[(i - REREAD) * THREADS + tid] = yq;
+        if (TV && i < KEEP) sh_y[i * THREADS + tid] = yq;
         float z[8], y[8];
         unpack8(zq, z);
         unpack8(yq, y);
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         // the second pass over y starts to travel while the statistics are combined
 #pragma unroll
         for (int i = 0; i < kWindow; ++i)
-          if (i < REREAD) yb[i] = row_load16<true>(yr, voff, i * kStride);
+          if (i < REREAD) yb[i] = row_load16<true>(yr, voff, (KEEP + i) * kStride);
       }
       // workgroup-wide offsets = the smallest ones; rescaling to them is exact
       const float wbz = -wave_max(-st.b), wby = -wave_max(-cs.b);
@@ -252,21 +253,24 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         const float bz2 = sh_norm[0], by2 = sh_norm[1], fz = sh_norm[2], fy = sh_norm[3];
         double acc0 = 0.0, acc1 = 0.0;
 #pragma unroll
-        for (int i = 0; i < NCHUNK; ++i) {
+        for (int j = 0; j < NCHUNK; ++j) {
+          // first the chunks of y that are read again (the LAST ones pass 1 read, a few microseconds
+          // ago: part of them is still in the L2), then the ones kept in LDS
+          const int i = (j < REREAD) ? KEEP + j : j - REREAD;
           asm volatile("" : "+v"(buf[i]));     // unpack again here: nothing unpacked in pass 1 is kept alive
           u32x4 zq = buf[i], yq;
-          if (i < REREAD) {
-            yq = yb[i % kWindow];              // last use of the row: non-temporal loads
-            if (i + kWindow < REREAD) yb[i % kWindow] = row_load16<true>(yr, voff, (i + kWindow) * kStride);
+          if (j < REREAD) {
+            yq = yb[j % kWindow];              // last use of the row: non-temporal loads
+            if (j + kWindow < REREAD) yb[j % kWindow] = row_load16<true>(yr, voff, (KEEP + j + kWindow) * kStride);
             if (i >= FULLCHUNKS && i * THREADS + tid >= nvec) yq = neg_inf;
           } else {
-            yq = sh_y[(i - REREAD) * THREADS + tid];     // parked with its lanes past the row already -inf
+            yq = sh_y[i * THREADS + tid];      // kept with its lanes past the row already -inf
           }
           if (i >= FULLCHUNKS && i * THREADS + tid >= nvec) zq = neg_inf;
           float z[8], y[8];
           unpack8(zq, z);
           unpack8(yq, y);
-          double& acc = (i & 1) ? acc1 : acc0;
+          double& acc = (j & 1) ? acc1 : acc0;
           auto mn = [&](int e) { return fast_exp2(fminf(fmaf(z[e], kLog2e, bz2) - fz, fmaf(y[e], kLog2e, by2) - fy)); };
           // eight entries among themselves (pairwise, as they are formed), then into float64
           const float q0 = (mn(0) + mn(1)) + (mn(2) + mn(3)), q1 = (mn(4) + mn(5)) + (mn(6) + mn(7));
