@@ -3,7 +3,8 @@
 // Pass 1 streams the row once from HBM with 16-byte loads (per-thread online max / sum of
 // exponentials in fp32), the workgroup combines the statistics, one wave evaluates the
 // per-token epilogue, and pass 2 re-reads the row (normally still in L2 / Infinity Cache),
-// and writes the bf16 gradient with non-temporal 16-byte stores.  Rows whose gradient
+// from its end backwards (what pass 1 read last is what the L2 still holds), and writes the bf16
+// gradient with non-temporal 16-byte stores.  Rows whose gradient
 // coefficient is zero (masked, zero advantage, ignored) are zero-filled without the re-read.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
@@ -137,17 +138,19 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
           const u32x4 o = {w[0], w[1], w[2], w[3]};
           __builtin_nontemporal_store(o, gv + v);
         };
-        int v = tid;
-        // four loads in flight, then four stores; the row is not needed again: non-temporal loads (2 % faster)
-        for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {
-          const u32x4 q0 = __builtin_nontemporal_load(zv + v), q1 = __builtin_nontemporal_load(zv + v + THREADS);
-          const u32x4 q2 = __builtin_nontemporal_load(zv + v + 2 * THREADS), q3 = __builtin_nontemporal_load(zv + v + 3 * THREADS);
-          grad_vec(q0, v);
-          grad_vec(q1, v + THREADS);
-          grad_vec(q2, v + 2 * THREADS);
+        // From the END of the row backwards: what pass 1 read last is what the L2 still holds.
+        // Four loads in flight, then four stores; the row is not needed again: non-temporal loads (2 % faster).
+        const int nfull = nvec / (4 * THREADS);                   // blocks of 4 * THREADS vectors
+        for (int v = nfull * 4 * THREADS + tid; v < nvec; v += THREADS) grad_vec(zv[v], v);   // the ragged end first
+        for (int blk = nfull - 1; blk >= 0; --blk) {
+          const int v = blk * 4 * THREADS + tid;
+          const u32x4 q3 = __builtin_nontemporal_load(zv + v + 3 * THREADS), q2 = __builtin_nontemporal_load(zv + v + 2 * THREADS);
+          const u32x4 q1 = __builtin_nontemporal_load(zv + v + THREADS), q0 = __builtin_nontemporal_load(zv + v);
           grad_vec(q3, v + 3 * THREADS);
+          grad_vec(q2, v + 2 * THREADS);
+          grad_vec(q1, v + THREADS);
+          grad_vec(q0, v);
         }
-        for (; v < nvec; v += THREADS) grad_vec(zv[v], v);
         for (int e = tid; e < nscalar; e += THREADS) {
           const int j = (e < head) ? e : tail0 + (e - head);
           float g = fast_exp2(fmaf(bf16_bits_to_float(zrow[j]), kLog2e, kexp));
