@@ -163,6 +163,25 @@ LossScratch scratch_of(void* base, size_t bytes, int64_t T) {
   return sc;
 }
 
+// Rows handed out at run time (the persistent one-workgroup-per-compute-unit kernels with the
+// gradient): possible when the caller's scratch has the counter and the per-row loss terms, the
+// grid is a multiple of the eight dies, every workgroup gets several rows, and the caller did not
+// ask for fixed rows.
+bool rows_at_run_time(const dppo_args_t* a, const LossScratch& sc, int64_t grid) {
+  return sc.counters && grid % 8 == 0 && a->T >= 4 * grid && !(a->flags & DPPO_FLAG_STATIC_ROWS);
+}
+// Points the kernel at the counter (cleared by a small kernel first: no memset, so a call stays
+// capturable) and at the per-row loss terms, which the reduction then sums instead of the
+// per-workgroup partial sums.
+dppo_status_t arm_rows_at_run_time(dppo::KParams& p, const dppo_args_t* a, const LossScratch& sc, const double** fin, int* fin_n, hipStream_t s) {
+  p.row_counters = sc.counters;
+  p.row_loss = sc.row_loss;
+  if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+  *fin = sc.row_loss;
+  *fin_n = static_cast<int>(a->T);
+  return DPPO_OK;
+}
+
 // Launch the loss kernel of one (already validated) call.  Afterwards the scalar loss is
 // loss_scale times the sum of fin[0 .. *fin_n) (per-workgroup partial sums, or per-row terms).
 dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc, const double** fin, int* fin_n, hipStream_t s) {
@@ -196,14 +215,8 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
       // with the gradient and several rows per workgroup: rows handed out at run time
-      const bool dyn = grad && sc.counters && grid % 8 == 0 && a->T >= 4 * grid && !(a->flags & DPPO_FLAG_STATIC_ROWS);
-      if (dyn) {
-        p.row_counters = sc.counters;
-        p.row_loss = sc.row_loss;
-        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
-        *fin = sc.row_loss;
-        *fin_n = static_cast<int>(a->T);
-      }
+      const bool dyn = grad && rows_at_run_time(a, sc, grid);
+      if (dyn && arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
       if (dppo::launch_fullvocab_resident(p, tv_full, grad, fr_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "fullvocab_resident";
       if (dyn) return DPPO_OK;
@@ -223,14 +236,8 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
       nparts = static_cast<int>(grid);
-      const bool dyn = sc.counters && grid % 8 == 0 && a->T >= 4 * grid && !(a->flags & DPPO_FLAG_STATIC_ROWS);
-      if (dyn) {
-        p.row_counters = sc.counters;
-        p.row_loss = sc.row_loss;
-        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
-        *fin = sc.row_loss;
-        *fin_n = static_cast<int>(a->T);
-      }
+      const bool dyn = rows_at_run_time(a, sc, grid);
+      if (dyn && arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
       if (dppo::launch_resident_long(p, long_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident_long";
       if (dyn) return DPPO_OK;
@@ -243,27 +250,17 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       // run time: the dies do not run at one speed, and the slowest one would end the kernel.  (The
       // forward-only form and the shapes with several workgroups per compute unit measure slower
       // that way: their waves run ahead of wave 0, which would have to wait for the counter.)
-      const bool want_dyn = grad && r_threads == 512 && per_cu == 1 && sc.counters && !(a->flags & DPPO_FLAG_STATIC_ROWS);
       bool dyn = false;
-      if (want_dyn) {
-        const int per_cu_dyn = resident_blocks_per_cu_cached(dev, grad, true, r_threads, r_chunks);
-        const int64_t grid_dyn = static_cast<int64_t>(cus) * per_cu_dyn;
-        if (grid_dyn % 8 == 0 && a->T >= 4 * grid_dyn && grid_dyn <= max_parts) {
+      if (grad && r_threads == 512 && per_cu == 1) {
+        // the form that draws its rows has its own register count, so its own occupancy
+        const int64_t grid_dyn = static_cast<int64_t>(cus) * resident_blocks_per_cu_cached(dev, grad, true, r_threads, r_chunks);
+        if (grid_dyn <= max_parts && rows_at_run_time(a, sc, grid_dyn)) {
           grid = grid_dyn;
-          per_cu = per_cu_dyn;
           dyn = true;
         }
       }
       nparts = static_cast<int>(grid);
-      // One workgroup per compute unit, the gradient, several rows per workgroup, and scratch for it:
-      // rows are handed out at run time (the dies do not run at one speed).
-      if (dyn) {
-        p.row_counters = sc.counters;
-        p.row_loss = sc.row_loss;
-        if (dppo::launch_clear_counters(sc.counters, s) != hipSuccess) return DPPO_ERR_LAUNCH;
-        *fin = sc.row_loss;
-        *fin_n = static_cast<int>(a->T);
-      }
+      if (dyn && arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
       if (dppo::launch_resident(p, grad, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident";
       if (p.row_counters) return DPPO_OK;
