@@ -131,6 +131,17 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
     __syncthreads();
     if (row >= p.T) return;            // every row already handed out: nothing to do, and no address to form
   }
+  // Fetched one row ahead, so that wave 0's gathers never wait on a load that queues behind the
+  // row's own run of loads (a wait for the top-K ids at the top of a row would be a wait for the
+  // whole run, with wave 0's statistics still to do when the other waves are through): the sampled
+  // id, and (wave 0, lane k < K) the id and log-prob of top-K entry k.
+  int a_next = p.sampled[row];
+  int tkid_next = -1;
+  float tklp_next = 0.f;
+  if (wid == 0 && lane < p.K) {
+    tkid_next = p.tk_ids[static_cast<int64_t>(row) * p.K + lane];
+    tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
+  }
   {
     const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
     if (!kLdsFirst) load_regs(zr);
@@ -138,12 +149,17 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
     if (kLdsFirst) load_regs(zr);
     load_window(zr, 0, false);
   }
-  int a_next = p.sampled[row];
 
   for (; row < p.T;) {
     const int a = uniform_i(a_next);
     const bool more = next < p.T;
     if (more) a_next = p.sampled[next];
+    const int tkid = tkid_next;
+    const float tklp = tklp_next;
+    if (more && wid == 0 && lane < p.K) {
+      tkid_next = p.tk_ids[static_cast<int64_t>(next) * p.K + lane];
+      tklp_next = p.tk_lp[static_cast<int64_t>(next) * p.K + lane];
+    }
     int drawn = 0;
     if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters, 1);     // the row after next
     int next2 = kNoRow;
@@ -164,11 +180,18 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
       TopkLane tk;
       tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
       rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f;
+      // Inputs of the epilogue, requested now so that they have arrived when it runs; the two
+      // gathered logits stay raw bit patterns until then (see below).
+      uint32_t za_bits = 0, tkz_bits = 0;
       if (wid == 0) {
-        rs.za = bf16_bits_to_float(zrow[a]);
+        za_bits = zrow[a];
         rs.lmu = p.mu_logp[row];
         rs.adv = p.adv[row];
-        tk = load_topk_lane(p, row, a, zrow, lane);
+        if (tkid >= 0 && tkid < p.V && tkid != a) {
+          tk.id = tkid;
+          tk.lp = tklp;
+          tkz_bits = zrow[tkid];
+        }
       }
       // ---- statistics: online over groups of two chunks (see the shorter kernel) ---------------
       PackedRowStat<DIAG> ps;
@@ -229,6 +252,12 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
       if (wid == 0) {
 #pragma unroll
         for (int i = 0; i < kLPark; ++i) sh_park[i * kWave + lane] = buf[kLReg - 1 - i];
+        // (the epilogue's inputs are looked at HERE, behind the statistics: moved up to where they
+        // were requested, their first use, be it a shift, would be a wait for the whole run of
+        // loads in front of them)
+        asm volatile("" : "+v"(za_bits), "+v"(rs.lmu), "+v"(rs.adv), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        rs.za = __uint_as_float(za_bits << 16);
+        tk.z = __uint_as_float(tkz_bits << 16);
         pre = row_pre(rs, tk, p.K > 0);
       }
       if (DYN && tid == 0) publish_row_after_next();
