@@ -109,20 +109,23 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     // all at once) has nothing to do, and must not form an address from "no row".
     if (row >= p.T) return;
   }
-  {
-    const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
-#pragma unroll
-    for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<kNtLoads>(zr, voff, i * kStride);
-  }
   // Fetched one row ahead, so that neither the row loop nor wave 0's gathers ever wait on a load
   // that queues behind the row's own refills: the sampled id, and (wave 0, lane k < K) the id
-  // and log-prob of top-K entry k.
+  // and log-prob of top-K entry k.  (For the first row too they are requested BEFORE the row: the
+  // compiler places one wait at the head of the loop for both ways into it, and it is as long as
+  // the longer of the two.)
   int a_next = p.sampled[row];
   int tkid_next = -1;
   float tklp_next = 0.f;
   if (wid == 0 && lane < p.K) {
     tkid_next = p.tk_ids[static_cast<int64_t>(row) * p.K + lane];
     tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  {
+    const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
+#pragma unroll
+    for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<kNtLoads>(zr, voff, i * kStride);
   }
 
   for (; row < p.T;) {
@@ -159,14 +162,17 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
       TopkLane tk;
       tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
       rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f;
+      // (The two gathered logits stay raw bit patterns until the statistics are through: their
+      // first use, be it a shift, placed up here would be a wait for every refill in front of them.)
+      uint32_t za_bits = 0, tkz_bits = 0;
       if (wid == 0) {
-        rs.za = bf16_bits_to_float(zrow[a]);
+        za_bits = zrow[a];
         rs.lmu = p.mu_logp[row];
         rs.adv = p.adv[row];
         if (tkid >= 0 && tkid < p.V && tkid != a) {
           tk.id = tkid;
           tk.lp = tklp;
-          tk.z = bf16_bits_to_float(zrow[tkid]);
+          tkz_bits = zrow[tkid];
         }
       }
       // ---- phases A+B, online over groups of GC chunks (PackedRowStat) -------------------------
@@ -228,6 +234,11 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
       if (kPark > 0 && wid == 0) {
 #pragma unroll
         for (int i = 0; i < kPark; ++i) sh_park[i * kWave + lane] = buf[NCHUNK - 1 - i];
+      }
+      if (wid == 0) {
+        asm volatile("" : "+v"(za_bits), "+v"(rs.lmu), "+v"(rs.adv), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        rs.za = __uint_as_float(za_bits << 16);
+        tk.z = __uint_as_float(tkz_bits << 16);
       }
       if (GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
       if (DYN && tid == 0) publish_row_after_next();
