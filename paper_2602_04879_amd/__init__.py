@@ -2,4 +2,4 @@
 C-ABI library, plus a thin ctypes binding.  Importing the package loads nothing; the HIP
 library is opened on first use by `paper_2602_04879_amd.binding`."""
 
-__all__ = ["binding", "workloads", "build"]
+__all__ = ["binding", "autograd", "workloads", "build"]
