@@ -72,3 +72,53 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, *, delta, variant=B.BINA
     if len(res) > 4:
         aux["diagnostics"] = res[4]
     return res[0], aux
+
+
+class _DppoLmheadLoss(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, hidden, weight, sampled_ids, mu_logp, advantages, mu_topk_ids, mu_topk_logp, opts):
+        if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16 or hidden.dim() != 2 or weight.dim() != 2:
+            raise ValueError("hidden [T, d] and weight [V, d]: bf16 matrices on the GPU")
+        if hidden.stride(1) != 1 or weight.stride(1) != 1 or hidden.shape[1] != weight.shape[1]:
+            raise ValueError("hidden and weight: contiguous rows of the same length d")
+        T, d = hidden.shape
+        V = weight.shape[0]
+        need_h, need_w = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        backward = need_h or need_w
+        batch = {"hidden": hidden.detach(), "weight": weight.detach(), "d": d, "V": V, "sampled_ids": sampled_ids, "mu_logp": mu_logp,
+                 "advantages": advantages, "delta": opts["delta"], "variant": opts["variant"], "loss_scale": opts["loss_scale"],
+                 "mu_topk_ids": mu_topk_ids, "mu_topk_logp": mu_topk_logp}
+        gw = torch.empty((V, d), dtype=torch.float32, device=hidden.device) if need_w else None
+        rule = {k: opts[k] for k in ("mask_rule", "eps_low", "eps_high", "ratio_cap") if k in opts}
+        res = B.run_lmhead(batch, backward=backward, chunk_rows=opts.get("chunk_rows", 0), diagnostics=opts.get("diagnostics", False),
+                           grad_weight=gw, flags=opts.get("flags", 0), **rule)
+        ctx.grads = (res["grad_hidden"] if need_h else None, gw)
+        side = [res[k] for k in ("divergence", "mask", "loss_tok")] + ([res["diagnostics"]] if res["diagnostics"] is not None else [])
+        ctx.mark_non_differentiable(*side)
+        return (res["loss"].reshape(()), *side)
+
+    @staticmethod
+    def backward(ctx, grad_loss, *unused):
+        gh, gw = ctx.grads
+        ctx.grads = None
+        one = _is_one(grad_loss)
+        if gh is not None and not one:
+            gh = (gh.float() * grad_loss.float()).to(torch.bfloat16)
+        if gw is not None:
+            # the library accumulates the weight's gradient in fp32; autograd wants the weight's own type
+            gw = (gw if one else gw * grad_loss.float()).to(torch.bfloat16)
+        return (gh, gw, None, None, None, None, None, None)
+
+
+def dppo_lmhead_loss(hidden, weight, sampled_ids, mu_logp, advantages, *, delta, variant=B.BINARY_TV, loss_scale=1.0,
+                     mu_topk_ids=None, mu_topk_logp=None, **opts):
+    """The same loss one step earlier (dppo_lmhead_loss_fwd[_bwd] of include/dppo.h): from the final
+    hidden states [T, d] and the lm_head weight [V, d], both bf16; the logits exist a chunk of
+    tokens at a time inside the call (forward only: never).  Returns the loss, with gradient paths
+    to `hidden` and `weight`, and the per-token outputs.  Options as for dppo_loss, plus chunk_rows."""
+    opts = dict(opts, delta=float(delta), variant=int(variant), loss_scale=float(loss_scale))
+    res = _DppoLmheadLoss.apply(hidden, weight, sampled_ids, mu_logp, advantages, mu_topk_ids, mu_topk_logp, opts)
+    aux = {"divergence": res[1], "mask": res[2], "loss_tok": res[3]}
+    if len(res) > 4:
+        aux["diagnostics"] = res[4]
+    return res[0], aux

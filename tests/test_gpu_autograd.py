@@ -66,3 +66,30 @@ def test_in_place_gradient_over_the_logits():
     torch.cuda.synchronize()
     assert torch.equal(leaf.grad, keep.grad) and torch.equal(loss.detach(), loss_ref.detach())
     assert leaf.grad.data_ptr() == storage          # the gradient lives in the logits' own storage
+
+
+def test_hidden_state_form_backward_matches_the_direct_call():
+    w = W.Workload("autograd_lm", 2, 150, 4160, W.TOPK_TV, 0.1, K=8, logit_std=3.0, noise_std=1.0, adv="normal", seed=95)
+    b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
+    gw_ref = torch.empty((b["V"], b["d"]), dtype=torch.float32, device=DEV)
+    ref = B.run_lmhead(b, chunk_rows=64, grad_weight=gw_ref)
+    h = b["hidden"].clone().requires_grad_(True)
+    wt = b["weight"].clone().requires_grad_(True)
+    loss, aux = A.dppo_lmhead_loss(h, wt, b["sampled_ids"], b["mu_logp"], b["advantages"], delta=b["delta"], variant=b["variant"],
+                                   loss_scale=b["loss_scale"], mu_topk_ids=b["mu_topk_ids"], mu_topk_logp=b["mu_topk_logp"], chunk_rows=64)
+    loss.backward()
+    torch.cuda.synchronize()
+    assert torch.equal(loss.detach().reshape(1), ref["loss"]) and torch.equal(aux["mask"], ref["mask"])
+    assert torch.equal(aux["divergence"], ref["divergence"])
+    assert torch.equal(h.grad, ref["grad_hidden"])
+    assert torch.equal(wt.grad, gw_ref.to(torch.bfloat16))
+    assert 0 < (aux["mask"] == 0).sum().item() < b["T"]
+    # forward only (no gradient path): no logit is written, same per-token results up to summation order
+    with torch.no_grad():
+        loss0, aux0 = A.dppo_lmhead_loss(b["hidden"], b["weight"], b["sampled_ids"], b["mu_logp"], b["advantages"], delta=b["delta"],
+                                         variant=b["variant"], loss_scale=b["loss_scale"], mu_topk_ids=b["mu_topk_ids"],
+                                         mu_topk_logp=b["mu_topk_logp"], chunk_rows=64)
+    torch.cuda.synchronize()
+    assert B.last_path() == "lmhead_fused"
+    assert torch.equal(aux0["mask"], ref["mask"])
+    assert torch.allclose(aux0["divergence"], ref["divergence"], rtol=1e-4, atol=1e-7)
