@@ -148,7 +148,7 @@ def test_one_wave_per_row_many_rows_per_wave_in_place_with_special_rows():
 
 def test_rows_handed_out_at_run_time_match_rows_fixed_by_index():
     """Long rows with the gradient and many rows per workgroup: the kernel hands its rows out at run
-    time (per-die counters, one loss term per row).  Every per-row output must be bit for bit what
+    time (one counter, one loss term per row).  Every per-row output must be bit for bit what
     the form with rows fixed by the workgroup index writes, run after run, ignored / zero-advantage
     / masked rows included; the scalar loss is summed per row in a fixed order, so it too repeats
     bit for bit; and a workspace of the minimum size falls back to the fixed rows."""
