@@ -226,6 +226,30 @@ def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
     _say(f"       {st}")
 
 
+@pytest.mark.parametrize("V", [180224, 237568])
+def test_long_rows_saturated_and_minus_inf(V):
+    """pi(a_t) -> 1, blocks of -inf across the parts of the row (registers, LDS, the tail that is
+    read twice), every logit hugely negative or hugely positive: on the long-row path."""
+    w = W.Workload("sat_long", 2, 8, V, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=43)
+    b = W.make_batch(w, DEV)
+    a = b["sampled_ids"].long()
+    rows = torch.arange(b["T"], device=DEV)
+    b["logits"][rows[:6], a[:6]] = torch.tensor([20.0, 30.0, 40.0, 50.0, 60.0, 80.0], device=DEV).bfloat16()
+    b["logits"][6:8, 1000:150000] = float("-inf")            # most of the register part
+    b["logits"][8:10, 120000:V - 5] = float("-inf")          # the LDS part and the tail
+    b["logits"][10, :] = -1.0e4
+    b["logits"][11, :] = -50.0
+    b["logits"][12, :] = 3.0e4
+    for r in range(6, 10):                                   # keep the sampled token finite in those rows
+        b["logits"][r, a[r]] = 1.0
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident_long"
+    assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["grad_logits"].float()).all()
+    st = P.compare_rows(b, res, np.arange(b["T"]))
+    _say(f"       {st}")
+
+
 def test_resident_saturated_rows():
     """pi(a_t) -> 1 on the register-resident path: 1 - pi(a_t) must keep its relative accuracy."""
     w = W.Workload("sat_res", 2, 8, 16384, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=41)
