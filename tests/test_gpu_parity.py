@@ -400,8 +400,12 @@ def test_saturated_and_minus_inf_logits():
 
 
 def test_empty_and_single_row():
+    # one row on every kernel path: two-pass, one wave per row, 256 and 512 threads, long rows
+    for V, path in ((513, "streaming"), (4096, "resident"), (32768, "resident"), (151936, "resident"), (256000, "resident_long")):
+        w1 = W.Workload("one", 1, 1, V, W.BINARY_TV, 0.1, logit_std=2.0, noise_std=0.5, adv="pm1", seed=2)
+        _run_and_compare(w1)
+        assert B.last_path() == path
     w = W.Workload("one", 1, 1, 513, W.BINARY_TV, 0.1, logit_std=2.0, noise_std=0.5, adv="pm1", seed=2)
-    _run_and_compare(w)
     b = W.make_batch(w, DEV)
     out = B.alloc_outputs(0, DEV)
     out["loss"].fill_(5.0)
