@@ -602,7 +602,11 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     capturable.  Capture forward+backward of two shapes (both kernel paths) in one graph, replay it
     several times with eager work and synchronisations in between, and compare every replay bit for
     bit with the eager result."""
-    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4090)]
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4090),
+              # rows handed out at run time (a counter-clearing kernel in front, no memset), and the long-row kernel
+              W.Workload("graph_dyn", 1, 4 * cus + 5, 100000, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=63),
+              W.Workload("graph_long", 1, 40, 200000, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=64)]
     batches = [W.make_batch(w, DEV, shift_sampled=1.0) for w in shapes]
     eager = []
     for b in batches:
@@ -619,7 +623,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
             for b, o, gr in zip(batches, outs, grads):
                 B.run_batch(b, out=o, grad=gr)          # enqueued on the capturing (current) stream
                 paths.add(B.last_path())
-    assert paths == {"resident", "streaming"}
+    assert paths == {"resident", "streaming", "resident_long"}
     scratch = torch.zeros(1 << 20, device=DEV)
     for rep in range(3):
         for o, gr in zip(outs, grads):                   # poison the outputs between replays
@@ -635,7 +639,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
             for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics"):
                 assert torch.equal(e[k], o[k]), (rep, k)
             assert torch.equal(e["grad_logits"], gr), rep
-    _say(f"       graph with both kernel paths replayed 3 times, bitwise equal to eager")
+    _say(f"       graph with the kernel paths {sorted(paths)} replayed 3 times, bitwise equal to eager")
 
 
 # --------------------------------------------------------------------------- measurement utilities
