@@ -304,6 +304,31 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
   // v_permlane16_swap per register pair), after which a lane owns 8 consecutive columns: one
   // 16-byte store, 64 contiguous bytes per row and instruction.  fp32: 16 bytes per lane as they are.
   const bool quad_aligned = ((reinterpret_cast<uintptr_t>(Cv) & 15u) == 0) && (ldc % 8 == 0);
+  if (OUT == kOutF32Add && FULL) {
+    // C += tile: what C holds is requested one block of 16 rows AHEAD of the block being added and
+    // stored (eight 16-byte loads per lane in flight behind eight stores), so that a lane waits for
+    // memory eight times per tile and not sixty-four times.  (Written as load - add - store per
+    // vector, the compiler keeps that order, every load behind the store in front of it.)
+    auto cptr = [&](int i, int j) {
+      const int row = m0 + wm * 128 + i * 16 + frow, col = n0 + wn * 128 + j * 16 + fk * 4;
+      return reinterpret_cast<f32x4*>(static_cast<float*>(Cv) + static_cast<int64_t>(row) * ldc + col);
+    };
+    f32x4 cur[8], nxt[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cur[j] = __builtin_nontemporal_load(cptr(0, j));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (i + 1 < 8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) nxt[j] = __builtin_nontemporal_load(cptr(i + 1, j));
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *cptr(i, j) = acc[i][j] + cur[j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = m0 + wm * 128 + i * 16 + frow;
