@@ -234,6 +234,14 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
     // XOR-ed with the row so that a 16-lane write spreads over the banks), from where the logits at
     // the sampled and the top-K ids that fall into this tile are picked.
     __shared__ float sh_part[2][kBM][3];
+    // the sampled ids of the lane's eight rows, requested in one go (one memory latency, which
+    // the barrier covers in part, instead of one per row block)
+    int samp[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = m0 + wm * 128 + i * 16 + frow;
+      samp[i] = (row < M) ? gs.sampled[row] : -1;
+    }
     __syncthreads();                       // every wave has read its last fragments: the stages can be overwritten
     unsigned char* half = wm ? lds1 : lds0;
     const int col0 = n0 + wn * 128;        // first column of this wave's quadrant
@@ -241,7 +249,7 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
     for (int i = 0; i < 8; ++i) {
       const int rl = i * 16 + frow;                       // row inside the wave's 128
       const int row = m0 + wm * 128 + rl;
-      const int a_loc = (row < M) ? gs.sampled[row] - col0 : -1;
+      const int a_loc = (row < M && samp[i] >= 0) ? samp[i] - col0 : -1;
       float z[8][4];
       float mx = -INFINITY;
 #pragma unroll
@@ -286,13 +294,22 @@ __device__ __forceinline__ void gemm_tile(unsigned char* lds0, unsigned char* ld
       const float t = c0 * fmaf(d0, sh_part[0][tid][1], sh_part[0][tid][2]) + c1 * fmaf(d1, sh_part[1][tid][1], sh_part[1][tid][2]);
       if (row < M) gs.part[static_cast<int64_t>(row) * gs.tiles_n + n0 / kBN] = f32x4{b, s, t, 0.f};
     }
+    // the rounded logits at the rows' sampled and top-K ids that fall into this tile; ids fetched
+    // four at a time (one memory latency per four entries)
     const int K1 = gs.Ktop + 1;
-    for (int idx = tid; idx < kBM * K1; idx += 256) {
-      const int rl = idx / K1, k = idx - rl * K1, row = m0 + rl;
-      if (row < M) {
-        const int id = (k == 0) ? gs.sampled[row] : gs.tk_ids[static_cast<int64_t>(row) * gs.Ktop + (k - 1)];
-        const int c = id - n0;
-        if (c >= 0 && c < kBN && id < N) {
+    for (int idx0 = tid; idx0 < kBM * K1; idx0 += 4 * 256) {
+      int id[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = idx0 + u * 256, rl = idx / K1, k = idx - rl * K1, row = m0 + rl;
+        id[u] = -1;
+        if (idx < kBM * K1 && row < M) id[u] = (k == 0) ? gs.sampled[row] : gs.tk_ids[static_cast<int64_t>(row) * gs.Ktop + (k - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = idx0 + u * 256, rl = idx / K1, k = idx - rl * K1, row = m0 + rl;
+        const int c = id[u] - n0;
+        if (id[u] >= 0 && c >= 0 && c < kBN && id[u] < N) {
           const unsigned char* src = ((rl >> 7) ? lds1 : lds0) + (rl & 127) * 512 + (((c >> 4) ^ (rl & 15)) << 5) + (c & 15) * 2;
           gs.gath[static_cast<int64_t>(row) * K1 + k] = bf16_bits_to_float(*reinterpret_cast<const uint16_t*>(src));
         }
