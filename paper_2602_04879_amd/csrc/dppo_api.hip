@@ -267,9 +267,11 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     } else {
       // 16-byte vectors need logits and grad rows to share their misalignment.
       const bool vec = !grad || (((lz - lg) & 15u) == 0);
-      // Workgroup size by row length; a few rows in flight per compute unit so that the re-read
-      // of pass 2 still finds the row in cache.
-      const int threads = (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
+      // Workgroup size by row length: few rows in flight per compute unit, so that the re-read of
+      // pass 2 still finds the row in cache.  Forward only there is no second pass, and many short
+      // workgroups are better: one row's epilogue then runs while the others' rows stream
+      // (V = 256000: 5.5 against 4.6 TB/s with 1024 threads).
+      const int threads = !grad ? 256 : (a->V >= 65536) ? 1024 : (a->V >= 8192 ? 512 : 256);
       const int per_cu = 2048 / threads;
       int64_t grid = static_cast<int64_t>(cus) * per_cu;
       if (grid > a->T) grid = a->T;

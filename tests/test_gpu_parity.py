@@ -433,7 +433,12 @@ def test_forward_only_matches_forward_backward_and_runs_are_bitwise_reproducible
     for k in ("loss", "loss_tok", "divergence", "mask"):
         assert torch.equal(r1[k], r2[k]), k                 # same path twice: bit for bit
         assert torch.equal(r1[k], rf[k]), k                 # forward-only == forward of fwd+bwd (same statistics code)
-        assert torch.equal(rs[k], rsf[k]), k                # ... on the two-pass kernel too
+    # the two-pass kernel runs forward-only calls with smaller workgroups (no second pass to keep
+    # the row in cache for): the same sums in another order
+    assert torch.equal(rs["mask"], rsf["mask"])
+    torch.testing.assert_close(rs["divergence"], rsf["divergence"], rtol=1e-4, atol=2e-7)
+    torch.testing.assert_close(rs["loss_tok"], rsf["loss_tok"], rtol=1e-4, atol=2e-7 * b["advantages"].abs().max().item())
+    torch.testing.assert_close(rs["loss"], rsf["loss"], rtol=1e-4, atol=1e-9)
     assert torch.equal(r1["grad_logits"], r2["grad_logits"])
     assert r1["grad_logits"].float().abs().max().item() > 0 and 0 < (r1["mask"] == 0).sum().item() < b["T"]
     # the two kernel paths differ only by summation order
