@@ -200,7 +200,7 @@ def ratio_clip_mask(adv, lpi_a, lmu_a, eps_low, eps_high):
 def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
               mu_topk_ids=None, mu_topk_logp=None, want_grad=True,
               mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=None,
-              mu_logits=None):
+              mu_logits=None, anchor_logp=None):
     """The whole hot path for T rows.
 
     logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
@@ -210,6 +210,11 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     (None or inf: no cap).  The FULL_TV / FULL_KL variants take the trust region on the exact
     divergence between the two next-token distributions (App. B) and need mu_logits [T, V], the
     rollout policy's logits (any shift of a row is immaterial); the ratio still uses mu_logp.
+    anchor_logp [T] (optional): log-prob of a_t under the policy the MASK is anchored to when that
+    is not the rollout policy, i.e. the trainer's recomputed pi_theta' (App. C.1: MiniRL and
+    MiniRL-TIS clip on r' = pi / pi_theta'; Sec. 5.2: the decoupled DPPO, whose divergence and
+    r' <> 1 test are taken against pi_theta').  It replaces mu_logp in the divergence and in the
+    mask; the weight min(r, C) and the loss keep r = pi / mu (Eq. unified_grad).
     Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
     ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None, and the
     diagnostics abs_diff [T] = |pi(a_t) - mu(a_t)|, entropy [T], mass_mu [T], mass_pi [T]
@@ -242,13 +247,14 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         lpi = logpi[a]
         lmu = float(mu_logp[t])
         r = np.exp(lpi - lmu)                        # step 2
-        mass_mu, mass_pi = np.exp(min(lmu, 0.0)), np.exp(lpi)
+        lanc = lmu if anchor_logp is None else float(anchor_logp[t])     # the mask's anchor policy at a_t
+        mass_mu, mass_pi = np.exp(min(lanc, 0.0)), np.exp(lpi)
         if variant == BINARY_TV:                     # step 3
-            D = binary_tv(lmu, lpi)
+            D = binary_tv(lanc, lpi)
         elif variant == BINARY_KL:
             pi_row = np.exp(logpi)
             one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()
-            D = binary_kl(lmu, lpi, one_minus_q)
+            D = binary_kl(lanc, lpi, one_minus_q)
         elif variant in (FULL_TV, FULL_KL):
             logmu = log_softmax(np.asarray(mu_logits[t], dtype=np.float64))
             D = full_tv(np.exp(logmu), np.exp(logpi)) if variant == FULL_TV else full_kl_from_logs(logmu, logpi)
@@ -256,14 +262,14 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         else:
             ids = mu_topk_ids[t] if (mu_topk_ids is not None) else None
             lps = mu_topk_logp[t] if (mu_topk_logp is not None) else None
-            p, q, po, qo = reduced_distributions(logpi, a, lmu, ids, lps)
+            p, q, po, qo = reduced_distributions(logpi, a, lanc, ids, lps)
             D = topk_tv(p, q, po, qo) if variant == TOPK_TV else topk_kl(p, q, po, qo)
             mass_mu, mass_pi = p.sum(), q.sum()
         A = float(advantages[t])
         if mask_rule == MASK_DIVERGENCE:             # step 4
-            M = dppo_mask(D, delta, A, lpi, lmu)
+            M = dppo_mask(D, delta, A, lpi, lanc)
         elif mask_rule == MASK_RATIO_CLIP:
-            M = ratio_clip_mask(A, lpi, lmu, eps_low, eps_high)
+            M = ratio_clip_mask(A, lpi, lanc, eps_low, eps_high)
         elif mask_rule == MASK_NONE:
             M = 1
         else:
@@ -275,7 +281,7 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         out["weight"][t] = w
         out["logp"][t] = lpi
         out["lse"][t] = z[a] - lpi
-        out["abs_diff"][t] = binary_tv(lmu, lpi)
+        out["abs_diff"][t] = binary_tv(lanc, lpi)
         out["entropy"][t] = entropy(logpi)
         out["mass_mu"][t] = mass_mu
         out["mass_pi"][t] = mass_pi

@@ -46,6 +46,7 @@ def oracle_rows(batch: dict, rows, want_grad=True) -> dict:
                        batch["advantages"][sel].cpu().numpy(), batch["delta"], batch["variant"],
                        batch["loss_scale"], tk_i, tk_l, want_grad=want_grad,
                        mu_logits=(batch["mu_logits"][sel][:, :V].float().cpu().numpy() if batch.get("mu_logits") is not None else None),
+                       anchor_logp=(batch["anchor_logp"][sel].cpu().numpy() if batch.get("anchor_logp") is not None else None),
                        **batch.get("rule", {}))
 
 
@@ -60,7 +61,9 @@ def compare_rows(batch: dict, res: dict, rows, check_grad=True, row_offset=0, re
     M = res["mask"][loc].cpu().numpy()
     A = batch["advantages"][torch.as_tensor(rows).to(batch["advantages"].device)].double().cpu().numpy()
     delta = float(np.float32(batch["delta"]))
-    lmu = batch["mu_logp"][torch.as_tensor(rows).to(batch["mu_logp"].device)].double().cpu().numpy()
+    # the policy the mask compares pi(a_t) with: the rollout policy unless the batch names another anchor
+    lsrc = batch["anchor_logp"] if batch.get("anchor_logp") is not None else batch["mu_logp"]
+    lmu = lsrc[torch.as_tensor(rows).to(lsrc.device)].double().cpu().numpy()
 
     with np.errstate(invalid="ignore"):
         errD = np.where(D == ref["divergence"], 0.0, np.abs(D - ref["divergence"]))      # equal infinities agree

@@ -58,6 +58,12 @@ MUTATIONS = [
     ("lm_head: weight gradient contracts the wrong index", 'out["grad_logits"].T @ np.asarray(hidden, dtype=np.float64) if want_grad',
      'out["grad_logits"].T[:, ::-1] @ np.asarray(hidden, dtype=np.float64) if want_grad'),
     ("lm_head: logits not rounded", "return bf16_round(hidden @ weight.T)", "return hidden @ weight.T"),
+    ("anchor ignored by the divergence mask", "M = dppo_mask(D, delta, A, lpi, lanc)", "M = dppo_mask(D, delta, A, lpi, lmu)"),
+    ("anchor ignored by the clip mask", "M = ratio_clip_mask(A, lpi, lanc, eps_low, eps_high)", "M = ratio_clip_mask(A, lpi, lmu, eps_low, eps_high)"),
+    ("anchor ignored by the divergence", "D = binary_tv(lanc, lpi)", "D = binary_tv(lmu, lpi)"),
+    ("anchor ignored by the reduced distributions", "reduced_distributions(logpi, a, lanc, ids, lps)", "reduced_distributions(logpi, a, lmu, ids, lps)"),
+    ("anchor leaks into the importance weight", "        lanc = lmu if anchor_logp is None else float(anchor_logp[t])",
+     "        lanc = lmu if anchor_logp is None else float(anchor_logp[t])\n        r = np.exp(lpi - lanc)\n        dummy = 0"),
     ("binary KL uses clamped-away 1-q", "one_minus_q = pi_row[:a].sum() + pi_row[a + 1:].sum()", "one_minus_q = pi_row[:a].sum()"),
 ]
 

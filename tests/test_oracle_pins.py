@@ -482,6 +482,69 @@ def test_unified_gradient_form_masks_and_cap():
             assert 0 < int((out["mask"] == 0).sum()) < h["T"]
 
 
+def test_mask_anchored_to_a_recomputed_policy_minirl_and_decoupled_dppo():
+    """App. C.1: MiniRL's clip mask is GRPO's with r' = pi / pi_theta' (the trainer's recomputed
+    policy) in place of r = pi / mu, while the weight min(r, C) keeps the rollout ratio; Sec. 5.2:
+    the decoupled DPPO takes divergence and direction test against pi_theta' too.  The anchor's
+    log-prob comes in as one more per-token input."""
+    h = _small_batch(O.BINARY_TV, 0, V=65, shift=3.0, noise=0.5)
+    rng = np.random.default_rng(5)
+    anchor = (h["mu_logp"].astype(np.float64) + rng.normal(0.0, 0.6, h["T"])).astype(np.float32)
+    anchor = np.minimum(anchor, 0.0)
+    base = _run(h)
+    # an anchor equal to the rollout policy changes nothing, under every rule
+    for kw in (dict(), dict(mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28), dict(mask_rule=O.MASK_NONE, ratio_cap=3.0)):
+        a, b = _run(h, **kw), _run(h, anchor_logp=h["mu_logp"], **kw)
+        for k in ("loss_tok", "divergence", "mask", "grad_logits", "ratio", "weight"):
+            np.testing.assert_array_equal(a[k], b[k])
+    # MiniRL / MiniRL-TIS: the GRPO mask evaluated on r', weight and loss on r
+    for C in (None, 3.0):
+        out = _run(h, anchor_logp=anchor, mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, ratio_cap=C)
+        want = [O.ratio_clip_mask(float(a), float(lp), float(la), 0.2, 0.28) for a, lp, la in zip(h["advantages"], out["logp"], anchor)]
+        np.testing.assert_array_equal(out["mask"], want)
+        grpo = _run(h, mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, ratio_cap=C)
+        assert (out["mask"] != grpo["mask"]).any()                           # the anchor matters on this batch
+        np.testing.assert_array_equal(out["ratio"], base["ratio"])           # r stays pi / mu
+        w = out["ratio"] if C is None else np.minimum(out["ratio"], C)
+        np.testing.assert_allclose(out["loss_tok"], -out["mask"].astype(np.float64) * w * h["advantages"], rtol=1e-12)
+        z = torch.tensor(h["logits"], dtype=torch.float64, requires_grad=True)
+        lp = torch.log_softmax(z, -1).gather(1, torch.tensor(h["sampled_ids"], dtype=torch.int64)[:, None]).squeeze(1)
+        coef = torch.tensor(out["mask"] * w * h["advantages"], dtype=torch.float64)
+        (-(coef * lp).sum() * h["loss_scale"]).backward()
+        np.testing.assert_allclose(out["grad_logits"], z.grad.numpy(), rtol=1e-9, atol=1e-15)
+    # r' on either side of the clip range while r sits inside it, and the other way round
+    one = dict(logits=np.log(np.array([[0.5, 0.3, 0.2]])), sampled_ids=np.array([0]), advantages=np.array([1.0]),
+               delta=0.1, variant=O.BINARY_TV, mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28)
+    assert O.dppo_loss(mu_logp=np.log([0.45]), anchor_logp=np.log([0.30]), **one)["mask"][0] == 0    # r = 1.11, r' = 1.67
+    assert O.dppo_loss(mu_logp=np.log([0.30]), anchor_logp=np.log([0.45]), **one)["mask"][0] == 1    # r = 1.67, r' = 1.11
+    assert O.dppo_loss(mu_logp=np.log([0.30]), **one)["mask"][0] == 0                                # GRPO on r
+    # decoupled DPPO: divergence and direction test against the anchor, in closed form (Eq. binary_tv)
+    dec = _run(h, anchor_logp=anchor)
+    lpi = dec["logp"]
+    np.testing.assert_allclose(dec["divergence"], np.abs(np.exp(anchor.astype(np.float64)) - np.exp(lpi)), rtol=1e-12, atol=1e-15)
+    A = h["advantages"].astype(np.float64)
+    blocked = (dec["divergence"] > h["delta"]) & (((A > 0) & (lpi > anchor)) | ((A < 0) & (lpi < anchor)))
+    np.testing.assert_array_equal(dec["mask"], 1 - blocked.astype(np.uint8))
+    np.testing.assert_array_equal(dec["ratio"], base["ratio"])
+    assert (dec["divergence"] != base["divergence"]).any()
+    one_d = dict(one, mask_rule=O.MASK_DIVERGENCE)
+    # pi(a) = 0.5, mu(a) = 0.45: D = 0.05 < delta = 0.1 keeps the token; against pi_theta'(a) = 0.30, D = 0.20 blocks it
+    assert O.dppo_loss(mu_logp=np.log([0.45]), **one_d)["mask"][0] == 1
+    blocked_row = O.dppo_loss(mu_logp=np.log([0.45]), anchor_logp=np.log([0.30]), **one_d)
+    assert blocked_row["mask"][0] == 0 and blocked_row["divergence"][0] == pytest.approx(0.2, rel=1e-12)
+    # the direction test looks at the anchor too: pi(a) = 0.5 is below mu(a) = 0.6 but above pi_theta'(a) = 0.3
+    assert O.dppo_loss(mu_logp=np.log([0.6]), anchor_logp=np.log([0.30]), **one_d)["mask"][0] == 0
+    assert O.dppo_loss(mu_logp=np.log([0.3]), anchor_logp=np.log([0.60]), **one_d)["mask"][0] == 1
+    # Top-K: the anchor takes the sampled token's place in the reduced distributions
+    hk = _small_batch(O.TOPK_KL, 8, V=65, shift=3.0, noise=0.5)
+    anchor_k = np.minimum(hk["mu_logp"] - 0.3, 0.0).astype(np.float32)
+    outk = _run(hk, anchor_logp=anchor_k)
+    for t in range(hk["T"]):
+        p, q, po, qo = O.reduced_distributions(O.log_softmax(hk["logits"][t].astype(np.float64)), int(hk["sampled_ids"][t]),
+                                               float(anchor_k[t]), hk["mu_topk_ids"][t], hk["mu_topk_logp"][t])
+        assert outk["divergence"][t] == pytest.approx(O.topk_kl(p, q, po, qo), rel=1e-12, abs=1e-15)
+
+
 # ------------------------------------------------------------------ exact divergence as the trust region (App. B)
 def test_full_kl_from_logs_is_the_library_relative_entropy():
     for V in (2, 9, 300):
