@@ -239,6 +239,7 @@ def main() -> int:
     ap.add_argument("--eps-low", type=float, default=0.2)
     ap.add_argument("--eps-high", type=float, default=0.28)
     ap.add_argument("--ratio-cap", type=float, default=0.0, help="C of the unified gradient form (0: no cap)")
+    ap.add_argument("--anchor", action="store_true", help="anchor the mask to a recomputed policy (mu_logp plus N(0, 0.3^2) noise): MiniRL with --mask-rule ratio_clip, the decoupled DPPO otherwise")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits (the boundary allows it); the logits are restored, untimed, before every step")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
     ap.add_argument("--static-rows", action="store_true", help="rows fixed by the workgroup index instead of handed out at run time")
@@ -282,6 +283,11 @@ def main() -> int:
     nrot = 1 if (in_place or batch.get("mu_logits") is not None) else max(1, min(128, -(-(4 << 30) // per_step_bytes)))
     copies = [(batch["logits"], grad)] + [(batch["logits"].clone(), torch.empty_like(grad)) for _ in range(nrot - 1)]
 
+    anchor = None
+    if args.anchor:
+        gen = torch.Generator(device=dev).manual_seed(w.seed + 77)
+        anchor = torch.minimum(batch["mu_logp"] + 0.3 * torch.randn(T, generator=gen, device=dev), torch.zeros_like(batch["mu_logp"]))
+
     def make_calls(logits_c, grad_c):
         cs = []
         for c0 in range(0, T, chunk):
@@ -295,7 +301,8 @@ def main() -> int:
                             batch["delta"], batch["variant"], batch["loss_scale"], o,
                             batch["mu_topk_ids"][sl] if K else None, batch["mu_topk_logp"][sl] if K else None,
                             V=V, flags=flags, grad_logits=grad_c[sl],
-                            mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
+                            mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None,
+                            anchor_logp=anchor[sl] if anchor is not None else None, **rule)
             a.ld = batch["ld"]
             cs.append((a, o))
         return cs
@@ -389,9 +396,9 @@ def main() -> int:
                                       "N(0, drift_std^2) after the rollout, so that a few tokens are masked; not part of "
                                       "the configuration string this workload stands for, byte-neutral"},
                    "delta": batch["delta"], "logits_dtype": "bf16", "ld": batch["ld"], "launches_per_step": launches,
-                   "kernel_path": path, "buffer_sets": nrot, "rows": "fixed by workgroup index" if args.static_rows else "library default", "mask_rule": args.mask_rule, "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
+                   "kernel_path": path, "buffer_sets": nrot, "rows": "fixed by workgroup index" if args.static_rows else "library default", "mask_rule": args.mask_rule, "mask_anchor": "recomputed policy (synthetic)" if args.anchor else "rollout policy", "ratio_cap": args.ratio_cap, "diagnostics": args.diagnostics, "grad": "none (forward only)" if args.forward_only else "in place over the logits" if in_place else "separate buffer"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics) else stored_traffic(args.workload, path),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.forward_only or in_place or args.diagnostics or args.anchor) else stored_traffic(args.workload, path),
                      "kernel": DOMINANT_KERNEL.get(path, path), "algorithmic_bytes_per_launch": alg_bytes_launch,
                      "step_ms_per_launch": step_ms_per_launch, "device_ceilings": ceilings,
                      "frac_of_copy_ceiling": (achieved / ceilings["copy_GBs"]) if ceilings else None,

@@ -137,6 +137,16 @@ typedef struct {
                                /* and may be NULL.  Must not overlap grad_logits.  r_t still   */
                                /* uses mu_logp                                                 */
   int64_t        mu_ld;        /* its row pitch in elements, mu_ld >= V                        */
+  const float*   anchor_logp;  /* [T] or NULL.  log-prob of a_t under the policy the MASK is    */
+                               /* anchored to when that is not the rollout policy: the trainer's*/
+                               /* recomputed pi_theta' of the decoupled objectives.  With       */
+                               /* DPPO_MASK_RATIO_CLIP this is MiniRL / MiniRL-TIS (App. C.1:   */
+                               /* the clip on r' = pi / pi_theta'); with the divergence mask the*/
+                               /* decoupled DPPO of Sec. 5.2 (D_t and the r' <> 1 test use it   */
+                               /* where they use mu_logp otherwise; for the Top-K / full-       */
+                               /* vocabulary variants pass that policy's top-K / logits too).   */
+                               /* The weight min(r, C) and the loss keep r = pi / mu.           */
+                               /* NULL: the mask is anchored to the rollout policy (DPPO, GRPO) */
   /* ---- outputs (fully overwritten) ---- */
   float*         loss;         /* [1]                                                          */
   float*         loss_tok;     /* [T] -M_t r_t A_t, unscaled; may be NULL                      */

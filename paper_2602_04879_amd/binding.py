@@ -34,7 +34,7 @@ class DppoArgs(C.Structure):
         ("K", C.c_int32), ("variant", C.c_int32),
         ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
         ("mask_rule", C.c_int32), ("eps_low", C.c_float), ("eps_high", C.c_float), ("ratio_cap", C.c_float),
-        ("mu_logits", C.c_void_p), ("mu_ld", C.c_int64),
+        ("mu_logits", C.c_void_p), ("mu_ld", C.c_int64), ("anchor_logp", C.c_void_p),
         ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
         ("mask", C.c_void_p), ("grad_logits", C.c_void_p), ("diagnostics", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("flags", C.c_uint32),
@@ -126,7 +126,8 @@ def workspace_bytes(T: int, V: int, K: int) -> int:
 
 def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, out,
               mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None,
-              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0, mu_logits=None) -> DppoArgs:
+              mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0, mu_logits=None,
+              anchor_logp=None) -> DppoArgs:
     """Fill a dppo_args_t from torch tensors.  `out` is a dict with loss [1] f32, divergence [T]
     f32, mask [T] u8, workspace (u8), optional loss_tok [T] f32."""
     T, ld = logits.shape[0], (logits.stride(0) if logits.shape[0] > 1 else logits.shape[1])
@@ -140,6 +141,7 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.mask_rule, a.eps_low, a.eps_high = mask_rule, eps_low, eps_high
     a.ratio_cap = 0.0 if ratio_cap is None else ratio_cap
     a.mu_logits = _ptr(mu_logits)
+    a.anchor_logp = _ptr(anchor_logp)
     a.mu_ld = 0 if mu_logits is None else (mu_logits.stride(0) if mu_logits.shape[0] > 1 else mu_logits.shape[1])
     a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])
@@ -315,7 +317,8 @@ def run_batch(batch: dict, backward: bool = True, in_place: bool = False, flags:
     args = make_args(logits, batch["sampled_ids"][sl], batch["mu_logp"][sl], batch["advantages"][sl],
                      batch["delta"], batch["variant"], batch["loss_scale"], out, tk_i, tk_l,
                      V=batch["V"], flags=flags, grad_logits=grad if backward else None,
-                     mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None, **rule)
+                     mu_logits=batch["mu_logits"][sl] if batch.get("mu_logits") is not None else None,
+                     anchor_logp=batch["anchor_logp"][sl] if batch.get("anchor_logp") is not None else None, **rule)
     args.ld = batch["ld"]
     if batch.get("mu_logits") is not None:
         args.mu_ld = batch["mu_logits"].stride(0)
@@ -354,7 +357,7 @@ def run_lmhead(batch: dict, backward: bool = True, chunk_rows: int = 0, out=None
     a = DppoLmheadArgs()
     a.loss = make_args(torch.empty((0, V), dtype=torch.bfloat16, device=dev), batch["sampled_ids"], batch["mu_logp"],
                        batch["advantages"], batch["delta"], batch["variant"], batch["loss_scale"], out,
-                       batch["mu_topk_ids"], batch["mu_topk_logp"], V=V, flags=flags, **rule)
+                       batch["mu_topk_ids"], batch["mu_topk_logp"], V=V, flags=flags, anchor_logp=batch.get("anchor_logp"), **rule)
     a.loss.T, a.loss.logits = T, None
     a.hidden, a.ld_hidden, a.d = h.data_ptr(), h.stride(0), d
     a.weight, a.ld_weight = w.data_ptr(), w.stride(0)

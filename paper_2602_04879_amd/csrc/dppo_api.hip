@@ -124,6 +124,7 @@ dppo::KParams make_kparams(const dppo_args_t* a, bool grad) {
   p.row_counters = nullptr;
   p.row_loss = nullptr;
   p.gath = nullptr;
+  p.anchor_logp = a->anchor_logp;
   p.ld = a->ld;
   p.T = static_cast<int32_t>(a->T);
   p.V = static_cast<int32_t>(a->V);
@@ -408,6 +409,7 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
       c.sampled_ids = a->loss.sampled_ids + r0;
       c.mu_logp = a->loss.mu_logp + r0;
       c.advantages = a->loss.advantages + r0;
+      c.anchor_logp = a->loss.anchor_logp ? a->loss.anchor_logp + r0 : nullptr;
       c.mu_topk_ids = a->loss.mu_topk_ids ? a->loss.mu_topk_ids + r0 * a->loss.K : nullptr;
       c.mu_topk_logp = a->loss.mu_topk_logp ? a->loss.mu_topk_logp + r0 * a->loss.K : nullptr;
       c.loss_tok = a->loss.loss_tok ? a->loss.loss_tok + r0 : nullptr;
@@ -450,6 +452,7 @@ dppo_status_t run_lmhead(const dppo_lmhead_args_t* a, void* stream, bool grad) {
     c.sampled_ids = a->loss.sampled_ids + r0;
     c.mu_logp = a->loss.mu_logp + r0;
     c.advantages = a->loss.advantages + r0;
+    c.anchor_logp = a->loss.anchor_logp ? a->loss.anchor_logp + r0 : nullptr;
     c.mu_topk_ids = a->loss.mu_topk_ids ? a->loss.mu_topk_ids + r0 * a->loss.K : nullptr;
     c.mu_topk_logp = a->loss.mu_topk_logp ? a->loss.mu_topk_logp + r0 * a->loss.K : nullptr;
     c.loss_tok = a->loss.loss_tok ? a->loss.loss_tok + r0 : nullptr;

@@ -42,6 +42,9 @@ struct KParams {
   // Hidden-state path, forward only: there is no logits matrix; the logit of the row's sampled id is
   // gath[row * (K + 1)], that of its top-K entry k is gath[row * (K + 1) + 1 + k].  Else nullptr.
   const float* gath;
+  // [T] log-prob of a_t under the policy the mask is anchored to, where that is not the rollout
+  // policy (App. C.1, MiniRL; Sec. 5.2, decoupled objective), or nullptr: mu_logp.
+  const float* anchor_logp;
 };
 
 // The subset of the kernel arguments the per-row epilogue needs.
@@ -57,6 +60,7 @@ struct EpiParams {
   int32_t mask_rule;
   float eps_low, eps_high, ratio_cap;
   const float* gath;
+  const float* anchor_logp;
 };
 __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   EpiParams e;
@@ -64,6 +68,7 @@ __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   e.V = p.V; e.K = p.K; e.variant = p.variant; e.delta = p.delta; e.loss_scale = p.loss_scale;
   e.mask_rule = p.mask_rule; e.eps_low = p.eps_low; e.eps_high = p.eps_high; e.ratio_cap = p.ratio_cap;
   e.gath = p.gath;
+  e.anchor_logp = p.anchor_logp;
   return e;
 }
 
@@ -369,9 +374,30 @@ __device__ __forceinline__ double one_minus_exp(double t, double exp_t) {
 struct RowScalars {
   int a;        // sampled id (valid: 0 <= a < V)
   float za;     // z[a_t]
-  float lmu;    // log mu(a_t)
+  float lmu;    // log mu(a_t): the importance ratio r = pi / mu
   float adv;    // A_t
+  float lanc;   // log-prob of a_t under the mask's anchor policy (= lmu unless the caller gave one)
 };
+// The three per-row scalars of the epilogue in ONE vector register, for kernels that hold them
+// across a whole row beside a resident row: lane 0 requests log mu(a_t), lane 1 the advantage, lane 2
+// the anchor's log-prob (the rollout policy's again if the caller gave none).  unpack_row_scalars
+// hands them out when the epilogue starts.
+template <typename P>
+__device__ __forceinline__ float load_row_scalars(const P& p, int row, int lane) {
+  const float* src = (lane == 0) ? p.mu_logp : (lane == 1) ? p.adv : (p.anchor_logp ? p.anchor_logp : p.mu_logp);
+  return (lane < 3) ? src[row] : 0.f;
+}
+// The anchor's log-prob of a row's sampled token: the caller's, else the rollout policy's.
+template <typename P>
+__device__ __forceinline__ float anchor_or(const P& p, int row, float lmu) {
+  return p.anchor_logp ? p.anchor_logp[row] : lmu;
+}
+__device__ __forceinline__ void unpack_row_scalars(float packed, RowScalars& rs) {
+  const int v = __float_as_int(packed);
+  rs.lmu = __int_as_float(__builtin_amdgcn_readlane(v, 0));
+  rs.adv = __int_as_float(__builtin_amdgcn_readlane(v, 1));
+  rs.lanc = __int_as_float(__builtin_amdgcn_readlane(v, 2));
+}
 struct TopkLane {   // lane k holds top-K entry k (k < 64); id < 0 marks "no entry"
   int id;
   float lp;     // log mu(id)
@@ -440,9 +466,9 @@ struct RowPre {
   // uniform over the wave
   Exp2Parts ea;        // 2^(z[a_t]*log2e)
   double xa0;          // z[a_t]*log2e
-  double pa;           // mu(a_t) = exp(min(log mu(a_t), 0))
+  double pa;           // p(a_t) = exp(min(log p(a_t), 0)), p the mask's anchor policy (mu unless given)
   double inv_pa_raw;   // exp(-log mu(a_t)), for r = pi(a_t) / mu(a_t)
-  double lmu, lmu_raw; // min(log mu(a_t), 0) and the value as given
+  double lmu, lmu_raw; // min(log p(a_t), 0) and log p(a_t) as given
   double A;            // advantage
   // of this lane's top-K entry (valid: the entry exists and is not a_t)
   bool valid;
@@ -456,10 +482,10 @@ __device__ __forceinline__ RowPre row_pre(RowScalars rs, TopkLane tk, bool topk)
   RowPre q;
   q.xa0 = static_cast<double>(rs.za) * kL;
   q.ea = exp2_parts(q.xa0);
-  q.lmu_raw = static_cast<double>(rs.lmu);
+  q.lmu_raw = static_cast<double>(rs.lanc);
   q.lmu = fmin(q.lmu_raw, 0.0);
   q.pa = exp2_d(q.lmu * kLog2eD);
-  q.inv_pa_raw = exp2_d(-q.lmu_raw * kLog2eD);
+  q.inv_pa_raw = exp2_d(-static_cast<double>(rs.lmu) * kLog2eD);
   q.A = static_cast<double>(rs.adv);
   q.valid = topk && tk.id >= 0;
   q.xk0 = 0.0; q.pk = 0.0; q.lpk = 0.0;

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         if (GRAD) {
           if (wid == 0) {
             RowScalars rs;
-            rs.a = a; rs.za = z_a; rs.lmu = p.mu_logp[row]; rs.adv = p.adv[row];
+            rs.a = a; rs.za = z_a; rs.lmu = p.mu_logp[row]; rs.adv = p.adv[row]; rs.lanc = anchor_or(p, row, rs.lmu);
             TopkLane tk;
             tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
             const RowResult res = row_epilogue_call(ep, row, rs, tk, zrow, bz, S_rest, T_rest, lane, 0.0);   // D = 0: not masked by it
@@ -228,6 +228,7 @@ __global__ __launch_bounds__(THREADS) void dppo_fullvocab_kernel(const KParams p
         rs.a = a;
         rs.za = z_a;
         rs.lmu = p.mu_logp[row];
+        rs.lanc = anchor_or(p, row, rs.lmu);
         rs.adv = p.adv[row];
         TopkLane tk;
         tk.id = -1; tk.lp = 0.f; tk.z = 0.f;

@@ -315,6 +315,7 @@ __global__ __launch_bounds__(kThreads) void dppo_fullvocab_resident_kernel(const
         rs.a = a;
         rs.za = z_a;
         rs.lmu = p.mu_logp[row];
+        rs.lanc = anchor_or(p, row, rs.lmu);
         rs.adv = p.adv[row];
         TopkLane tk;
         tk.id = -1; tk.lp = 0.f; tk.z = 0.f;

@@ -50,6 +50,7 @@ __global__ __launch_bounds__(256) void dppo_lmhead_rows_kernel(const KParams p, 
   rs.a = a;
   rs.za = za;
   rs.lmu = p.mu_logp[row];
+  rs.lanc = anchor_or(p, row, rs.lmu);
   rs.adv = p.adv[row];
   const TopkLane tk = load_topk_lane(p, row, a, nullptr, lane);
   const EpiParams ep = epi_params(p);

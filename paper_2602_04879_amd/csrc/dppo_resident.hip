@@ -161,14 +161,14 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
       RowScalars rs;
       TopkLane tk;
       tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
-      rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f;
+      rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f; rs.lanc = 0.f;
       // (The two gathered logits stay raw bit patterns until the statistics are through: their
       // first use, be it a shift, placed up here would be a wait for every refill in front of them.)
       uint32_t za_bits = 0, tkz_bits = 0;
+      float packed_scalars = 0.f;
       if (wid == 0) {
         za_bits = zrow[a];
-        rs.lmu = p.mu_logp[row];
-        rs.adv = p.adv[row];
+        packed_scalars = load_row_scalars(p, row, lane);      // log mu(a_t), A_t, the anchor's log-prob: one register
         if (tkid >= 0 && tkid < p.V && tkid != a) {
           tk.id = tkid;
           tk.lp = tklp;
@@ -236,7 +236,8 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
         for (int i = 0; i < kPark; ++i) sh_park[i * kWave + lane] = buf[NCHUNK - 1 - i];
       }
       if (wid == 0) {
-        asm volatile("" : "+v"(za_bits), "+v"(rs.lmu), "+v"(rs.adv), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        asm volatile("" : "+v"(za_bits), "+v"(packed_scalars), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        unpack_row_scalars(packed_scalars, rs);
         rs.za = __uint_as_float(za_bits << 16);
         tk.z = __uint_as_float(tkz_bits << 16);
       }

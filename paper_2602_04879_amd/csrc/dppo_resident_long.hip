@@ -179,14 +179,14 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
       RowScalars rs;
       TopkLane tk;
       tk.id = -1; tk.lp = 0.f; tk.z = 0.f;
-      rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f;
+      rs.a = a; rs.za = 0.f; rs.lmu = 0.f; rs.adv = 0.f; rs.lanc = 0.f;
       // Inputs of the epilogue, requested now so that they have arrived when it runs; the two
       // gathered logits stay raw bit patterns until then (see below).
       uint32_t za_bits = 0, tkz_bits = 0;
+      float packed_scalars = 0.f;
       if (wid == 0) {
         za_bits = zrow[a];
-        rs.lmu = p.mu_logp[row];
-        rs.adv = p.adv[row];
+        packed_scalars = load_row_scalars(p, row, lane);      // log mu(a_t), A_t, the anchor's log-prob: one register
         if (tkid >= 0 && tkid < p.V && tkid != a) {
           tk.id = tkid;
           tk.lp = tklp;
@@ -255,7 +255,8 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
         // (the epilogue's inputs are looked at HERE, behind the statistics: moved up to where they
         // were requested, their first use, be it a shift, would be a wait for the whole run of
         // loads in front of them)
-        asm volatile("" : "+v"(za_bits), "+v"(rs.lmu), "+v"(rs.adv), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        asm volatile("" : "+v"(za_bits), "+v"(packed_scalars), "+v"(tkz_bits), "+v"(tk.lp), "+v"(tk.id));
+        unpack_row_scalars(packed_scalars, rs);
         rs.za = __uint_as_float(za_bits << 16);
         tk.z = __uint_as_float(tkz_bits << 16);
         pre = row_pre(rs, tk, p.K > 0);

@@ -89,6 +89,7 @@ __global__ __launch_bounds__(THREADS) void dppo_streaming_kernel(const KParams p
         rs.a = a;
         rs.za = bf16_bits_to_float(zrow[a]);
         rs.lmu = p.mu_logp[row];
+        rs.lanc = anchor_or(p, row, rs.lmu);
         rs.adv = p.adv[row];
         const TopkLane tk = load_topk_lane(p, row, a, zrow, lane);
         const RowResult res = row_epilogue_call(ep, row, rs, tk, zrow, b, S_rest, T_rest, lane);

@@ -76,7 +76,7 @@ WORKLOADS = {
     "c6_qwen3_full_kl": Workload("c6_qwen3_full_kl", 16, 2048, 151936, FULL_KL, 0.05, mu_full=True,
                                  logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
                                  adv="group_norm", group=8, seed=1002),
-    # The headline recipe at the vocabulary of the paper's other model family (Sec. 5, alignment
+    # The headline recipe at the vocabulary of the paper's other model family (Sec. 7, alignment
     # runs on Gemma-2: 256000 entries, rows of 500 KiB), half the rows: the long-row kernel.
     "c8_vocab256k_binary_tv": Workload("c8_vocab256k_binary_tv", 16, 1024, 256000, BINARY_TV, 0.2,
                                        logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,

@@ -293,3 +293,25 @@ def test_rows_handed_out_at_run_time_match_rows_fixed_by_index(variant, delta):
     st = P.compare_rows(b, runs[0], rows)
     assert 0 < (runs[0]["mask"] == 0).sum().item() < T
     _say(f"       {st}")
+
+
+@pytest.mark.parametrize("variant,delta", FULL)
+@pytest.mark.parametrize("V", [4096, 151936])
+def test_mask_anchored_to_a_recomputed_policy(variant, delta, V):
+    """anchor_logp with the exact divergences (both kernels): the direction test of the mask looks at
+    the anchor (the divergence is that of the two rows given, whichever policy the second one is)."""
+    w = W.Workload("full_anchor", 2, 20, V, variant, delta, mu_full=True, logit_std=3.0, noise_std=1.0, adv="normal", seed=101)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    g = torch.Generator(device="cpu").manual_seed(9)
+    b["anchor_logp"] = torch.minimum(b["mu_logp"] + torch.randn(b["T"], generator=g).to(DEV) * 1.5, torch.zeros_like(b["mu_logp"]))
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == ("fullvocab_resident" if V > 100000 else "fullvocab")
+    st = P.compare_rows(b, res, rows, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    res0 = B.run_batch(dict(b, anchor_logp=None))
+    torch.cuda.synchronize()
+    assert (res0["mask"] != res["mask"]).any()
+    _say(f"       {st}")

@@ -34,7 +34,8 @@ def _oracle(b, rows, **rule):
     tk_l = b["mu_topk_logp"][sel].cpu().numpy() if b["mu_topk_logp"] is not None else None
     return O.lmhead_dppo_loss(b["hidden"][sel].float().cpu().numpy(), b["weight"].float().cpu().numpy(),
                               b["sampled_ids"][sel].cpu().numpy(), b["mu_logp"][sel].cpu().numpy(),
-                              b["advantages"][sel].cpu().numpy(), b["delta"], b["variant"], b["loss_scale"], tk_i, tk_l, **rule)
+                              b["advantages"][sel].cpu().numpy(), b["delta"], b["variant"], b["loss_scale"], tk_i, tk_l,
+                              anchor_logp=(b["anchor_logp"][sel].cpu().numpy() if b.get("anchor_logp") is not None else None), **rule)
 
 
 def _check_grad_hidden(b, res, rows, ref, skip=None):
@@ -498,3 +499,28 @@ def test_empty_batch_and_single_token():
     torch.cuda.synchronize()
     assert res["loss"].item() == 0.0
     _run_and_compare(w, 64, shift=1.0, backward=False)
+
+
+def test_mask_anchored_to_a_recomputed_policy_on_the_hidden_state_path():
+    """anchor_logp on both forms of the hidden-state path (through a chunk of logits with the
+    gradients, and forward only from tile statistics): MiniRL-TIS (App. C.1)."""
+    w = W.Workload("lm_anchor", 2, 150, 4160, W.BINARY_KL, 0.05, logit_std=3.0, noise_std=1.0, adv="normal", seed=99)
+    b = W.make_lmhead_batch(w, 128, DEV, exact=True, shift_sampled=2.0)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    b["anchor_logp"] = torch.minimum(b["mu_logp"] + torch.randn(b["T"], generator=g).to(DEV) * 0.5, torch.zeros_like(b["mu_logp"]))
+    rule = dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, ratio_cap=3.0)
+    b["rule"] = rule
+    rows = np.arange(b["T"])
+    ref = _oracle(b, rows, **rule)
+    for backward in (True, False):
+        res = B.run_lmhead(b, backward=backward, chunk_rows=64, diagnostics=True, **rule)
+        torch.cuda.synchronize()
+        st = P.compare_rows(dict(b, logits=None), res, rows, check_grad=False, ref=ref)
+        P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+        if backward:
+            _check_grad_hidden(b, res, rows, ref)
+        assert 0 < st["masked"] < b["T"]
+    plain = dict(b, anchor_logp=None)
+    res0 = B.run_lmhead(plain, backward=False, chunk_rows=64, **rule)
+    torch.cuda.synchronize()
+    assert (res0["mask"] != res["mask"]).any()

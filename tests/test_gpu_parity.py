@@ -291,6 +291,47 @@ def test_mask_rules_and_ratio_cap(rule, V, flags):
         assert (r > rule["ratio_cap"]).any()           # the cap bites on some tokens
 
 
+@pytest.mark.parametrize("V,path", [(4096, "resident"), (4090, "streaming"), (16384, "resident"), (151936, "resident"), (200000, "resident_long")])
+@pytest.mark.parametrize("variant,K,rule", [
+    (W.BINARY_TV, 0, dict()),                                                           # decoupled DPPO (Sec. 5.2)
+    (W.TOPK_KL, 20, dict()),
+    (W.BINARY_KL, 0, dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28)),      # MiniRL (App. C.1)
+    (W.BINARY_TV, 0, dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, ratio_cap=3.0)),   # MiniRL-TIS
+])
+def test_mask_anchored_to_a_recomputed_policy(V, path, variant, K, rule):
+    """anchor_logp: the mask (and the divergence it gates on) compares pi with the trainer's
+    recomputed policy instead of the rollout policy; weight and loss keep r = pi / mu."""
+    w = W.Workload("anchor", 3, 30, V, variant, 0.05 if variant in (W.BINARY_KL, W.TOPK_KL) else 0.2, K=K,
+                   logit_std=3.0, noise_std=1.0, adv="normal", seed=97)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    noise = torch.randn(b["T"], generator=g).to(DEV) * 0.5
+    b["anchor_logp"] = torch.minimum(b["mu_logp"] + noise, torch.zeros_like(b["mu_logp"]))
+    b["rule"] = rule
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, diagnostics=True, **rule)
+    torch.cuda.synchronize()
+    assert B.last_path() == path
+    st = P.compare_rows(b, res, rows, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    # the anchor matters on this batch: without it masks or divergences differ
+    plain = dict(b)
+    plain["anchor_logp"] = None
+    res0 = B.run_batch(plain, **rule)
+    torch.cuda.synchronize()
+    assert (res0["mask"] != res["mask"]).any() or (res0["divergence"] != res["divergence"]).any()
+    # ... and an anchor equal to the rollout policy is the same as none, bit for bit
+    same = dict(b)
+    same["anchor_logp"] = b["mu_logp"].clone()
+    res1 = B.run_batch(same, **rule)
+    torch.cuda.synchronize()
+    for k in ("loss", "loss_tok", "divergence", "mask", "grad_logits"):
+        assert torch.equal(res0[k], res1[k]), k
+    assert 0 < st["masked"] < b["T"]
+    _say(f"       {st}")
+
+
 # --------------------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("V,ld", [(1, 1), (1, 8), (2, 2), (7, 7), (8, 8), (9, 11), (63, 63), (1001, 1001),
                                   (1000, 1003), (4097, 4100), (32768 + 5, 32768 + 8)])
