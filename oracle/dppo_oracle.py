@@ -60,6 +60,7 @@ import numpy as np
 
 BINARY_TV, BINARY_KL, TOPK_TV, TOPK_KL, FULL_TV, FULL_KL = 0, 1, 2, 3, 4, 5
 MASK_DIVERGENCE, MASK_RATIO_CLIP, MASK_NONE = 0, 1, 2
+RELAX_HIGH, RELAX_LOW = 1, 2      # which clip threshold goes to infinity for low-probability tokens (Sec. 6)
 VARIANT_NAMES = {BINARY_TV: "binary_tv", BINARY_KL: "binary_kl",
                  TOPK_TV: "topk_tv", TOPK_KL: "topk_kl",
                  FULL_TV: "full_tv", FULL_KL: "full_kl"}
@@ -191,7 +192,10 @@ def ratio_clip_mask(adv, lpi_a, lmu_a, eps_low, eps_high):
     """PPO / GRPO(-ClipHigher) mask of App. C.1 and App. E: 0 iff (A > 0 and r > 1 + eps_high) or
     (A < 0 and r < 1 - eps_low), 1 otherwise; r compared in the log domain."""
     d = lpi_a - lmu_a
-    if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):
+    # an infinite eps_high never blocks; eps_low >= 1 puts the lower bound at or below 0, which no ratio undercuts
+    hi = np.log1p(eps_high)
+    lo = np.log1p(-eps_low) if eps_low < 1.0 else -np.inf
+    if (adv > 0.0 and d > hi) or (adv < 0.0 and d < lo):
         return 0
     return 1
 
@@ -200,7 +204,7 @@ def ratio_clip_mask(adv, lpi_a, lmu_a, eps_low, eps_high):
 def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale=1.0,
               mu_topk_ids=None, mu_topk_logp=None, want_grad=True,
               mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=None,
-              mu_logits=None, anchor_logp=None):
+              mu_logits=None, anchor_logp=None, relax_alpha=0.0, relax_sides=0):
     """The whole hot path for T rows.
 
     logits [T, V] (any float dtype; widened to float64), sampled_ids [T] int,
@@ -215,6 +219,9 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     MiniRL-TIS clip on r' = pi / pi_theta'; Sec. 5.2: the decoupled DPPO, whose divergence and
     r' <> 1 test are taken against pi_theta').  It replaces mu_logp in the divergence and in the
     mask; the weight min(r, C) and the loss keep r = pi / mu (Eq. unified_grad).
+    relax_alpha, relax_sides (ratio-clip mask only; Sec. 6): for tokens the ROLLOUT policy gave a
+    probability below alpha, the upper clip threshold (RELAX_HIGH), the lower one (RELAX_LOW) or both
+    are set to infinity.  mu(a_t) < alpha is evaluated as log mu(a_t) < log alpha.
     Returns a dict: loss (float), loss_tok [T], divergence [T], mask [T] uint8,
     ratio [T], logp [T] (log pi(a_t)), lse [T], grad_logits [T, V] float64 or None, and the
     diagnostics abs_diff [T] = |pi(a_t) - mu(a_t)|, entropy [T], mass_mu [T], mass_pi [T]
@@ -269,7 +276,13 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
         if mask_rule == MASK_DIVERGENCE:             # step 4
             M = dppo_mask(D, delta, A, lpi, lanc)
         elif mask_rule == MASK_RATIO_CLIP:
-            M = ratio_clip_mask(A, lpi, lanc, eps_low, eps_high)
+            lo_eps, hi_eps = eps_low, eps_high
+            if relax_alpha > 0.0 and lmu < np.log(float(relax_alpha)):      # a low-probability token (Sec. 6)
+                if relax_sides & RELAX_HIGH:
+                    hi_eps = np.inf
+                if relax_sides & RELAX_LOW:
+                    lo_eps = np.inf
+            M = ratio_clip_mask(A, lpi, lanc, lo_eps, hi_eps)
         elif mask_rule == MASK_NONE:
             M = 1
         else:

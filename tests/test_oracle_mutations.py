@@ -37,10 +37,14 @@ MUTATIONS = [
     ("grad: sign", "(loss_scale * M * A * w) * g", "(-loss_scale * M * A * w) * g"),
     ("cap: max instead of min", "min(r, float(ratio_cap))", "max(r, float(ratio_cap))"),
     ("cap ignored in the gradient", "(loss_scale * M * A * w) * g", "(loss_scale * M * A * r) * g"),
-    ("clip mask: eps_low and eps_high swapped", "if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):",
-     "if (adv > 0.0 and d > np.log1p(eps_low)) or (adv < 0.0 and d < np.log1p(-eps_high)):"),
-    ("clip mask: symmetric in the advantage", "if (adv > 0.0 and d > np.log1p(eps_high)) or (adv < 0.0 and d < np.log1p(-eps_low)):",
-     "if d > np.log1p(eps_high) or d < np.log1p(-eps_low):"),
+    ("clip mask: eps_low and eps_high swapped", "    hi = np.log1p(eps_high)\n    lo = np.log1p(-eps_low) if eps_low < 1.0 else -np.inf",
+     "    hi = np.log1p(eps_low)\n    lo = np.log1p(-eps_high) if eps_high < 1.0 else -np.inf"),
+    ("clip mask: symmetric in the advantage", "if (adv > 0.0 and d > hi) or (adv < 0.0 and d < lo):", "if d > hi or d < lo:"),
+    ("relaxation: sides swapped", "                if relax_sides & RELAX_HIGH:\n                    hi_eps = np.inf\n                if relax_sides & RELAX_LOW:\n                    lo_eps = np.inf",
+     "                if relax_sides & RELAX_LOW:\n                    hi_eps = np.inf\n                if relax_sides & RELAX_HIGH:\n                    lo_eps = np.inf"),
+    ("relaxation: applied to the likely tokens", "if relax_alpha > 0.0 and lmu < np.log(float(relax_alpha)):", "if relax_alpha > 0.0 and lmu > np.log(float(relax_alpha)):"),
+    ("relaxation: keyed on the trainer's probability", "if relax_alpha > 0.0 and lmu < np.log(float(relax_alpha)):", "if relax_alpha > 0.0 and lpi < np.log(float(relax_alpha)):"),
+    ("relaxation: applied to every token", "if relax_alpha > 0.0 and lmu < np.log(float(relax_alpha)):", "if relax_alpha > 0.0:"),
     ("mask rule none still masks", "            M = 1\n", "            M = dppo_mask(D, delta, A, lpi, lmu)\n"),
     ("entropy sign", "return float(-(pi[nz] * logpi[nz]).sum())", "return float((pi[nz] * logpi[nz]).sum())"),
     ("covered mass of pi uses mu", "mass_mu, mass_pi = p.sum(), q.sum()", "mass_mu, mass_pi = p.sum(), p.sum()"),
@@ -59,7 +63,7 @@ MUTATIONS = [
      'out["grad_logits"].T[:, ::-1] @ np.asarray(hidden, dtype=np.float64) if want_grad'),
     ("lm_head: logits not rounded", "return bf16_round(hidden @ weight.T)", "return hidden @ weight.T"),
     ("anchor ignored by the divergence mask", "M = dppo_mask(D, delta, A, lpi, lanc)", "M = dppo_mask(D, delta, A, lpi, lmu)"),
-    ("anchor ignored by the clip mask", "M = ratio_clip_mask(A, lpi, lanc, eps_low, eps_high)", "M = ratio_clip_mask(A, lpi, lmu, eps_low, eps_high)"),
+    ("anchor ignored by the clip mask", "M = ratio_clip_mask(A, lpi, lanc, lo_eps, hi_eps)", "M = ratio_clip_mask(A, lpi, lmu, lo_eps, hi_eps)"),
     ("anchor ignored by the divergence", "D = binary_tv(lanc, lpi)", "D = binary_tv(lmu, lpi)"),
     ("anchor ignored by the reduced distributions", "reduced_distributions(logpi, a, lanc, ids, lps)", "reduced_distributions(logpi, a, lmu, ids, lps)"),
     ("anchor leaks into the importance weight", "        lanc = lmu if anchor_logp is None else float(anchor_logp[t])",

@@ -545,6 +545,39 @@ def test_mask_anchored_to_a_recomputed_policy_minirl_and_decoupled_dppo():
         assert outk["divergence"][t] == pytest.approx(O.topk_kl(p, q, po, qo), rel=1e-12, abs=1e-15)
 
 
+def test_clip_relaxed_for_low_probability_tokens():
+    """Sec. 6: the clip threshold goes to infinity, on the upper side (Relax-high), the lower side
+    (Relax-low) or both, for tokens whose ROLLOUT probability is below alpha; all others keep
+    GRPO's range.  Truth table over sign(A) x r outside / inside the range x mu(a) below / above alpha."""
+    eps_low, eps_high, alpha = 0.2, 0.28, 0.1
+    for sides in (0, O.RELAX_HIGH, O.RELAX_LOW, O.RELAX_HIGH | O.RELAX_LOW):
+        for mu_a in (0.02, 0.0999, 0.1001, 0.5):
+            for r in (0.5, 0.79, 1.0, 1.29, 4.0):
+                pi_a = mu_a * r
+                if pi_a >= 1.0:
+                    continue
+                for adv in (-1.0, 0.0, 1.0):
+                    z = np.log(np.array([[pi_a, (1 - pi_a) * 0.6, (1 - pi_a) * 0.4]]))
+                    out = O.dppo_loss(z, np.array([0]), np.log([mu_a]), np.array([adv]), 0.1, O.BINARY_TV, mask_rule=O.MASK_RATIO_CLIP,
+                                      eps_low=eps_low, eps_high=eps_high, relax_alpha=alpha, relax_sides=sides)
+                    low = mu_a < alpha
+                    hi_blocks = adv > 0 and r > 1 + eps_high and not (low and sides & O.RELAX_HIGH)
+                    lo_blocks = adv < 0 and r < 1 - eps_low and not (low and sides & O.RELAX_LOW)
+                    assert out["mask"][0] == (0 if (hi_blocks or lo_blocks) else 1), (sides, mu_a, r, adv)
+                    assert out["ratio"][0] == pytest.approx(r, rel=1e-12)
+    # alpha = 0 (GRPO) and "no side" are the plain clip mask; both sides with alpha = 1 is no mask at all
+    h = _small_batch(O.BINARY_TV, 0, V=65, shift=3.0, noise=0.5)
+    clip = dict(mask_rule=O.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28)
+    grpo = _run(h, **clip)
+    np.testing.assert_array_equal(_run(h, relax_alpha=0.0, relax_sides=3, **clip)["mask"], grpo["mask"])
+    np.testing.assert_array_equal(_run(h, relax_alpha=0.5, relax_sides=0, **clip)["mask"], grpo["mask"])
+    assert np.all(_run(h, relax_alpha=1.0, relax_sides=3, **clip)["mask"][np.exp(h["mu_logp"]) < 1.0] == 1)
+    both = _run(h, relax_alpha=0.3, relax_sides=3, **clip)
+    assert (both["mask"] != grpo["mask"]).any() and np.all(both["mask"] >= grpo["mask"])      # relaxing only ever unmasks
+    # the DPPO mask ignores the relaxation
+    np.testing.assert_array_equal(_run(h, relax_alpha=0.5, relax_sides=3)["mask"], _run(h)["mask"])
+
+
 # ------------------------------------------------------------------ exact divergence as the trust region (App. B)
 def test_full_kl_from_logs_is_the_library_relative_entropy():
     for V in (2, 9, 300):
