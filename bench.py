@@ -239,6 +239,8 @@ def main() -> int:
     ap.add_argument("--eps-low", type=float, default=0.2)
     ap.add_argument("--eps-high", type=float, default=0.28)
     ap.add_argument("--ratio-cap", type=float, default=0.0, help="C of the unified gradient form (0: no cap)")
+    ap.add_argument("--relax-alpha", type=float, default=0.0, help="with --mask-rule ratio_clip: rollout probability below which the clip is relaxed (Sec. 6)")
+    ap.add_argument("--relax-sides", type=int, default=3, help="1: upper threshold, 2: lower, 3: both")
     ap.add_argument("--anchor", action="store_true", help="anchor the mask to a recomputed policy (mu_logp plus N(0, 0.3^2) noise): MiniRL with --mask-rule ratio_clip, the decoupled DPPO otherwise")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits (the boundary allows it); the logits are restored, untimed, before every step")
     ap.add_argument("--force-streaming", action="store_true", help="time the general two-pass kernel")
@@ -276,7 +278,8 @@ def main() -> int:
     grad = batch["logits"] if in_place else torch.empty_like(batch["logits"])
     out = B.alloc_outputs(T, dev, want_diagnostics=args.diagnostics)
     rule = {"mask_rule": {"dppo": B.MASK_DIVERGENCE, "ratio_clip": B.MASK_RATIO_CLIP, "none": B.MASK_NONE}[args.mask_rule],
-            "eps_low": args.eps_low, "eps_high": args.eps_high, "ratio_cap": args.ratio_cap}
+            "eps_low": args.eps_low, "eps_high": args.eps_high, "ratio_cap": args.ratio_cap,
+            "relax_alpha": args.relax_alpha, "relax_sides": args.relax_sides if args.relax_alpha > 0 else 0}
     # A small working set would otherwise be served by the 256 MB Infinity Cache step after step:
     # consecutive steps then rotate among enough copies of (logits, gradient) to make 4 GiB.
     per_step_bytes = 2 * batch["logits"].numel() * 2

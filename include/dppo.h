@@ -93,8 +93,13 @@ typedef enum {
   DPPO_ERR_WORKSPACE = 6,         /* workspace NULL or smaller than dppo_workspace_bytes()     */
   DPPO_ERR_LAUNCH = 7,            /* the HIP runtime refused a launch (see hipGetLastError)    */
   DPPO_ERR_VALUE = 8              /* delta, loss_scale, eps_* or ratio_cap is NaN, eps_low not */
-                                  /* in [0, 1), eps_high < 0, or mask_rule unknown             */
+                                  /* in [0, 1), eps_high < 0, relax_alpha outside [0, 1],      */
+                                  /* relax_sides or mask_rule unknown                          */
 } dppo_status_t;
+
+/* relax_sides */
+#define DPPO_RELAX_HIGH 1u           /* eps_high = infinity for low-probability tokens          */
+#define DPPO_RELAX_LOW 2u            /* eps_low = infinity (no lower bound) for them             */
 
 /* flags */
 #define DPPO_FLAG_FORCE_STREAMING 1u /* use the general kernels even where a register-resident
@@ -131,6 +136,11 @@ typedef struct {
   float          ratio_cap;    /* C of Eq. unified_grad: the gradient weight is M min(r, C) A  */
                                /* (held constant) and the loss term -M min(r, C) A.            */
                                /* <= 0 or +inf: no cap (C = infinity, as DPPO uses)            */
+  float          relax_alpha;  /* DPPO_MASK_RATIO_CLIP only (Sec. 6): for tokens whose ROLLOUT  */
+                               /* probability mu(a_t) is below alpha the clip thresholds named */
+                               /* by relax_sides are infinite.  0: none (GRPO); in [0, 1].     */
+                               /* "mu(a_t) < alpha" is evaluated as log mu(a_t) < log alpha     */
+  uint32_t       relax_sides;  /* DPPO_RELAX_HIGH | DPPO_RELAX_LOW: Relax-high, Relax-low, both */
   const void*    mu_logits;    /* bf16 [T, mu_ld]: the rollout policy's logits over the same   */
                                /* vocabulary (log-probs are logits too; any per-row shift is   */
                                /* immaterial).  DPPO_FULL_TV / DPPO_FULL_KL only, else ignored */

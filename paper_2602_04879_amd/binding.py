@@ -18,6 +18,7 @@ NDIAG = 8
 DIAG_RATIO, DIAG_LOGP, DIAG_ABS_DIFF, DIAG_ENTROPY, DIAG_MASS_MU, DIAG_MASS_PI = 0, 1, 2, 3, 4, 5
 FLAG_FORCE_STREAMING = 1
 FLAG_STATIC_ROWS = 2
+RELAX_HIGH, RELAX_LOW = 1, 2
 WORKSPACE_BYTES = 65536       # the smallest workspace any call accepts; workspace_bytes(T, V, K) is what a call wants
 
 # DPPO_LIB overrides the library path (e.g. a build with other compile-time settings).
@@ -34,6 +35,7 @@ class DppoArgs(C.Structure):
         ("K", C.c_int32), ("variant", C.c_int32),
         ("advantages", C.c_void_p), ("delta", C.c_float), ("loss_scale", C.c_float),
         ("mask_rule", C.c_int32), ("eps_low", C.c_float), ("eps_high", C.c_float), ("ratio_cap", C.c_float),
+        ("relax_alpha", C.c_float), ("relax_sides", C.c_uint32),
         ("mu_logits", C.c_void_p), ("mu_ld", C.c_int64), ("anchor_logp", C.c_void_p),
         ("loss", C.c_void_p), ("loss_tok", C.c_void_p), ("divergence", C.c_void_p),
         ("mask", C.c_void_p), ("grad_logits", C.c_void_p), ("diagnostics", C.c_void_p),
@@ -127,7 +129,7 @@ def workspace_bytes(T: int, V: int, K: int) -> int:
 def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_scale, out,
               mu_topk_ids=None, mu_topk_logp=None, V=None, flags=0, grad_logits=None,
               mask_rule=MASK_DIVERGENCE, eps_low=0.2, eps_high=0.2, ratio_cap=0.0, mu_logits=None,
-              anchor_logp=None) -> DppoArgs:
+              anchor_logp=None, relax_alpha=0.0, relax_sides=0) -> DppoArgs:
     """Fill a dppo_args_t from torch tensors.  `out` is a dict with loss [1] f32, divergence [T]
     f32, mask [T] u8, workspace (u8), optional loss_tok [T] f32."""
     T, ld = logits.shape[0], (logits.stride(0) if logits.shape[0] > 1 else logits.shape[1])
@@ -142,6 +144,7 @@ def make_args(logits, sampled_ids, mu_logp, advantages, delta, variant, loss_sca
     a.ratio_cap = 0.0 if ratio_cap is None else ratio_cap
     a.mu_logits = _ptr(mu_logits)
     a.anchor_logp = _ptr(anchor_logp)
+    a.relax_alpha, a.relax_sides = relax_alpha, relax_sides
     a.mu_ld = 0 if mu_logits is None else (mu_logits.stride(0) if mu_logits.shape[0] > 1 else mu_logits.shape[1])
     a.loss, a.loss_tok = _ptr(out["loss"]), _ptr(out.get("loss_tok"))
     a.divergence, a.mask = _ptr(out["divergence"]), _ptr(out["mask"])

@@ -1,6 +1,7 @@
 // C ABI of the DPPO loss library: argument checks, kernel-path choice, launches.
 #include <hip/hip_runtime.h>
 #include <cmath>
+#include <limits>
 #include <atomic>
 #include <cstdint>
 #include <mutex>
@@ -85,6 +86,7 @@ dppo_status_t check_args(const dppo_args_t* a, bool grad, bool own_scratch = fal
   if (std::isnan(a->delta) || std::isnan(a->loss_scale) || std::isnan(a->ratio_cap)) return DPPO_ERR_VALUE;
   if (a->mask_rule < DPPO_MASK_DIVERGENCE || a->mask_rule > DPPO_MASK_NONE) return DPPO_ERR_VALUE;
   if (a->mask_rule == DPPO_MASK_RATIO_CLIP && !(a->eps_low >= 0.f && a->eps_low < 1.f && a->eps_high >= 0.f)) return DPPO_ERR_VALUE;
+  if (!(a->relax_alpha >= 0.f && a->relax_alpha <= 1.f) || (a->relax_sides & ~(DPPO_RELAX_HIGH | DPPO_RELAX_LOW))) return DPPO_ERR_VALUE;
   if (!own_scratch) {
     if (!a->workspace || a->workspace_bytes < DPPO_WORKSPACE_BYTES) return DPPO_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(a->workspace) & 7u) return DPPO_ERR_ALIGN;
@@ -125,6 +127,9 @@ dppo::KParams make_kparams(const dppo_args_t* a, bool grad) {
   p.row_loss = nullptr;
   p.gath = nullptr;
   p.anchor_logp = a->anchor_logp;
+  const bool relax = a->mask_rule == DPPO_MASK_RATIO_CLIP && a->relax_alpha > 0.f && a->relax_sides != 0;
+  p.relax_log_alpha = relax ? std::log(static_cast<double>(a->relax_alpha)) : -std::numeric_limits<double>::infinity();
+  p.relax_sides = relax ? static_cast<int32_t>(a->relax_sides) : 0;
   p.ld = a->ld;
   p.T = static_cast<int32_t>(a->T);
   p.V = static_cast<int32_t>(a->V);
@@ -519,7 +524,7 @@ const char* dppo_status_str(dppo_status_t status) {
     case DPPO_ERR_K: return "bad K: need 0 <= K <= DPPO_KMAX and top-K pointers when K > 0";
     case DPPO_ERR_WORKSPACE: return "workspace missing or smaller than dppo_workspace_bytes() (dppo_loss_fwd_bwd_static: the static scratch array has no device address)";
     case DPPO_ERR_LAUNCH: return "HIP kernel launch failed (or the stream does not belong to the current device)";
-    case DPPO_ERR_VALUE: return "bad value: NaN delta / loss_scale / ratio_cap, unknown mask_rule, or clip range outside 0 <= eps_low < 1, eps_high >= 0";
+    case DPPO_ERR_VALUE: return "bad value: NaN delta / loss_scale / ratio_cap, unknown mask_rule, or clip range outside 0 <= eps_low < 1, eps_high >= 0, relax_alpha outside [0, 1] or unknown relax_sides";
   }
   return "unknown status";
 }

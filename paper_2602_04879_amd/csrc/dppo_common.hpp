@@ -45,6 +45,11 @@ struct KParams {
   // [T] log-prob of a_t under the policy the mask is anchored to, where that is not the rollout
   // policy (App. C.1, MiniRL; Sec. 5.2, decoupled objective), or nullptr: mu_logp.
   const float* anchor_logp;
+  // Clip relaxation for low-probability tokens (Sec. 6; ratio-clip mask only): a token is one if
+  // log mu(a_t) < relax_log_alpha (-infinity: none), and then the sides in relax_sides (1: upper,
+  // 2: lower threshold) do not block.
+  double relax_log_alpha;
+  int32_t relax_sides;
 };
 
 // The subset of the kernel arguments the per-row epilogue needs.
@@ -61,6 +66,8 @@ struct EpiParams {
   float eps_low, eps_high, ratio_cap;
   const float* gath;
   const float* anchor_logp;
+  double relax_log_alpha;
+  int32_t relax_sides;
 };
 __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   EpiParams e;
@@ -69,6 +76,8 @@ __device__ __forceinline__ EpiParams epi_params(const KParams& p) {
   e.mask_rule = p.mask_rule; e.eps_low = p.eps_low; e.eps_high = p.eps_high; e.ratio_cap = p.ratio_cap;
   e.gath = p.gath;
   e.anchor_logp = p.anchor_logp;
+  e.relax_log_alpha = p.relax_log_alpha;
+  e.relax_sides = p.relax_sides;
   return e;
 }
 
@@ -470,6 +479,7 @@ struct RowPre {
   double inv_pa_raw;   // exp(-log mu(a_t)), for r = pi(a_t) / mu(a_t)
   double lmu, lmu_raw; // min(log p(a_t), 0) and log p(a_t) as given
   double A;            // advantage
+  bool low;            // a low-probability token of the clip relaxation: log mu(a_t) of the rollout policy < log alpha
   // of this lane's top-K entry (valid: the entry exists and is not a_t)
   bool valid;
   Exp2Parts ek;        // 2^(z[id]*log2e)
@@ -477,7 +487,7 @@ struct RowPre {
   double pk, lpk;      // mu(id) and min(log mu(id), 0)
 };
 
-__device__ __forceinline__ RowPre row_pre(RowScalars rs, TopkLane tk, bool topk) {
+__device__ __forceinline__ RowPre row_pre(RowScalars rs, TopkLane tk, bool topk, double relax_log_alpha) {
   constexpr double kL = static_cast<double>(kLog2e);
   RowPre q;
   q.xa0 = static_cast<double>(rs.za) * kL;
@@ -485,6 +495,7 @@ __device__ __forceinline__ RowPre row_pre(RowScalars rs, TopkLane tk, bool topk)
   q.lmu_raw = static_cast<double>(rs.lanc);
   q.lmu = fmin(q.lmu_raw, 0.0);
   q.pa = exp2_d(q.lmu * kLog2eD);
+  q.low = static_cast<double>(rs.lmu) < relax_log_alpha;
   q.inv_pa_raw = exp2_d(-static_cast<double>(rs.lmu) * kLog2eD);
   q.A = static_cast<double>(rs.adv);
   q.valid = topk && tk.id >= 0;
@@ -582,7 +593,10 @@ __device__ __forceinline__ RowResult row_post(const P& p, int row, const RowPre&
     blocked = (D > static_cast<double>(p.delta)) && ((A > 0.0 && lpi > q.lmu_raw) || (A < 0.0 && lpi < q.lmu_raw));
   } else if (p.mask_rule == 1) {
     const double dl = lpi - q.lmu_raw;     // log r, compared with log(1 + eps_high) and log(1 - eps_low)
-    blocked = (A > 0.0 && dl > log1p(static_cast<double>(p.eps_high))) || (A < 0.0 && dl < log1p(-static_cast<double>(p.eps_low)));
+    // Sec. 6: for tokens the rollout policy gave less than alpha, the named thresholds are infinite
+    const bool hi_on = !(q.low && (p.relax_sides & 1)), lo_on = !(q.low && (p.relax_sides & 2));
+    blocked = (A > 0.0 && hi_on && dl > log1p(static_cast<double>(p.eps_high))) ||
+              (A < 0.0 && lo_on && dl < log1p(-static_cast<double>(p.eps_low)));
   } else {
     blocked = false;
   }
@@ -636,7 +650,7 @@ __device__ __forceinline__ RowResult row_epilogue(const EpiParams& p, int row, R
                                                   const uint16_t* zrow, float b, double S_rest, double T_rest, int lane,
                                                   double D_full = 0.0) {
   const bool topk = (p.variant == kTopkTV || p.variant == kTopkKL) && p.K > 0;
-  const RowPre q = row_pre(rs, tk, topk);
+  const RowPre q = row_pre(rs, tk, topk, p.relax_log_alpha);
   RowOut o;
   const RowResult res = row_post(p, row, q, rs.a, zrow, b, S_rest, T_rest, lane, D_full, o);
   row_store(p, row, o, lane);

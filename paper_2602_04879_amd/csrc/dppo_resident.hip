@@ -241,10 +241,10 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
         rs.za = __uint_as_float(za_bits << 16);
         tk.z = __uint_as_float(tkz_bits << 16);
       }
-      if (GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
+      if (GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0, p.relax_log_alpha);
       if (DYN && tid == 0) publish_row_after_next();
       __syncthreads();
-      if (!GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0);
+      if (!GRAD && kInlineEpilogue && wid == 0) pre = row_pre(rs, tk, p.K > 0, p.relax_log_alpha);
       if (DYN) next2 = uniform_i(sh_row[par]);
       // ---- epilogue on wave 0 -----------------------------------------------------------
       RowOut ro;

@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kLThreads, 2) void dppo_resident_long_kernel(const 
         unpack_row_scalars(packed_scalars, rs);
         rs.za = __uint_as_float(za_bits << 16);
         tk.z = __uint_as_float(tkz_bits << 16);
-        pre = row_pre(rs, tk, p.K > 0);
+        pre = row_pre(rs, tk, p.K > 0, p.relax_log_alpha);
       }
       if (DYN && tid == 0) publish_row_after_next();
       __syncthreads();

@@ -332,6 +332,30 @@ def test_mask_anchored_to_a_recomputed_policy(V, path, variant, K, rule):
     _say(f"       {st}")
 
 
+@pytest.mark.parametrize("V,path", [(4096, "resident"), (4090, "streaming"), (32768, "resident"), (151936, "resident"), (200000, "resident_long")])
+@pytest.mark.parametrize("sides", [B.RELAX_HIGH, B.RELAX_LOW, B.RELAX_HIGH | B.RELAX_LOW])
+def test_clip_relaxed_for_low_probability_tokens(V, path, sides):
+    """Sec. 6: the ratio-clip mask with its upper, lower or both thresholds infinite for tokens whose
+    rollout probability is below alpha (Relax-high / Relax-low / Relax-both)."""
+    w = W.Workload("relax", 3, 40, V, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=103)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    rule = dict(mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28, relax_alpha=0.1, relax_sides=sides)
+    b["rule"] = rule
+    rows = np.arange(b["T"])
+    ref = P.oracle_rows(b, rows)
+    res = B.run_batch(b, diagnostics=True, **rule)
+    torch.cuda.synchronize()
+    assert B.last_path() == path
+    st = P.compare_rows(b, res, rows, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    grpo = B.run_batch(b, mask_rule=B.MASK_RATIO_CLIP, eps_low=0.2, eps_high=0.28)
+    torch.cuda.synchronize()
+    assert torch.all(res["mask"] >= grpo["mask"])                                  # relaxing only ever unmasks
+    if sides == (B.RELAX_HIGH | B.RELAX_LOW):
+        assert (res["mask"] != grpo["mask"]).any()
+    _say(f"       {st}")
+
+
 # --------------------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("V,ld", [(1, 1), (1, 8), (2, 2), (7, 7), (8, 8), (9, 11), (63, 63), (1001, 1001),
                                   (1000, 1003), (4097, 4100), (32768 + 5, 32768 + 8)])

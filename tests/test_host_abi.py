@@ -79,6 +79,10 @@ def _valid_args():
     (lambda a: setattr(a, "mask_rule", -1), 8),
     (lambda a: (setattr(a, "mask_rule", B.MASK_RATIO_CLIP), setattr(a, "eps_low", 1.0), setattr(a, "eps_high", 0.2)), 8),
     (lambda a: (setattr(a, "mask_rule", B.MASK_RATIO_CLIP), setattr(a, "eps_low", 0.2), setattr(a, "eps_high", -0.1)), 8),
+    (lambda a: setattr(a, "relax_alpha", 1.5), 8),
+    (lambda a: setattr(a, "relax_alpha", -0.1), 8),
+    (lambda a: setattr(a, "relax_alpha", float("nan")), 8),
+    (lambda a: setattr(a, "relax_sides", 4), 8),
     (lambda a: setattr(a, "diagnostics", 0x5008), 3),
 ])
 def test_argument_validation_codes(mutate, code):
