@@ -38,7 +38,8 @@ class _DppoLoss(torch.autograd.Function):
                            mu_topk_ids, mu_topk_logp, grad_logits=grad, mu_logits=mu_logits,
                            mask_rule=opts.get("mask_rule", B.MASK_DIVERGENCE), eps_low=opts.get("eps_low", 0.2),
                            eps_high=opts.get("eps_high", 0.2), ratio_cap=opts.get("ratio_cap", 0.0), flags=opts.get("flags", 0),
-                           anchor_logp=opts.get("anchor_logp"))
+                           anchor_logp=opts.get("anchor_logp"), relax_alpha=opts.get("relax_alpha", 0.0),
+                           relax_sides=opts.get("relax_sides", 0))
         (B.dppo_loss_fwd_bwd if need_grad else B.dppo_loss_fwd)(args)
         ctx.grad_logits = grad
         side = [out[k] for k in ("divergence", "mask", "loss_tok")] + ([out["diagnostics"]] if out["diagnostics"] is not None else [])
@@ -67,7 +68,8 @@ def dppo_loss(logits, sampled_ids, mu_logp, advantages, *, delta, variant=B.BINA
     """loss (a 0-d fp32 tensor with a gradient path to `logits`) and a dict of the per-token
     outputs.  Keyword options: mask_rule, eps_low, eps_high, ratio_cap (the baselines of the
     unified gradient form), anchor_logp (the mask anchored to a recomputed policy: MiniRL, the
-    decoupled objective), diagnostics, in_place, flags."""
+    decoupled objective), relax_alpha / relax_sides (the clip relaxed for low-probability tokens),
+    diagnostics, in_place, flags."""
     opts = dict(opts, delta=float(delta), variant=int(variant), loss_scale=float(loss_scale))
     res = _DppoLoss.apply(logits, sampled_ids, mu_logp, advantages, mu_topk_ids, mu_topk_logp, mu_logits, opts)
     aux = {"divergence": res[1], "mask": res[2], "loss_tok": res[3]}
@@ -91,7 +93,7 @@ class _DppoLmheadLoss(torch.autograd.Function):
                  "advantages": advantages, "delta": opts["delta"], "variant": opts["variant"], "loss_scale": opts["loss_scale"],
                  "mu_topk_ids": mu_topk_ids, "mu_topk_logp": mu_topk_logp, "anchor_logp": opts.get("anchor_logp")}
         gw = torch.empty((V, d), dtype=torch.float32, device=hidden.device) if need_w else None
-        rule = {k: opts[k] for k in ("mask_rule", "eps_low", "eps_high", "ratio_cap") if k in opts}
+        rule = {k: opts[k] for k in ("mask_rule", "eps_low", "eps_high", "ratio_cap", "relax_alpha", "relax_sides") if k in opts}
         res = B.run_lmhead(batch, backward=backward, chunk_rows=opts.get("chunk_rows", 0), diagnostics=opts.get("diagnostics", False),
                            grad_weight=gw, flags=opts.get("flags", 0), **rule)
         ctx.grads = (res["grad_hidden"] if need_h else None, gw)
