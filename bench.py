@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c3_qwen3_binary_tv"
-DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "resident_long": "dppo_resident_long_kernel", "streaming": "dppo_streaming_kernel",
+DOMINANT_KERNEL = {"resident": "dppo_resident_kernel", "resident_long": "dppo_resident_long_kernel", "resident_multi": "dppo_resident_multi_kernel",
+                   "streaming": "dppo_streaming_kernel",
                    "fullvocab": "dppo_fullvocab_kernel", "fullvocab_resident": "dppo_fullvocab_resident_kernel"}
 
 

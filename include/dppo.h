@@ -105,7 +105,8 @@ typedef enum {
 #define DPPO_FLAG_FORCE_STREAMING 1u /* use the general kernels even where a register-resident
                                         one applies (testing / comparison)                     */
 #define DPPO_FLAG_STATIC_ROWS 2u     /* never hand rows out at run time: every workgroup takes the
-                                        rows its index fixes (testing / comparison)            */
+                                        rows its index fixes, one row at a time (testing /
+                                        comparison)                                            */
 
 typedef struct {
   /* ---- inputs ---- */
@@ -224,7 +225,9 @@ size_t dppo_args_size(void);
 
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
  * "resident" (row held in registers between the two passes), "resident_long" (rows of 155657 ..
- * 262144 entries with the gradient: registers, LDS and a short tail read twice), "streaming" (row re-read),
+ * 262144 entries with the gradient: registers, LDS and a short tail read twice), "resident_multi"
+ * (rows of 24584 .. 65536 entries with the gradient, many of them per call: groups of two to four
+ * rows held in registers), "streaming" (row re-read),
  * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
  * backward, and the forward-only TV form, on long aligned rows: the trainer's row held in
  * registers, the rollout row streamed past it); "lmhead" after a dppo_lmhead_* call that went

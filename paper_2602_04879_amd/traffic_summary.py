@@ -46,7 +46,7 @@ def counter_avg(directory: str, kernel_substr: str, counter: str) -> float:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--path", required=True, choices=["resident", "resident_long", "streaming", "fullvocab", "fullvocab_resident"])
+    ap.add_argument("--path", required=True, choices=["resident", "resident_long", "resident_multi", "streaming", "fullvocab", "fullvocab_resident"])
     ap.add_argument("--probe-fetch", required=True)
     ap.add_argument("--probe-write", required=True)
     ap.add_argument("--fetch", required=True)

@@ -226,6 +226,79 @@ def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
     _say(f"       {st}")
 
 
+@pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(30000, 4, 24), (32768, 4, 24), (41000, 3, 12), (49152, 3, 2), (50304, 2, 32),
+                                                             (57352, 2, 32), (65536, 2, 32)])
+def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, groups_per_cu):
+    """Rows of middle length, forward + backward, many rows per compute unit: groups of 4 / 3 / 2
+    consecutive rows per workgroup, handed out at run time (V = 49152: the few groups of a short
+    call, fixed by the workgroup index), the last group incomplete.  Ignored, zero-advantage and
+    masked rows, sampled tokens at both ends of the row and on chunk borders; per-token outputs
+    against the oracle on 3000 rows (the first and last groups among them), gradients on a sample
+    of those; run after run bit for bit the same; in place; and the one-row form (other shapes,
+    so other summation orders) writes the same masks."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = groups_per_cu * cus * rows_per_group + 37
+    w = W.Workload("groups", 1, T, V, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=71)
+    b = W.make_batch(w, DEV, shift_sampled=2.0)
+    b["advantages"] = torch.randn(T, device=DEV)
+    b["sampled_ids"][::17] = -1
+    b["advantages"][5::19] = 0.0
+    special = [0, 7, 8, 4095, 4096, 4097, V // 2, V - 4097, V - 9, V - 8, V - 1]
+    for t, a in zip(range(2, 2 + 3 * len(special), 3), special):
+        b["sampled_ids"][t] = max(0, min(a, V - 1))
+        b["sampled_ids"][T - 1 - t] = max(0, min(a, V - 1))      # and in the last groups
+    runs = [B.run_batch(b, diagnostics=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident_multi"
+    for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics", "grad_logits"):
+        assert torch.equal(runs[0][k], runs[1][k]), k
+    fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    assert torch.equal(fixed["mask"], runs[0]["mask"])
+    assert abs(runs[0]["loss"].item() - fixed["loss"].item()) <= 1e-5 * abs(fixed["loss"].item())
+    rows = np.arange(T)
+    some = np.unique(np.concatenate([rows[:1000], rows[-1000:], rows[1000:-1000:max(1, (T - 2000) // 1000)]]))
+    masked = 0
+    for r0 in range(0, len(some), 1024):
+        rr = some[r0:r0 + 1024]
+        ref = P.oracle_rows(b, rr, want_grad=False)
+        st = P.compare_rows(b, runs[0], rr, check_grad=False, ref=ref)
+        masked += st["masked"]
+    _full_size_properties(b, runs[0])
+    assert masked > 50
+    st = P.compare_rows(b, runs[0], np.unique(np.concatenate([np.arange(0, 40), some[::53], rows[-40:]])))
+    inp = B.run_batch(b, in_place=True, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident_multi"
+    assert torch.equal(inp["grad_logits"], runs[0]["grad_logits"]) and torch.equal(inp["loss_tok"], runs[0]["loss_tok"])
+    _say(f"       masked={masked} {st}")
+
+
+def test_groups_of_rows_saturated_and_minus_inf():
+    """pi(a_t) -> 1, blocks of -inf, every logit hugely negative or hugely positive: in groups of rows."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = 24 * cus * 4
+    w = W.Workload("sat_groups", 1, T, 32768, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=0.2, adv="pm1", seed=73)
+    b = W.make_batch(w, DEV)
+    a = b["sampled_ids"].long()
+    rows = torch.arange(b["T"], device=DEV)
+    b["logits"][rows[:6], a[:6]] = torch.tensor([20.0, 30.0, 40.0, 50.0, 60.0, 80.0], device=DEV).bfloat16()
+    b["logits"][6:8, 1000:30000] = float("-inf")
+    b["logits"][8:10, 5:32768 - 5] = float("-inf")
+    b["logits"][10, :] = -1.0e4
+    b["logits"][11, :] = -50.0
+    b["logits"][12, :] = 3.0e4
+    for r in range(6, 10):                                   # keep the sampled token finite in those rows
+        b["logits"][r, a[r]] = 1.0
+    res = B.run_batch(b, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident_multi"
+    assert torch.isfinite(res["divergence"]).all() and torch.isfinite(res["grad_logits"].float()).all()
+    st = P.compare_rows(b, res, np.arange(64))
+    _say(f"       {st}")
+
+
 @pytest.mark.parametrize("V", [180224, 237568])
 def test_long_rows_saturated_and_minus_inf(V):
     """pi(a_t) -> 1, blocks of -inf across the parts of the row (registers, LDS, the tail that is
@@ -574,7 +647,8 @@ def _full_size_properties(b, res):
     assert torch.all(res["grad_logits"][zero] == 0)
 
 
-@pytest.mark.parametrize("name,path", [("c3_qwen3_binary_tv", "resident"), ("c4_qwen3_topk_tv", "resident"), ("c8_vocab256k_binary_tv", "resident_long")])
+@pytest.mark.parametrize("name,path", [("c3_qwen3_binary_tv", "resident"), ("c4_qwen3_topk_tv", "resident"), ("c8_vocab256k_binary_tv", "resident_long"),
+                                       ("c9_vocab32k_binary_tv", "resident_multi")])
 def test_full_size_headline_configs(name, path):
     w = W.WORKLOADS[name]
     _say(f"[case] full size {name} T={w.T} V={w.V}")
