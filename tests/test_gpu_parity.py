@@ -238,7 +238,8 @@ def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, group
     so other summation orders) writes the same masks."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     T = groups_per_cu * cus * rows_per_group + 37
-    w = W.Workload("groups", 1, T, V, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=71)
+    K = 100 if V == 49152 else 20                                  # (beyond one wave's 64 lanes once)
+    w = W.Workload("groups", 1, T, V, W.TOPK_KL, 0.05, K=K, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=71)
     b = W.make_batch(w, DEV, shift_sampled=2.0)
     b["advantages"] = torch.randn(T, device=DEV)
     b["sampled_ids"][::17] = -1
@@ -750,7 +751,10 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4090),
               # rows handed out at run time (a counter-clearing kernel in front, no memset), and the long-row kernel
               W.Workload("graph_dyn", 1, 4 * cus + 5, 100000, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=63),
-              W.Workload("graph_long", 1, 40, 200000, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=64)]
+              W.Workload("graph_long", 1, 40, 200000, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=64),
+              # groups of rows per workgroup: fixed by the workgroup index (2 per compute unit), and handed out at run time
+              W.Workload("graph_groups", 1, 2 * cus * 3 + 2, 49152, W.BINARY_KL, 0.05, logit_std=3.0, noise_std=1.0, adv="normal", seed=65),
+              W.Workload("graph_groups_dyn", 1, 12 * cus * 3 + 1, 49152, W.TOPK_TV, 0.2, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=66)]
     batches = [W.make_batch(w, DEV, shift_sampled=1.0) for w in shapes]
     eager = []
     for b in batches:
@@ -767,7 +771,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
             for b, o, gr in zip(batches, outs, grads):
                 B.run_batch(b, out=o, grad=gr)          # enqueued on the capturing (current) stream
                 paths.add(B.last_path())
-    assert paths == {"resident", "streaming", "resident_long"}
+    assert paths == {"resident", "streaming", "resident_long", "resident_multi"}
     scratch = torch.zeros(1 << 20, device=DEV)
     for rep in range(3):
         for o, gr in zip(outs, grads):                   # poison the outputs between replays
