@@ -18,8 +18,8 @@
 // With many groups per compute unit they are handed out at run time (one atomic counter, drawn one
 // group ahead: the dies do not run at one speed); with few, fixed by the workgroup index (a unit
 // of hand-out that is an eighth of a compute unit's whole share balances worse than none).  The
-// loss terms go to one slot per row either way.  Rows past T in the last group are views of zero bytes: nothing is read or
-// written for them.
+// loss terms go to one slot per row either way.  Rows past T in the last group are views of zero
+// bytes: nothing is read or written for them.
 // Preconditions (checked by the host): V % 8 == 0, 512 (RC - 2) < V / 8 <= 512 RC, logits and
 // grad_logits 16-byte aligned with ld % 8 == 0, p.row_loss set (p.row_counters: groups at run time).
 #include "dppo_common.hpp"
@@ -30,7 +30,9 @@ namespace dppo {
 namespace {
 
 constexpr int kMThreads = 512;
-constexpr int kMTailChunks = 2;   // chunks of a row whose lanes can lie past its end: the last two at most (the host takes a shape with less slack than that)
+// Chunks of a row whose lanes can lie past its end: the last two at most (the host takes a shape
+// only with less slack than that).
+constexpr int kMTailChunks = 2;
 
 template <int ROWS, int RC, bool DIAG, bool DYN>
 __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const KParams p) {
