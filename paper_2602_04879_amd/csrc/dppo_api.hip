@@ -61,13 +61,13 @@ bool stream_device(hipStream_t s, int* dev) {
 
 // Workgroups per compute unit of a register-resident shape: a constant of (device, shape, form),
 // asked of the runtime once and kept.
-int resident_blocks_per_cu_cached(int dev, bool grad, bool dyn, int threads, int chunks) {
-  static std::atomic<int> cache[64][4][2][41];
-  if (dev < 0 || dev >= 64 || chunks < 0 || chunks > 40) return dppo::resident_blocks_per_cu(grad, dyn, threads, chunks);
-  std::atomic<int>& slot = cache[dev][(grad ? 1 : 0) + (dyn ? 2 : 0)][threads == 512 ? 1 : 0][chunks];
+int resident_blocks_per_cu_cached(int dev, bool grad, bool dyn, bool ragged, int threads, int chunks) {
+  static std::atomic<int> cache[64][8][3][41];
+  if (dev < 0 || dev >= 64 || chunks < 0 || chunks > 40) return dppo::resident_blocks_per_cu(grad, dyn, ragged, threads, chunks);
+  std::atomic<int>& slot = cache[dev][(grad ? 1 : 0) + (dyn ? 2 : 0) + (ragged ? 4 : 0)][threads == 512 ? 2 : threads == 256 ? 1 : 0][chunks];
   int n = slot.load(std::memory_order_relaxed);
   if (n == 0) {
-    n = dppo::resident_blocks_per_cu(grad, dyn, threads, chunks);
+    n = dppo::resident_blocks_per_cu(grad, dyn, ragged, threads, chunks);
     slot.store(n, std::memory_order_relaxed);
   }
   return n;
@@ -217,17 +217,20 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     const bool full = (a->variant == DPPO_FULL_TV || a->variant == DPPO_FULL_KL);
 
     const uintptr_t lz = reinterpret_cast<uintptr_t>(a->logits), lg = reinterpret_cast<uintptr_t>(a->grad_logits);
-    // Register-resident kernel: rows of 1024 .. 155648 entries, a multiple of 8, 16-byte aligned.
+    // Register-resident kernel: rows of 1024 .. 155648 entries.  A multiple of 8 and 16-byte aligned:
+    // the plain form; else its ragged form, if logits and gradient share their misalignment.
     int r_threads = 0, r_chunks = 0;
-    const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0 &&
-                          dppo::resident_shape(a->V, &r_threads, &r_chunks);
+    const bool aligned = (a->V % 8 == 0) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0;
+    const bool ragged = !aligned && (!grad || ((lz - lg) & 15u) == 0);
+    const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (aligned || ragged) &&
+                          dppo::resident_shape(a->V, ragged, &r_threads, &r_chunks);
     // Longer rows, forward + backward: the long-row form of the same kernel, up to 262144 entries.
-    const int long_chunks = (!full && grad && !resident && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (a->ld % 8 == 0) && ((lz | lg) & 15u) == 0)
+    const int long_chunks = (!full && grad && !resident && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && aligned)
                                 ? dppo::resident_long_chunks(a->V) : 0;
     // Rows of middle length, forward + backward, when rows can be handed out at run time and every
     // compute unit gets several groups of them: several rows per workgroup.
     int m_rows = 0, m_chunks = 0;
-    const bool m_shape = resident && grad && dppo::resident_multi_shape(a->V, &m_rows, &m_chunks);
+    const bool m_shape = resident && aligned && grad && dppo::resident_multi_shape(a->V, &m_rows, &m_chunks);
     const int64_t m_groups = m_shape ? (a->T + m_rows - 1) / m_rows : 0;
     const MultiThresholds m_from = multi_thresholds(m_rows);
     const bool multi_dyn = m_shape && sc.row_loss && !(a->flags & DPPO_FLAG_STATIC_ROWS) && cus % 8 == 0 && m_groups >= m_from.dyn * cus;
@@ -278,7 +281,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       g_last_path = "resident_multi";
       return DPPO_OK;
     } else if (resident) {
-      int per_cu = resident_blocks_per_cu_cached(dev, grad, false, r_threads, r_chunks);
+      int per_cu = resident_blocks_per_cu_cached(dev, grad, false, ragged, r_threads, r_chunks);
       int64_t grid = static_cast<int64_t>(cus) * per_cu;
       if (grid > a->T) grid = a->T;
       if (grid > max_parts) grid = max_parts;
@@ -289,7 +292,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       bool dyn = false;
       if (grad && r_threads == 512 && per_cu == 1) {
         // the form that draws its rows has its own register count, so its own occupancy
-        const int64_t grid_dyn = static_cast<int64_t>(cus) * resident_blocks_per_cu_cached(dev, grad, true, r_threads, r_chunks);
+        const int64_t grid_dyn = static_cast<int64_t>(cus) * resident_blocks_per_cu_cached(dev, grad, true, ragged, r_threads, r_chunks);
         if (grid_dyn <= max_parts && rows_at_run_time(a, sc, grid_dyn)) {
           grid = grid_dyn;
           dyn = true;
@@ -297,7 +300,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       }
       nparts = static_cast<int>(grid);
       if (dyn && arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
-      if (dppo::launch_resident(p, grad, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      if (dppo::launch_resident(p, grad, ragged, r_threads, r_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident";
       if (p.row_counters) return DPPO_OK;
     } else {

@@ -11,12 +11,14 @@ hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, 
 
 // Register-resident kernel (fused forward+backward, or forward only).  A shape is (threads per workgroup, 16-byte
 // chunks per thread); resident_shape() picks the smallest instantiated one that covers a row of
-// V entries (false: none does, or V is not a multiple of 8).  Needs 16-byte aligned rows of
-// logits and grad.  resident_blocks_per_cu() is the occupancy the runtime reports for a shape (dyn: of the form
-// that hands its rows out at run time).
-bool resident_shape(int64_t V, int* threads, int* chunks);
-hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s);
-int resident_blocks_per_cu(bool grad, bool dyn, int threads, int chunks);
+// V entries (false: none does).  ragged = false: V a multiple of 8 and 16-byte aligned rows of logits and
+// grad.  ragged = true: any V, any pitch, rows 2-byte aligned; logits and grad must share their
+// misalignment (address mod 16); the kernel reads the aligned 16-byte blocks that hold a row and
+// writes the row's own entries only.  resident_blocks_per_cu() is the occupancy the runtime reports
+// for a shape (dyn: of the form that hands its rows out at run time).
+bool resident_shape(int64_t V, bool ragged, int* threads, int* chunks);
+hipError_t launch_resident(const KParams& p, bool grad, bool ragged, int threads, int chunks, int grid, hipStream_t s);
+int resident_blocks_per_cu(bool grad, bool dyn, bool ragged, int threads, int chunks);
 
 // Register-resident kernel for rows too long for the register file alone (forward+backward only):
 // part of the row in registers, part in LDS, the rest passed through twice.  resident_long_chunks()

@@ -20,7 +20,9 @@
 // them per compute unit, each running its own row's epilogue.
 //
 // Preconditions (checked by the host): V % 8 == 0, V/8 <= THREADS*NCHUNK, logits and
-// grad_logits 16-byte aligned with ld % 8 == 0.
+// grad_logits 16-byte aligned with ld % 8 == 0.  The RAGGED form lifts the alignment conditions
+// (any V, any pitch, rows 2-byte aligned, logits and grad_logits sharing their misalignment): it
+// works on the aligned FRAME of a row, the 16-byte blocks that hold it.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 #include "dppo_resident_parts.hpp"
@@ -55,7 +57,16 @@ constexpr int kChunkStep = 4;
 // compiler lands within a register or two of that limit, on either side).
 constexpr int resident_min_waves(int threads, int nchunk) { return threads == 512 ? 2 : (nchunk <= 16 ? 3 : 2); }
 
-template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN>
+// RAGGED = true: rows that do not start on a 16-byte boundary or whose length is not a multiple
+// of 8 (a vocabulary of 50257 entries; a pitch that is not a multiple of 8).  A row is then
+// handled in its FRAME: the 16-byte blocks from the one holding its first entry to the one holding
+// its last.  With h = (row address mod 16) / 2 the row occupies entries h .. h+V-1 of the frame;
+// entries of the first and last block outside that range (the neighbouring rows' bytes, or up
+// to 14 bytes in front of the first row and 2 behind the last: within an aligned block that holds
+// row data, so in mapped memory) are read, turned into -inf in the resident copy, and never
+// written: the gradient's first and last block, where incomplete, leave as 2-byte stores of the
+// row's own entries, the blocks between them as 16-byte stores.
+template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN, bool RAGGED>
 __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
   constexpr int NW = THREADS / kWave;
@@ -76,7 +87,7 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
   int par = 0;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
-  const int nvec = p.V >> 3;
+  const int nvec_aligned = p.V >> 3;
   const uint32_t row_bytes = static_cast<uint32_t>(p.V) * 2u;
   const uint32_t voff = static_cast<uint32_t>(tid) * 16u;
   const u32x4 neg_inf = {kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair};
@@ -122,8 +133,19 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
   }
   __builtin_amdgcn_sched_barrier(0);
+  // RAGGED: entries of the frame in front of the row, 0..7 (else 0)
+  auto head_of = [&](int r) -> int {
+    return RAGGED ? static_cast<int>(((reinterpret_cast<uintptr_t>(logits) + static_cast<uint64_t>(r * pitch)) >> 1) & 7u) : 0;
+  };
+  // View of a row for loading (has = false: of zero bytes).  RAGGED: of its frame, up to the end of
+  // the 4-byte word holding the row's last entry (the range check works per word).
+  auto load_view = [&](int r, bool has) -> row_rsrc_t {
+    if (!RAGGED) return make_row_rsrc(logits + r * pitch, has ? row_bytes : 0u);
+    const int h = head_of(r);
+    return make_row_rsrc(logits + r * pitch - 2 * h, has ? ((static_cast<uint32_t>(h + p.V) * 2u + 3u) & ~3u) : 0u);
+  };
   {
-    const row_rsrc_t zr = make_row_rsrc(logits + row * pitch, row_bytes);
+    const row_rsrc_t zr = load_view(row, true);
 #pragma unroll
     for (int i = 0; i < NCHUNK; ++i) buf[i] = row_load16<kNtLoads>(zr, voff, i * kStride);
   }
@@ -148,11 +170,17 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     const uint16_t* zrow = p.logits + static_cast<int64_t>(row) * p.ld;
     // The workgroup's next row; without one the refills go through a resource of zero bytes:
     // their loads touch no memory.
-    const row_rsrc_t zn = make_row_rsrc(logits + (more ? next : row) * pitch, more ? row_bytes : 0u);
-    const int avec = a >> 3;
+    const row_rsrc_t zn = load_view(more ? next : row, more);
+    // RAGGED: the row in its frame: h entries in front of it, nvec 16-byte blocks in all, the last
+    // one (block vl = chunk il of thread tl, il among the last kChunkStep + 1 chunks) holding t of
+    // the row's entries.
+    const int h = head_of(row);
+    const int nvec = RAGGED ? (h + p.V + 7) >> 3 : nvec_aligned;
+    const int vl = nvec - 1, il = vl / THREADS, tl = vl - il * THREADS, t = h + p.V - 8 * vl;
+    const int avec = (a + h) >> 3;
     const int ia = live ? avec / THREADS : -1;               // chunk holding a_t (uniform)
     const bool owner = live && (avec - ia * THREADS == tid);
-    const int sub = a & 7;
+    const int sub = (a + h) & 7;
 
     RowCoef rc;
     rc.coef = 0.f; rc.kexp = 0.f; rc.g_a = 0.f;
@@ -188,6 +216,13 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
         for (int i = 0; i < GC; ++i) {
           if (g0 + i < NCHUNK && g0 + i == ia) {
             if (owner) buf[g0 + i < NCHUNK ? g0 + i : 0] = patch16(buf[g0 + i < NCHUNK ? g0 + i : 0], sub, 0xFF80u);
+          }
+          // RAGGED: what the frame's first and last block hold beside the row is -inf from here on
+          if (RAGGED && g0 + i == 0) {
+            if (tid == 0 && h > 0) buf[0] = keep16(buf[0], h, 8);
+          }
+          if (RAGGED && g0 + i < NCHUNK && g0 + i >= NCHUNK - kChunkStep - 1 && g0 + i == il) {
+            if (tid == tl && t < 8) buf[g0 + i < NCHUNK ? g0 + i : 0] = keep16(buf[g0 + i < NCHUNK ? g0 + i : 0], 0, t);
           }
         }
         u32x4 v[GC];
@@ -315,7 +350,11 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     // in the order the next row's arithmetic will consume them.
     if (GRAD) {
       char* gr = grad + row * pitch;
-      const row_desc_t gout = make_row_desc(gr, row_bytes);
+      // RAGGED: the 16-byte stores cover the frame's complete blocks only: the view ends in front of
+      // an incomplete last block, and the thread holding an incomplete first block gives its store
+      // an offset out of range, so that it is dropped.
+      const row_desc_t gout = RAGGED ? make_row_desc(gr - 2 * h, static_cast<uint32_t>((h + p.V) >> 3) * 16u) : make_row_desc(gr, row_bytes);
+      const uint32_t voff0 = (RAGGED && h > 0 && tid == 0) ? 0x80000000u : voff;
       const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
       if (rc.coef == 0.f) {
         // Masked, zero-advantage or ignored row: its gradient is exactly zero whatever the logits
@@ -323,8 +362,19 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
 #pragma unroll
         for (int i = 0; i < NCHUNK; ++i) buf[i] = neg_inf;
       }
+      if (RAGGED) {
+        // the row's own entries of an incomplete first / last block, two bytes at a time
+        const row_desc_t gex = make_row_desc(gr, row_bytes);
+        if (tid == 0 && h > 0) store_entries_untracked(gex, grad8(buf[0], rc.kexp, sgn), h, 8, -h);
 #pragma unroll
-      for (int i = 0; i < NCHUNK; ++i) row_store16_untracked(gout, voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
+        for (int c = (NCHUNK > kChunkStep + 1 ? NCHUNK - kChunkStep - 1 : 0); c < NCHUNK; ++c) {
+          if (c == il) {
+            if (tid == tl && t < 8) store_entries_untracked(gex, grad8(buf[c], rc.kexp, sgn), 0, t, 8 * vl - h);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NCHUNK; ++i) row_store16_untracked(gout, i == 0 ? voff0 : voff, i * kStride, grad8(buf[i], rc.kexp, sgn));
       // Keep the instruction scheduler from hoisting the refills above the stores: a refill can
       // only reuse its chunk's registers once the store has been given them (a vector-memory load
       // into those registers then queues behind that store).
@@ -357,14 +407,14 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
 // against 256 threads x 4 chunks: 4.9 against 4.1 TB/s.  From 16384 entries on, the 256-thread
 // shapes measure the same or better (V = 16384: 4.94 against 4.83 TB/s with 64 threads x 32 chunks).
 // Rows are handed out at run time when the host sets p.row_counters.
-template <int THREADS, int NCHUNK>
+template <int THREADS, int NCHUNK, bool RAGGED>
 hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
   const bool diag = p.diag != nullptr;
   constexpr bool kDyn = (THREADS == 512);     // the forms with run-time rows exist for the 512-thread shapes, with the gradient
   const bool dyn = kDyn && grad && p.row_counters != nullptr;
   if (p.row_counters != nullptr && !dyn) return hipErrorInvalidValue;
   const dim3 g(grid), b(THREADS);
-#define DPPO_FORM(G, D, Y) hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, G, D, Y>), g, b, 0, s, p)
+#define DPPO_FORM(G, D, Y) hipLaunchKernelGGL((dppo_resident_kernel<THREADS, NCHUNK, G, D, Y, RAGGED>), g, b, 0, s, p)
   if (grad) {
     if (diag) { if (dyn) DPPO_FORM(true, true, kDyn); else DPPO_FORM(true, true, false); }
     else      { if (dyn) DPPO_FORM(true, false, kDyn); else DPPO_FORM(true, false, false); }
@@ -375,14 +425,14 @@ hipError_t launch_shape(const KParams& p, bool grad, int grid, hipStream_t s) {
   return hipGetLastError();
 }
 // The diagnostics form needs a few more registers; its occupancy bounds both.
-template <int THREADS, int NCHUNK>
+template <int THREADS, int NCHUNK, bool RAGGED>
 int occupancy_shape(bool grad, bool dyn) {
   int n = 0;
   constexpr bool kDyn = (THREADS == 512);
   hipError_t e;
-  if (grad && dyn && kDyn) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, kDyn>, THREADS, 0);
-  else if (grad)           e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, false>, THREADS, 0);
-  else                     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true, false>, THREADS, 0);
+  if (grad && dyn && kDyn) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, kDyn, RAGGED>, THREADS, 0);
+  else if (grad)           e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, true, true, false, RAGGED>, THREADS, 0);
+  else                     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dppo_resident_kernel<THREADS, NCHUNK, false, true, false, RAGGED>, THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 
@@ -392,26 +442,28 @@ int occupancy_shape(bool grad, bool dyn) {
   X(64, 4) X(64, 8) X(64, 12) X(64, 16) X(256, 4) X(256, 8) X(256, 12) X(256, 16) X(256, 20) \
   X(512, 12) X(512, 16) X(512, 20) X(512, 24) X(512, 28) X(512, 32) X(512, 36) X(512, 38)
 
-bool resident_shape(int64_t V, int* threads, int* chunks) {
-  if (V < 1024 || V % 8 != 0) return false;
-  const int64_t nvec = V / 8;
+bool resident_shape(int64_t V, bool ragged, int* threads, int* chunks) {
+  if (V < 1024 || (!ragged && V % 8 != 0)) return false;
+  // 16-byte blocks of a row: V / 8; of a row's frame (ragged): between these two, by where the row starts
+  const int64_t nvec_min = ragged ? (V + 7) / 8 : V / 8, nvec_max = ragged ? (V + 14) / 8 : V / 8;
   // (a shape is only taken with less than kChunkStep chunks of slack: the kernel turns lanes past
   // the row into -inf in its last kChunkStep chunks only)
-#define DPPO_TRY(T, C) if (nvec <= static_cast<int64_t>(T) * C) { *threads = T; *chunks = C; return nvec > static_cast<int64_t>(T) * (C - kChunkStep); }
+  // (ragged: the shortest frame may end exactly with chunk C - kChunkStep - 1, whose last block the kernel still looks at)
+#define DPPO_TRY(T, C) if (nvec_max <= static_cast<int64_t>(T) * C) { *threads = T; *chunks = C; return nvec_min + (ragged ? 1 : 0) > static_cast<int64_t>(T) * (C - kChunkStep); }
   DPPO_SHAPES(DPPO_TRY)
 #undef DPPO_TRY
   return false;
 }
 
-hipError_t launch_resident(const KParams& p, bool grad, int threads, int chunks, int grid, hipStream_t s) {
-#define DPPO_LAUNCH(T, C) if (threads == T && chunks == C) return launch_shape<T, C>(p, grad, grid, s);
+hipError_t launch_resident(const KParams& p, bool grad, bool ragged, int threads, int chunks, int grid, hipStream_t s) {
+#define DPPO_LAUNCH(T, C) if (threads == T && chunks == C) return ragged ? launch_shape<T, C, true>(p, grad, grid, s) : launch_shape<T, C, false>(p, grad, grid, s);
   DPPO_SHAPES(DPPO_LAUNCH)
 #undef DPPO_LAUNCH
   return hipErrorInvalidValue;
 }
 
-int resident_blocks_per_cu(bool grad, bool dyn, int threads, int chunks) {
-#define DPPO_OCC(T, C) if (threads == T && chunks == C) return occupancy_shape<T, C>(grad, dyn);
+int resident_blocks_per_cu(bool grad, bool dyn, bool ragged, int threads, int chunks) {
+#define DPPO_OCC(T, C) if (threads == T && chunks == C) return ragged ? occupancy_shape<T, C, true>(grad, dyn) : occupancy_shape<T, C, false>(grad, dyn);
   DPPO_SHAPES(DPPO_OCC)
 #undef DPPO_OCC
   return 1;

@@ -22,6 +22,34 @@ __device__ __forceinline__ u32x4 patch16(u32x4 v, int sub, uint32_t bits) {
   return r;
 }
 
+// Keep the 16-bit entries lo .. hi-1 of a packed vector, the others become bf16 -inf.
+__device__ __forceinline__ u32x4 keep16(u32x4 v, int lo, int hi) {
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const bool k0 = (2 * d >= lo && 2 * d < hi), k1 = (2 * d + 1 >= lo && 2 * d + 1 < hi);
+    const uint32_t keep = (k0 ? 0x0000ffffu : 0u) | (k1 ? 0xffff0000u : 0u);
+    w[d] = (w[d] & keep) | (kNegInfPair & ~keep);
+  }
+  const u32x4 r = {w[0], w[1], w[2], w[3]};
+  return r;
+}
+
+// Entries lo .. hi-1 of a packed vector stored two bytes at a time: entry e goes to entry
+// e + shift of the row the descriptor covers (range-checked).  Issued from inline assembly like
+// row_store16_untracked, with the same wait states around each store.
+__device__ __forceinline__ void store_entries_untracked(row_desc_t d, u32x4 o, int lo, int hi, int shift) {
+  const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (e >= lo && e < hi) {
+      const uint32_t val = (e & 1) ? (w[e >> 1] >> 16) : w[e >> 1];
+      const uint32_t off = static_cast<uint32_t>(e + shift) * 2u;
+      asm volatile("s_nop 4\n\tbuffer_store_short %0, %1, %2, 0 offen\n\ts_nop 1" ::"v"(val), "v"(off), "s"(d) : "memory");
+    }
+  }
+}
+
 // One packed word (two bf16): returns e0 + e1 and adds e*x to t, with x = z*log2e + b and
 // e = 2^x (t feeds the entropy; a vanished term, e = 0 with x = -inf, adds nothing).
 __device__ __forceinline__ float accum2(uint32_t w, float b, float& t) {

@@ -100,8 +100,16 @@ def test_qwen3_vocab_small_t(name):
     (256000, 256000, "resident_long"), # a Gemma-2 sized vocabulary: 62.5 chunks
     (262144, 262144, "resident_long"), # longest row of this form: 64 chunks exactly full
     (262152, 262152, "streaming"),     # one vector more: the two-pass kernel
-    (40004, 40004, "streaming"),       # V not a multiple of 8
-    (16384, 16388, "streaming"),       # pitch not a multiple of 8: rows not 16-byte aligned
+    (40004, 40004, "resident"),        # V not a multiple of 8: the ragged form (rows start 0, 8, 0, 8 bytes into a 16-byte block)
+    (16384, 16388, "resident"),        # pitch not a multiple of 8: rows not 16-byte aligned, the ragged form
+    (50257, 50257, "resident"),        # a GPT-2 sized vocabulary: odd, so every row starts 2 bytes further into its block
+    (50257, 50264, "resident"),        # ... in a pitch that is a multiple of 8: aligned rows, ragged end
+    (151643, 151643, "resident"),      # 512 x 38, odd
+    (155641, 155647, "resident"),      # the longest ragged row: a frame of 19456 blocks at most
+    (155642, 155642, "streaming"),     # one entry more: a frame of 19457 blocks for some rows
+    (8190, 8190, "resident"),          # frames of 1024 or 1025 blocks: 256 threads x 8 chunks, the shorter frame ending with chunk 3
+    (8181, 8181, "resident"),          # frames of 1023 or 1024 blocks: one wave x 16 chunks
+    (1030, 1031, "resident"),          # smallest ragged shapes
 ])
 @pytest.mark.parametrize("variant,K", [(W.BINARY_KL, 0), (W.TOPK_KL, 20)])
 def test_resident_shapes_and_fallback(V, ld, expect, variant, K):
@@ -365,7 +373,7 @@ def test_mask_rules_and_ratio_cap(rule, V, flags):
         assert (r > rule["ratio_cap"]).any()           # the cap bites on some tokens
 
 
-@pytest.mark.parametrize("V,path", [(4096, "resident"), (4090, "streaming"), (16384, "resident"), (151936, "resident"), (200000, "resident_long")])
+@pytest.mark.parametrize("V,path", [(4096, "resident"), (1000, "streaming"), (4091, "resident"), (16384, "resident"), (151936, "resident"), (200000, "resident_long")])
 @pytest.mark.parametrize("variant,K,rule", [
     (W.BINARY_TV, 0, dict()),                                                           # decoupled DPPO (Sec. 5.2)
     (W.TOPK_KL, 20, dict()),
@@ -406,7 +414,7 @@ def test_mask_anchored_to_a_recomputed_policy(V, path, variant, K, rule):
     _say(f"       {st}")
 
 
-@pytest.mark.parametrize("V,path", [(4096, "resident"), (4090, "streaming"), (32768, "resident"), (151936, "resident"), (200000, "resident_long")])
+@pytest.mark.parametrize("V,path", [(4096, "resident"), (1000, "streaming"), (4091, "resident"), (32768, "resident"), (151936, "resident"), (200000, "resident_long")])
 @pytest.mark.parametrize("sides", [B.RELAX_HIGH, B.RELAX_LOW, B.RELAX_HIGH | B.RELAX_LOW])
 def test_clip_relaxed_for_low_probability_tokens(V, path, sides):
     """Sec. 6: the ratio-clip mask with its upper, lower or both thresholds infinite for tokens whose
@@ -440,10 +448,12 @@ def test_ragged_vocab_and_pitch(V, ld, variant, K):
     _run_and_compare(w, ld=ld)      # with ld > V the pad columns hold a poison value that must not be read
 
 
-def test_pitch_columns_untouched_and_canaries():
-    """Writes stay inside [T, V) of grad_logits and inside [T) of the per-token outputs."""
-    w = W.Workload("canary", 4, 9, 1000, W.TOPK_KL, 0.05, K=7, logit_std=2.0, noise_std=0.5, adv="normal", seed=5)
-    ld = 1016
+@pytest.mark.parametrize("V,ld,path", [(1000, 1016, "streaming"), (5003, 5011, "resident"), (5003, 5003, "resident"), (50257, 50264, "resident")])
+def test_pitch_columns_untouched_and_canaries(V, ld, path):
+    """Writes stay inside [T, V) of grad_logits and inside [T) of the per-token outputs: in the
+    two-pass kernel, and in the ragged form of the register-resident one, which works on the aligned
+    16-byte blocks around a row and must write the row's own entries only."""
+    w = W.Workload("canary", 4, 9, V, W.TOPK_KL, 0.05, K=7, logit_std=2.0, noise_std=0.5, adv="normal", seed=5)
     b = W.make_batch(w, DEV, ld=ld)
     T, V = b["T"], b["V"]
     pad = 64
@@ -456,11 +466,57 @@ def test_pitch_columns_untouched_and_canaries():
     out["divergence"], out["loss_tok"], out["mask"] = dbuf[pad:pad + T], lbuf[pad:pad + T], mbuf[pad:pad + T]
     res = B.run_batch(b, out=out, grad=grad)
     torch.cuda.synchronize()
+    assert B.last_path() == path
     assert torch.all(gbuf[:pad] == 7.0) and torch.all(gbuf[pad + T * ld:] == 7.0)
     assert torch.all(grad[:, V:] == 7.0)
     for buf, v in ((dbuf, -3.0), (lbuf, -3.0), (mbuf, 9)):
         assert torch.all(buf[:pad] == v) and torch.all(buf[pad + T:] == v)
     P.compare_rows(b, res, np.arange(T))
+
+
+@pytest.mark.parametrize("V,ld", [(100003, 100003), (50257, 50257), (151643, 151646), (12345, 12345)])
+def test_ragged_rows_in_registers_with_special_rows(V, ld):
+    """Odd vocabularies (every row starts another 2 bytes into its 16-byte block) on the register-resident
+    kernel, many rows per workgroup (rows handed out at run time where the shape has one workgroup per
+    compute unit): sampled tokens in the first and last block of the row, ignored / zero-advantage /
+    masked rows; every per-token output against the oracle, gradients on a sample; rows fixed by the
+    workgroup index, forward only and in place write the same; nothing outside [T, V) is written."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    T = 4 * cus + 37
+    w = W.Workload("ragged_rows", 1, T, V, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=81)
+    b = W.make_batch(w, DEV, ld=ld, shift_sampled=2.0)
+    b["advantages"] = torch.randn(T, device=DEV)
+    b["sampled_ids"][::17] = -1
+    b["advantages"][5::19] = 0.0
+    special = [0, 1, 6, 7, 8, 9, V - 10, V - 9, V - 8, V - 7, V - 2, V - 1]
+    for i, a in enumerate(special * 4):                      # rows 2 .. 49: every head offset meets every special id
+        b["sampled_ids"][2 + i] = a
+    pad = 64
+    gbuf = torch.full((T * ld + 2 * pad,), 7.0, dtype=torch.bfloat16, device=DEV)
+    grad = gbuf[pad:pad + T * ld].view(T, ld)
+    res = B.run_batch(b, diagnostics=True, grad=grad)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    assert torch.all(gbuf[:pad] == 7.0) and torch.all(gbuf[pad + T * ld:] == 7.0) and torch.all(grad[:, V:] == 7.0)
+    rows = np.arange(T)
+    ref = P.oracle_rows(b, rows, want_grad=False)
+    st = P.compare_rows(b, res, rows, check_grad=False, ref=ref)
+    P.check_loss_scalar(b, res, float(ref["loss_tok"].sum()))
+    P.compare_rows(b, res, np.unique(np.concatenate([np.arange(0, 52), rows[::41], rows[-9:]])))
+    assert st["masked"] > 50
+    fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
+    fwd = B.run_batch(b, diagnostics=True, backward=False)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    for k in ("loss_tok", "divergence", "mask", "diagnostics"):
+        assert torch.equal(fixed[k], res[k]), k
+        assert torch.equal(fwd[k], res[k]), k
+    assert torch.equal(fixed["grad_logits"][:, :V], grad[:, :V])
+    inp = B.run_batch(b, in_place=True, diagnostics=True)
+    torch.cuda.synchronize()
+    assert B.last_path() == "resident"
+    assert torch.equal(inp["grad_logits"][:, :V], grad[:, :V]) and torch.equal(inp["loss_tok"], res["loss_tok"])
+    _say(f"       {st}")
 
 
 def test_misaligned_gradient_buffer_takes_elementwise_path():
@@ -471,6 +527,7 @@ def test_misaligned_gradient_buffer_takes_elementwise_path():
     grad = gbuf[3:3 + T * V].view(T, V)      # 6 bytes off the logits' alignment
     res = B.run_batch(b, grad=grad)
     torch.cuda.synchronize()
+    assert B.last_path() == "streaming"
     P.compare_rows(b, res, np.arange(T))
     # logits themselves at an odd element offset
     lbuf = torch.zeros(T * V + 8, dtype=torch.bfloat16, device=DEV)
@@ -480,9 +537,13 @@ def test_misaligned_gradient_buffer_takes_elementwise_path():
     res = B.run_batch(b2)
     torch.cuda.synchronize()
     P.compare_rows(b2, res, np.arange(T))
+    # in place both share the misalignment: the ragged form of the register-resident kernel, whose
+    # first frame begins 10 bytes in front of the first row
     res = B.run_batch(b2, in_place=True)
     torch.cuda.synchronize()
+    assert B.last_path() == "resident"
     P.compare_rows(b, res, np.arange(T))
+    assert torch.all(lbuf[:5] == 0) and torch.all(lbuf[5 + T * V:] == 0)
 
 
 def test_ignored_rows_padding_ids_and_zero_advantage():
@@ -748,7 +809,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     several times with eager work and synchronisations in between, and compare every replay bit for
     bit with the eager result."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4090),
+    shapes = [W.scaled(W.WORKLOADS["c2_binary_kl"], n_seq=2, seq_len=96), W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=1000),
+              W.scaled(W.WORKLOADS["c1_tiny_binary_tv"], K=8, variant=W.TOPK_TV, V=4091),     # the ragged form of the register-resident kernel
               # rows handed out at run time (a counter-clearing kernel in front, no memset), and the long-row kernel
               W.Workload("graph_dyn", 1, 4 * cus + 5, 100000, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=63),
               W.Workload("graph_long", 1, 40, 200000, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=64),

@@ -42,9 +42,11 @@ def _both(w, shift=2.0):
 def test_static_scratch_entry_point_matches_the_workspace_one_twice_in_a_row():
     big = W.Workload("static_big", 3, 250, 16384, W.TOPK_TV, 0.1, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=51)
     small = W.Workload("static_small", 2, 9, 3001, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=1.0, adv="normal", seed=52)
+    tiny = W.Workload("static_tiny", 2, 9, 601, W.BINARY_KL, 0.05, logit_std=2.0, noise_std=1.0, adv="normal", seed=52)
     assert B.lib().dppo_static_init() == 0
     assert _both(big) == "resident"          # 750 rows on every compute unit: all partial sums in use
-    assert _both(small) == "streaming"       # then a smaller call: 18 workgroups, stale sums beside them
+    assert _both(small) == "resident"        # then a smaller call: 18 workgroups (ragged rows), stale sums beside them
+    assert _both(tiny) == "streaming"        # and the two-pass kernel
     assert _both(big) == "resident"
 
 
