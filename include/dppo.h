@@ -111,19 +111,19 @@ typedef enum {
 typedef struct {
   /* ---- inputs ---- */
   const void*    logits;       /* bf16 [T, ld] row-major; only columns 0..V-1 are used.  (Where */
-                               /* rows are not 16-byte aligned a kernel may fetch the aligned  */
-                               /* 16-byte blocks that hold a row: what such a block holds      */
-                               /* beside the row - pad columns, a neighbouring row, up to 14   */
+                               /* rows do not start on a 128-byte line a kernel may fetch the  */
+                               /* whole aligned lines that hold a row: what such a line holds  */
+                               /* beside the row - pad columns, a neighbouring row, up to 126  */
                                /* bytes in front of the first row, 2 behind the last - is      */
                                /* fetched and ignored, and never written in grad_logits.)      */
   int64_t        T;            /* rows (response tokens; the caller packs responses only)      */
   int64_t        V;            /* vocabulary size, 1 <= V < 2^31                               */
-  int64_t        ld;           /* row pitch in elements, ld >= V (any value; with V % 8 == 0   */
-                               /* rows whose start is 16-byte aligned take the fastest path,   */
-                               /* and rows that start on a 128-byte line, ld % 64 == 0, are    */
-                               /* another 8 % faster; other rows of 1024 .. 155641 entries     */
-                               /* still take a register-resident kernel if logits and          */
-                               /* grad_logits have the same address modulo 16)                 */
+  int64_t        ld;           /* row pitch in elements, ld >= V (any value; fastest with      */
+                               /* V % 8 == 0 and rows that start on 128-byte lines, i.e.       */
+                               /* ld % 64 == 0 and a 128-byte aligned base; other rows of      */
+                               /* 1024 .. 155585 entries still take a register-resident kernel */
+                               /* if logits and grad_logits have the same address modulo 16,   */
+                               /* a few per cent slower)                                       */
   const int32_t* sampled_ids;  /* [T] a_t.  An id outside [0, V) marks an ignored row:         */
                                /* divergence 0, mask 0, no loss term, zero gradient row        */
   const float*   mu_logp;      /* [T] log mu(a_t|s_t) as returned by the rollout engine        */

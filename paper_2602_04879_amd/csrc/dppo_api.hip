@@ -221,9 +221,17 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     // the plain form; else its ragged form, if logits and gradient share their misalignment.
     int r_threads = 0, r_chunks = 0;
     const bool aligned = (a->V % 8 == 0) && (a->ld % 8 == 0) && ((lz | (grad ? lg : 0)) & 15u) == 0;
-    const bool ragged = !aligned && (!grad || ((lz - lg) & 15u) == 0);
-    const bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (aligned || ragged) &&
-                          dppo::resident_shape(a->V, ragged, &r_threads, &r_chunks);
+    const bool ragged_ok = !grad || ((lz - lg) & 15u) == 0;
+    // Rows of 16384 entries and more that are 16-byte aligned but do not start on 128-byte lines
+    // are faster in the ragged form, whose accesses are whole lines (measured +1.4 % at 20008
+    // entries, +5 % at 32008 .. 151944; shorter rows lose 2-10 %), unless the form with several
+    // rows per workgroup takes them (decided below).
+    const bool on_lines = aligned && (a->ld % 64 == 0) && ((lz | (grad ? lg : 0)) & 127u) == 0;
+    int l_threads = 0, l_chunks = 0;
+    const bool prefer_lines = aligned && !on_lines && ragged_ok && a->V >= 16384 && dppo::resident_shape(a->V, true, &l_threads, &l_chunks);
+    bool ragged = !aligned && ragged_ok;
+    bool resident = !full && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && (aligned || ragged) &&
+                    dppo::resident_shape(a->V, ragged, &r_threads, &r_chunks);
     // Longer rows, forward + backward: the long-row form of the same kernel, up to 262144 entries.
     const int long_chunks = (!full && grad && !resident && !(a->flags & DPPO_FLAG_FORCE_STREAMING) && aligned)
                                 ? dppo::resident_long_chunks(a->V) : 0;
@@ -235,6 +243,11 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     const MultiThresholds m_from = multi_thresholds(m_rows);
     const bool multi_dyn = m_shape && sc.row_loss && !(a->flags & DPPO_FLAG_STATIC_ROWS) && cus % 8 == 0 && m_groups >= m_from.dyn * cus;
     const bool multi = multi_dyn || (m_shape && sc.row_loss && !(a->flags & DPPO_FLAG_STATIC_ROWS) && m_from.fixed > 0 && m_groups >= m_from.fixed * cus);
+    if (resident && !multi && prefer_lines) {
+      ragged = true;
+      r_threads = l_threads;
+      r_chunks = l_chunks;
+    }
     const bool tv_full = a->variant == DPPO_FULL_TV;
     const int fr_chunks = (full && !(a->flags & DPPO_FLAG_FORCE_STREAMING)) ? dppo::fullvocab_resident_chunks(p, tv_full, grad) : 0;
     if (fr_chunks) {

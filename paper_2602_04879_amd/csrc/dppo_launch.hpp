@@ -13,7 +13,7 @@ hipError_t launch_streaming(const KParams& p, bool vec, bool grad, int threads, 
 // chunks per thread); resident_shape() picks the smallest instantiated one that covers a row of
 // V entries (false: none does).  ragged = false: V a multiple of 8 and 16-byte aligned rows of logits and
 // grad.  ragged = true: any V, any pitch, rows 2-byte aligned; logits and grad must share their
-// misalignment (address mod 16); the kernel reads the aligned 16-byte blocks that hold a row and
+// misalignment (address mod 16); the kernel reads the aligned 128-byte lines that hold a row and
 // writes the row's own entries only.  resident_blocks_per_cu() is the occupancy the runtime reports
 // for a shape (dyn: of the form that hands its rows out at run time).
 bool resident_shape(int64_t V, bool ragged, int* threads, int* chunks);

@@ -22,7 +22,8 @@
 // Preconditions (checked by the host): V % 8 == 0, V/8 <= THREADS*NCHUNK, logits and
 // grad_logits 16-byte aligned with ld % 8 == 0.  The RAGGED form lifts the alignment conditions
 // (any V, any pitch, rows 2-byte aligned, logits and grad_logits sharing their misalignment): it
-// works on the aligned FRAME of a row, the 16-byte blocks that hold it.
+// works on the aligned FRAME of a row, the 16-byte blocks from the start of the 128-byte line that
+// holds its first entry to the block that holds its last.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 #include "dppo_resident_parts.hpp"
@@ -58,14 +59,18 @@ constexpr int kChunkStep = 4;
 constexpr int resident_min_waves(int threads, int nchunk) { return threads == 512 ? 2 : (nchunk <= 16 ? 3 : 2); }
 
 // RAGGED = true: rows that do not start on a 16-byte boundary or whose length is not a multiple
-// of 8 (a vocabulary of 50257 entries; a pitch that is not a multiple of 8).  A row is then
-// handled in its FRAME: the 16-byte blocks from the one holding its first entry to the one holding
-// its last.  With h = (row address mod 16) / 2 the row occupies entries h .. h+V-1 of the frame;
-// entries of the first and last block outside that range (the neighbouring rows' bytes, or up
-// to 14 bytes in front of the first row and 2 behind the last: within an aligned block that holds
-// row data, so in mapped memory) are read, turned into -inf in the resident copy, and never
-// written: the gradient's first and last block, where incomplete, leave as 2-byte stores of the
-// row's own entries, the blocks between them as 16-byte stores.
+// of 8 (a vocabulary of 50257 entries; a pitch that is not a multiple of 8), and rows that start
+// on one but not on a 128-byte line.  A row is then handled in its FRAME: the 16-byte blocks from
+// the start of the 128-byte line holding its first entry to the block holding its last, so that
+// every wave-level access of 1 KiB is eight whole lines, as with aligned rows (a frame that starts
+// at the row's own first block, wherever in a line that is, measured 6-9 % slower: nine lines per
+// access, partial lines at both ends of a store).  With h = (row address mod 128) / 2 the row
+// occupies entries h .. h+V-1 of the frame; what the frame holds in front of the row (up to 126
+// bytes: the end of the previous row, pad columns, or bytes in front of the first row) and in its
+// last block behind it (and up to 2 bytes behind the last row) lies within an aligned line
+// that holds row data, so in mapped memory; it is read, turned into -inf in the resident copy,
+// and never written: of the gradient only complete blocks of the row's own entries leave as
+// 16-byte stores, an incomplete first or last block as 2-byte stores of the row's own entries.
 template <int THREADS, int NCHUNK, bool GRAD, bool DIAG, bool DYN, bool RAGGED>
 __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void dppo_resident_kernel(const KParams p) {
   static_assert(NCHUNK <= 40, "the chunk switch below is written out for up to 40 chunks");
@@ -133,9 +138,9 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     tklp_next = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
   }
   __builtin_amdgcn_sched_barrier(0);
-  // RAGGED: entries of the frame in front of the row, 0..7 (else 0)
+  // RAGGED: entries of the frame in front of the row, 0..63 (else 0)
   auto head_of = [&](int r) -> int {
-    return RAGGED ? static_cast<int>(((reinterpret_cast<uintptr_t>(logits) + static_cast<uint64_t>(r * pitch)) >> 1) & 7u) : 0;
+    return RAGGED ? static_cast<int>(((reinterpret_cast<uintptr_t>(logits) + static_cast<uint64_t>(r * pitch)) >> 1) & 63u) : 0;
   };
   // View of a row for loading (has = false: of zero bytes).  RAGGED: of its frame, up to the end of
   // the 4-byte word holding the row's last entry (the range check works per word).
@@ -217,9 +222,10 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
           if (g0 + i < NCHUNK && g0 + i == ia) {
             if (owner) buf[g0 + i < NCHUNK ? g0 + i : 0] = patch16(buf[g0 + i < NCHUNK ? g0 + i : 0], sub, 0xFF80u);
           }
-          // RAGGED: what the frame's first and last block hold beside the row is -inf from here on
+          // RAGGED: what the frame holds in front of the row (in its first eight blocks at most: threads
+          // 0..7 of chunk 0) and behind it in its last block is -inf from here on
           if (RAGGED && g0 + i == 0) {
-            if (tid == 0 && h > 0) buf[0] = keep16(buf[0], h, 8);
+            if (tid < 8 && h > 8 * tid) buf[0] = keep16(buf[0], min(h - 8 * tid, 8), 8);
           }
           if (RAGGED && g0 + i < NCHUNK && g0 + i >= NCHUNK - kChunkStep - 1 && g0 + i == il) {
             if (tid == tl && t < 8) buf[g0 + i < NCHUNK ? g0 + i : 0] = keep16(buf[g0 + i < NCHUNK ? g0 + i : 0], 0, t);
@@ -350,11 +356,11 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
     // in the order the next row's arithmetic will consume them.
     if (GRAD) {
       char* gr = grad + row * pitch;
-      // RAGGED: the 16-byte stores cover the frame's complete blocks only: the view ends in front of
-      // an incomplete last block, and the thread holding an incomplete first block gives its store
-      // an offset out of range, so that it is dropped.
+      // RAGGED: the 16-byte stores cover the row's complete blocks only: the view ends in front of
+      // an incomplete last block, and the threads holding the blocks in front of the row's first
+      // complete one give their store an offset out of range, so that it is dropped.
       const row_desc_t gout = RAGGED ? make_row_desc(gr - 2 * h, static_cast<uint32_t>((h + p.V) >> 3) * 16u) : make_row_desc(gr, row_bytes);
-      const uint32_t voff0 = (RAGGED && h > 0 && tid == 0) ? 0x80000000u : voff;
+      const uint32_t voff0 = (RAGGED && tid < 8 && h > 8 * tid) ? 0x80000000u : voff;
       const uint32_t sgn = (rc.coef < 0.f) ? 0x80008000u : 0u;
       if (rc.coef == 0.f) {
         // Masked, zero-advantage or ignored row: its gradient is exactly zero whatever the logits
@@ -365,7 +371,7 @@ __global__ __launch_bounds__(THREADS, resident_min_waves(THREADS, NCHUNK)) void 
       if (RAGGED) {
         // the row's own entries of an incomplete first / last block, two bytes at a time
         const row_desc_t gex = make_row_desc(gr, row_bytes);
-        if (tid == 0 && h > 0) store_entries_untracked(gex, grad8(buf[0], rc.kexp, sgn), h, 8, -h);
+        if (tid == (h >> 3) && (h & 7) != 0) store_entries_untracked(gex, grad8(buf[0], rc.kexp, sgn), h & 7, 8, 8 * (h >> 3) - h);
 #pragma unroll
         for (int c = (NCHUNK > kChunkStep + 1 ? NCHUNK - kChunkStep - 1 : 0); c < NCHUNK; ++c) {
           if (c == il) {
@@ -444,8 +450,8 @@ int occupancy_shape(bool grad, bool dyn) {
 
 bool resident_shape(int64_t V, bool ragged, int* threads, int* chunks) {
   if (V < 1024 || (!ragged && V % 8 != 0)) return false;
-  // 16-byte blocks of a row: V / 8; of a row's frame (ragged): between these two, by where the row starts
-  const int64_t nvec_min = ragged ? (V + 7) / 8 : V / 8, nvec_max = ragged ? (V + 14) / 8 : V / 8;
+  // 16-byte blocks of a row: V / 8; of a row's frame (ragged): between these two, by where in a 128-byte line the row starts
+  const int64_t nvec_min = ragged ? (V + 7) / 8 : V / 8, nvec_max = ragged ? (V + 70) / 8 : V / 8;
   // (a shape is only taken with less than kChunkStep chunks of slack: the kernel turns lanes past
   // the row into -inf in its last kChunkStep chunks only)
   // (ragged: the shortest frame may end exactly with chunk C - kChunkStep - 1, whose last block the kernel still looks at)

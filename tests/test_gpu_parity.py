@@ -105,10 +105,11 @@ def test_qwen3_vocab_small_t(name):
     (50257, 50257, "resident"),        # a GPT-2 sized vocabulary: odd, so every row starts 2 bytes further into its block
     (50257, 50264, "resident"),        # ... in a pitch that is a multiple of 8: aligned rows, ragged end
     (151643, 151643, "resident"),      # 512 x 38, odd
-    (155641, 155647, "resident"),      # the longest ragged row: a frame of 19456 blocks at most
-    (155642, 155642, "streaming"),     # one entry more: a frame of 19457 blocks for some rows
-    (8190, 8190, "resident"),          # frames of 1024 or 1025 blocks: 256 threads x 8 chunks, the shorter frame ending with chunk 3
-    (8181, 8181, "resident"),          # frames of 1023 or 1024 blocks: one wave x 16 chunks
+    (155585, 155591, "resident"),      # the longest ragged row: a frame of 19456 blocks at most
+    (155586, 155586, "streaming"),     # one entry more: a frame of 19457 blocks for some rows
+    (8190, 8190, "resident"),          # frames of 1024 to 1032 blocks: 256 threads x 8 chunks, the shortest frame ending with chunk 3
+    (8181, 8181, "streaming"),         # frames of 1023 to 1031 blocks: no shape takes all of them within its slack
+    (100008, 100008, "resident"),      # 16-byte aligned rows that do not start on 128-byte lines: the ragged form, on whole lines
     (1030, 1031, "resident"),          # smallest ragged shapes
 ])
 @pytest.mark.parametrize("variant,K", [(W.BINARY_KL, 0), (W.TOPK_KL, 20)])
