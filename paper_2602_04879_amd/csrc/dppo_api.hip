@@ -189,16 +189,13 @@ dppo_status_t arm_rows_at_run_time(dppo::KParams& p, const dppo_args_t* a, const
 }
 
 // Rows of middle length in groups of rows per workgroup: the number of groups per compute unit from
-// which that form is taken with groups fixed by the workgroup index, and with groups handed out at
-// run time (0: never).  A group is 23 us of a compute unit's time: with few of them a call ends
+// which that form is taken.  A group is 23 us of a compute unit's time: with few of them a call ends
 // sooner on the one-row shapes, whose unit of work is a row.  Measured, per shape: groups of 4
 // rows (V up to 32768) gain 1 % at 16 groups per compute unit, 5 % at 32, 7.5 % at 64, and lose
-// below; groups of 2 (up to 65536) gain 1.5-7 % from 32 on; groups of 3 (up to 49152, where the
-// one-row shape is a single workgroup of 96 KiB rows per compute unit) gain 8-14 % at any size.
-struct MultiThresholds { int64_t fixed, dyn; };
-MultiThresholds multi_thresholds(int rows) {
-  return rows == 3 ? MultiThresholds{2, 12} : rows == 4 ? MultiThresholds{0, 24} : MultiThresholds{0, 32};
-}
+// below; groups of 2 (up to 65536) gain 1.5-7 % from 32 on; groups of 3 (up to 49152, against
+// two workgroups of 512 threads x 12 chunks per compute unit) are even up to 8 groups per compute
+// unit and gain 0-3 % at 16, 3.5-6 % at 32.
+int64_t multi_min_groups(int rows) { return rows == 3 ? 16 : rows == 4 ? 24 : 32; }
 
 // Launch the loss kernel of one (already validated) call.  Afterwards the scalar loss is
 // loss_scale times the sum of fin[0 .. *fin_n) (per-workgroup partial sums, or per-row terms).
@@ -240,9 +237,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     int m_rows = 0, m_chunks = 0;
     const bool m_shape = resident && aligned && grad && dppo::resident_multi_shape(a->V, &m_rows, &m_chunks);
     const int64_t m_groups = m_shape ? (a->T + m_rows - 1) / m_rows : 0;
-    const MultiThresholds m_from = multi_thresholds(m_rows);
-    const bool multi_dyn = m_shape && sc.row_loss && !(a->flags & DPPO_FLAG_STATIC_ROWS) && cus % 8 == 0 && m_groups >= m_from.dyn * cus;
-    const bool multi = multi_dyn || (m_shape && sc.row_loss && !(a->flags & DPPO_FLAG_STATIC_ROWS) && m_from.fixed > 0 && m_groups >= m_from.fixed * cus);
+    const bool multi = m_shape && sc.counters && !(a->flags & DPPO_FLAG_STATIC_ROWS) && m_groups >= multi_min_groups(m_rows) * cus;
     if (resident && !multi && prefer_lines) {
       ragged = true;
       r_threads = l_threads;
@@ -286,10 +281,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     } else if (resident && multi) {
       // rows of middle length, forward + backward: groups of rows per workgroup, one workgroup per compute unit
       nparts = static_cast<int>(cus);
-      p.row_loss = sc.row_loss;
-      *fin = sc.row_loss;
-      *fin_n = static_cast<int>(a->T);
-      if (multi_dyn && arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
+      if (arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
       if (dppo::launch_resident_multi(p, m_rows, m_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident_multi";
       return DPPO_OK;

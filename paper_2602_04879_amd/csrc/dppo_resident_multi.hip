@@ -15,13 +15,14 @@
 //                one more barrier;
 //   gradient     all ROWS x RC chunks in one run of stores, then the next group in one run of loads.
 //
-// With many groups per compute unit they are handed out at run time (one atomic counter, drawn one
-// group ahead: the dies do not run at one speed); with few, fixed by the workgroup index (a unit
-// of hand-out that is an eighth of a compute unit's whole share balances worse than none).  The
-// loss terms go to one slot per row either way.  Rows past T in the last group are views of zero
+// Groups are handed out at run time (one atomic counter, drawn one group ahead: the dies do not run
+// at one speed); the loss terms go to one slot per row.  The host takes this form only when a
+// compute unit gets many groups: a group is 23 us of its time, and with few of them a call ends
+// sooner on the one-row shapes, whose unit of work is a row (groups fixed by the workgroup index
+// were measured too: never ahead of both).  Rows past T in the last group are views of zero
 // bytes: nothing is read or written for them.
 // Preconditions (checked by the host): V % 8 == 0, 512 (RC - 2) < V / 8 <= 512 RC, logits and
-// grad_logits 16-byte aligned with ld % 8 == 0, p.row_loss set (p.row_counters: groups at run time).
+// grad_logits 16-byte aligned with ld % 8 == 0, p.row_counters and p.row_loss set.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 #include "dppo_resident_parts.hpp"
@@ -34,7 +35,7 @@ constexpr int kMThreads = 512;
 // only with less slack than that).
 constexpr int kMTailChunks = 2;
 
-template <int ROWS, int RC, bool DIAG, bool DYN>
+template <int ROWS, int RC, bool DIAG>
 __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const KParams p) {
   constexpr int NW = kMThreads / kWave, NCHUNK = ROWS * RC;
   static_assert(ROWS >= 2 && ROWS <= NW, "one epilogue wave per row of the group");
@@ -60,21 +61,16 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
 
   u32x4 buf[NCHUNK];                            // the resident group
 
-  // DYN: groups handed out at run time, drawn from a counter one group ahead.  Otherwise fixed by
-  // the workgroup index (the workgroups of one die take neighbouring groups).
-  int grp = first_row_of_workgroup();
-  int next = grp + static_cast<int>(gridDim.x);
-  if (DYN) {
-    if (tid == 0) {
-      sh_grp[0] = atomicAdd(p.row_counters, 1);
-      sh_grp[1] = atomicAdd(p.row_counters, 1);
-    }
-    __syncthreads();
-    grp = uniform_i(sh_grp[0]);
-    next = uniform_i(sh_grp[1]);
-    __syncthreads();
+  // groups are handed out at run time, drawn from a counter one group ahead
+  if (tid == 0) {
+    sh_grp[0] = atomicAdd(p.row_counters, 1);
+    sh_grp[1] = atomicAdd(p.row_counters, 1);
   }
-  // (a workgroup without a group forms no address)
+  __syncthreads();
+  int grp = uniform_i(sh_grp[0]);
+  int next = uniform_i(sh_grp[1]);
+  __syncthreads();
+  // (a workgroup that starts when every group has been handed out forms no address)
   if (grp >= ngroups) return;
 
   // Fetched one group ahead, before the group's own loads (so that nothing at the top of a group
@@ -117,7 +113,7 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
     if (more) a_vec_next = load_ids(next);
     // request the group after next now; the answer is looked at before this group's barrier
     int drawn = 0;
-    if (DYN && more && tid == 0) drawn = atomicAdd(p.row_counters, 1);
+    if (more && tid == 0) drawn = atomicAdd(p.row_counters, 1);
     const int tkid = tkid_next;
     const float tklp = tklp_next;
     if (more) load_topk(next, tkid_next, tklp_next);
@@ -204,9 +200,9 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
       tk.z = __uint_as_float(tkz_bits << 16);
       if (elive) pre = row_pre(rs, tk, p.K > 0, p.relax_log_alpha);
     }
-    if (DYN && tid == 0) sh_grp[par] = more ? drawn : kNone;
+    if (tid == 0) sh_grp[par] = more ? drawn : kNone;
     __syncthreads();
-    const int next2 = DYN ? uniform_i(sh_grp[par]) : (more ? next + static_cast<int>(gridDim.x) : kNone);
+    const int next2 = uniform_i(sh_grp[par]);
     par ^= 1;
     RowOut ro;
     if (wid < ROWS) {
@@ -308,19 +304,17 @@ bool resident_multi_shape(int64_t V, int* rows, int* chunks) {
 }
 
 hipError_t launch_resident_multi(const KParams& p, int rows, int chunks, int grid, hipStream_t s) {
-  if (!p.grad || !p.row_loss) return hipErrorInvalidValue;
-  const bool diag = p.diag != nullptr, dyn = p.row_counters != nullptr;
+  if (!p.grad || !p.row_loss || !p.row_counters) return hipErrorInvalidValue;
+  const bool diag = p.diag != nullptr;
   const dim3 g(grid), b(kMThreads);
-#define DPPO_FORM(R, C, D, Y) hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, D, Y>), g, b, 0, s, p)
 #define DPPO_LAUNCH(R, C) \
   if (rows == R && chunks == C) { \
-    if (diag) { if (dyn) DPPO_FORM(R, C, true, true); else DPPO_FORM(R, C, true, false); } \
-    else      { if (dyn) DPPO_FORM(R, C, false, true); else DPPO_FORM(R, C, false, false); } \
+    if (diag) hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, true>), g, b, 0, s, p); \
+    else hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, false>), g, b, 0, s, p); \
     return hipGetLastError(); \
   }
   DPPO_MULTI_SHAPES(DPPO_LAUNCH)
 #undef DPPO_LAUNCH
-#undef DPPO_FORM
   return hipErrorInvalidValue;
 }
 

@@ -235,12 +235,11 @@ def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
     _say(f"       {st}")
 
 
-@pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(30000, 4, 24), (32768, 4, 24), (41000, 3, 12), (49152, 3, 2), (50304, 2, 32),
+@pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(30000, 4, 24), (32768, 4, 24), (41000, 3, 16), (49152, 3, 16), (50304, 2, 32),
                                                              (57352, 2, 32), (65536, 2, 32)])
 def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, groups_per_cu):
     """Rows of middle length, forward + backward, many rows per compute unit: groups of 4 / 3 / 2
-    consecutive rows per workgroup, handed out at run time (V = 49152: the few groups of a short
-    call, fixed by the workgroup index), the last group incomplete.  Ignored, zero-advantage and
+    consecutive rows per workgroup, handed out at run time, the last group incomplete.  Ignored, zero-advantage and
     masked rows, sampled tokens at both ends of the row and on chunk borders; per-token outputs
     against the oracle on 3000 rows (the first and last groups among them), gradients on a sample
     of those; run after run bit for bit the same; in place; and the one-row form (other shapes,
@@ -815,9 +814,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
               # rows handed out at run time (a counter-clearing kernel in front, no memset), and the long-row kernel
               W.Workload("graph_dyn", 1, 4 * cus + 5, 100000, W.TOPK_KL, 0.05, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=63),
               W.Workload("graph_long", 1, 40, 200000, W.BINARY_TV, 0.2, logit_std=3.0, noise_std=1.0, adv="normal", seed=64),
-              # groups of rows per workgroup: fixed by the workgroup index (2 per compute unit), and handed out at run time
-              W.Workload("graph_groups", 1, 2 * cus * 3 + 2, 49152, W.BINARY_KL, 0.05, logit_std=3.0, noise_std=1.0, adv="normal", seed=65),
-              W.Workload("graph_groups_dyn", 1, 12 * cus * 3 + 1, 49152, W.TOPK_TV, 0.2, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=66)]
+              # groups of rows per workgroup, handed out at run time
+              W.Workload("graph_groups_dyn", 1, 16 * cus * 3 + 1, 49152, W.TOPK_TV, 0.2, K=20, logit_std=3.0, noise_std=1.0, adv="normal", seed=66)]
     batches = [W.make_batch(w, DEV, shift_sampled=1.0) for w in shapes]
     eager = []
     for b in batches:
