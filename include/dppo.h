@@ -234,7 +234,7 @@ size_t dppo_args_size(void);
 /* Name of the kernel path the last successful dppo_loss_* call on this thread chose:
  * "resident" (row held in registers between the two passes), "resident_long" (rows of 155657 ..
  * 262144 entries with the gradient: registers, LDS and a short tail read twice), "resident_multi"
- * (rows of 24584 .. 65536 entries with the gradient, many of them per call: groups of two to four
+ * (rows of 16392 .. 65536 entries with the gradient, many of them per call: groups of two to six
  * rows held in registers), "streaming" (row re-read),
  * "fullvocab" (the two-row kernel of the DPPO_FULL_* variants) or "fullvocab_resident" (their
  * backward, and the forward-only TV form, on long aligned rows: the trainer's row held in

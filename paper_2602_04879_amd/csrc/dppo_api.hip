@@ -192,10 +192,10 @@ dppo_status_t arm_rows_at_run_time(dppo::KParams& p, const dppo_args_t* a, const
 // which that form is taken.  A group is 23 us of a compute unit's time: with few of them a call ends
 // sooner on the one-row shapes, whose unit of work is a row.  Measured, per shape: groups of 4
 // rows (V up to 32768) gain 1 % at 16 groups per compute unit, 5 % at 32, 7.5 % at 64, and lose
-// below; groups of 2 (up to 65536) gain 1.5-7 % from 32 on; groups of 3 (up to 49152, against
-// two workgroups of 512 threads x 12 chunks per compute unit) are even up to 8 groups per compute
-// unit and gain 0-3 % at 16, 3.5-6 % at 32.
-int64_t multi_min_groups(int rows) { return rows == 3 ? 16 : rows == 4 ? 24 : 32; }
+// below; groups of 6 (up to 24576) are even at 16, gain 4 % at 24, 6 % at 32; groups of 2 (up to
+// 65536) gain 1.5-7 % from 32 on; groups of 3 (up to 40960 / 49152) are even at 8-12 groups per
+// compute unit and gain 0-3 % at 16, 3.5-9 % at 32.
+int64_t multi_min_groups(int rows) { return rows == 3 ? 16 : rows == 2 ? 32 : 24; }
 
 // Launch the loss kernel of one (already validated) call.  Afterwards the scalar loss is
 // loss_scale times the sum of fin[0 .. *fin_n) (per-workgroup partial sums, or per-row terms).

@@ -32,7 +32,7 @@ hipError_t launch_resident_long(const KParams& p, int chunks, int grid, hipStrea
 // consecutive rows of `chunks` x 512 x 16 bytes each per workgroup, one workgroup per compute unit,
 // groups handed out at run time, one loss term per row (p.row_counters and p.row_loss must be set).  resident_multi_shape()
 // gives the group shape for a row of V entries, false where the form does not apply (V not a
-// multiple of 8, or not within two chunks below 32768, 49152, 57344 or 65536).  Needs 16-byte aligned rows of logits and grad.
+// multiple of 8, or not within two chunks of 1024 entries below 24576, 32768, 40960, 49152, 57344 or 65536).  Needs 16-byte aligned rows of logits and grad.
 bool resident_multi_shape(int64_t V, int* rows, int* chunks);
 hipError_t launch_resident_multi(const KParams& p, int rows, int chunks, int grid, hipStream_t s);
 

@@ -56,10 +56,11 @@ constexpr int kChunkStep = 4;
 // workgroup of two waves per SIMD, except the shortest (12 chunks: 48 registers of row data; left
 // to itself the compiler takes 130 registers, two over the limit for a second workgroup per compute
 // unit, which is worth 8-14 % on those rows of 96 KiB); the 256-thread shapes (one wave per SIMD
-// and workgroup) keep three workgroups per compute unit up to 16 chunks (a budget of 168
+// and workgroup) keep four workgroups per compute unit up to 12 chunks (the 12-chunk shape too
+// compiled to 130 registers: +3..8 % on rows of 36-48 KiB) and three with 16 chunks (a budget of 168
 // registers; left to itself the compiler lands within a register or two of that limit, on either
-// side; a fourth workgroup, 128 registers, spills and measured 7-12 % slower).
-constexpr int resident_min_waves(int threads, int nchunk) { return threads == 512 ? (nchunk <= 12 ? 4 : 2) : (nchunk <= 16 ? 3 : 2); }
+// side; a fourth workgroup there, 128 registers, spills and measured 7-12 % slower).
+constexpr int resident_min_waves(int threads, int nchunk) { return threads == 512 ? (nchunk <= 12 ? 4 : 2) : (nchunk <= 12 ? 4 : nchunk <= 16 ? 3 : 2); }
 
 // RAGGED = true: rows that do not start on a 16-byte boundary or whose length is not a multiple
 // of 8 (a vocabulary of 50257 entries; a pitch that is not a multiple of 8), and rows that start

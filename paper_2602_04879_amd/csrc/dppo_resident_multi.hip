@@ -1,4 +1,4 @@
-// Register-resident kernel for rows of middle length (24 584 .. 65 536 entries, 48 .. 128 KiB):
+// Register-resident kernel for rows of middle length (16 392 .. 65 536 entries, 32 .. 128 KiB):
 // fused forward+backward, SEVERAL rows per workgroup.
 //
 // The memory system serves a compute unit best in long bursts of one direction: the kernel for
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
     // With the diagnostics the float64 arithmetic of the epilogue finds no registers beside the
     // resident group: an epilogue wave parks its last chunks in shared memory around it (its own
     // 16 bytes per lane and chunk, no synchronisation) instead of spilling to scratch memory.
-    constexpr int kPark = DIAG ? 16 : 0;
+    constexpr int kPark = DIAG ? (NCHUNK > 32 ? 20 : 16) : 0;
     __shared__ u32x4 sh_park[kPark > 0 ? ROWS * kPark * kWave : 1];
     if (kPark > 0 && wid < ROWS) {
 #pragma unroll
@@ -287,11 +287,12 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
 
 }  // namespace
 
-// (rows per group, chunks per row): rows of up to 32768, 49152, 57344, 65536 entries, each taken
-// with less than two chunks of slack (lanes past the end of a row idle: at a quarter of slack the
-// form measured no faster than one row per workgroup).  (Eight rows of up to 16384 entries measured
-// 4 % faster than one row per workgroup only from 64 groups per compute unit on: not instantiated.)
-#define DPPO_MULTI_SHAPES(X) X(4, 8) X(3, 12) X(2, 14) X(2, 16)
+// (rows per group, chunks per row): rows of up to 24576, 32768, 40960, 49152, 57344, 65536 entries,
+// each taken with less than two chunks of slack (lanes past the end of a row idle: at a quarter of
+// slack the form measured no faster than one row per workgroup).  (Eight rows of up to 16384 entries
+// measured 4 % faster than one row per workgroup only from 64 groups per compute unit on: not
+// instantiated.)
+#define DPPO_MULTI_SHAPES(X) X(6, 6) X(4, 8) X(3, 10) X(3, 12) X(2, 14) X(2, 16)
 
 // Rows per group and chunks per row for a row of V entries, false where this form does not apply.
 bool resident_multi_shape(int64_t V, int* rows, int* chunks) {

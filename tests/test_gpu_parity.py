@@ -235,10 +235,10 @@ def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
     _say(f"       {st}")
 
 
-@pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(30000, 4, 24), (32768, 4, 24), (41000, 3, 16), (49152, 3, 16), (50304, 2, 32),
+@pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(24576, 6, 24), (20488, 6, 24), (30000, 4, 24), (32768, 4, 24), (40960, 3, 16), (41000, 3, 16), (49152, 3, 16), (50304, 2, 32),
                                                              (57352, 2, 32), (65536, 2, 32)])
 def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, groups_per_cu):
-    """Rows of middle length, forward + backward, many rows per compute unit: groups of 4 / 3 / 2
+    """Rows of middle length, forward + backward, many rows per compute unit: groups of 6 / 4 / 3 / 2
     consecutive rows per workgroup, handed out at run time, the last group incomplete.  Ignored, zero-advantage and
     masked rows, sampled tokens at both ends of the row and on chunk borders; per-token outputs
     against the oracle on 3000 rows (the first and last groups among them), gradients on a sample
