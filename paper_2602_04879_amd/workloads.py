@@ -85,6 +85,12 @@ WORKLOADS = {
     # count (the headline's, twice over): the kernel that takes several rows per workgroup.
     "c9_vocab32k_binary_tv": Workload("c9_vocab32k_binary_tv", 64, 1024, 32768, BINARY_TV, 0.1, logit_std=3.0,
                                       noise_std=0.1, boost_frac=0.01, boost=8.0, adv="normal", seed=1009),
+    # The headline recipe with the vocabulary cut to an odd length (a trainer that slices the padding
+    # of the embedding matrix off the logits), half the rows: no row starts on a 16-byte boundary but
+    # every eighth: the ragged form of the register-resident kernel.
+    "c10_vocab151643_binary_tv": Workload("c10_vocab151643_binary_tv", 16, 1024, 151643, BINARY_TV, 0.2,
+                                          logit_std=3.0, noise_std=0.05, zipf_s=1.1, drift_frac=0.05, drift_std=1.5,
+                                          adv="group_norm", group=8, seed=1010),
     # The headline shape entered one step earlier: final hidden states of a d = 4096 model (the
     # Qwen3-8B size) and its lm_head weight; the logits exist one chunk of tokens at a time.
     "c7_qwen3_lmhead_binary_tv": Workload("c7_qwen3_lmhead_binary_tv", 16, 2048, 151936, BINARY_TV, 0.2, d_model=4096,

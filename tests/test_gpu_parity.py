@@ -710,7 +710,7 @@ def _full_size_properties(b, res):
 
 
 @pytest.mark.parametrize("name,path", [("c3_qwen3_binary_tv", "resident"), ("c4_qwen3_topk_tv", "resident"), ("c8_vocab256k_binary_tv", "resident_long"),
-                                       ("c9_vocab32k_binary_tv", "resident_multi")])
+                                       ("c9_vocab32k_binary_tv", "resident_multi"), ("c10_vocab151643_binary_tv", "resident")])
 def test_full_size_headline_configs(name, path):
     w = W.WORKLOADS[name]
     _say(f"[case] full size {name} T={w.T} V={w.V}")
