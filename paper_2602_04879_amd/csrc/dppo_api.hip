@@ -235,7 +235,8 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
     // Rows of middle length, forward + backward, when rows can be handed out at run time and every
     // compute unit gets several groups of them: several rows per workgroup.
     int m_rows = 0, m_chunks = 0;
-    const bool m_shape = resident && aligned && grad && dppo::resident_multi_shape(a->V, &m_rows, &m_chunks);
+    const bool m_ragged = !on_lines;        // (resident and not aligned: the ragged form applies, see above)
+    const bool m_shape = resident && grad && ragged_ok && dppo::resident_multi_shape(a->V, m_ragged, &m_rows, &m_chunks);
     const int64_t m_groups = m_shape ? (a->T + m_rows - 1) / m_rows : 0;
     const bool multi = m_shape && sc.counters && !(a->flags & DPPO_FLAG_STATIC_ROWS) && m_groups >= multi_min_groups(m_rows) * cus;
     if (resident && !multi && prefer_lines) {
@@ -282,7 +283,7 @@ dppo_status_t launch_loss(const dppo_args_t* a, bool grad, const LossScratch& sc
       // rows of middle length, forward + backward: groups of rows per workgroup, one workgroup per compute unit
       nparts = static_cast<int>(cus);
       if (arm_rows_at_run_time(p, a, sc, fin, fin_n, s) != DPPO_OK) return DPPO_ERR_LAUNCH;
-      if (dppo::launch_resident_multi(p, m_rows, m_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
+      if (dppo::launch_resident_multi(p, m_ragged, m_rows, m_chunks, nparts, s) != hipSuccess) return DPPO_ERR_LAUNCH;
       g_last_path = "resident_multi";
       return DPPO_OK;
     } else if (resident) {

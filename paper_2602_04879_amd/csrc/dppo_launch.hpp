@@ -33,8 +33,9 @@ hipError_t launch_resident_long(const KParams& p, int chunks, int grid, hipStrea
 // groups handed out at run time, one loss term per row (p.row_counters and p.row_loss must be set).  resident_multi_shape()
 // gives the group shape for a row of V entries, false where the form does not apply (V not a
 // multiple of 8, or not within two chunks of 1024 entries below 24576, 32768, 40960, 49152, 57344 or 65536).  Needs 16-byte aligned rows of logits and grad.
-bool resident_multi_shape(int64_t V, int* rows, int* chunks);
-hipError_t launch_resident_multi(const KParams& p, int rows, int chunks, int grid, hipStream_t s);
+// ragged: as for the one-row kernel.
+bool resident_multi_shape(int64_t V, bool ragged, int* rows, int* chunks);
+hipError_t launch_resident_multi(const KParams& p, bool ragged, int rows, int chunks, int grid, hipStream_t s);
 
 // Two-row kernel of the exact full-vocabulary variants (tv: total variation, else KL).
 hipError_t launch_fullvocab(const KParams& p, bool tv, bool grad, int threads, int grid, hipStream_t s);

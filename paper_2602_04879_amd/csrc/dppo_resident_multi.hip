@@ -22,7 +22,9 @@
 // were measured too: never ahead of both).  Rows past T in the last group are views of zero
 // bytes: nothing is read or written for them.
 // Preconditions (checked by the host): V % 8 == 0, 512 (RC - 2) < V / 8 <= 512 RC, logits and
-// grad_logits 16-byte aligned with ld % 8 == 0, p.row_counters and p.row_loss set.
+// grad_logits 16-byte aligned with ld % 8 == 0 (the RAGGED form: any V and pitch, rows 2-byte
+// aligned, logits and grad_logits with the same address modulo 16, every frame within the shape),
+// p.row_counters and p.row_loss set.
 #include "dppo_common.hpp"
 #include "dppo_launch.hpp"
 #include "dppo_resident_parts.hpp"
@@ -35,7 +37,13 @@ constexpr int kMThreads = 512;
 // only with less slack than that).
 constexpr int kMTailChunks = 2;
 
-template <int ROWS, int RC, bool DIAG>
+// RAGGED = true: rows that do not start on a 128-byte line, or whose length is not a multiple of 8,
+// handled as in the one-row kernel's ragged form: a row in its FRAME, the aligned 16-byte blocks
+// from the start of the line holding its first entry (h = (row address mod 128) / 2 entries in
+// front of it) to the block holding its last; what the frame holds beside the row is read, turned
+// into -inf in the resident copy, and never written (incomplete first / last blocks of the
+// gradient leave as 2-byte stores of the row's own entries).
+template <int ROWS, int RC, bool DIAG, bool RAGGED>
 __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const KParams p) {
   constexpr int NW = kMThreads / kWave, NCHUNK = ROWS * RC;
   static_assert(ROWS >= 2 && ROWS <= NW, "one epilogue wave per row of the group");
@@ -49,7 +57,7 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
   int par = 0;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wid = uniform_i(tid / kWave);
-  const int nvec = p.V >> 3;
+  const int nvec_aligned = p.V >> 3;
   const uint32_t row_bytes = static_cast<uint32_t>(p.V) * 2u;
   const uint32_t voff = static_cast<uint32_t>(tid) * 16u;
   const u32x4 neg_inf = {kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair};
@@ -89,13 +97,20 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
       lp = p.tk_lp[static_cast<int64_t>(row) * p.K + lane];
     }
   };
-  // One run of loads: the ROWS x RC chunks of group g (has = false: views of zero bytes).
+  // RAGGED: entries of the frame in front of the row, 0..63 (else 0)
+  auto head_of = [&](int r) -> int {
+    return RAGGED ? static_cast<int>(((reinterpret_cast<uintptr_t>(logits) + static_cast<uint64_t>(r * pitch)) >> 1) & 63u) : 0;
+  };
+  // One run of loads: the ROWS x RC chunks of group g (has = false: views of zero bytes).  RAGGED:
+  // views of the rows' frames, up to the end of the 4-byte word holding a row's last entry.
   auto load_group = [&](int g, bool has) {
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
       const int row = (has ? g : 0) * ROWS + r;
       const bool ok = has && row < p.T;
-      const row_rsrc_t zr = make_row_rsrc(logits + (ok ? row : 0) * pitch, ok ? row_bytes : 0u);
+      const int hr = ok ? head_of(row) : 0;
+      const row_rsrc_t zr = make_row_rsrc(logits + (ok ? row : 0) * pitch - 2 * hr,
+                                          ok ? (RAGGED ? ((static_cast<uint32_t>(hr + p.V) * 2u + 3u) & ~3u) : row_bytes) : 0u);
 #pragma unroll
       for (int i = 0; i < RC; ++i) buf[r * RC + i] = row_load16<false>(zr, voff, i * kStride);
     }
@@ -148,10 +163,15 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
     for (int r = 0; r < ROWS; ++r) {
       const int a = __builtin_amdgcn_readlane(a_vec, r);
       const bool live = (a >= 0 && a < p.V);
-      const int avec = a >> 3;
+      // RAGGED: the row in its frame: h entries in front of it, nvec blocks in all, the last one
+      // (block vl = chunk il of thread tl) holding t of the row's entries
+      const int h = head_of(row0 + r);
+      const int nvec = RAGGED ? (h + p.V + 7) >> 3 : nvec_aligned;
+      const int vl = nvec - 1, il = vl / kMThreads, tl = vl - il * kMThreads, t = h + p.V - 8 * vl;
+      const int avec = (a + h) >> 3;
       const int ia = live ? avec / kMThreads : -1;             // chunk of the row holding a_t (uniform)
       const bool owner = live && (avec - ia * kMThreads == tid);
-      const int sub = a & 7;
+      const int sub = (a + h) & 7;
       PackedRowStat<DIAG> ps;
 #pragma unroll
       for (int g0 = 0; g0 < RC; g0 += 2) {
@@ -161,6 +181,14 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
         for (int i = 0; i < 2; ++i) {
           if (g0 + i == ia) {
             if (owner) buf[r * RC + g0 + i] = patch16(buf[r * RC + g0 + i], sub, 0xFF80u);
+          }
+          // RAGGED: what the frame holds in front of the row (threads 0..7 of chunk 0) and behind it
+          // in its last block is -inf from here on
+          if (RAGGED && g0 + i == 0) {
+            if (tid < 8 && h > 8 * tid) buf[r * RC] = keep16(buf[r * RC], min(h - 8 * tid, 8), 8);
+          }
+          if (RAGGED && g0 + i >= RC - kMTailChunks - 1 && g0 + i == il) {
+            if (tid == tl && t < 8) buf[r * RC + g0 + i] = keep16(buf[r * RC + g0 + i], 0, t);
           }
         }
         u32x4 v[2];
@@ -187,7 +215,7 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
     // With the diagnostics the float64 arithmetic of the epilogue finds no registers beside the
     // resident group: an epilogue wave parks its last chunks in shared memory around it (its own
     // 16 bytes per lane and chunk, no synchronisation) instead of spilling to scratch memory.
-    constexpr int kPark = DIAG ? (NCHUNK > 32 ? 20 : 16) : 0;
+    constexpr int kPark = DIAG ? (NCHUNK > 32 ? (RAGGED ? 24 : 20) : 16) : 0;
     __shared__ u32x4 sh_park[kPark > 0 ? ROWS * kPark * kWave : 1];
     if (kPark > 0 && wid < ROWS) {
 #pragma unroll
@@ -254,15 +282,34 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
       const int row = row0 + r;
       const bool ok = row < p.T;
       const float coef = uniform_f(sh_rc[r].coef), kexp = uniform_f(sh_rc[r].kexp);
-      const row_desc_t gout = make_row_desc(grad + (ok ? row : 0) * pitch, ok ? row_bytes : 0u);
+      char* gr = grad + (ok ? row : 0) * pitch;
+      // RAGGED: the 16-byte stores cover the row's complete blocks only: the view ends in front of
+      // an incomplete last block, and the threads holding the blocks in front of the row's first
+      // complete one give their store an offset out of range, so that it is dropped.
+      const int h = ok ? head_of(row) : 0;
+      const row_desc_t gout = RAGGED ? make_row_desc(gr - 2 * h, ok ? static_cast<uint32_t>((h + p.V) >> 3) * 16u : 0u)
+                                     : make_row_desc(gr, ok ? row_bytes : 0u);
+      const uint32_t voff0 = (RAGGED && tid < 8 && h > 8 * tid) ? 0x80000000u : voff;
       const uint32_t sgn = (coef < 0.f) ? 0x80008000u : 0u;
       if (coef == 0.f) {
         // masked, zero-advantage or ignored row: exact zeros (2^-inf) whatever the logits hold
 #pragma unroll
         for (int i = 0; i < RC; ++i) buf[r * RC + i] = neg_inf;
       }
+      if (RAGGED && ok) {
+        // the row's own entries of an incomplete first / last block, two bytes at a time
+        const row_desc_t gex = make_row_desc(gr, row_bytes);
+        const int vl = ((h + p.V + 7) >> 3) - 1, il = vl / kMThreads, tl = vl - il * kMThreads, t = h + p.V - 8 * vl;
+        if (tid == (h >> 3) && (h & 7) != 0) store_entries_untracked(gex, grad8(buf[r * RC], kexp, sgn), h & 7, 8, 8 * (h >> 3) - h);
 #pragma unroll
-      for (int i = 0; i < RC; ++i) row_store16_untracked(gout, voff, i * kStride, grad8(buf[r * RC + i], kexp, sgn));
+        for (int c = (RC > kMTailChunks + 1 ? RC - kMTailChunks - 1 : 0); c < RC; ++c) {
+          if (c == il) {
+            if (tid == tl && t < 8) store_entries_untracked(gex, grad8(buf[r * RC + c], kexp, sgn), 0, t, 8 * vl - h);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < RC; ++i) row_store16_untracked(gout, i == 0 ? voff0 : voff, i * kStride, grad8(buf[r * RC + i], kexp, sgn));
     }
     // (a refill can only reuse its chunk's registers once the store has been given them)
     __builtin_amdgcn_sched_barrier(0);
@@ -273,7 +320,7 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
       const int a = __builtin_amdgcn_readlane(a_vec, r);
-      if (a >= 0 && a < p.V && ((a >> 3) & (kMThreads - 1)) == tid) {
+      if (a >= 0 && a < p.V && (((a + head_of(row0 + r)) >> 3) & (kMThreads - 1)) == tid) {
         if (sh_rc[r].coef != 0.f) {
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           reinterpret_cast<uint16_t*>(grad + (row0 + r) * pitch)[a] = float_to_bf16_bits(sh_rc[r].g_a);
@@ -295,27 +342,32 @@ __global__ __launch_bounds__(kMThreads, 2) void dppo_resident_multi_kernel(const
 #define DPPO_MULTI_SHAPES(X) X(6, 6) X(4, 8) X(3, 10) X(3, 12) X(2, 14) X(2, 16)
 
 // Rows per group and chunks per row for a row of V entries, false where this form does not apply.
-bool resident_multi_shape(int64_t V, int* rows, int* chunks) {
-  if (V % 8 != 0) return false;
-  const int64_t nvec = V / 8;
-#define DPPO_TRY(R, C) if (nvec <= static_cast<int64_t>(kMThreads) * C) { *rows = R; *chunks = C; return nvec > static_cast<int64_t>(kMThreads) * (C - kMTailChunks); }
+bool resident_multi_shape(int64_t V, bool ragged, int* rows, int* chunks) {
+  if (!ragged && V % 8 != 0) return false;
+  // 16-byte blocks of a row; of a row's frame (ragged): between these two, by where in a 128-byte line the row starts
+  const int64_t nvec_min = ragged ? (V + 7) / 8 : V / 8, nvec_max = ragged ? (V + 70) / 8 : V / 8;
+  // (the kernel would also take a frame that ends exactly with chunk C - kMTailChunks - 1; with two
+  // chunks of slack it is no faster than one row per workgroup, so the host does not ask for that)
+#define DPPO_TRY(R, C) if (nvec_max <= static_cast<int64_t>(kMThreads) * C) { *rows = R; *chunks = C; return nvec_min > static_cast<int64_t>(kMThreads) * (C - kMTailChunks); }
   DPPO_MULTI_SHAPES(DPPO_TRY)
 #undef DPPO_TRY
   return false;
 }
 
-hipError_t launch_resident_multi(const KParams& p, int rows, int chunks, int grid, hipStream_t s) {
+hipError_t launch_resident_multi(const KParams& p, bool ragged, int rows, int chunks, int grid, hipStream_t s) {
   if (!p.grad || !p.row_loss || !p.row_counters) return hipErrorInvalidValue;
   const bool diag = p.diag != nullptr;
   const dim3 g(grid), b(kMThreads);
+#define DPPO_FORM(R, C, D, G) hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, D, G>), g, b, 0, s, p)
 #define DPPO_LAUNCH(R, C) \
   if (rows == R && chunks == C) { \
-    if (diag) hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, true>), g, b, 0, s, p); \
-    else hipLaunchKernelGGL((dppo_resident_multi_kernel<R, C, false>), g, b, 0, s, p); \
+    if (ragged) { if (diag) DPPO_FORM(R, C, true, true); else DPPO_FORM(R, C, false, true); } \
+    else        { if (diag) DPPO_FORM(R, C, true, false); else DPPO_FORM(R, C, false, false); } \
     return hipGetLastError(); \
   }
   DPPO_MULTI_SHAPES(DPPO_LAUNCH)
 #undef DPPO_LAUNCH
+#undef DPPO_FORM
   return hipErrorInvalidValue;
 }
 

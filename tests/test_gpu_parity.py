@@ -236,7 +236,9 @@ def test_long_rows_handed_out_at_run_time_and_fixed_with_special_rows(V):
 
 
 @pytest.mark.parametrize("V,rows_per_group,groups_per_cu", [(24576, 6, 24), (20488, 6, 24), (30000, 4, 24), (32768, 4, 24), (40960, 3, 16), (41000, 3, 16), (49152, 3, 16), (50304, 2, 32),
-                                                             (57352, 2, 32), (65536, 2, 32)])
+                                                             (57352, 2, 32), (65536, 2, 32),
+                                                             # the ragged form: odd vocabularies, and rows that are 16-byte aligned but not on 128-byte lines
+                                                             (24499, 6, 24), (32003, 4, 24), (40001, 3, 16), (50257, 2, 32), (32008, 4, 24)])
 def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, groups_per_cu):
     """Rows of middle length, forward + backward, many rows per compute unit: groups of 6 / 4 / 3 / 2
     consecutive rows per workgroup, handed out at run time, the last group incomplete.  Ignored, zero-advantage and
@@ -256,9 +258,12 @@ def test_groups_of_rows_per_workgroup_with_special_rows(V, rows_per_group, group
     for t, a in zip(range(2, 2 + 3 * len(special), 3), special):
         b["sampled_ids"][t] = max(0, min(a, V - 1))
         b["sampled_ids"][T - 1 - t] = max(0, min(a, V - 1))      # and in the last groups
-    runs = [B.run_batch(b, diagnostics=True) for _ in range(2)]
+    pad = 64
+    gbuf = torch.full((T * V + 2 * pad,), 7.0, dtype=torch.bfloat16, device=DEV)     # canaries around the gradient
+    runs = [B.run_batch(b, diagnostics=True, grad=gbuf[pad:pad + T * V].view(T, V)), B.run_batch(b, diagnostics=True)]
     torch.cuda.synchronize()
     assert B.last_path() == "resident_multi"
+    assert torch.all(gbuf[:pad] == 7.0) and torch.all(gbuf[pad + T * V:] == 7.0)
     for k in ("loss", "loss_tok", "divergence", "mask", "diagnostics", "grad_logits"):
         assert torch.equal(runs[0][k], runs[1][k]), k
     fixed = B.run_batch(b, diagnostics=True, flags=B.FLAG_STATIC_ROWS)
