@@ -268,7 +268,7 @@ def test_rows_handed_out_at_run_time_match_rows_fixed_by_index(variant, delta):
     workgroup index writes, the scalar loss repeatable bit for bit, a minimum-size workspace falling
     back to fixed rows; ignored and zero-advantage rows included; a sample against the oracle."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    T = 4 * cus + 29
+    T = 12 * cus + 29
     w = W.Workload("dynfull", 1, T, 100000, variant, delta, mu_full=True, logit_std=3.0, noise_std=0.7, zipf_s=1.1, adv="normal", seed=127)
     b = W.make_batch(w, DEV, shift_sampled=1.0)
     b["advantages"] = torch.randn(T, device=DEV)
@@ -289,7 +289,7 @@ def test_rows_handed_out_at_run_time_match_rows_fixed_by_index(variant, delta):
         assert torch.equal(runs[0]["loss"], r["loss"])
     assert torch.equal(fixed["loss"], rmin["loss"])
     assert abs(runs[0]["loss"].item() - fixed["loss"].item()) <= 1e-6 * abs(fixed["loss"].item())
-    rows = np.arange(T)[::8]
+    rows = np.arange(T)[::24]
     st = P.compare_rows(b, runs[0], rows)
     assert 0 < (runs[0]["mask"] == 0).sum().item() < T
     _say(f"       {st}")
