@@ -526,6 +526,52 @@ def test_ragged_rows_in_registers_with_special_rows(V, ld):
     _say(f"       {st}")
 
 
+@pytest.mark.parametrize("V,ld,T,variant,K,off,path", [
+    (37372, 37372, 17416, W.TOPK_KL, 70, 8, "resident_multi"),
+    (58002, 58013, 17237, W.TOPK_TV, 20, 1, "resident_multi"),
+    (21787, 21790, 45892, W.TOPK_TV, 20, 1, "resident_multi"),
+    (50450, 50461, 19817, W.BINARY_TV, 0, 5, "resident_multi"),
+    (49872, 49872, 20051, W.BINARY_TV, 0, 24, "resident_multi"),
+    (6682, 6720, 26116, W.BINARY_TV, 0, 24, "resident"),
+    (2363, 2363, 52226, W.BINARY_TV, 0, 1, "resident"),
+    (122024, 122025, 8195, W.TOPK_KL, 70, 0, "resident"),
+    (154736, 154737, 6462, W.BINARY_KL, 0, 0, "resident"),
+    (174024, 174080, 5744, W.TOPK_KL, 70, 0, "resident_long"),
+])
+def test_fast_paths_agree_with_the_two_pass_kernel_on_odd_layouts(V, ld, T, variant, K, off, path):
+    """Vocabulary sizes, pitches and buffer offsets (in elements, the same for logits and gradient)
+    off every boundary the fast kernels like, at sizes the oracle would take minutes for: the
+    register-resident kernels (plain and ragged, one row and groups of rows) against the general
+    two-pass kernel on the same call: masks equal outside the 1e-5 band around delta, divergences,
+    loss terms and gradients within the parity tolerances, and no byte outside [T, V) written."""
+    delta = 0.05 if variant in (W.BINARY_KL, W.TOPK_KL) else 0.15
+    w = W.Workload("layouts", 1, T, V, variant, delta, K=K, logit_std=3.0, noise_std=1.0, zipf_s=1.1, adv="normal", seed=V + T)
+    b = W.make_batch(w, DEV, ld=ld, shift_sampled=2.0)
+    b["advantages"] = torch.randn(T, device=DEV)
+    b["sampled_ids"][::23] = -1
+    for i, a in enumerate([0, 1, 7, 8, V - 1, V - 2, V - 8, V - 9, V // 2] * 6):
+        b["sampled_ids"][3 + 5 * i] = a
+    big = torch.zeros(T * ld + 64, dtype=torch.bfloat16, device=DEV)
+    big[off:off + T * ld] = b["logits"].reshape(-1)
+    b["logits"] = big[off:off + T * ld].view(T, ld)
+    gbuf = torch.full((T * ld + 64,), 7.0, dtype=torch.bfloat16, device=DEV)
+    grad = gbuf[off:off + T * ld].view(T, ld)
+    r = B.run_batch(b, diagnostics=True, grad=grad)
+    assert B.last_path() == path
+    s = B.run_batch(b, diagnostics=True, flags=B.FLAG_FORCE_STREAMING)
+    torch.cuda.synchronize()
+    assert torch.all(gbuf[:off] == 7.0) and torch.all(gbuf[off + T * ld:] == 7.0) and torch.all(grad[:, V:] == 7.0)
+    D1, D2 = r["divergence"].double(), s["divergence"].double()
+    same = r["mask"] == s["mask"]
+    assert torch.all(same | ((D1 - delta).abs() < 1e-5))
+    assert torch.all((D1 - D2).abs() <= 1e-6 + 1e-4 * D2.abs())
+    lt1, lt2 = r["loss_tok"].double()[same], s["loss_tok"].double()[same]
+    assert torch.all((lt1 - lt2).abs() <= 1e-5 * (1 + lt2.abs()))
+    g1, g2 = grad[:, :V].float()[same], s["grad_logits"][:, :V].float()[same]
+    assert torch.all((g1 - g2).abs() <= 2e-2 * g2.abs() + 1e-30)
+    assert 0 < (r["mask"] == 0).sum().item() < T
+
+
 def test_misaligned_gradient_buffer_takes_elementwise_path():
     w = W.Workload("misaligned", 2, 7, 2051, W.BINARY_TV, 0.1, logit_std=2.0, noise_std=0.5, adv="pm1", seed=3)
     b = W.make_batch(w, DEV)
